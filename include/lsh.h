@@ -1,0 +1,158 @@
+/*
+ * lsh.h -- C ABI of the MI355X (gfx950) library for batched l2 LSH hash evaluation.
+ *
+ * The operation (paper: "Fast Locality Sensitive Hashing with Theoretical
+ * Guarantee", FastLSH):
+ *
+ *   E2LSH   (Sec. 2.2, Eq. 1):  h_{a,b}(v)   = floor((a^T v + b) / w),   a in R^n
+ *   FastLSH (Sec. 3.1, Eq. 5):  h_{a~,b~}(v) = floor((a~^T S(v) + b~) / w~), a~ in R^m
+ *
+ * where S(.) keeps m sampled coordinates of v in draw order (Sec. 3.1, first
+ * step), a / a~ have i.i.d. N(0,1) entries and b / b~ is uniform on [0, w).
+ * All k hash functions are evaluated for all N vectors; here k is the TOTAL
+ * number of functions (the paper's k functions per table times L tables,
+ * Sec. 3.2), function j belonging to table j / (k/L).
+ *
+ * Conventions
+ *   - Every function returns an int status: LSH_OK (0) or a negative LSH_ERR_*.
+ *     Nothing throws or aborts.  lsh_status_string() names a status.
+ *   - "d_" arguments are DEVICE pointers owned by the caller; they must be valid
+ *     on the device that was current when the params object was created.  All
+ *     other pointers are HOST pointers.
+ *   - data is row-major fp32 [N][n], 16-byte-aligned base; outputs are row-major.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Hash
+ *     calls only enqueue work on it and never synchronise; the caller keeps
+ *     data/outputs alive until the stream has drained.
+ *   - N = 0 is LSH_OK and launches nothing.
+ *   - The params object and its device tables belong to the library and are
+ *     freed by lsh_params_destroy().  One object may be used from several host
+ *     threads for hashing; create/destroy are not thread-safe against its use.
+ */
+#ifndef LSH_H
+#define LSH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LSH_OK 0
+#define LSH_ERR_INVALID_ARG (-1) /* null pointer, zero size, m > n, bad w, k % L != 0 ... */
+#define LSH_ERR_ALLOC (-2)       /* host or device allocation failed */
+#define LSH_ERR_HIP (-3)         /* a HIP runtime call or kernel launch failed */
+#define LSH_ERR_UNSUPPORTED (-4) /* no kernel covers this shape (see each call) */
+#define LSH_ERR_NO_DEVICE (-5)   /* params object has no device tables (no GPU at create) */
+
+/* flags of lsh_params_create_ex */
+#define LSH_SAMPLE_WITHOUT_REPLACEMENT 0u /* m distinct coordinates per function (default) */
+#define LSH_SAMPLE_WITH_REPLACEMENT 1u    /* m i.i.d. draws: the multiset of Sec. 3.1 */
+
+typedef struct lsh_params lsh_params_t; /* opaque */
+
+/*
+ * Draw the k hash functions (Sec. 3.1: S_j, a~_j, b~_j for j < k; Sec. 2.2 when
+ * m == n) and, if a GPU is present, upload their tables to the current device.
+ *   n     vector dimension (>= 1)
+ *   k     number of hash functions (>= 1)
+ *   m     sampled dimensions per function, 1 <= m <= n; m == n means no
+ *         sampling: S_j = (0..n-1) and the functions are E2LSH functions
+ *   w     bucket width, finite and > 0
+ *   seed  the tables are a pure function of (n, k, m, w, seed, flags): each
+ *         element is one Philox4x64-10 block keyed by seed and indexed by
+ *         (table, j, i); N(0,1) by Box-Muller; without replacement = the first
+ *         m steps of a Fisher-Yates shuffle
+ *   out   receives the object (host pointer to a pointer)
+ * Errors: INVALID_ARG, ALLOC, HIP.  Without a GPU the object is still created
+ * (getters work) and hash calls return LSH_ERR_NO_DEVICE.
+ */
+int lsh_params_create(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
+                      lsh_params_t **out);
+int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
+                         uint32_t flags, lsh_params_t **out);
+void lsh_params_destroy(lsh_params_t *params);
+
+/*
+ * Host copies of the canonical tables (for inspection and bit-exact checks).
+ *   indices [k*m]  S_j[i], 0-based coordinate numbers, draw order (row j = function j)
+ *   coeffs  [k*m]  a~_j[i]
+ *   offsets [k]    b~_j
+ * Caller provides the arrays.  Errors: INVALID_ARG.
+ */
+int lsh_params_get_indices(const lsh_params_t *params, uint32_t *out);
+int lsh_params_get_coeffs(const lsh_params_t *params, float *out);
+int lsh_params_get_offsets(const lsh_params_t *params, float *out);
+/* the six scalars: n, k, m, flags as uint32; w; seed.  Any out pointer may be NULL. */
+int lsh_params_get_shape(const lsh_params_t *params, uint32_t *n, uint32_t *k, uint32_t *m,
+                         uint32_t *flags, float *w, uint64_t *seed);
+
+/*
+ * FastLSH bucket ids (Eq. 5): d_out_buckets[v*k + j] = floor((a~_j^T S_j(v) + b~_j) / w)
+ * as int32 (saturating), for v < N, j < k.  Sampled-projection kernel: each vector
+ * tile is read from HBM once, kept in LDS, and every function gathers its m
+ * coordinates from there.  fp32 accumulation.
+ * Errors: INVALID_ARG (null pointers), NO_DEVICE, UNSUPPORTED (n > 32768), HIP.
+ */
+int lsh_hash_fastlsh(const lsh_params_t *params, const float *d_data, uint64_t N,
+                     int32_t *d_out_buckets, void *stream);
+
+/*
+ * E2LSH bucket ids (Eq. 1) by a dense [N x n] . [n x k] fp32 MFMA contraction with the
+ * floor((. + b) / w) epilogue fused.  Requires params created with m == n
+ * (INVALID_ARG otherwise).  Same output layout as lsh_hash_fastlsh, and the two agree
+ * on such params up to fp32 summation order.
+ */
+int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
+                   int32_t *d_out_buckets, void *stream);
+
+/*
+ * Sign hashes for angular similarity (Sec. 5: FastLSH on normalised data; the sign form
+ * of the sampled projection): bit j = [a~_j^T S_j(v) >= 0]; function j is bit j % 64
+ * (bit 0 least significant) of d_out_words[v * ceil(k/64) + j / 64]; unused high bits of
+ * the last word are 0.  b~ and w are not used.
+ */
+int lsh_hash_signs(const lsh_params_t *params, const float *d_data, uint64_t N,
+                   uint64_t *d_out_words, void *stream);
+
+/*
+ * Compound keys (Sec. 3.2: H(v) is the concatenation of the codes of one table).  The k
+ * ids of a vector form L groups of g = k/L consecutive ids; d_out_keys[v*L + l] =
+ * sum_t uint32(h_{l*g+t}) * C^(g-1-t) mod 2^64 with C = 0x9E3779B97F4A7C15.  (The lossless
+ * concatenation itself is d_buckets viewed as [N][L][g].)
+ * Errors: INVALID_ARG (L == 0 or k % L != 0).
+ */
+int lsh_pack_keys(const lsh_params_t *params, const int32_t *d_buckets, uint64_t N, uint32_t L,
+                  uint64_t *d_out_keys, void *stream);
+
+/*
+ * lsh_hash_fastlsh followed by lsh_pack_keys in one kernel: the ids never reach HBM.
+ * UNSUPPORTED unless g = k/L is a power of two <= 64 (use the two calls otherwise).
+ */
+int lsh_hash_fastlsh_keys(const lsh_params_t *params, const float *d_data, uint64_t N, uint32_t L,
+                          uint64_t *d_out_keys, void *stream);
+
+/*
+ * Raw fp32 projections a~_j^T S_j(v) (before + b, / w, floor), d_out_proj[v*k + j]; for
+ * accuracy checks.  lsh_project_e2lsh requires m == n and uses the MFMA path.
+ */
+int lsh_project_fastlsh(const lsh_params_t *params, const float *d_data, uint64_t N,
+                        float *d_out_proj, void *stream);
+int lsh_project_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
+                      float *d_out_proj, void *stream);
+
+/*
+ * Timing aid for callers without HIP bindings: records two events around `reps`
+ * back-to-back launches of one hash call on `stream`, waits for them, and returns the
+ * mean milliseconds per launch in *ms_per_launch.  `which`: 0 fastlsh ids, 1 e2lsh ids,
+ * 2 signs, 3 pack_keys (d_in = ids), 4 fastlsh_keys.  L is used by 3 and 4.  This call
+ * DOES synchronise (on its own events only).
+ */
+int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, uint64_t N,
+                      uint32_t L, void *d_out, void *stream, int reps, float *ms_per_launch);
+
+const char *lsh_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSH_H */

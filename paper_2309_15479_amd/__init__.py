@@ -1,0 +1,11 @@
+"""MI355X (gfx950) batched l2 LSH hash evaluation: FastLSH (sampled projection), dense
+E2LSH on the fp32 matrix cores, sign hashes and compound-key packing, behind the C ABI of
+``include/lsh.h``.  This package is only the Python binding (argument marshalling); all
+arithmetic runs in the HIP kernels of ``liblsh.so``."""
+from .binding import (LshError, LshParams, hash_e2lsh, hash_fastlsh, hash_fastlsh_keys, hash_signs,
+                      library_path, load_library, pack_keys, project_e2lsh, project_fastlsh,
+                      time_launches)
+
+__all__ = ["LshError", "LshParams", "hash_e2lsh", "hash_fastlsh", "hash_fastlsh_keys", "hash_signs",
+           "library_path", "load_library", "pack_keys", "project_e2lsh", "project_fastlsh",
+           "time_launches"]

@@ -1,0 +1,226 @@
+"""ctypes binding of liblsh.so; names and arguments mirror include/lsh.h.
+
+PyTorch is used for device memory and streams only: tensors are passed as raw device
+pointers, the current torch stream as the hipStream_t.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblsh.so")
+_lib = None
+
+LSH_OK = 0
+SAMPLE_WITHOUT_REPLACEMENT = 0
+SAMPLE_WITH_REPLACEMENT = 1
+
+EXPORTS = [
+    "lsh_params_create", "lsh_params_create_ex", "lsh_params_destroy", "lsh_params_get_indices",
+    "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape", "lsh_hash_fastlsh",
+    "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
+    "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
+]
+
+
+class LshError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads liblsh.so (built by paper_2309_15479_amd/build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2309_15479_amd.build` "
+            "(there is no fallback implementation)")
+    try:
+        import torch  # noqa: F401  -- so that liblsh binds to the HIP runtime torch already loaded
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_LIB_PATH)
+    u32, u64, f32, p, i = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int
+    lib.lsh_params_create.argtypes = [u32, u32, u32, f32, u64, ctypes.POINTER(p)]
+    lib.lsh_params_create_ex.argtypes = [u32, u32, u32, f32, u64, u32, ctypes.POINTER(p)]
+    lib.lsh_params_destroy.argtypes = [p]
+    lib.lsh_params_destroy.restype = None
+    for name in ("lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets"):
+        getattr(lib, name).argtypes = [p, p]
+    lib.lsh_params_get_shape.argtypes = [p, p, p, p, p, p, p]
+    for name in ("lsh_hash_fastlsh", "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_project_fastlsh",
+                 "lsh_project_e2lsh"):
+        getattr(lib, name).argtypes = [p, p, u64, p, p]
+    lib.lsh_pack_keys.argtypes = [p, p, u64, u32, p, p]
+    lib.lsh_hash_fastlsh_keys.argtypes = [p, p, u64, u32, p, p]
+    lib.lsh_time_launches.argtypes = [p, i, p, u64, u32, p, p, i, ctypes.POINTER(f32)]
+    lib.lsh_status_string.argtypes = [i]
+    lib.lsh_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load_library().lsh_status_string(int(status)).decode()
+
+
+def _check(status, what):
+    if status != LSH_OK:
+        raise LshError(status, what)
+
+
+class LshParams:
+    """Owns one lsh_params_t (the k hash functions and their device tables)."""
+
+    def __init__(self, n, k, m, w, seed, with_replacement=False):
+        lib = load_library()
+        handle = ctypes.c_void_p()
+        flags = SAMPLE_WITH_REPLACEMENT if with_replacement else SAMPLE_WITHOUT_REPLACEMENT
+        _check(lib.lsh_params_create_ex(n, k, m, w, seed, flags, ctypes.byref(handle)),
+               "lsh_params_create_ex")
+        self._h = handle
+        self.n, self.k, self.m, self.w, self.seed = int(n), int(k), int(m), float(w), int(seed)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().lsh_params_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("params object is closed")
+        return self._h
+
+    def indices(self):
+        out = np.empty((self.k, self.m), np.uint32)
+        _check(load_library().lsh_params_get_indices(self.handle, out.ctypes.data), "get_indices")
+        return out
+
+    def coeffs(self):
+        out = np.empty((self.k, self.m), np.float32)
+        _check(load_library().lsh_params_get_coeffs(self.handle, out.ctypes.data), "get_coeffs")
+        return out
+
+    def offsets(self):
+        out = np.empty(self.k, np.float32)
+        _check(load_library().lsh_params_get_offsets(self.handle, out.ctypes.data), "get_offsets")
+        return out
+
+    def shape(self):
+        n, k, m, fl = (ctypes.c_uint32() for _ in range(4))
+        w, seed = ctypes.c_float(), ctypes.c_uint64()
+        _check(load_library().lsh_params_get_shape(self.handle, *(ctypes.addressof(x) for x in
+                                                                  (n, k, m, fl, w, seed))), "get_shape")
+        return dict(n=n.value, k=k.value, m=m.value, flags=fl.value, w=w.value, seed=seed.value)
+
+
+def _stream(stream):
+    if stream is not None:
+        return ctypes.c_void_p(int(stream))
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_in(t, dtype, cols):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()
+            and t.dim() == 2 and t.shape[1] == cols):
+        raise ValueError(f"expected a contiguous CUDA tensor [N,{cols}] of {dtype}")
+    return t
+
+
+def _out(data, N, cols, dtype, out):
+    import torch
+    if out is None:
+        return torch.empty((N, cols), dtype=dtype, device=data.device)
+    _dev_in(out, dtype, cols)
+    if out.shape[0] != N:
+        raise ValueError("output has the wrong number of rows")
+    return out
+
+
+def _hash_call(name, params, data, cols, dtype, out, stream):
+    import torch
+    _dev_in(data, torch.float32, params.n)
+    N = data.shape[0]
+    out = _out(data, N, cols, dtype, out)
+    fn = getattr(load_library(), name)
+    _check(fn(params.handle, data.data_ptr(), N, out.data_ptr(), _stream(stream)), name)
+    return out
+
+
+def hash_fastlsh(params, data, out=None, stream=None):
+    import torch
+    return _hash_call("lsh_hash_fastlsh", params, data, params.k, torch.int32, out, stream)
+
+
+def hash_e2lsh(params, data, out=None, stream=None):
+    import torch
+    return _hash_call("lsh_hash_e2lsh", params, data, params.k, torch.int32, out, stream)
+
+
+def hash_signs(params, data, out=None, stream=None):
+    """Packed sign bits as int64 words [N, ceil(k/64)] (bit patterns of the uint64 words)."""
+    import torch
+    return _hash_call("lsh_hash_signs", params, data, (params.k + 63) // 64, torch.int64, out, stream)
+
+
+def project_fastlsh(params, data, out=None, stream=None):
+    import torch
+    return _hash_call("lsh_project_fastlsh", params, data, params.k, torch.float32, out, stream)
+
+
+def project_e2lsh(params, data, out=None, stream=None):
+    import torch
+    return _hash_call("lsh_project_e2lsh", params, data, params.k, torch.float32, out, stream)
+
+
+def pack_keys(params, buckets, L, out=None, stream=None):
+    """64-bit keys as int64 [N, L] (bit patterns of the uint64 keys)."""
+    import torch
+    _dev_in(buckets, torch.int32, params.k)
+    N = buckets.shape[0]
+    out = _out(buckets, N, L, torch.int64, out)
+    _check(load_library().lsh_pack_keys(params.handle, buckets.data_ptr(), N, L, out.data_ptr(),
+                                        _stream(stream)), "lsh_pack_keys")
+    return out
+
+
+def hash_fastlsh_keys(params, data, L, out=None, stream=None):
+    import torch
+    _dev_in(data, torch.float32, params.n)
+    N = data.shape[0]
+    out = _out(data, N, L, torch.int64, out)
+    _check(load_library().lsh_hash_fastlsh_keys(params.handle, data.data_ptr(), N, L, out.data_ptr(),
+                                                _stream(stream)), "lsh_hash_fastlsh_keys")
+    return out
+
+
+_WHICH = {"fastlsh": 0, "e2lsh": 1, "signs": 2, "pack_keys": 3, "fastlsh_keys": 4}
+
+
+def time_launches(params, which, d_in, d_out, L=0, reps=10, stream=None):
+    """Mean milliseconds per launch of one hash call, by HIP events on the launch stream."""
+    ms = ctypes.c_float()
+    _check(load_library().lsh_time_launches(params.handle, _WHICH[which], d_in.data_ptr(), d_in.shape[0],
+                                            L, d_out.data_ptr(), _stream(stream), reps, ctypes.byref(ms)),
+           "lsh_time_launches")
+    return float(ms.value)

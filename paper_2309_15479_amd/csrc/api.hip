@@ -1,0 +1,270 @@
+// C ABI of liblsh (see include/lsh.h): argument checks, table upload, dispatch.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <new>
+
+#include "lsh_internal.h"
+
+namespace lsh {
+
+uint32_t sampled_chunk();
+uint32_t dense_col_tile();
+
+void free_tables(lsh_params *p) {
+    if (p->device < 0) return;
+    int prev = -1;
+    if (hipGetDevice(&prev) == hipSuccess && prev != p->device) (void)hipSetDevice(p->device);
+    if (p->d_samples) (void)hipFree(p->d_samples);
+    if (p->d_off) (void)hipFree(p->d_off);
+    if (p->d_dense) (void)hipFree(p->d_dense);
+    p->d_samples = nullptr;
+    p->d_off = nullptr;
+    p->d_dense = nullptr;
+    if (prev >= 0 && prev != p->device) (void)hipSetDevice(prev);
+    p->device = -1;
+}
+
+// Builds the kernel-side layouts from the canonical tables and copies them to the
+// current device.  Returns LSH_OK with p->device == -1 when there is no GPU.
+int upload_tables(lsh_params *p) {
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
+        (void)hipGetLastError();
+        return LSH_OK;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return LSH_ERR_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return LSH_ERR_HIP;
+    p->num_cus = prop.multiProcessorCount;
+    p->plan = plan_sampled(p->n, p->k, p->m);
+    p->device = dev;
+
+    const uint32_t chunk = sampled_chunk();
+    const uint32_t m_pad = (p->m + chunk - 1) / chunk * chunk;
+    const uint32_t kpad = p->plan.supported ? p->plan.kpad : (p->k + 63) / 64 * 64;
+    p->kpad_dense = 0;
+    if (p->m == p->n) p->kpad_dense = (p->k + dense_col_tile() - 1) / dense_col_tile() * dense_col_tile();
+    const uint32_t off_len = kpad > p->kpad_dense ? kpad : p->kpad_dense;
+
+    int rc = LSH_OK;
+    try {
+        std::vector<float> off(off_len, 0.f);
+        for (uint32_t j = 0; j < p->k; ++j) off[j] = p->off[j];
+        if (hipMalloc(&p->d_off, off.size() * sizeof(float)) != hipSuccess) rc = LSH_ERR_ALLOC;
+        if (rc == LSH_OK &&
+            hipMemcpy(p->d_off, off.data(), off.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+            rc = LSH_ERR_HIP;
+
+        if (rc == LSH_OK && p->plan.supported) {
+            // sample-major [m_pad][kpad]; padding entries read the tile's zero slot
+            const uint32_t zero_slot = p->n * p->plan.rt * 4u;
+            std::vector<Sample> tab((size_t)m_pad * kpad, Sample{zero_slot, 0.f});
+            for (uint32_t j = 0; j < p->k; ++j)
+                for (uint32_t i = 0; i < p->m; ++i) {
+                    Sample &s = tab[(size_t)i * kpad + j];
+                    s.lds_byte_offset = p->idx[(size_t)j * p->m + i] * p->plan.rt * 4u;
+                    s.coef = p->coef[(size_t)j * p->m + i];
+                }
+            if (hipMalloc(&p->d_samples, tab.size() * sizeof(Sample)) != hipSuccess) rc = LSH_ERR_ALLOC;
+            if (rc == LSH_OK && hipMemcpy(p->d_samples, tab.data(), tab.size() * sizeof(Sample),
+                                          hipMemcpyHostToDevice) != hipSuccess)
+                rc = LSH_ERR_HIP;
+        }
+        if (rc == LSH_OK && p->kpad_dense) {
+            // m == n: S_j is the identity, so the canonical coefficient table IS the dense
+            // matrix A [k][n]; rows up to the tile grid are zero
+            std::vector<float> dense((size_t)p->kpad_dense * p->n, 0.f);
+            std::copy(p->coef.begin(), p->coef.end(), dense.begin());
+            if (hipMalloc(&p->d_dense, dense.size() * sizeof(float)) != hipSuccess) rc = LSH_ERR_ALLOC;
+            if (rc == LSH_OK && hipMemcpy(p->d_dense, dense.data(), dense.size() * sizeof(float),
+                                          hipMemcpyHostToDevice) != hipSuccess)
+                rc = LSH_ERR_HIP;
+        }
+    } catch (const std::bad_alloc &) {
+        rc = LSH_ERR_ALLOC;
+    }
+    if (rc != LSH_OK) {
+        (void)hipGetLastError();
+        free_tables(p);
+    }
+    return rc;
+}
+
+namespace {
+
+int check_hash_args(const lsh_params *p, const void *d_in, const void *d_out) {
+    if (!p || !d_in || !d_out) return LSH_ERR_INVALID_ARG;
+    if (p->device < 0) return LSH_ERR_NO_DEVICE;
+    return LSH_OK;
+}
+
+bool is_pow2(uint32_t x) { return x && !(x & (x - 1)); }
+
+}  // namespace
+}  // namespace lsh
+
+using namespace lsh;
+
+extern "C" {
+
+int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
+                         lsh_params_t **out) {
+    if (!out) return LSH_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!n || !k || !m || m > n || !(w > 0.f) || !std::isfinite(w)) return LSH_ERR_INVALID_ARG;
+    if (flags & ~LSH_SAMPLE_WITH_REPLACEMENT) return LSH_ERR_INVALID_ARG;
+    if ((uint64_t)k * m > (1ull << 31)) return LSH_ERR_INVALID_ARG;
+    lsh_params *p = new (std::nothrow) lsh_params;
+    if (!p) return LSH_ERR_ALLOC;
+    p->n = n; p->k = k; p->m = m; p->w = w; p->seed = seed; p->flags = flags;
+    int rc = generate_tables(n, k, m, w, seed, flags, p->idx, p->coef, p->off);
+    if (rc == LSH_OK) rc = upload_tables(p);
+    if (rc != LSH_OK) {
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return LSH_OK;
+}
+
+int lsh_params_create(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, lsh_params_t **out) {
+    return lsh_params_create_ex(n, k, m, w, seed, LSH_SAMPLE_WITHOUT_REPLACEMENT, out);
+}
+
+void lsh_params_destroy(lsh_params_t *p) {
+    if (!p) return;
+    free_tables(p);
+    delete p;
+}
+
+int lsh_params_get_indices(const lsh_params_t *p, uint32_t *out) {
+    if (!p || !out) return LSH_ERR_INVALID_ARG;
+    std::copy(p->idx.begin(), p->idx.end(), out);
+    return LSH_OK;
+}
+
+int lsh_params_get_coeffs(const lsh_params_t *p, float *out) {
+    if (!p || !out) return LSH_ERR_INVALID_ARG;
+    std::copy(p->coef.begin(), p->coef.end(), out);
+    return LSH_OK;
+}
+
+int lsh_params_get_offsets(const lsh_params_t *p, float *out) {
+    if (!p || !out) return LSH_ERR_INVALID_ARG;
+    std::copy(p->off.begin(), p->off.end(), out);
+    return LSH_OK;
+}
+
+int lsh_params_get_shape(const lsh_params_t *p, uint32_t *n, uint32_t *k, uint32_t *m, uint32_t *flags,
+                         float *w, uint64_t *seed) {
+    if (!p) return LSH_ERR_INVALID_ARG;
+    if (n) *n = p->n;
+    if (k) *k = p->k;
+    if (m) *m = p->m;
+    if (flags) *flags = p->flags;
+    if (w) *w = p->w;
+    if (seed) *seed = p->seed;
+    return LSH_OK;
+}
+
+int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {
+    int rc = check_hash_args(p, d_data, d_out);
+    if (rc != LSH_OK || N == 0) return rc;
+    return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
+}
+
+int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, float *d_out, void *stream) {
+    int rc = check_hash_args(p, d_data, d_out);
+    if (rc != LSH_OK || N == 0) return rc;
+    return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);
+}
+
+int lsh_hash_signs(const lsh_params_t *p, const float *d_data, uint64_t N, uint64_t *d_out, void *stream) {
+    int rc = check_hash_args(p, d_data, d_out);
+    if (rc != LSH_OK || N == 0) return rc;
+    return launch_sampled(p, Epilogue::Signs, d_data, N, d_out, 0, stream);
+}
+
+int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N, uint32_t L,
+                          uint64_t *d_out, void *stream) {
+    int rc = check_hash_args(p, d_data, d_out);
+    if (rc != LSH_OK) return rc;
+    if (!L || p->k % L) return LSH_ERR_INVALID_ARG;
+    const uint32_t g = p->k / L;
+    if (!is_pow2(g) || g > 64) return LSH_ERR_UNSUPPORTED;
+    if (N == 0) return LSH_OK;
+    return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
+}
+
+int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {
+    int rc = check_hash_args(p, d_data, d_out);
+    if (rc != LSH_OK) return rc;
+    if (p->m != p->n) return LSH_ERR_INVALID_ARG;
+    if (N == 0) return LSH_OK;
+    return launch_dense(p, false, d_data, N, d_out, stream);
+}
+
+int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, float *d_out, void *stream) {
+    int rc = check_hash_args(p, d_data, d_out);
+    if (rc != LSH_OK) return rc;
+    if (p->m != p->n) return LSH_ERR_INVALID_ARG;
+    if (N == 0) return LSH_OK;
+    return launch_dense(p, true, d_data, N, d_out, stream);
+}
+
+int lsh_pack_keys(const lsh_params_t *p, const int32_t *d_ids, uint64_t N, uint32_t L, uint64_t *d_keys,
+                  void *stream) {
+    int rc = check_hash_args(p, d_ids, d_keys);
+    if (rc != LSH_OK) return rc;
+    if (!L || p->k % L) return LSH_ERR_INVALID_ARG;
+    if (N == 0) return LSH_OK;
+    return launch_pack(p, d_ids, N, L, d_keys, stream);
+}
+
+int lsh_time_launches(const lsh_params_t *p, int which, const void *d_in, uint64_t N, uint32_t L,
+                      void *d_out, void *stream, int reps, float *ms_per_launch) {
+    if (!ms_per_launch || reps <= 0 || which < 0 || which > 4) return LSH_ERR_INVALID_ARG;
+    int rc = check_hash_args(p, d_in, d_out);
+    if (rc != LSH_OK) return rc;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    if (hipEventCreate(&t0) != hipSuccess) return LSH_ERR_HIP;
+    if (hipEventCreate(&t1) != hipSuccess) {
+        (void)hipEventDestroy(t0);
+        return LSH_ERR_HIP;
+    }
+    rc = hipEventRecord(t0, s) == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+    for (int r = 0; r < reps && rc == LSH_OK; ++r) {
+        switch (which) {
+            case 0: rc = lsh_hash_fastlsh(p, (const float *)d_in, N, (int32_t *)d_out, stream); break;
+            case 1: rc = lsh_hash_e2lsh(p, (const float *)d_in, N, (int32_t *)d_out, stream); break;
+            case 2: rc = lsh_hash_signs(p, (const float *)d_in, N, (uint64_t *)d_out, stream); break;
+            case 3: rc = lsh_pack_keys(p, (const int32_t *)d_in, N, L, (uint64_t *)d_out, stream); break;
+            default: rc = lsh_hash_fastlsh_keys(p, (const float *)d_in, N, L, (uint64_t *)d_out, stream);
+        }
+    }
+    if (rc == LSH_OK && hipEventRecord(t1, s) != hipSuccess) rc = LSH_ERR_HIP;
+    if (rc == LSH_OK && hipEventSynchronize(t1) != hipSuccess) rc = LSH_ERR_HIP;
+    float ms = 0.f;
+    if (rc == LSH_OK && hipEventElapsedTime(&ms, t0, t1) != hipSuccess) rc = LSH_ERR_HIP;
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (rc == LSH_OK) *ms_per_launch = ms / (float)reps;
+    return rc;
+}
+
+const char *lsh_status_string(int status) {
+    switch (status) {
+        case LSH_OK: return "ok";
+        case LSH_ERR_INVALID_ARG: return "invalid argument";
+        case LSH_ERR_ALLOC: return "allocation failed";
+        case LSH_ERR_HIP: return "HIP runtime error";
+        case LSH_ERR_UNSUPPORTED: return "unsupported shape";
+        case LSH_ERR_NO_DEVICE: return "params object has no device tables";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

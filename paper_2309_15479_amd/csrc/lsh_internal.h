@@ -1,0 +1,71 @@
+// Internal declarations shared by the host and device translation units of liblsh.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "lsh.h"
+
+namespace lsh {
+
+// One entry of the device table of the sampled-projection kernel: where to read in the
+// LDS tile (byte offset of the sampled coordinate's slot) and the coefficient.
+struct Sample {
+    uint32_t lds_byte_offset;
+    float coef;
+};
+
+// How the sampled kernel is launched for one params object; fixed at create time.
+struct SampledPlan {
+    uint32_t rt = 0;         // vectors interleaved per LDS slot (1, 2, 4 or 8)
+    uint32_t sub = 0;        // sub-tiles of rt vectors per workgroup tile
+    uint32_t block = 0;      // threads per workgroup = functions per workgroup
+    uint32_t kblocks = 0;    // workgroups along the function axis
+    uint32_t kpad = 0;       // block * kblocks >= k
+    uint32_t lds_bytes = 0;  // dynamic LDS per workgroup
+    bool reg_table = false;  // m == 32: (offset, coef) lists live in registers
+    bool supported = false;
+};
+
+}  // namespace lsh
+
+struct lsh_params {
+    uint32_t n = 0, k = 0, m = 0, flags = 0;
+    float w = 0.f;
+    uint64_t seed = 0;
+    // canonical host tables
+    std::vector<uint32_t> idx;  // [k][m]
+    std::vector<float> coef;    // [k][m]
+    std::vector<float> off;     // [k]
+    // device side
+    int device = -1;  // -1: no device tables
+    int num_cus = 0;
+    lsh::SampledPlan plan;
+    lsh::Sample *d_samples = nullptr;  // [m][kpad], sample-major
+    float *d_off = nullptr;            // [kpad]
+    float *d_dense = nullptr;          // [kpad_dense][n] when m == n (row j = a_j), else null
+    uint32_t kpad_dense = 0;
+};
+
+namespace lsh {
+
+// host: draws the canonical tables (returns LSH_OK / LSH_ERR_*)
+int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
+                    std::vector<uint32_t> &idx, std::vector<float> &coef, std::vector<float> &off);
+
+// device: plan + upload + launches (defined in the .hip files)
+SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m);
+int upload_tables(lsh_params *p);
+void free_tables(lsh_params *p);
+
+enum class Epilogue : int { Ids = 0, Proj = 1, Signs = 2, Keys = 3 };
+int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
+                   uint32_t L, void *stream);
+int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
+                 void *stream);
+int launch_pack(const lsh_params *p, const int32_t *d_ids, uint64_t N, uint32_t L,
+                uint64_t *d_keys, void *stream);
+
+constexpr uint64_t kKeyMultiplier = 0x9E3779B97F4A7C15ull;
+
+}  // namespace lsh

@@ -1,0 +1,239 @@
+"""GPU parity: every output of the HIP library, through the C ABI, against the CPU oracle on
+the same seeded inputs.  Small shapes are compared element by element on all rows; the
+full-size workloads on a fixed sample of rows (first/last tile plus random rows), in the
+launch configuration the benchmark times."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from parity import check_ids, check_proj, check_signs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+THREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def lsh():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2309_15479_amd as lib
+    lib.load_library()           # raises if the HIP library is missing: no fallback
+    return lib
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def _tables(p):
+    return p.indices(), p.coeffs(), p.offsets()
+
+
+def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=True):
+    """Runs every entry point on data_gpu and checks the given rows against the oracle."""
+    idx, coef, off = _tables(p)
+    rows_t = torch.as_tensor(np.asarray(rows), device=data_gpu.device)
+    sub = data_gpu[rows_t].cpu().numpy()
+    stats = {}
+    ora = oracle.fastlsh(sub, idx, coef, off, p.w, nthreads=THREADS,
+                         want=("proj", "abs_sum", "ids", "frac"))
+    ids_gpu = lsh.hash_fastlsh(p, data_gpu)
+    proj_gpu = lsh.project_fastlsh(p, data_gpu)
+    torch.cuda.synchronize()
+    stats["proj_worst"] = check_proj(proj_gpu[rows_t].cpu().numpy(), ora, label + " fastlsh proj")
+    stats["ids_excluded"] = check_ids(ids_gpu[rows_t].cpu().numpy(), ora, label + " fastlsh ids")
+    if dense:
+        assert p.m == p.n
+        ora_d = oracle.e2lsh(sub, coef, off, p.w, nthreads=THREADS, want=("proj", "abs_sum", "ids", "frac"))
+        ids_d = lsh.hash_e2lsh(p, data_gpu)
+        proj_d = lsh.project_e2lsh(p, data_gpu)
+        torch.cuda.synchronize()
+        stats["dense_proj_worst"] = check_proj(proj_d[rows_t].cpu().numpy(), ora_d, label + " e2lsh proj")
+        stats["dense_ids_excluded"] = check_ids(ids_d[rows_t].cpu().numpy(), ora_d, label + " e2lsh ids")
+    if signs:
+        w_ora, pr, npd = oracle.signs(sub, idx, coef, nthreads=THREADS, want_proj=True, want_norm_prod=True)
+        w_gpu = lsh.hash_signs(p, data_gpu)
+        torch.cuda.synchronize()
+        stats["signs_excluded"] = check_signs(w_gpu[rows_t].cpu().numpy().view(np.uint64), w_ora, pr, npd,
+                                              p.k, label + " signs")
+    if L:
+        keys = lsh.pack_keys(p, ids_gpu, L)
+        torch.cuda.synchronize()
+        ids_host = ids_gpu[rows_t].cpu().numpy()
+        want = oracle.pack_keys(ids_host, L)
+        assert np.array_equal(keys[rows_t].cpu().numpy().view(np.uint64), want), label + " keys"
+        g = p.k // L
+        if g & (g - 1) == 0 and g <= 64:
+            fused = lsh.hash_fastlsh_keys(p, data_gpu, L)
+            torch.cuda.synchronize()
+            assert torch.equal(fused, keys), label + " fused keys"
+    return stats
+
+
+# ---------------------------------------------------------------------------------------
+# the tiny workload: all rows, FastLSH and its E2LSH twin (m = n, same seed)
+# ---------------------------------------------------------------------------------------
+
+def test_tiny_all_rows(lsh):
+    wl, data = workloads.make_data("tiny", "cuda")
+    rows = np.arange(wl.N)
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
+        say("tiny fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="tiny"))
+    with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
+        say("tiny e2lsh", _compare_all(lsh, p, data, rows, L=wl.L, label="tiny-dense", dense=True))
+
+
+# ---------------------------------------------------------------------------------------
+# ragged and degenerate shapes, every tile variant of the sampled kernel
+# ---------------------------------------------------------------------------------------
+
+RAGGED = [
+    # N, n, k, m, w, seed, with_replacement, L
+    (1, 128, 64, 32, 4.0, 21, False, 8),
+    (7, 100, 70, 30, 2.5, 22, True, 7),          # the paper's m = 30; k, n not multiples of anything
+    (33, 37, 130, 37, 1.0, 23, False, 13),       # m = n (dense twin below), odd n
+    (1003, 128, 512, 32, 16.0, 24, False, 32),   # several tiles and a ragged tail
+    (257, 960, 1024, 128, 1.0, 25, False, 64),   # 32-vector tiles, streamed lists
+    (41, 960, 100, 1, 0.75, 26, True, 0),        # m = 1, w not a power of two
+    (29, 4096, 192, 64, 8.0, 27, False, 0),      # 8-vector tiles
+    (13, 8000, 64, 100, 3.0, 28, True, 0),       # 4-vector tiles
+    (9, 16384, 128, 512, 1.0, 29, False, 0),     # 2-vector tiles
+    (5, 30000, 64, 40, 1.0, 30, False, 0),       # 1-vector tiles
+    (300, 64, 2100, 16, 2.0, 31, False, 0),      # more functions than one workgroup holds
+]
+
+
+@pytest.mark.parametrize("N,n,k,m,w,seed,repl,L", RAGGED)
+def test_ragged_shapes(lsh, N, n, k, m, w, seed, repl, L):
+    say(f"case N={N} n={n} k={k} m={m} w={w} seed={seed} repl={repl} L={L}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    data = torch.randn((N, n), generator=g, device="cuda") * 3.0
+    with lsh.LshParams(n, k, m, w, seed, with_replacement=repl) as p:
+        say(_compare_all(lsh, p, data, np.arange(N), L=L, label=f"ragged{seed}", dense=(m == n)))
+
+
+@pytest.mark.parametrize("N,n,k", [(130, 128, 128), (129, 100, 200), (1, 37, 5), (515, 36, 257), (64, 4096, 64)])
+def test_dense_shapes(lsh, N, n, k):
+    say(f"dense case N={N} n={n} k={k}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(N * 7 + n)
+    data = torch.randn((N, n), generator=g, device="cuda") * 2.0
+    with lsh.LshParams(n, k, n, 1.5, N + n + k) as p:
+        say(_compare_all(lsh, p, data, np.arange(N), label=f"dense{N}x{n}x{k}", dense=True, signs=False))
+
+
+def test_empty_input_and_errors(lsh):
+    with lsh.LshParams(128, 64, 32, 4.0, 1) as p:
+        data = torch.empty((0, 128), device="cuda")
+        assert lsh.hash_fastlsh(p, data).shape == (0, 64)
+        assert lsh.hash_signs(p, data).shape == (0, 1)
+        x = torch.zeros((4, 128), device="cuda")
+        with pytest.raises(lsh.LshError) as e:          # dense path needs m == n
+            lsh.hash_e2lsh(p, x)
+        assert e.value.status == -1
+        ids = lsh.hash_fastlsh(p, x)
+        with pytest.raises(lsh.LshError) as e:          # k % L != 0
+            lsh.pack_keys(p, ids, 5)
+        assert e.value.status == -1
+        with pytest.raises(lsh.LshError) as e:          # k % L != 0 on the fused path too
+            lsh.hash_fastlsh_keys(p, x, 5)
+        assert e.value.status == -1
+    with lsh.LshParams(40000, 8, 4, 1.0, 1) as p:       # one vector does not fit in LDS
+        with pytest.raises(lsh.LshError) as e:
+            lsh.hash_fastlsh(p, torch.zeros((2, 40000), device="cuda"))
+        assert e.value.status == -4
+    with lsh.LshParams(96, 48, 8, 1.0, 1) as p:         # g = 48 / 4 = 12: fused keys unsupported
+        with pytest.raises(lsh.LshError) as e:
+            lsh.hash_fastlsh_keys(p, torch.zeros((2, 96), device="cuda"), 4)
+        assert e.value.status == -4
+
+
+def test_zero_vector_and_sign_of_zero(lsh):
+    # v = 0: every projection is exactly 0, so h_j = floor(b_j / w) = 0 and every sign bit is 1
+    with lsh.LshParams(128, 100, 32, 4.0, 3) as p:
+        x = torch.zeros((3, 128), device="cuda")
+        assert int(lsh.hash_fastlsh(p, x).abs().max()) == 0
+        words = lsh.hash_signs(p, x).cpu().numpy().view(np.uint64)
+        assert int(words[0, 0]) == 2 ** 64 - 1 and int(words[0, 1]) == 2 ** 36 - 1
+
+
+def test_scaling_invariance_on_gpu(lsh):
+    # (alpha v, alpha w, alpha b) gives the same ids (Sec. 4.2 fact); exact for alpha = 2^t,
+    # which needs identical tables, so the seed is kept and only w scales: b = u*w scales too
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    data = torch.randn((500, 128), generator=g, device="cuda")
+    with lsh.LshParams(128, 256, 32, 4.0, 9) as p1, lsh.LshParams(128, 256, 32, 32.0, 9) as p2:
+        assert np.array_equal(p1.offsets() * np.float32(8), p2.offsets())
+        h1 = lsh.hash_fastlsh(p1, data)
+        h2 = lsh.hash_fastlsh(p2, data * 8.0)
+        assert torch.equal(h1, h2)
+
+
+# ---------------------------------------------------------------------------------------
+# full-size workloads, sampled rows, benchmark launch configuration
+# ---------------------------------------------------------------------------------------
+
+def _sampled(N, count):
+    return workloads.sample_rows(N, count).numpy()
+
+
+def test_sift_full_size(lsh):
+    wl, data = workloads.make_data("sift", "cuda")
+    rows = _sampled(wl.N, 4096)
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
+        say("sift fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="sift"))
+    with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
+        say("sift e2lsh", _compare_all(lsh, p, data, rows, label="sift-dense", dense=True, signs=False))
+
+
+def test_gist_full_size(lsh):
+    wl, data = workloads.make_data("gist", "cuda")
+    rows = _sampled(wl.N, 2048)
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
+        say("gist fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="gist", signs=False))
+    with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
+        say("gist e2lsh", _compare_all(lsh, p, data, rows, label="gist-dense", dense=True, signs=False))
+
+
+def test_highdim_full_size(lsh):
+    wl, data = workloads.make_data("highdim", "cuda")
+    rows = _sampled(wl.N, 1024)
+    # planted near-duplicates and their sources: collision counts must separate them from random pairs
+    src = wl.extra["planted_src"].numpy()
+    planted_rows = np.arange(wl.N - wl.planted, wl.N)
+    for m in wl.m:
+        with lsh.LshParams(wl.n, wl.k, m, wl.w, wl.seed) as p:
+            say(f"highdim m={m}", _compare_all(lsh, p, data, rows, label=f"highdim-m{m}", signs=False))
+            ids = lsh.hash_fastlsh(p, data)
+            a = ids[torch.as_tensor(planted_rows[:256], device="cuda")]
+            b = ids[torch.as_tensor(src[:256], device="cuda")]
+            c = ids[torch.as_tensor(src[1:257], device="cuda")]
+            near = (a == b).float().mean().item()
+            far = (a == c).float().mean().item()
+            say(f"  collision rate planted {near:.3f} random {far:.3f}")
+            assert near > far + 0.2
+    with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
+        say("highdim e2lsh", _compare_all(lsh, p, data, rows[:512], label="highdim-dense", dense=True, signs=False))
+
+
+def test_angular_full_size(lsh):
+    wl, data = workloads.make_data("angular", "cuda")
+    rows = _sampled(wl.N, 1024)
+    idxs = torch.as_tensor(rows, device="cuda")
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
+        idx, coef, _ = _tables(p)
+        sub = data[idxs].cpu().numpy()
+        w_ora, pr, npd = oracle.signs(sub, idx, coef, nthreads=THREADS, want_proj=True, want_norm_prod=True)
+        w_gpu = lsh.hash_signs(p, data)
+        torch.cuda.synchronize()
+        ex = check_signs(w_gpu[idxs].cpu().numpy().view(np.uint64), w_ora, pr, npd, p.k, "angular")
+        say("angular signs excluded fraction", ex)
