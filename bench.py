@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the LSH hash-evaluation hot path on one MI355X.
+
+One step = one pass of the whole path over the SIFT-shaped batch (N = 1,000,000 vectors,
+n = 128, k = 512 functions, m = 32 sampled coordinates, w = 16), inputs resident in HBM:
+
+    FastLSH bucket ids  ->  key packing (L = 32 keys of 16 ids)  ->  dense E2LSH bucket ids
+    (m = n, same seed)  ->  sign hashes
+
+Prints ONE JSON line.  `value` is hashes per second over the whole step: a step evaluates
+3*N*k hash functions (N*k FastLSH, N*k E2LSH, N*k sign hashes).  Per-kernel times come
+from HIP events recorded on the launch stream inside the timed region.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
+# plain (non-packed) fp32 vector FMA: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
+VALU_FP32_PEAK_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
+
+
+def cpu_baseline(wl, data, p_fast, p_dense, budget_s=12.0):
+    """Times the CPU oracle (all host threads) on a bounded sample of rows of the same batch."""
+    import numpy as np
+    import oracle
+    threads = oracle.max_threads()
+    tabs_f = (p_fast.indices(), p_fast.coeffs(), p_fast.offsets())
+    tabs_d = (p_dense.coeffs(), p_dense.offsets())
+
+    def run(rows):
+        t0 = time.perf_counter()
+        ids = oracle.fastlsh(rows, *tabs_f, wl.w, nthreads=threads)["ids"]
+        oracle.pack_keys(ids, wl.L)
+        oracle.e2lsh(rows, *tabs_d, wl.w, nthreads=threads)
+        oracle.signs(rows, tabs_f[0], tabs_f[1], nthreads=threads)
+        return time.perf_counter() - t0
+
+    pilot = data[:2048].cpu().numpy()
+    t_pilot = run(pilot)
+    count = int(max(2048, min(data.shape[0], 2048 * budget_s / max(t_pilot, 1e-6))))
+    rows = data[:count].cpu().numpy()
+    t = run(rows)
+    return {"value": 3.0 * count * wl.k / t, "unit": "hashes/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {count} rows of the same batch, all four stages, {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (rows shard trivially, but no "
+                 "multi-GPU path exists); use --gpus 1")
+
+    import torch
+    import paper_2309_15479_amd as lsh
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    lsh.load_library()
+    dev = "cuda:0"
+    wl, data = workloads.make_data("sift", dev)
+    N, n, k, m, L = wl.N, wl.n, wl.k, wl.m[0], wl.L
+    p_fast = lsh.LshParams(n, k, m, wl.w, wl.seed)
+    p_dense = lsh.LshParams(n, k, n, wl.w, wl.seed)
+    ids_f = torch.empty((N, k), dtype=torch.int32, device=dev)
+    ids_d = torch.empty((N, k), dtype=torch.int32, device=dev)
+    keys = torch.empty((N, L), dtype=torch.int64, device=dev)
+    words = torch.empty((N, (k + 63) // 64), dtype=torch.int64, device=dev)
+
+    stages = ["fastlsh", "pack_keys", "e2lsh", "signs"]
+
+    def step(events=None):
+        def mark():
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()          # on torch's current stream = the stream the library launches on
+                events.append(e)
+        mark()
+        lsh.hash_fastlsh(p_fast, data, out=ids_f)
+        mark()
+        lsh.pack_keys(p_fast, ids_f, L, out=keys)
+        mark()
+        lsh.hash_e2lsh(p_dense, data, out=ids_d)
+        mark()
+        lsh.hash_signs(p_fast, data, out=words)
+        mark()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev = []
+        step(ev)
+        all_events.append(ev)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms = {s: 0.0 for s in stages}
+    for ev in all_events:
+        for i, s in enumerate(stages):
+            ms[s] += ev[i].elapsed_time(ev[i + 1])
+    ms = {s: v / args.steps for s, v in ms.items()}
+
+    def hbm(bytes_per_launch, t_ms):
+        a = bytes_per_launch / (t_ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": a / HBM_PEAK_GBS, "traffic": None}
+
+    rooflines = {
+        # algorithmic bytes per vector: 4n read + 4k written (ids) / 8 per 64 functions (signs)
+        "fastlsh": hbm(N * (4 * n + 4 * k), ms["fastlsh"]),
+        "pack_keys": hbm(N * (4 * k + 8 * L), ms["pack_keys"]),
+        "signs": hbm(N * (4 * n + 8 * ((k + 63) // 64)), ms["signs"]),
+    }
+    tf = 2.0 * N * n * k / (ms["e2lsh"] * 1e-3) / 1e12
+    rooflines["e2lsh"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": tf / MFMA_FP32_PEAK_TFLOPS, "traffic": None}
+    # the sampled kernels' arithmetic against the plain fp32 vector ceiling, for context
+    for s in ("fastlsh", "signs"):
+        alu = 2.0 * N * k * m / (ms[s] * 1e-3) / 1e12
+        rooflines[s]["alu_tflops"] = alu
+        rooflines[s]["alu_frac_of_plain_fp32_vector_peak"] = alu / VALU_FP32_PEAK_TFLOPS
+    dominant = max(stages, key=lambda s: ms[s])
+
+    hashes_per_step = 3.0 * N * k
+    out = {
+        "metric": "hashes/sec (N*k per sec), FastLSH vs E2LSH, 1 GPU",
+        "value": hashes_per_step * args.steps / elapsed,
+        "unit": "hashes/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "sift-shaped: N=1000000 n=128 k=512 m=32 w=16 L=32, 100-cluster mixture in [0,255]",
+                   "step": "fastlsh ids + key packing + dense e2lsh ids (m=n) + sign hashes",
+                   "hashes_per_step": hashes_per_step},
+        "vectors_per_s": N * args.steps / elapsed,
+        "kernel_ms": ms,
+        "fastlsh_hashes_per_s": N * k / (ms["fastlsh"] * 1e-3),
+        "e2lsh_hashes_per_s": N * k / (ms["e2lsh"] * 1e-3),
+        "fastlsh_speedup_over_e2lsh": ms["e2lsh"] / ms["fastlsh"],
+        "dominant_kernel": dominant,
+        "roofline": rooflines[dominant],
+        "rooflines": rooflines,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, data, p_fast, p_dense)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -23,7 +23,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Hash
  *     calls only enqueue work on it and never synchronise; the caller keeps
  *     data/outputs alive until the stream has drained.
- *   - N = 0 is LSH_OK and launches nothing.
+ *   - N = 0 is LSH_OK and launches nothing (data/output pointers may then be NULL).
  *   - The params object and its device tables belong to the library and are
  *     freed by lsh_params_destroy().  One object may be used from several host
  *     threads for hashing; create/destroy are not thread-safe against its use.

@@ -94,8 +94,10 @@ int upload_tables(lsh_params *p) {
 
 namespace {
 
-int check_hash_args(const lsh_params *p, const void *d_in, const void *d_out) {
-    if (!p || !d_in || !d_out) return LSH_ERR_INVALID_ARG;
+// N == 0 is valid with any data/out pointers (an empty tensor has no storage)
+int check_hash_args(const lsh_params *p, const void *d_in, const void *d_out, uint64_t N) {
+    if (!p) return LSH_ERR_INVALID_ARG;
+    if (N && (!d_in || !d_out)) return LSH_ERR_INVALID_ARG;
     if (p->device < 0) return LSH_ERR_NO_DEVICE;
     return LSH_OK;
 }
@@ -170,26 +172,26 @@ int lsh_params_get_shape(const lsh_params_t *p, uint32_t *n, uint32_t *k, uint32
 }
 
 int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {
-    int rc = check_hash_args(p, d_data, d_out);
+    int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
 }
 
 int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, float *d_out, void *stream) {
-    int rc = check_hash_args(p, d_data, d_out);
+    int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);
 }
 
 int lsh_hash_signs(const lsh_params_t *p, const float *d_data, uint64_t N, uint64_t *d_out, void *stream) {
-    int rc = check_hash_args(p, d_data, d_out);
+    int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     return launch_sampled(p, Epilogue::Signs, d_data, N, d_out, 0, stream);
 }
 
 int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N, uint32_t L,
                           uint64_t *d_out, void *stream) {
-    int rc = check_hash_args(p, d_data, d_out);
+    int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK) return rc;
     if (!L || p->k % L) return LSH_ERR_INVALID_ARG;
     const uint32_t g = p->k / L;
@@ -199,7 +201,7 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
 }
 
 int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {
-    int rc = check_hash_args(p, d_data, d_out);
+    int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK) return rc;
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
@@ -207,7 +209,7 @@ int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32
 }
 
 int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, float *d_out, void *stream) {
-    int rc = check_hash_args(p, d_data, d_out);
+    int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK) return rc;
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
@@ -216,7 +218,7 @@ int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, fl
 
 int lsh_pack_keys(const lsh_params_t *p, const int32_t *d_ids, uint64_t N, uint32_t L, uint64_t *d_keys,
                   void *stream) {
-    int rc = check_hash_args(p, d_ids, d_keys);
+    int rc = check_hash_args(p, d_ids, d_keys, N);
     if (rc != LSH_OK) return rc;
     if (!L || p->k % L) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
@@ -226,7 +228,7 @@ int lsh_pack_keys(const lsh_params_t *p, const int32_t *d_ids, uint64_t N, uint3
 int lsh_time_launches(const lsh_params_t *p, int which, const void *d_in, uint64_t N, uint32_t L,
                       void *d_out, void *stream, int reps, float *ms_per_launch) {
     if (!ms_per_launch || reps <= 0 || which < 0 || which > 4) return LSH_ERR_INVALID_ARG;
-    int rc = check_hash_args(p, d_in, d_out);
+    int rc = check_hash_args(p, d_in, d_out, N);
     if (rc != LSH_OK) return rc;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipEvent_t t0 = nullptr, t1 = nullptr;

@@ -48,6 +48,7 @@ def test_null_and_flag_arguments():
     assert lib.lsh_params_create_ex(8, 4, 4, 1.0, 1, 7, ctypes.byref(h)) == -1
     assert lib.lsh_params_get_indices(None, None) == -1
     assert lib.lsh_hash_fastlsh(None, None, 1, None, None) == -1
+    assert lib.lsh_hash_fastlsh(None, None, 0, None, None) == -1   # no params object
     lib.lsh_params_destroy(None)          # no-op
 
 
