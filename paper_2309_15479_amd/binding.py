@@ -19,7 +19,8 @@ SAMPLE_WITH_REPLACEMENT = 1
 
 EXPORTS = [
     "lsh_params_create", "lsh_params_create_ex", "lsh_params_destroy", "lsh_params_get_indices",
-    "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape", "lsh_hash_fastlsh",
+    "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape", "lsh_params_get_schedule",
+    "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
 ]
@@ -57,6 +58,7 @@ def load_library():
     for name in ("lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets"):
         getattr(lib, name).argtypes = [p, p]
     lib.lsh_params_get_shape.argtypes = [p, p, p, p, p, p, p]
+    lib.lsh_params_get_schedule.argtypes = [p, p, p, p, p, p]
     for name in ("lsh_hash_fastlsh", "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_project_fastlsh",
                  "lsh_project_e2lsh"):
         getattr(lib, name).argtypes = [p, p, u64, p, p]
@@ -123,6 +125,17 @@ class LshParams:
         out = np.empty(self.k, np.float32)
         _check(load_library().lsh_params_get_offsets(self.handle, out.ctypes.data), "get_offsets")
         return out
+
+    def schedule(self):
+        """(order u32 [k, steps], group, classes, modelled_passes) of the sampled kernel."""
+        steps, group, classes = (ctypes.c_uint32() for _ in range(3))
+        passes = ctypes.c_uint64()
+        lib = load_library()
+        _check(lib.lsh_params_get_schedule(self.handle, None, ctypes.addressof(steps), ctypes.addressof(group),
+                                           ctypes.addressof(classes), ctypes.addressof(passes)), "get_schedule")
+        order = np.empty((self.k, steps.value), np.uint32)
+        _check(lib.lsh_params_get_schedule(self.handle, order.ctypes.data, None, None, None, None), "get_schedule")
+        return order, group.value, classes.value, passes.value
 
     def shape(self):
         n, k, m, fl = (ctypes.c_uint32() for _ in range(4))

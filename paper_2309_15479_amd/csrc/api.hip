@@ -8,7 +8,6 @@
 
 namespace lsh {
 
-uint32_t sampled_chunk();
 uint32_t dense_col_tile();
 
 void free_tables(lsh_params *p) {
@@ -38,11 +37,9 @@ int upload_tables(lsh_params *p) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return LSH_ERR_HIP;
     p->num_cus = prop.multiProcessorCount;
-    p->plan = plan_sampled(p->n, p->k, p->m);
     p->device = dev;
 
-    const uint32_t chunk = sampled_chunk();
-    const uint32_t m_pad = (p->m + chunk - 1) / chunk * chunk;
+    const uint32_t m_pad = p->plan.m_pad;
     const uint32_t kpad = p->plan.supported ? p->plan.kpad : (p->k + 63) / 64 * 64;
     p->kpad_dense = 0;
     if (p->m == p->n) p->kpad_dense = (p->k + dense_col_tile() - 1) / dense_col_tile() * dense_col_tile();
@@ -58,14 +55,26 @@ int upload_tables(lsh_params *p) {
             rc = LSH_ERR_HIP;
 
         if (rc == LSH_OK && p->plan.supported) {
-            // sample-major [m_pad][kpad]; padding entries read the tile's zero slot
-            const uint32_t zero_slot = p->n * p->plan.rt * 4u;
-            std::vector<Sample> tab((size_t)m_pad * kpad, Sample{zero_slot, 0.f});
+            // step-major [m_pad][kpad] in scheduled order; padding samples (and the lanes
+            // beyond k) read a zero slot with coefficient 0
+            const SampledPlan &pl = p->plan;
+            const uint32_t slot_bytes = pl.sp * pl.rt * 4u;
+            std::vector<Sample> tab((size_t)m_pad * kpad, Sample{p->n * slot_bytes, 0.f});
             for (uint32_t j = 0; j < p->k; ++j)
-                for (uint32_t i = 0; i < p->m; ++i) {
+                for (uint32_t i = 0; i < m_pad; ++i) {
                     Sample &s = tab[(size_t)i * kpad + j];
-                    s.lds_byte_offset = p->idx[(size_t)j * p->m + i] * p->plan.rt * 4u;
-                    s.coef = p->coef[(size_t)j * p->m + i];
+                    const uint32_t e = p->order[(size_t)j * m_pad + i];
+                    if (e & kPadSample) {
+                        s.lds_byte_offset = (p->n + (e & ~kPadSample)) * slot_bytes;
+                        // the zero slot whose class equals the requested one
+                        const uint32_t want = e & ~kPadSample;
+                        for (uint32_t z = p->n; z < p->n + pl.classes; ++z)
+                            if (z % pl.classes == want) s.lds_byte_offset = z * slot_bytes;
+                        s.coef = 0.f;
+                    } else {
+                        s.lds_byte_offset = p->idx[(size_t)j * p->m + e] * slot_bytes;
+                        s.coef = p->coef[(size_t)j * p->m + e];
+                    }
                 }
             if (hipMalloc(&p->d_samples, tab.size() * sizeof(Sample)) != hipSuccess) rc = LSH_ERR_ALLOC;
             if (rc == LSH_OK && hipMemcpy(p->d_samples, tab.data(), tab.size() * sizeof(Sample),
@@ -122,6 +131,17 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
     if (!p) return LSH_ERR_ALLOC;
     p->n = n; p->k = k; p->m = m; p->w = w; p->seed = seed; p->flags = flags;
     int rc = generate_tables(n, k, m, w, seed, flags, p->idx, p->coef, p->off);
+    if (rc == LSH_OK) {
+        p->plan = plan_sampled(n, k, m);
+        if (p->plan.supported) {
+            try {
+                p->schedule_cost = schedule_samples(p->idx, k, m, p->plan.m_pad, p->plan.group,
+                                                    p->plan.classes, p->order);
+            } catch (const std::bad_alloc &) {
+                rc = LSH_ERR_ALLOC;
+            }
+        }
+    }
     if (rc == LSH_OK) rc = upload_tables(p);
     if (rc != LSH_OK) {
         delete p;
@@ -168,6 +188,18 @@ int lsh_params_get_shape(const lsh_params_t *p, uint32_t *n, uint32_t *k, uint32
     if (flags) *flags = p->flags;
     if (w) *w = p->w;
     if (seed) *seed = p->seed;
+    return LSH_OK;
+}
+
+int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *steps, uint32_t *group,
+                            uint32_t *classes, uint64_t *modelled_passes) {
+    if (!p) return LSH_ERR_INVALID_ARG;
+    if (!p->plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (steps) *steps = p->plan.m_pad;
+    if (group) *group = p->plan.group;
+    if (classes) *classes = p->plan.classes;
+    if (modelled_passes) *modelled_passes = p->schedule_cost;
+    if (order) std::copy(p->order.begin(), p->order.end(), order);
     return LSH_OK;
 }
 

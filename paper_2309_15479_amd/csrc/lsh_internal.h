@@ -16,16 +16,25 @@ struct Sample {
 };
 
 // How the sampled kernel is launched for one params object; fixed at create time.
+// LDS tile layout: [coordinate slot][sub-tile (+1 pad slot when sub > 1)][rt vectors],
+// n coordinate slots followed by `classes` zero slots (one per bank class).
 struct SampledPlan {
-    uint32_t rt = 0;         // vectors interleaved per LDS slot (1, 2, 4 or 8)
-    uint32_t sub = 0;        // sub-tiles of rt vectors per workgroup tile
+    uint32_t rt = 0;         // vectors per LDS read (4: 16-byte reads, 2: 8-byte, 1: 4-byte)
+    uint32_t sub = 0;        // sub-tiles of rt vectors per workgroup tile (8, 4, 2 or 1)
+    uint32_t sp = 0;         // sub-tile slots per coordinate: sub + 1 (odd) or 1
+    uint32_t group = 0;      // lanes served together by one pass of an LDS read
+    uint32_t classes = 0;    // bank classes: slots c, c' collide iff c % classes == c' % classes
+    uint32_t m_pad = 0;      // samples per function, padded to the register chunk
     uint32_t block = 0;      // threads per workgroup = functions per workgroup
     uint32_t kblocks = 0;    // workgroups along the function axis
     uint32_t kpad = 0;       // block * kblocks >= k
     uint32_t lds_bytes = 0;  // dynamic LDS per workgroup
-    bool reg_table = false;  // m == 32: (offset, coef) lists live in registers
+    bool reg_table = false;  // register-list kernel: (offset, coef) lists live in VGPRs
+    uint32_t prefetch = 0;   // register-list kernel: 64-coordinate chunks fetched per wave and tile
     bool supported = false;
 };
+
+constexpr uint32_t kPadSample = 0x80000000u;  // schedule entry: padding sample | bank class
 
 }  // namespace lsh
 
@@ -41,7 +50,9 @@ struct lsh_params {
     int device = -1;  // -1: no device tables
     int num_cus = 0;
     lsh::SampledPlan plan;
-    lsh::Sample *d_samples = nullptr;  // [m][kpad], sample-major
+    std::vector<uint32_t> order;       // [k][m_pad] visiting order of each function's samples
+    uint64_t schedule_cost = 0;        // modelled LDS passes (see schedule.cpp)
+    lsh::Sample *d_samples = nullptr;  // [m_pad][kpad], step-major
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n] when m == n (row j = a_j), else null
     uint32_t kpad_dense = 0;
@@ -52,6 +63,10 @@ namespace lsh {
 // host: draws the canonical tables (returns LSH_OK / LSH_ERR_*)
 int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
                     std::vector<uint32_t> &idx, std::vector<float> &coef, std::vector<float> &off);
+
+// host: bank-conflict-free visiting order of every function's samples (schedule.cpp)
+uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,
+                          uint32_t group, uint32_t classes, std::vector<uint32_t> &order_out);
 
 // device: plan + upload + launches (defined in the .hip files)
 SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m);

@@ -3,14 +3,20 @@
 //   p_j(v) = sum_{i<m} a~_j[i] * v[S_j[i]],   h_j(v) = floor((p_j(v) + b~_j) / w)
 //
 // Mapping: one lane = one hash function j; one workgroup = a tile of SUB*RT vectors times
-// `blockDim.x` functions.  The vector tile is read from HBM once (coalesced along the
-// coordinate axis) and kept in LDS with RT vectors interleaved per coordinate slot
-// ([sub-tile][coordinate][RT]), so that one 4*RT-byte LDS read fetches the sampled
-// coordinate of RT vectors and feeds RT FMAs.  Each lane walks its own (LDS offset,
-// coefficient) list; there is no cross-lane reduction.  The lists are stored
-// sample-major ([i][j]) so that a wave reads them coalesced; when m equals the register
-// chunk they are loaded once per workgroup and stay in VGPRs while the workgroup loops
-// over its tiles.
+// blockDim.x functions.  The vector tile is read from HBM once (coalesced along the
+// coordinate axis) and kept in LDS as [coordinate][sub-tile][RT vectors], so that one
+// 4*RT-byte LDS read fetches a sampled coordinate of RT vectors, and the SUB reads of one
+// sample differ only in their immediate offset.  Each lane walks its own list of
+// (LDS offset, coefficient) pairs; there is no cross-lane reduction.
+//
+// The gather is LDS-bandwidth bound, so the order in which a lane visits its samples is
+// chosen on the host (schedule.cpp) such that the lanes served together by one pass of an
+// LDS read (16 consecutive lanes for 16-byte reads) hit distinct bank classes.  With more
+// than one sub-tile the coordinate stride is padded to an odd number of 16-byte slots, which
+// keeps "distinct coordinates mod 16" equivalent to "distinct bank classes" for every
+// sub-tile.  The lists are stored step-major ([step][function]) so that a wave reads them
+// coalesced.  Two kernels: sampled_reg_kernel keeps a list of one chunk in VGPRs for the
+// whole launch; sampled_kernel streams longer lists through registers for every tile.
 #include <hip/hip_runtime.h>
 
 #include "lsh_internal.h"
@@ -18,26 +24,12 @@
 namespace lsh {
 namespace {
 
-constexpr int kChunk = 32;             // samples held in registers at a time
-constexpr uint32_t kLdsBudget = 144u * 1024u;  // of the CU's 160 KB
-
-template <int RT>
-struct VecOf;
-template <>
-struct VecOf<1> { using type = float; };
-template <>
-struct VecOf<2> { using type = float2; };
-template <>
-struct VecOf<4> { using type = float4; };
+constexpr int kChunk = 32;                     // samples held in registers at a time
+constexpr uint32_t kLdsBudget = 158u * 1024u;  // of the CU's 160 KB
 
 template <int RT>
 __device__ __forceinline__ void lds_read_slot(const char *slot, float (&x)[RT]) {
-    if constexpr (RT == 8) {
-        const float4 lo = *reinterpret_cast<const float4 *>(slot);
-        const float4 hi = *reinterpret_cast<const float4 *>(slot + 16);
-        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
-        x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
-    } else if constexpr (RT == 4) {
+    if constexpr (RT == 4) {
         const float4 q = *reinterpret_cast<const float4 *>(slot);
         x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
     } else if constexpr (RT == 2) {
@@ -50,10 +42,7 @@ __device__ __forceinline__ void lds_read_slot(const char *slot, float (&x)[RT]) 
 
 template <int RT>
 __device__ __forceinline__ void lds_write_slot(float *slot, const float (&x)[RT]) {
-    if constexpr (RT == 8) {
-        *reinterpret_cast<float4 *>(slot) = make_float4(x[0], x[1], x[2], x[3]);
-        *reinterpret_cast<float4 *>(slot + 4) = make_float4(x[4], x[5], x[6], x[7]);
-    } else if constexpr (RT == 4) {
+    if constexpr (RT == 4) {
         *reinterpret_cast<float4 *>(slot) = make_float4(x[0], x[1], x[2], x[3]);
     } else if constexpr (RT == 2) {
         *reinterpret_cast<float2 *>(slot) = make_float2(x[0], x[1]);
@@ -62,10 +51,17 @@ __device__ __forceinline__ void lds_write_slot(float *slot, const float (&x)[RT]
     }
 }
 
+// Empty volatile asm through which four accumulators flow: it emits nothing, but the FMAs
+// that produce its inputs cannot be sunk below it (nor the next ones hoisted above), which
+// keeps them inside the scheduling region they were written in.
+__device__ __forceinline__ void pin(float (&v)[4]) {
+    asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+}
+
 struct SampledArgs {
     const float *data;   // [N][n]
     uint64_t N;
-    uint32_t n, k, m_pad, kpad;
+    uint32_t n, k, m_pad, kpad, classes;
     const Sample *tab;   // [m_pad][kpad]
     const float *off;    // [kpad]
     float w, inv_w;
@@ -75,55 +71,79 @@ struct SampledArgs {
     uint32_t L, g;       // key groups (Epilogue::Keys)
 };
 
-// Epilogue for one (vector, function): `row` is uniform in the workgroup, so the wave-wide
-// ballot and shuffles below are executed by whole waves.
-__device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row, uint32_t j, float p, float b,
-                                       uint64_t key_pow) {
-    if (row >= a.N) return;
-    if (a.epilogue == (int)Epilogue::Proj) {
-        if (j < a.k) reinterpret_cast<float *>(a.out)[row * a.k + j] = p;
-        return;
-    }
-    if (a.epilogue == (int)Epilogue::Signs) {
-        const uint64_t word = __ballot(j < a.k && p >= 0.f);
-        const uint32_t words = (a.k + 63) / 64;
-        if ((threadIdx.x & 63) == 0 && j < a.k)
-            reinterpret_cast<uint64_t *>(a.out)[row * words + (j >> 6)] = word;
-        return;
-    }
-    const float q = a.w_is_pow2 ? (p + b) * a.inv_w : (p + b) / a.w;
-    const int h = (int)floorf(q);
-    if (a.epilogue == (int)Epilogue::Ids) {
-        if (j < a.k) reinterpret_cast<int32_t *>(a.out)[row * a.k + j] = h;
-    } else {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64
-        uint64_t term = (uint64_t)(uint32_t)h * key_pow;
-        for (uint32_t d = a.g >> 1; d >= 1; d >>= 1) term += __shfl_xor(term, (int)d);
-        if (j < a.k && (j % a.g) == 0) reinterpret_cast<uint64_t *>(a.out)[row * a.L + j / a.g] = term;
+// One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.
+template <int RT, int SUB>
+__device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint32_t j,
+                                       const float (&acc)[SUB][RT], float b, uint64_t key_pow) {
+    const bool live = j < a.k;
+    switch (a.epilogue) {
+        case (int)Epilogue::Ids: {
+            int32_t *out = reinterpret_cast<int32_t *>(a.out);
+#pragma unroll
+            for (int s = 0; s < SUB; ++s)
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const uint64_t row = row0 + s * RT + r;
+                    const float q = a.w_is_pow2 ? (acc[s][r] + b) * a.inv_w : (acc[s][r] + b) / a.w;
+                    if (live && row < a.N) out[row * a.k + j] = (int)floorf(q);
+                }
+            break;
+        }
+        case (int)Epilogue::Proj: {
+            float *out = reinterpret_cast<float *>(a.out);
+#pragma unroll
+            for (int s = 0; s < SUB; ++s)
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const uint64_t row = row0 + s * RT + r;
+                    if (live && row < a.N) out[row * a.k + j] = acc[s][r];
+                }
+            break;
+        }
+        case (int)Epilogue::Signs: {
+            uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
+            const uint32_t words = (a.k + 63) / 64;
+#pragma unroll
+            for (int s = 0; s < SUB; ++s)
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const uint64_t row = row0 + s * RT + r;  // uniform: whole waves reach the ballot
+                    const uint64_t word = __ballot(live && acc[s][r] >= 0.f);
+                    if ((threadIdx.x & 63) == 0 && live && row < a.N) out[row * words + (j >> 6)] = word;
+                }
+            break;
+        }
+        default: {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64
+            uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
+#pragma unroll
+            for (int s = 0; s < SUB; ++s)
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const uint64_t row = row0 + s * RT + r;
+                    const float q = a.w_is_pow2 ? (acc[s][r] + b) * a.inv_w : (acc[s][r] + b) / a.w;
+                    uint64_t term = (uint64_t)(uint32_t)(int)floorf(q) * key_pow;
+                    for (uint32_t d = a.g >> 1; d >= 1; d >>= 1) term += __shfl_xor(term, (int)d);
+                    if (live && row < a.N && (j % a.g) == 0) out[row * a.L + j / a.g] = term;
+                }
+        }
     }
 }
 
-// REG: m_pad == kChunk, the lane's whole list stays in registers across tiles.
-template <int RT, int SUB, bool REG>
-__global__ __launch_bounds__(REG ? 512 : 1024) void sampled_kernel(const SampledArgs a) {
-    extern __shared__ __align__(16) float tile[];  // [SUB][n + 1][RT]; slot n holds zeros
+// Streamed-list kernel: every tile, each lane streams its (offset, coefficient) list through
+// registers one chunk at a time and applies the chunk to all SUB sub-tiles.
+template <int RT, int SUB>
+__global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
+    extern __shared__ __align__(16) float tile[];  // [n + classes][SP][RT]
+    constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
+    constexpr uint32_t kTileRows = RT * SUB;
     const uint32_t n = a.n;
     const uint32_t j = blockIdx.y * blockDim.x + threadIdx.x;  // < kpad
-    const uint32_t slots = n + 1;
-    constexpr uint32_t kTileRows = RT * SUB;
     const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
-
-    Sample s[kChunk];
-    if constexpr (REG) {
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) s[i] = a.tab[(size_t)i * a.kpad + j];
-    }
     const float b = a.off[j];
 
-    // the zero slot of every sub-tile (target of padding samples)
-    if (threadIdx.x < SUB * RT) {
-        const uint32_t st = threadIdx.x / RT, r = threadIdx.x % RT;
-        tile[((size_t)st * slots + n) * RT + r] = 0.f;
-    }
+    // zero slots: the targets of padding samples
+    for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x)
+        tile[(size_t)n * SP * RT + e] = 0.f;
 
     uint64_t key_pow = 1;  // C^(g-1-t) for this lane's position t in its key group
     if (a.epilogue == (int)Epilogue::Keys) {
@@ -131,113 +151,233 @@ __global__ __launch_bounds__(REG ? 512 : 1024) void sampled_kernel(const Sampled
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
     }
 
+    // wave w loads the 64-coordinate chunks q = w, w + nwaves, ... of the tile; chunk q is
+    // coordinates (q / SUB) * 64 .. + 63 of sub-tile q % SUB
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint32_t nchunks = SUB * ((n + 63) / 64);
+
+    const char *base = reinterpret_cast<const char *>(tile);
     for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
         const uint64_t row0 = t * kTileRows;
         __syncthreads();  // every lane is done reading the previous tile
-        for (uint32_t e = threadIdx.x; e < SUB * n; e += blockDim.x) {
-            const uint32_t st = e / n, c = e - st * n;
-            float x[RT];
+        for (uint32_t q = wave; q < nchunks; q += nwaves) {
+            const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
+            if (c < n) {
+                float x[RT];
 #pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                const uint64_t row = row0 + (uint64_t)st * RT + r;
-                x[r] = row < a.N ? a.data[row * n + c] : 0.f;
+                for (int r = 0; r < RT; ++r) {
+                    const uint64_t row = row0 + (uint64_t)st * RT + r;
+                    x[r] = row < a.N ? a.data[row * n + c] : 0.f;
+                }
+                lds_write_slot<RT>(tile + ((size_t)c * SP + st) * RT, x);
             }
-            lds_write_slot<RT>(tile + ((size_t)st * slots + c) * RT, x);
         }
         __syncthreads();
 
-        if constexpr (REG) {
-            // lists already in registers: finish one sub-tile (RT vectors) at a time
-#pragma unroll 1
-            for (int st = 0; st < SUB; ++st) {
-                const char *base = reinterpret_cast<const char *>(tile + (size_t)st * slots * RT);
-                float acc[RT];
+        float acc[SUB][RT];
 #pragma unroll
-                for (int r = 0; r < RT; ++r) acc[r] = 0.f;
+        for (int st = 0; st < SUB; ++st)
 #pragma unroll
-                for (int i = 0; i < kChunk; ++i) {
-                    float x[RT];
-                    lds_read_slot<RT>(base + s[i].lds_byte_offset, x);
+            for (int r = 0; r < RT; ++r) acc[st][r] = 0.f;
+
+        for (uint32_t i0 = 0; i0 < a.m_pad; i0 += kChunk) {
+            Sample s[kChunk];
 #pragma unroll
-                    for (int r = 0; r < RT; ++r) acc[r] = fmaf(s[i].coef, x[r], acc[r]);
-                    // keep the scheduler from hoisting every LDS read of the sub-tile to the
-                    // front (which would need more registers than a lane has)
-                    if ((i & 7) == 7) __builtin_amdgcn_sched_barrier(0);
-                }
+            for (int i = 0; i < kChunk; ++i) s[i] = a.tab[(size_t)(i0 + i) * a.kpad + j];
 #pragma unroll
-                for (int r = 0; r < RT; ++r)
-                    finish(a, row0 + (uint64_t)st * RT + r, j, acc[r], b, key_pow);
-            }
-        } else {
-            // lists streamed through registers one chunk at a time, each chunk applied to
-            // every sub-tile before the next is fetched
-            float acc[SUB][RT];
-#pragma unroll
-            for (int st = 0; st < SUB; ++st)
-#pragma unroll
-                for (int r = 0; r < RT; ++r) acc[st][r] = 0.f;
-            for (uint32_t i0 = 0; i0 < a.m_pad; i0 += kChunk) {
-#pragma unroll
-                for (int i = 0; i < kChunk; ++i) s[i] = a.tab[(size_t)(i0 + i) * a.kpad + j];
+            for (int i = 0; i < kChunk; ++i) {
+                const char *slot = base + s[i].lds_byte_offset;
 #pragma unroll
                 for (int st = 0; st < SUB; ++st) {
-                    const char *base = reinterpret_cast<const char *>(tile + (size_t)st * slots * RT);
+                    float x[RT];
+                    lds_read_slot<RT>(slot + st * RT * 4, x);
 #pragma unroll
-                    for (int i = 0; i < kChunk; ++i) {
-                        float x[RT];
-                        lds_read_slot<RT>(base + s[i].lds_byte_offset, x);
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) acc[st][r] = fmaf(s[i].coef, x[r], acc[st][r]);
-                    }
+                    for (int r = 0; r < RT; ++r) acc[st][r] = fmaf(s[i].coef, x[r], acc[st][r]);
                 }
             }
-#pragma unroll
-            for (int st = 0; st < SUB; ++st)
-#pragma unroll
-                for (int r = 0; r < RT; ++r)
-                    finish(a, row0 + (uint64_t)st * RT + r, j, acc[st][r], b, key_pow);
         }
+        finish<RT, SUB>(a, row0, j, acc, b, key_pow);
     }
 }
 
-template <int RT, int SUB>
-int launch_variant(const lsh_params *p, const SampledArgs &args, dim3 grid, dim3 block,
-                   hipStream_t stream) {
-    const SampledPlan &pl = p->plan;
-    auto fn = pl.reg_table ? &sampled_kernel<RT, SUB, true> : &sampled_kernel<RT, SUB, false>;
+// Register-list kernel for m_pad == kChunk: a lane's whole list stays in VGPRs while the
+// workgroup walks its tiles.  The LDS tile is double buffered: the next tile's vectors are
+// fetched from HBM into registers before the current tile is processed and written to the
+// other buffer afterwards, so one barrier per tile suffices and HBM latency hides behind the
+// gather.  The gather itself is software pipelined by hand (reads of sample i+1 are issued
+// with the FMAs of sample i); scheduling barriers keep the compiler from hoisting every LDS
+// read of the tile to the front, which would need more registers than a lane has.
+// PF = 64-coordinate chunks each wave fetches per tile (see launch_sampled).
+template <int SUB, int PF>
+__global__ __launch_bounds__(512) void sampled_reg_kernel(const SampledArgs a) {
+    constexpr int RT = 4;
+    extern __shared__ __align__(16) float tile[];  // 2 x [n + classes][SP][RT]
+    constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
+    constexpr uint32_t kTileRows = RT * SUB;
+    const uint32_t n = a.n;
+    const uint32_t j = blockIdx.y * blockDim.x + threadIdx.x;  // < kpad
+    const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
+    const uint32_t buf_floats = (n + a.classes) * SP * RT;
+
+    Sample s[kChunk];
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) s[i] = a.tab[(size_t)i * a.kpad + j];
+    const float b = a.off[j];
+
+    for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x) {
+        tile[(size_t)n * SP * RT + e] = 0.f;
+        tile[buf_floats + (size_t)n * SP * RT + e] = 0.f;
+    }
+
+    uint64_t key_pow = 1;
+    if (a.epilogue == (int)Epilogue::Keys) {
+        const uint32_t t = j % a.g;
+        for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
+    }
+
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint32_t nchunks = SUB * ((n + 63) / 64);
+
+    float pre[PF][RT];
+    auto fetch = [&](uint64_t row0) {
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            const uint32_t q = wave + f * nwaves;
+            const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const uint64_t row = row0 + (uint64_t)st * RT + r;
+                pre[f][r] = (q < nchunks && c < n && row < a.N) ? a.data[row * n + c] : 0.f;
+            }
+        }
+    };
+    auto stash = [&](float *buf) {
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            const uint32_t q = wave + f * nwaves;
+            const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
+            if (q < nchunks && c < n) lds_write_slot<RT>(buf + ((size_t)c * SP + st) * RT, pre[f]);
+        }
+    };
+
+    uint64_t t = blockIdx.x;
+    if (t < ntiles) {
+        fetch(t * kTileRows);
+        stash(tile);
+    }
+    __syncthreads();
+    uint32_t cur = 0;
+    for (; t < ntiles; t += gridDim.x) {
+        const uint64_t row0 = t * kTileRows;
+        const uint64_t t_next = t + gridDim.x;
+        if (t_next < ntiles) fetch(t_next * kTileRows);
+
+        const char *base = reinterpret_cast<const char *>(tile + cur * buf_floats);
+        float acc[SUB][RT];
+#pragma unroll
+        for (int st = 0; st < SUB; ++st)
+#pragma unroll
+            for (int r = 0; r < RT; ++r) acc[st][r] = 0.f;
+
+        float4 xa[SUB], xb[SUB];
+#pragma unroll
+        for (int st = 0; st < SUB; ++st)
+            xa[st] = *reinterpret_cast<const float4 *>(base + s[0].lds_byte_offset + st * 16);
+#pragma unroll
+        for (int i = 0; i < kChunk; i += 2) {
+            // region: reads of sample i+1 may interleave with the FMAs of sample i, nothing else
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int st = 0; st < SUB; ++st)
+                xb[st] = *reinterpret_cast<const float4 *>(base + s[i + 1].lds_byte_offset + st * 16);
+#pragma unroll
+            for (int st = 0; st < SUB; ++st) {
+                acc[st][0] = fmaf(s[i].coef, xa[st].x, acc[st][0]);
+                acc[st][1] = fmaf(s[i].coef, xa[st].y, acc[st][1]);
+                acc[st][2] = fmaf(s[i].coef, xa[st].z, acc[st][2]);
+                acc[st][3] = fmaf(s[i].coef, xa[st].w, acc[st][3]);
+                pin(acc[st]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + 2 < kChunk) {
+#pragma unroll
+                for (int st = 0; st < SUB; ++st)
+                    xa[st] = *reinterpret_cast<const float4 *>(base + s[i + 2].lds_byte_offset + st * 16);
+            }
+#pragma unroll
+            for (int st = 0; st < SUB; ++st) {
+                acc[st][0] = fmaf(s[i + 1].coef, xb[st].x, acc[st][0]);
+                acc[st][1] = fmaf(s[i + 1].coef, xb[st].y, acc[st][1]);
+                acc[st][2] = fmaf(s[i + 1].coef, xb[st].z, acc[st][2]);
+                acc[st][3] = fmaf(s[i + 1].coef, xb[st].w, acc[st][3]);
+                pin(acc[st]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        finish<RT, SUB>(a, row0, j, acc, b, key_pow);
+
+        if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
+        __syncthreads();  // next buffer complete; everyone is done with the current one
+        cur ^= 1;
+    }
+}
+
+template <typename Kernel>
+int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 grid, dim3 block,
+                  hipStream_t stream) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)pl.lds_bytes);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return LSH_ERR_HIP;
-    hipLaunchKernelGGL(fn, grid, block, pl.lds_bytes, stream, args);
+    hipLaunchKernelGGL(fn, grid, block, lds_bytes, stream, args);
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
 
 }  // namespace
 
-// Tile shape by dimension: as many interleaved vectors as fit the LDS budget.
+uint32_t sampled_chunk() { return kChunk; }
+
+// Tile shape by dimension: as many vectors as fit the LDS budget.
 SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
     SampledPlan pl;
-    const uint64_t slot_bytes = 4ull * (n + 1ull);
-    if (slot_bytes * 32 <= kLdsBudget) { pl.rt = 8; pl.sub = 4; }
-    else if (slot_bytes * 8 <= kLdsBudget) { pl.rt = 8; pl.sub = 1; }
-    else if (slot_bytes * 4 <= kLdsBudget) { pl.rt = 4; pl.sub = 1; }
-    else if (slot_bytes * 2 <= kLdsBudget) { pl.rt = 2; pl.sub = 1; }
-    else if (slot_bytes <= kLdsBudget) { pl.rt = 1; pl.sub = 1; }
-    else return pl;  // unsupported: one vector does not fit in LDS
-    pl.lds_bytes = (uint32_t)(slot_bytes * pl.rt * pl.sub);
+    auto fits = [&](uint32_t rt, uint32_t sub, uint32_t classes) {
+        const uint64_t sp = sub == 1 ? 1 : sub + 1;
+        const uint64_t bytes = (uint64_t)(n + classes) * sp * rt * 4;
+        if (bytes > kLdsBudget) return false;
+        pl.rt = rt; pl.sub = sub; pl.sp = (uint32_t)sp; pl.classes = classes;
+        pl.group = rt == 4 ? 16 : 32;
+        pl.lds_bytes = (uint32_t)bytes;
+        return true;
+    };
+    // 16-byte reads: 16 lanes per pass over 16 classes; 8-byte: 32 lanes over 32; 4-byte:
+    // 32 lanes over 64 banks
+    if (!(fits(4, 8, 16) || fits(4, 4, 16) || fits(4, 2, 16) || fits(4, 1, 16) || fits(2, 1, 32) ||
+          fits(1, 1, 64)))
+        return pl;  // unsupported: one vector does not fit in LDS
+    pl.m_pad = (m + kChunk - 1) / kChunk * kChunk;
     const uint32_t k64 = (k + 63) / 64 * 64;
-    pl.reg_table = (m <= (uint32_t)kChunk);
-    // register-resident lists need up to 256 VGPRs per lane: at most 512 lanes per workgroup
+    // Register-list kernel: lists of one chunk, 16-byte slots, two tile buffers in LDS, at most
+    // 4 prefetch chunks per wave; its lanes need up to 256 VGPRs, so at most 512 per workgroup.
+    pl.reg_table = false;
+    if (pl.m_pad == (uint32_t)kChunk && pl.rt == 4 && 2 * pl.lds_bytes <= kLdsBudget) {
+        const uint32_t block = k64 >= 512 ? 512 : k64;
+        const uint32_t chunks = pl.sub * ((n + 63) / 64);
+        const uint32_t pf = (chunks + block / 64 - 1) / (block / 64);
+        if (pf <= 4) {
+            pl.reg_table = true;
+            pl.prefetch = pf <= 1 ? 1 : (pf <= 2 ? 2 : 4);
+        }
+    }
     const uint32_t max_block = pl.reg_table ? 512 : 1024;
-    pl.block = k64 >= max_block ? max_block : (k64 >= 512 ? 512 : (k64 >= 256 ? 256 : k64));
+    pl.block = k64 >= max_block ? max_block : k64;
     pl.kblocks = (k64 + pl.block - 1) / pl.block;
     pl.kpad = pl.block * pl.kblocks;
     pl.supported = true;
     return pl;
 }
-
-uint32_t sampled_chunk() { return kChunk; }
 
 int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                    uint32_t L, void *stream) {
@@ -248,8 +388,9 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     a.N = N;
     a.n = p->n;
     a.k = p->k;
-    a.m_pad = (p->m + kChunk - 1) / kChunk * kChunk;
+    a.m_pad = pl.m_pad;
     a.kpad = pl.kpad;
+    a.classes = pl.classes;
     a.tab = p->d_samples;
     a.off = p->d_off;
     a.w = p->w;
@@ -262,19 +403,35 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     a.g = L ? p->k / L : 1;
     const uint64_t tile_rows = (uint64_t)pl.rt * pl.sub;
     const uint64_t ntiles = (N + tile_rows - 1) / tile_rows;
-    // persistent workgroups: a few per CU, count a multiple of 8 so that the kblocks
-    // workgroups that share a vector tile land on the same XCD (and its L2)
-    const uint32_t per_cu = pl.lds_bytes > 72 * 1024 ? 1 : (pl.lds_bytes > 36 * 1024 ? 2 : 4);
+    // persistent workgroups: as many per CU as LDS and waves allow (at most 2048 lanes), count
+    // a multiple of 8 so that the kblocks workgroups sharing a vector tile land on one XCD
+    const uint32_t lds_bytes = pl.reg_table ? 2 * pl.lds_bytes : pl.lds_bytes;
+    uint32_t per_cu = kLdsBudget / lds_bytes;
+    const uint32_t by_lanes = (pl.reg_table ? 512 : 2048) / pl.block;  // 256-VGPR lanes: 512 per CU
+    if (per_cu > by_lanes) per_cu = by_lanes;
+    if (per_cu < 1) per_cu = 1;
     uint64_t gx = (uint64_t)p->num_cus * per_cu / pl.kblocks;
     gx = gx < 8 ? 8 : gx / 8 * 8;
     if (gx > ntiles) gx = ntiles;
     dim3 grid((uint32_t)gx, pl.kblocks), block(pl.block);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (pl.rt == 8 && pl.sub == 4) return launch_variant<8, 4>(p, a, grid, block, s);
-    if (pl.rt == 8) return launch_variant<8, 1>(p, a, grid, block, s);
-    if (pl.rt == 4) return launch_variant<4, 1>(p, a, grid, block, s);
-    if (pl.rt == 2) return launch_variant<2, 1>(p, a, grid, block, s);
-    return launch_variant<1, 1>(p, a, grid, block, s);
+    if (pl.reg_table) {
+#define LSH_REG_CASE(SUB_, PF_) \
+    if (pl.sub == SUB_ && pl.prefetch == PF_) \
+        return launch_kernel(&sampled_reg_kernel<SUB_, PF_>, lds_bytes, a, grid, block, s);
+        LSH_REG_CASE(8, 1) LSH_REG_CASE(8, 2) LSH_REG_CASE(8, 4)
+        LSH_REG_CASE(4, 1) LSH_REG_CASE(4, 2) LSH_REG_CASE(4, 4)
+        LSH_REG_CASE(2, 1) LSH_REG_CASE(2, 2) LSH_REG_CASE(2, 4)
+        LSH_REG_CASE(1, 1) LSH_REG_CASE(1, 2) LSH_REG_CASE(1, 4)
+#undef LSH_REG_CASE
+        return LSH_ERR_UNSUPPORTED;
+    }
+    if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8>, lds_bytes, a, grid, block, s);
+    if (pl.rt == 4 && pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4>, lds_bytes, a, grid, block, s);
+    if (pl.rt == 4 && pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2>, lds_bytes, a, grid, block, s);
+    if (pl.rt == 4) return launch_kernel(&sampled_kernel<4, 1>, lds_bytes, a, grid, block, s);
+    if (pl.rt == 2) return launch_kernel(&sampled_kernel<2, 1>, lds_bytes, a, grid, block, s);
+    return launch_kernel(&sampled_kernel<1, 1>, lds_bytes, a, grid, block, s);
 }
 
 }  // namespace lsh

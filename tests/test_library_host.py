@@ -72,3 +72,53 @@ def test_tables_bit_identical_to_oracle(n, k, m, w, seed, repl):
         s = p.shape()
         assert (s["n"], s["k"], s["m"], s["flags"], s["seed"]) == (n, k, m, int(repl), seed)
         assert s["w"] == np.float32(w)
+
+
+def _pass_groups(k, group):
+    """Functions served by one pass of an LDS read, as the header documents them."""
+    quads = {32: [list(range(8)), list(range(8, 16))],
+             16: [[0, 3, 5, 6], [1, 2, 4, 7], [8, 11, 13, 14], [9, 10, 12, 15]]}[group]
+    out = []
+    for w0 in range(0, k, 64):
+        for qs in quads:
+            fn = [w0 + 4 * q + t for q in qs for t in range(4) if w0 + 4 * q + t < k]
+            if fn:
+                out.append(np.array(fn))
+    return out
+
+
+@pytest.mark.parametrize("n,k,m,repl", [(128, 512, 32, False), (100, 70, 30, True), (960, 200, 128, False),
+                                        (16384, 96, 40, False), (30000, 64, 33, True)])
+def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
+    """The kernel may visit a function's samples in any order (a projection is a sum); the
+    schedule must hold every canonical sample exactly once plus padding, and its modelled
+    cost must be what its own entries imply."""
+    with binding.LshParams(n, k, m, 1.0, 77, with_replacement=repl) as p:
+        order, group, classes, passes = p.schedule()
+        idx = p.indices()
+        steps = order.shape[1]
+        assert steps % 32 == 0 and m <= steps < m + 32
+        pad = (order & 0x80000000) != 0
+        assert (pad.sum(axis=1) == steps - m).all()
+        for j in range(k):
+            assert sorted(order[j][~pad[j]].tolist()) == list(range(m))
+        assert ((order[pad] & 0x7fffffff) < classes).all()
+        # recompute the modelled cost: per lane group and step, the most popular class
+        cls = np.where(pad, order & 0x7fffffff,
+                       np.take_along_axis(idx, np.where(pad, 0, order).astype(np.int64), axis=1) % classes)
+        groups = _pass_groups(k, group)
+        total = 0
+        for fn in groups:
+            block = cls[fn]                                  # [lanes, steps]
+            for i in range(steps):
+                total += np.bincount(block[:, i], minlength=classes).max()
+        assert total == passes
+        assert passes >= len(groups) * steps
+        # far better than visiting samples in draw order
+        naive = 0
+        for fn in groups:
+            block = idx[fn] % classes
+            for i in range(m):
+                naive += np.bincount(block[:, i], minlength=classes).max()
+        if m >= 30 and k >= group:
+            assert passes / (len(groups) * steps) < 0.75 * naive / (len(groups) * m)

@@ -106,6 +106,7 @@ RAGGED = [
     (13, 8000, 64, 100, 3.0, 28, True, 0),       # 4-vector tiles
     (9, 16384, 128, 512, 1.0, 29, False, 0),     # 2-vector tiles
     (5, 30000, 64, 40, 1.0, 30, False, 0),       # 1-vector tiles
+    (3, 40384, 64, 33, 1.0, 32, True, 0),        # the largest dimension one LDS tile holds
     (300, 64, 2100, 16, 2.0, 31, False, 0),      # more functions than one workgroup holds
 ]
 
@@ -146,9 +147,9 @@ def test_empty_input_and_errors(lsh):
         with pytest.raises(lsh.LshError) as e:          # k % L != 0 on the fused path too
             lsh.hash_fastlsh_keys(p, x, 5)
         assert e.value.status == -1
-    with lsh.LshParams(40000, 8, 4, 1.0, 1) as p:       # one vector does not fit in LDS
+    with lsh.LshParams(50000, 8, 4, 1.0, 1) as p:       # one vector does not fit in LDS
         with pytest.raises(lsh.LshError) as e:
-            lsh.hash_fastlsh(p, torch.zeros((2, 40000), device="cuda"))
+            lsh.hash_fastlsh(p, torch.zeros((2, 50000), device="cuda"))
         assert e.value.status == -4
     with lsh.LshParams(96, 48, 8, 1.0, 1) as p:         # g = 48 / 4 = 12: fused keys unsupported
         with pytest.raises(lsh.LshError) as e:
