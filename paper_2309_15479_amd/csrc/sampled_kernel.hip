@@ -211,7 +211,7 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
 // read of the tile to the front, which would need more registers than a lane has.
 // PF = 64-coordinate chunks each wave fetches per tile (see launch_sampled).
 template <int SUB, int PF>
-__global__ __launch_bounds__(512) void sampled_reg_kernel(const SampledArgs a) {
+__global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a) {
     constexpr int RT = 4;
     extern __shared__ __align__(16) float tile[];  // 2 x [n + classes][SP][RT]
     constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
@@ -359,16 +359,22 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
         return pl;  // unsupported: one vector does not fit in LDS
     pl.m_pad = (m + kChunk - 1) / kChunk * kChunk;
     const uint32_t k64 = (k + 63) / 64 * 64;
-    // Register-list kernel: lists of one chunk, 16-byte slots, two tile buffers in LDS, at most
-    // 4 prefetch chunks per wave; its lanes need up to 256 VGPRs, so at most 512 per workgroup.
+    // Register-list kernel: lists of one chunk, 16-byte slots, two tile buffers in LDS.  Small
+    // tiles (8 or 4 vectors) measured fastest: several workgroups share a CU and one's
+    // epilogue overlaps the others' gathers.  At most 8 prefetch chunks per wave.
     pl.reg_table = false;
-    if (pl.m_pad == (uint32_t)kChunk && pl.rt == 4 && 2 * pl.lds_bytes <= kLdsBudget) {
+    if (pl.m_pad == (uint32_t)kChunk && pl.rt == 4) {
         const uint32_t block = k64 >= 512 ? 512 : k64;
-        const uint32_t chunks = pl.sub * ((n + 63) / 64);
-        const uint32_t pf = (chunks + block / 64 - 1) / (block / 64);
-        if (pf <= 4) {
+        for (uint32_t sub : {2u, 1u}) {
+            const uint64_t sp = sub == 1 ? 1 : sub + 1;
+            const uint64_t bytes = (uint64_t)(n + 16) * sp * 16;
+            const uint32_t chunks = sub * ((n + 63) / 64);
+            const uint32_t pf = (chunks + block / 64 - 1) / (block / 64);
+            if (2 * bytes > kLdsBudget || pf > 8) continue;
+            fits(4, sub, 16);
             pl.reg_table = true;
-            pl.prefetch = pf <= 1 ? 1 : (pf <= 2 ? 2 : 4);
+            pl.prefetch = pf <= 1 ? 1 : (pf <= 2 ? 2 : (pf <= 4 ? 4 : 8));
+            break;
         }
     }
     const uint32_t max_block = pl.reg_table ? 512 : 1024;
@@ -407,7 +413,8 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     // a multiple of 8 so that the kblocks workgroups sharing a vector tile land on one XCD
     const uint32_t lds_bytes = pl.reg_table ? 2 * pl.lds_bytes : pl.lds_bytes;
     uint32_t per_cu = kLdsBudget / lds_bytes;
-    const uint32_t by_lanes = (pl.reg_table ? 512 : 2048) / pl.block;  // 256-VGPR lanes: 512 per CU
+    // register-list kernel: 4 waves per SIMD (up to 128 VGPRs per lane), else 8
+    const uint32_t by_lanes = (pl.reg_table ? 1024 : 2048) / pl.block;
     if (per_cu > by_lanes) per_cu = by_lanes;
     if (per_cu < 1) per_cu = 1;
     uint64_t gx = (uint64_t)p->num_cus * per_cu / pl.kblocks;
@@ -419,10 +426,8 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
 #define LSH_REG_CASE(SUB_, PF_) \
     if (pl.sub == SUB_ && pl.prefetch == PF_) \
         return launch_kernel(&sampled_reg_kernel<SUB_, PF_>, lds_bytes, a, grid, block, s);
-        LSH_REG_CASE(8, 1) LSH_REG_CASE(8, 2) LSH_REG_CASE(8, 4)
-        LSH_REG_CASE(4, 1) LSH_REG_CASE(4, 2) LSH_REG_CASE(4, 4)
-        LSH_REG_CASE(2, 1) LSH_REG_CASE(2, 2) LSH_REG_CASE(2, 4)
-        LSH_REG_CASE(1, 1) LSH_REG_CASE(1, 2) LSH_REG_CASE(1, 4)
+        LSH_REG_CASE(2, 1) LSH_REG_CASE(2, 2) LSH_REG_CASE(2, 4) LSH_REG_CASE(2, 8)
+        LSH_REG_CASE(1, 1) LSH_REG_CASE(1, 2) LSH_REG_CASE(1, 4) LSH_REG_CASE(1, 8)
 #undef LSH_REG_CASE
         return LSH_ERR_UNSUPPORTED;
     }
