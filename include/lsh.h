@@ -95,7 +95,10 @@ int lsh_params_get_shape(const lsh_params_t *params, uint32_t *n, uint32_t *k, u
  * four functions numbered {0,3,5,6}, {1,2,4,7}, {8,11,13,14}, {9,10,12,15} (run q = functions
  * 4q..4q+3), as measured for 16-byte LDS reads on gfx950.
  *   order [k*steps]  entry (j, i) = position in function j's canonical list (0..m-1), or
- *                    0x80000000 | class for a padding sample (coefficient 0)
+ *                    0x80000000 | class for a padding sample (coefficient 0), or 0xFFFFFFFF
+ *                    (unused tail: for large n the lists are cut by coordinate range and
+ *                    padded per range and per 64 functions, so rows differ in length; steps
+ *                    is then the longest row)
  *   modelled_passes  sum over lane groups and steps of the largest number of lanes sharing a
  *                    class (k/group * steps when the schedule is conflict-free)
  * Any out pointer may be NULL.  Errors: INVALID_ARG, UNSUPPORTED (n too large for the kernel).

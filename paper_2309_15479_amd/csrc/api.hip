@@ -17,9 +17,11 @@ void free_tables(lsh_params *p) {
     if (p->d_samples) (void)hipFree(p->d_samples);
     if (p->d_off) (void)hipFree(p->d_off);
     if (p->d_dense) (void)hipFree(p->d_dense);
+    if (p->d_chunk_info) (void)hipFree(p->d_chunk_info);
     p->d_samples = nullptr;
     p->d_off = nullptr;
     p->d_dense = nullptr;
+    p->d_chunk_info = nullptr;
     if (prev >= 0 && prev != p->device) (void)hipSetDevice(prev);
     p->device = -1;
 }
@@ -54,7 +56,48 @@ int upload_tables(lsh_params *p) {
             hipMemcpy(p->d_off, off.data(), off.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
             rc = LSH_ERR_HIP;
 
-        if (rc == LSH_OK && p->plan.supported) {
+        if (rc == LSH_OK && p->plan.supported && p->plan.chunked) {
+            // per wave and coordinate range: [steps][64] entries in scheduled order, offsets
+            // relative to the range's first coordinate
+            const SampledPlan &pl = p->plan;
+            const uint32_t slot_bytes = pl.sp * pl.rt * 4u;
+            const uint32_t waves = kpad / 64, real_waves = (p->k + 63) / 64;
+            std::vector<uint2> info((size_t)waves * pl.nchunks, make_uint2(0, 0));
+            std::vector<Sample> tab(p->order.size() ? p->order.size() : 1, Sample{pl.chunk * slot_bytes, 0.f});
+            size_t base = 0;
+            for (uint32_t w = 0; w < real_waves; ++w)
+                for (uint32_t q = 0; q < pl.nchunks; ++q) {
+                    const uint32_t steps = p->chunk_steps[(size_t)w * pl.nchunks + q];
+                    info[(size_t)w * pl.nchunks + q] = make_uint2((uint32_t)base, steps);
+                    for (uint32_t st = 0; st < steps; ++st)
+                        for (uint32_t l = 0; l < 64; ++l) {
+                            Sample &s = tab[base + (size_t)st * 64 + l];
+                            const uint32_t e = p->order[base + (size_t)st * 64 + l];
+                            const uint32_t j = w * 64 + l;
+                            if ((e & kPadSample) || j >= p->k) {
+                                const uint32_t want = e & ~kPadSample;
+                                for (uint32_t z = pl.chunk; z < pl.chunk + pl.classes; ++z)
+                                    if (z % pl.classes == want) s.lds_byte_offset = z * slot_bytes;
+                                s.coef = 0.f;
+                            } else {
+                                const uint32_t c = p->idx[(size_t)j * p->m + e];
+                                s.lds_byte_offset = (c - q * pl.chunk) * slot_bytes;
+                                s.coef = p->coef[(size_t)j * p->m + e];
+                            }
+                        }
+                    base += (size_t)steps * 64;
+                }
+            if (hipMalloc(&p->d_samples, tab.size() * sizeof(Sample)) != hipSuccess) rc = LSH_ERR_ALLOC;
+            if (rc == LSH_OK && hipMemcpy(p->d_samples, tab.data(), tab.size() * sizeof(Sample),
+                                          hipMemcpyHostToDevice) != hipSuccess)
+                rc = LSH_ERR_HIP;
+            if (rc == LSH_OK && hipMalloc(&p->d_chunk_info, info.size() * sizeof(uint2)) != hipSuccess)
+                rc = LSH_ERR_ALLOC;
+            if (rc == LSH_OK && hipMemcpy(p->d_chunk_info, info.data(), info.size() * sizeof(uint2),
+                                          hipMemcpyHostToDevice) != hipSuccess)
+                rc = LSH_ERR_HIP;
+        }
+        if (rc == LSH_OK && p->plan.supported && !p->plan.chunked) {
             // step-major [m_pad][kpad] in scheduled order; padding samples (and the lanes
             // beyond k) read a zero slot with coefficient 0
             const SampledPlan &pl = p->plan;
@@ -135,8 +178,11 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
         p->plan = plan_sampled(n, k, m);
         if (p->plan.supported) {
             try {
-                p->schedule_cost = schedule_samples(p->idx, k, m, p->plan.m_pad, p->plan.group,
-                                                    p->plan.classes, p->order);
+                const SampledPlan &pl = p->plan;
+                p->schedule_cost =
+                    pl.chunked ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 8, pl.group, pl.classes,
+                                                  p->chunk_steps, p->order)
+                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, p->order);
             } catch (const std::bad_alloc &) {
                 rc = LSH_ERR_ALLOC;
             }
@@ -194,12 +240,39 @@ int lsh_params_get_shape(const lsh_params_t *p, uint32_t *n, uint32_t *k, uint32
 int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *steps, uint32_t *group,
                             uint32_t *classes, uint64_t *modelled_passes) {
     if (!p) return LSH_ERR_INVALID_ARG;
-    if (!p->plan.supported) return LSH_ERR_UNSUPPORTED;
-    if (steps) *steps = p->plan.m_pad;
-    if (group) *group = p->plan.group;
-    if (classes) *classes = p->plan.classes;
+    const SampledPlan &pl = p->plan;
+    if (!pl.supported) return LSH_ERR_UNSUPPORTED;
+    uint32_t nsteps = pl.m_pad;
+    if (pl.chunked) {  // longest concatenation of a wave's per-range lists
+        nsteps = 0;
+        for (uint32_t w = 0; w < (p->k + 63) / 64; ++w) {
+            uint32_t total = 0;
+            for (uint32_t q = 0; q < pl.nchunks; ++q) total += p->chunk_steps[(size_t)w * pl.nchunks + q];
+            nsteps = total > nsteps ? total : nsteps;
+        }
+    }
+    if (steps) *steps = nsteps;
+    if (group) *group = pl.group;
+    if (classes) *classes = pl.classes;
     if (modelled_passes) *modelled_passes = p->schedule_cost;
-    if (order) std::copy(p->order.begin(), p->order.end(), order);
+    if (!order) return LSH_OK;
+    if (!pl.chunked) {
+        std::copy(p->order.begin(), p->order.end(), order);
+        return LSH_OK;
+    }
+    std::fill(order, order + (size_t)p->k * nsteps, 0xFFFFFFFFu);
+    size_t base = 0;
+    for (uint32_t w = 0; w < (p->k + 63) / 64; ++w) {
+        uint32_t at = 0;
+        for (uint32_t q = 0; q < pl.nchunks; ++q) {
+            const uint32_t len = p->chunk_steps[(size_t)w * pl.nchunks + q];
+            for (uint32_t st = 0; st < len; ++st)
+                for (uint32_t l = 0; l < 64 && w * 64 + l < p->k; ++l)
+                    order[(size_t)(w * 64 + l) * nsteps + at + st] = p->order[base + (size_t)st * 64 + l];
+            at += len;
+            base += (size_t)len * 64;
+        }
+    }
     return LSH_OK;
 }
 

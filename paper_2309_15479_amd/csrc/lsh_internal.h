@@ -30,6 +30,8 @@ struct SampledPlan {
     uint32_t kpad = 0;       // block * kblocks >= k
     uint32_t lds_bytes = 0;  // dynamic LDS per workgroup
     bool reg_table = false;  // register-list kernel: (offset, coef) lists live in VGPRs
+    bool chunked = false;    // chunked kernel: lists bucketed by coordinate range
+    uint32_t chunk = 0, nchunks = 0;  // chunked kernel: coordinates per range, number of ranges
     uint32_t prefetch = 0;   // register-list kernel: 64-coordinate chunks fetched per wave and tile
     bool supported = false;
 };
@@ -52,7 +54,9 @@ struct lsh_params {
     lsh::SampledPlan plan;
     std::vector<uint32_t> order;       // [k][m_pad] visiting order of each function's samples
     uint64_t schedule_cost = 0;        // modelled LDS passes (see schedule.cpp)
-    lsh::Sample *d_samples = nullptr;  // [m_pad][kpad], step-major
+    std::vector<uint32_t> chunk_steps; // chunked plan: [waves][nchunks] list length
+    lsh::Sample *d_samples = nullptr;  // flat: [m_pad][kpad] step-major; chunked: per wave and range, [steps][64]
+    void *d_chunk_info = nullptr;      // chunked plan: uint2 {first entry, steps} [kpad/64][nchunks]
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n] when m == n (row j = a_j), else null
     uint32_t kpad_dense = 0;
@@ -67,6 +71,10 @@ int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, 
 // host: bank-conflict-free visiting order of every function's samples (schedule.cpp)
 uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,
                           uint32_t group, uint32_t classes, std::vector<uint32_t> &order_out);
+
+uint64_t schedule_chunked(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t chunk,
+                          uint32_t nchunks, uint32_t step_quantum, uint32_t group, uint32_t classes,
+                          std::vector<uint32_t> &steps_out, std::vector<uint32_t> &order_out);
 
 // device: plan + upload + launches (defined in the .hip files)
 SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m);

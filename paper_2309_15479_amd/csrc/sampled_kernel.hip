@@ -69,6 +69,9 @@ struct SampledArgs {
     int epilogue;        // Epilogue
     void *out;
     uint32_t L, g;       // key groups (Epilogue::Keys)
+    // chunked kernel only
+    uint32_t chunk, nchunks;     // coordinates per LDS chunk, number of chunks
+    const uint2 *chunk_info;     // [waves][nchunks] {first table entry, steps}
 };
 
 // One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.
@@ -326,6 +329,94 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
     }
 }
 
+// Chunked kernel for large n (or long lists at large n): the tile holds 4*SUB vectors times a
+// range of `chunk` coordinates, so that enough vectors share one pass over the lists to keep
+// list traffic (L2 -> registers) well below the LDS gather traffic.  Every function's samples
+// are bucketed by coordinate range on the host; the 64 lists of a wave for one range are
+// padded to a common length (wave-uniform trip count) and bank-scheduled like the flat lists.
+// Accumulators persist across the ranges of a tile.
+template <int SUB>
+__global__ __launch_bounds__(512, 4) void sampled_chunked_kernel(const SampledArgs a) {
+    constexpr int RT = 4;
+    constexpr int kStep = 8;  // list entries fetched at a time; list lengths are multiples of it
+    extern __shared__ __align__(16) float tile[];  // [chunk + classes][SP][RT]
+    constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
+    constexpr uint32_t kTileRows = RT * SUB;
+    const uint32_t n = a.n;
+    const uint32_t j = blockIdx.y * blockDim.x + threadIdx.x;  // < kpad
+    const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
+    const float b = a.off[j];
+
+    for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x)
+        tile[(size_t)a.chunk * SP * RT + e] = 0.f;
+
+    uint64_t key_pow = 1;
+    if (a.epilogue == (int)Epilogue::Keys) {
+        const uint32_t t = j % a.g;
+        for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
+    }
+
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint32_t wave_global = __builtin_amdgcn_readfirstlane(j >> 6);
+    const uint32_t pieces = SUB * ((a.chunk + 63) / 64);  // 64-coordinate pieces of one chunk
+    const char *base = reinterpret_cast<const char *>(tile);
+
+    for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const uint64_t row0 = t * kTileRows;
+        float acc[SUB][RT];
+#pragma unroll
+        for (int st = 0; st < SUB; ++st)
+#pragma unroll
+            for (int r = 0; r < RT; ++r) acc[st][r] = 0.f;
+
+        for (uint32_t q = 0; q < a.nchunks; ++q) {
+            const uint32_t c0 = q * a.chunk;
+            __syncthreads();  // every lane is done reading the previous chunk
+            for (uint32_t pc = wave; pc < pieces; pc += nwaves) {
+                const uint32_t st = pc % SUB, cc = (pc / SUB) * 64 + lane;
+                if (cc < a.chunk && c0 + cc < n) {
+                    float x[RT];
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) {
+                        const uint64_t row = row0 + (uint64_t)st * RT + r;
+                        x[r] = row < a.N ? a.data[row * n + c0 + cc] : 0.f;
+                    }
+                    lds_write_slot<RT>(tile + ((size_t)cc * SP + st) * RT, x);
+                }
+            }
+            __syncthreads();
+
+            const uint2 info = a.chunk_info[(size_t)wave_global * a.nchunks + q];
+            const Sample *list = a.tab + info.x + lane;
+            for (uint32_t s0 = 0; s0 < info.y; s0 += kStep) {
+                Sample e[kStep];
+#pragma unroll
+                for (int i = 0; i < kStep; ++i) e[i] = list[(size_t)(s0 + i) * 64];
+#pragma unroll
+                for (int i = 0; i < kStep; ++i) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    float4 x[SUB];
+#pragma unroll
+                    for (int st = 0; st < SUB; ++st)
+                        x[st] = *reinterpret_cast<const float4 *>(base + e[i].lds_byte_offset + st * 16);
+#pragma unroll
+                    for (int st = 0; st < SUB; ++st) {
+                        acc[st][0] = fmaf(e[i].coef, x[st].x, acc[st][0]);
+                        acc[st][1] = fmaf(e[i].coef, x[st].y, acc[st][1]);
+                        acc[st][2] = fmaf(e[i].coef, x[st].z, acc[st][2]);
+                        acc[st][3] = fmaf(e[i].coef, x[st].w, acc[st][3]);
+                        pin(acc[st]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        finish<RT, SUB>(a, row0, j, acc, b, key_pow);
+    }
+}
+
 template <typename Kernel>
 int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 grid, dim3 block,
                   hipStream_t stream) {
@@ -377,7 +468,20 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
             break;
         }
     }
-    const uint32_t max_block = pl.reg_table ? 512 : 1024;
+    // Chunked kernel: when a full-dimension tile would hold fewer than 16 vectors and the lists
+    // do not stay in registers.  16 vectors x `chunk` coordinates, two workgroups per CU.
+    pl.chunked = false;
+    if (!pl.reg_table && (pl.rt != 4 || pl.sub < 4)) {
+        const uint32_t slot = 5 * 16;                                // SUB = 4: 5 slots of 16 bytes
+        const uint32_t cmax = (kLdsBudget / 2 / slot - 16) / 16 * 16;
+        pl.nchunks = (n + cmax - 1) / cmax;
+        pl.chunk = ((n + pl.nchunks - 1) / pl.nchunks + 15) / 16 * 16;
+        pl.nchunks = (n + pl.chunk - 1) / pl.chunk;
+        pl.rt = 4; pl.sub = 4; pl.sp = 5; pl.classes = 16; pl.group = 16;
+        pl.lds_bytes = (pl.chunk + 16) * slot;
+        pl.chunked = true;
+    }
+    const uint32_t max_block = (pl.reg_table || pl.chunked) ? 512 : 1024;
     pl.block = k64 >= max_block ? max_block : k64;
     pl.kblocks = (k64 + pl.block - 1) / pl.block;
     pl.kpad = pl.block * pl.kblocks;
@@ -407,6 +511,9 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     a.out = d_out;
     a.L = L;
     a.g = L ? p->k / L : 1;
+    a.chunk = pl.chunk;
+    a.nchunks = pl.nchunks;
+    a.chunk_info = static_cast<const uint2 *>(p->d_chunk_info);
     const uint64_t tile_rows = (uint64_t)pl.rt * pl.sub;
     const uint64_t ntiles = (N + tile_rows - 1) / tile_rows;
     // persistent workgroups: as many per CU as LDS and waves allow (at most 2048 lanes), count
@@ -414,7 +521,7 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     const uint32_t lds_bytes = pl.reg_table ? 2 * pl.lds_bytes : pl.lds_bytes;
     uint32_t per_cu = kLdsBudget / lds_bytes;
     // register-list kernel: 4 waves per SIMD (up to 128 VGPRs per lane), else 8
-    const uint32_t by_lanes = (pl.reg_table ? 1024 : 2048) / pl.block;
+    const uint32_t by_lanes = ((pl.reg_table || pl.chunked) ? 1024 : 2048) / pl.block;
     if (per_cu > by_lanes) per_cu = by_lanes;
     if (per_cu < 1) per_cu = 1;
     uint64_t gx = (uint64_t)p->num_cus * per_cu / pl.kblocks;
@@ -431,6 +538,7 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
 #undef LSH_REG_CASE
         return LSH_ERR_UNSUPPORTED;
     }
+    if (pl.chunked) return launch_kernel(&sampled_chunked_kernel<4>, lds_bytes, a, grid, block, s);
     if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8>, lds_bytes, a, grid, block, s);
     if (pl.rt == 4 && pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4>, lds_bytes, a, grid, block, s);
     if (pl.rt == 4 && pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2>, lds_bytes, a, grid, block, s);

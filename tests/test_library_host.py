@@ -88,7 +88,7 @@ def _pass_groups(k, group):
 
 
 @pytest.mark.parametrize("n,k,m,repl", [(128, 512, 32, False), (100, 70, 30, True), (960, 200, 128, False),
-                                        (16384, 96, 40, False), (30000, 64, 33, True)])
+                                        (4096, 520, 30, False)])
 def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
     """The kernel may visit a function's samples in any order (a projection is a sum); the
     schedule must hold every canonical sample exactly once plus padding, and its modelled
@@ -103,7 +103,7 @@ def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
         for j in range(k):
             assert sorted(order[j][~pad[j]].tolist()) == list(range(m))
         assert ((order[pad] & 0x7fffffff) < classes).all()
-        # recompute the modelled cost: per lane group and step, the most popular class
+        # recompute the modelled cost: per pass group and step, the most popular class
         cls = np.where(pad, order & 0x7fffffff,
                        np.take_along_axis(idx, np.where(pad, 0, order).astype(np.int64), axis=1) % classes)
         groups = _pass_groups(k, group)
@@ -122,3 +122,27 @@ def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
                 naive += np.bincount(block[:, i], minlength=classes).max()
         if m >= 30 and k >= group:
             assert passes / (len(groups) * steps) < 0.75 * naive / (len(groups) * m)
+
+
+@pytest.mark.parametrize("n,k,m,repl", [(16384, 96, 40, False), (30000, 64, 33, True), (4096, 200, 256, False)])
+def test_chunked_gather_schedule_is_a_padded_permutation(n, k, m, repl):
+    """Large n: the lists are cut by coordinate range and padded per range and per 64
+    functions.  Every canonical sample must still appear exactly once, ranges in ascending
+    order, and the 64 functions of a wave must have rows of equal length."""
+    with binding.LshParams(n, k, m, 1.0, 78, with_replacement=repl) as p:
+        order, group, classes, passes = p.schedule()
+        idx = p.indices().astype(np.int64)
+        unused = order == 0xFFFFFFFF
+        pad = ~unused & ((order & 0x80000000) != 0)
+        real = ~unused & ~pad
+        assert group == 16 and classes == 16
+        used_len = (~unused).sum(axis=1)
+        for w0 in range(0, k, 64):
+            assert len(set(used_len[w0:w0 + 64].tolist())) == 1
+            assert (used_len[w0:w0 + 64] % 8 == 0).all()
+        for j in range(k):
+            row = order[j][real[j]]
+            assert sorted(row.tolist()) == list(range(m))
+            assert not unused[j][:used_len[j]].any()           # the unused part is a tail
+        assert ((order[pad] & 0x7fffffff) < classes).all()
+        assert passes >= (~unused).sum() / group
