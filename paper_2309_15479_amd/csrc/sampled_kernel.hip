@@ -74,46 +74,79 @@ struct SampledArgs {
     const uint2 *chunk_info;     // [waves][nchunks] {first table entry, steps}
 };
 
-// One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.
+// 4 x 4 transpose across the four lanes of a quad: on entry lane u holds x[t] = value of
+// (function u of the quad, vector t); on exit x[t] = value of (function t, vector u).
+// Two butterfly stages of quad-permute DPP moves (no LDS traffic).
+__device__ __forceinline__ void quad_transpose(uint32_t (&x)[4]) {
+    const bool odd = threadIdx.x & 1, hi = threadIdx.x & 2;
+    constexpr int kXor1 = 0xB1, kXor2 = 0x4E;  // quad_perm [1,0,3,2] and [2,3,0,1]
+    uint32_t t0 = odd ? x[0] : x[1], t1 = odd ? x[2] : x[3];
+    t0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)t0, kXor1, 0xf, 0xf, true);
+    t1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)t1, kXor1, 0xf, 0xf, true);
+    if (odd) { x[0] = t0; x[2] = t1; } else { x[1] = t0; x[3] = t1; }
+    t0 = hi ? x[0] : x[2];
+    t1 = hi ? x[1] : x[3];
+    t0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)t0, kXor2, 0xf, 0xf, true);
+    t1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)t1, kXor2, 0xf, 0xf, true);
+    if (hi) { x[0] = t0; x[1] = t1; } else { x[2] = t0; x[3] = t1; }
+}
+
+// One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.  A vector
+// memory instruction costs the memory pipeline about the same whether a lane moves 4 or 16
+// bytes, and this kernel issues one store per (wave, vector): so with 4-vector slots the ids
+// of a quad of lanes are transposed in registers first and leave as 16-byte stores (four
+// consecutive functions of one vector per lane), and sign words leave one store per tile.
 template <int RT, int SUB>
 __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint32_t j,
                                        const float (&acc)[SUB][RT], float b, uint64_t key_pow) {
     const bool live = j < a.k;
     switch (a.epilogue) {
-        case (int)Epilogue::Ids: {
-            int32_t *out = reinterpret_cast<int32_t *>(a.out);
-#pragma unroll
-            for (int s = 0; s < SUB; ++s)
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const uint64_t row = row0 + s * RT + r;
-                    const float q = a.w_is_pow2 ? (acc[s][r] + b) * a.inv_w : (acc[s][r] + b) / a.w;
-                    if (live && row < a.N) out[row * a.k + j] = (int)floorf(q);
-                }
-            break;
-        }
+        case (int)Epilogue::Ids:
         case (int)Epilogue::Proj: {
-            float *out = reinterpret_cast<float *>(a.out);
+            const bool ids = a.epilogue == (int)Epilogue::Ids;
+            uint32_t *out = reinterpret_cast<uint32_t *>(a.out);
+            const bool wide = RT == 4 && (a.k & 3) == 0;
 #pragma unroll
-            for (int s = 0; s < SUB; ++s)
+            for (int s = 0; s < SUB; ++s) {
+                uint32_t v[RT];
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const float p = acc[s][r];
+                    const float q = a.w_is_pow2 ? (p + b) * a.inv_w : (p + b) / a.w;
+                    v[r] = ids ? (uint32_t)(int)floorf(q) : __float_as_uint(p);
+                }
+                if constexpr (RT == 4) {
+                    if (wide) {  // uniform
+                        quad_transpose(v);
+                        const uint64_t row = row0 + s * RT + (threadIdx.x & 3);
+                        const uint32_t j4 = j & ~3u;
+                        if (j4 < a.k && row < a.N)
+                            *reinterpret_cast<uint4 *>(out + row * a.k + j4) = make_uint4(v[0], v[1], v[2], v[3]);
+                        continue;
+                    }
+                }
 #pragma unroll
                 for (int r = 0; r < RT; ++r) {
                     const uint64_t row = row0 + s * RT + r;
-                    if (live && row < a.N) out[row * a.k + j] = acc[s][r];
+                    if (live && row < a.N) out[row * a.k + j] = v[r];
                 }
+            }
             break;
         }
         case (int)Epilogue::Signs: {
             uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
             const uint32_t words = (a.k + 63) / 64;
+            const uint32_t lane = threadIdx.x & 63;
+            uint64_t mine = 0;  // lane v of the wave keeps the word of the tile's vector v
 #pragma unroll
             for (int s = 0; s < SUB; ++s)
 #pragma unroll
                 for (int r = 0; r < RT; ++r) {
-                    const uint64_t row = row0 + s * RT + r;  // uniform: whole waves reach the ballot
-                    const uint64_t word = __ballot(live && acc[s][r] >= 0.f);
-                    if ((threadIdx.x & 63) == 0 && live && row < a.N) out[row * words + (j >> 6)] = word;
+                    const uint64_t word = __ballot(live && acc[s][r] >= 0.f);  // whole waves get here
+                    if (lane == (uint32_t)(s * RT + r)) mine = word;
                 }
+            const uint64_t row = row0 + lane;
+            if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k && row < a.N) out[row * words + (j >> 6)] = mine;
             break;
         }
         default: {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64

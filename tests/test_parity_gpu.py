@@ -131,6 +131,21 @@ def test_dense_shapes(lsh, N, n, k):
         say(_compare_all(lsh, p, data, np.arange(N), label=f"dense{N}x{n}x{k}", dense=True, signs=False))
 
 
+@pytest.mark.parametrize("k,L", [(64, 16), (64, 1), (512, 2), (1024, 2), (96, 8), (60, 60), (256, 32), (100, 5)])
+def test_pack_keys_group_sizes(lsh, k, L):
+    """Key packing is exact integer work: bit-exact against the oracle for every group size
+    (16-byte quad path, generic path, one id per key), on ids that use the full int32 range."""
+    N = 777
+    g = torch.Generator(device="cuda")
+    g.manual_seed(k * 131 + L)
+    ids = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, k), generator=g, device="cuda", dtype=torch.int64).to(torch.int32)
+    with lsh.LshParams(128, k, 8, 1.0, 5) as p:
+        keys = lsh.pack_keys(p, ids, L)
+        torch.cuda.synchronize()
+        want = oracle.pack_keys(ids.cpu().numpy(), L)
+        assert np.array_equal(keys.cpu().numpy().view(np.uint64), want)
+
+
 def test_empty_input_and_errors(lsh):
     with lsh.LshParams(128, 64, 32, 4.0, 1) as p:
         data = torch.empty((0, 128), device="cuda")
