@@ -19,6 +19,7 @@
 // every lane then reads 4 consecutive floats (one 16-byte LDS read) per group.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "lsh_internal.h"
@@ -435,9 +436,13 @@ int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N
 #define LSH_SHORT_CASE(V_, P_, W_) \
     if (vec4 == V_ && proj == P_ && pw == W_) { \
         auto fn = &dense_short_kernel<V_, P_, W_>; \
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)lds_bytes) != hipSuccess) \
-            return LSH_ERR_HIP; \
+        static std::atomic<bool> granted{false};  /* the attribute call costs ~1 ms: once per kernel */ \
+        if (!granted.load(std::memory_order_acquire)) { \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
+                return LSH_ERR_HIP; \
+            granted.store(true, std::memory_order_release); \
+        } \
         hipLaunchKernelGGL(fn, g2, b2, lds_bytes, s, a); \
     }
         LSH_SHORT_CASE(true, false, true) LSH_SHORT_CASE(true, false, false)

@@ -19,6 +19,9 @@
 // whole launch; sampled_kernel streams longer lists through registers for every tile.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <unordered_map>
+
 #include "lsh_internal.h"
 
 namespace lsh {
@@ -91,19 +94,40 @@ __device__ __forceinline__ void quad_transpose(uint32_t (&x)[4]) {
     if (hi) { x[0] = t0; x[1] = t1; } else { x[2] = t0; x[3] = t1; }
 }
 
+// Sum of a 64-bit value over each aligned group of g consecutive lanes (g a power of two
+// <= 64); every lane of the group gets the sum.  Steps inside a row of 16 lanes are DPP moves
+// (quad permutes, half-row and row mirrors: no LDS traffic, the resource the gather is short
+// of); only the steps across rows use the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_u64(uint64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)v, CTRL, 0xf, 0xf, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(v >> 32), CTRL, 0xf, 0xf, true);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t group_sum(uint64_t v, uint32_t g) {
+    if (g >= 2) v += dpp_u64<0xB1>(v);    // quad_perm [1,0,3,2]
+    if (g >= 4) v += dpp_u64<0x4E>(v);    // quad_perm [2,3,0,1]
+    if (g >= 8) v += dpp_u64<0x141>(v);   // row_half_mirror: the other quad of the half row
+    if (g >= 16) v += dpp_u64<0x140>(v);  // row_mirror: the other half of the row
+    if (g >= 32) v += __shfl_xor(v, 16);
+    if (g >= 64) v += __shfl_xor(v, 32);
+    return v;
+}
+
 // One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.  A vector
 // memory instruction costs the memory pipeline about the same whether a lane moves 4 or 16
 // bytes, and this kernel issues one store per (wave, vector): so with 4-vector slots the ids
 // of a quad of lanes are transposed in registers first and leave as 16-byte stores (four
 // consecutive functions of one vector per lane), and sign words leave one store per tile.
-template <int RT, int SUB>
+template <int RT, int SUB, int EP>
 __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint32_t j,
                                        const float (&acc)[SUB][RT], float b, uint64_t key_pow) {
     const bool live = j < a.k;
-    switch (a.epilogue) {
+    switch (EP) {
         case (int)Epilogue::Ids:
         case (int)Epilogue::Proj: {
-            const bool ids = a.epilogue == (int)Epilogue::Ids;
+            constexpr bool ids = EP == (int)Epilogue::Ids;
             uint32_t *out = reinterpret_cast<uint32_t *>(a.out);
             const bool wide = RT == 4 && (a.k & 3) == 0;
 #pragma unroll
@@ -157,9 +181,8 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
                 for (int r = 0; r < RT; ++r) {
                     const uint64_t row = row0 + s * RT + r;
                     const float q = a.w_is_pow2 ? (acc[s][r] + b) * a.inv_w : (acc[s][r] + b) / a.w;
-                    uint64_t term = (uint64_t)(uint32_t)(int)floorf(q) * key_pow;
-                    for (uint32_t d = a.g >> 1; d >= 1; d >>= 1) term += __shfl_xor(term, (int)d);
-                    if (live && row < a.N && (j % a.g) == 0) out[row * a.L + j / a.g] = term;
+                    const uint64_t key = group_sum((uint64_t)(uint32_t)(int)floorf(q) * key_pow, a.g);
+                    if (live && row < a.N && (j % a.g) == 0) out[row * a.L + j / a.g] = key;
                 }
         }
     }
@@ -167,7 +190,7 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
 
 // Streamed-list kernel: every tile, each lane streams its (offset, coefficient) list through
 // registers one chunk at a time and applies the chunk to all SUB sub-tiles.
-template <int RT, int SUB>
+template <int RT, int SUB, int EP>
 __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
     extern __shared__ __align__(16) float tile[];  // [n + classes][SP][RT]
     constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
@@ -182,7 +205,7 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
         tile[(size_t)n * SP * RT + e] = 0.f;
 
     uint64_t key_pow = 1;  // C^(g-1-t) for this lane's position t in its key group
-    if (a.epilogue == (int)Epilogue::Keys) {
+    if (EP == (int)Epilogue::Keys) {
         const uint32_t t = j % a.g;
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
     }
@@ -234,7 +257,7 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
                 }
             }
         }
-        finish<RT, SUB>(a, row0, j, acc, b, key_pow);
+        finish<RT, SUB, EP>(a, row0, j, acc, b, key_pow);
     }
 }
 
@@ -246,7 +269,7 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
 // with the FMAs of sample i); scheduling barriers keep the compiler from hoisting every LDS
 // read of the tile to the front, which would need more registers than a lane has.
 // PF = 64-coordinate chunks each wave fetches per tile (see launch_sampled).
-template <int SUB, int PF>
+template <int SUB, int PF, int EP>
 __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a) {
     constexpr int RT = 4;
     extern __shared__ __align__(16) float tile[];  // 2 x [n + classes][SP][RT]
@@ -268,7 +291,7 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
     }
 
     uint64_t key_pow = 1;
-    if (a.epilogue == (int)Epilogue::Keys) {
+    if (EP == (int)Epilogue::Keys) {
         const uint32_t t = j % a.g;
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
     }
@@ -354,7 +377,7 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        finish<RT, SUB>(a, row0, j, acc, b, key_pow);
+        finish<RT, SUB, EP>(a, row0, j, acc, b, key_pow);
 
         if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
         __syncthreads();  // next buffer complete; everyone is done with the current one
@@ -368,7 +391,7 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
 // are bucketed by coordinate range on the host; the 64 lists of a wave for one range are
 // padded to a common length (wave-uniform trip count) and bank-scheduled like the flat lists.
 // Accumulators persist across the ranges of a tile.
-template <int SUB>
+template <int SUB, int EP>
 __global__ __launch_bounds__(512, 4) void sampled_chunked_kernel(const SampledArgs a) {
     constexpr int RT = 4;
     constexpr int kStep = 8;  // list entries fetched at a time; list lengths are multiples of it
@@ -384,7 +407,7 @@ __global__ __launch_bounds__(512, 4) void sampled_chunked_kernel(const SampledAr
         tile[(size_t)a.chunk * SP * RT + e] = 0.f;
 
     uint64_t key_pow = 1;
-    if (a.epilogue == (int)Epilogue::Keys) {
+    if (EP == (int)Epilogue::Keys) {
         const uint32_t t = j % a.g;
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
     }
@@ -446,16 +469,28 @@ __global__ __launch_bounds__(512, 4) void sampled_chunked_kernel(const SampledAr
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        finish<RT, SUB>(a, row0, j, acc, b, key_pow);
+        finish<RT, SUB, EP>(a, row0, j, acc, b, key_pow);
     }
+}
+
+// hipFuncSetAttribute costs about a millisecond of host time: raise a kernel's dynamic LDS
+// limit once (per kernel and size), not per launch.
+int ensure_lds_limit(const void *fn, uint32_t lds_bytes) {
+    static std::mutex mu;
+    static std::unordered_map<const void *, uint32_t> granted;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = granted.find(fn);
+    if (it != granted.end() && it->second >= lds_bytes) return LSH_OK;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+        return LSH_ERR_HIP;
+    granted[fn] = lds_bytes;
+    return LSH_OK;
 }
 
 template <typename Kernel>
 int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 grid, dim3 block,
                   hipStream_t stream) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return LSH_ERR_HIP;
+    if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP;
     hipLaunchKernelGGL(fn, grid, block, lds_bytes, stream, args);
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
@@ -562,22 +597,39 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     if (gx > ntiles) gx = ntiles;
     dim3 grid((uint32_t)gx, pl.kblocks), block(pl.block);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // one instantiation per epilogue: a run-time switch inside the kernels costs registers
+    // (spills) in the gather loop
+#define LSH_EP_CASES(CALL) \
+    switch (ep) { \
+        case Epilogue::Ids: CALL((int)Epilogue::Ids) break; \
+        case Epilogue::Proj: CALL((int)Epilogue::Proj) break; \
+        case Epilogue::Signs: CALL((int)Epilogue::Signs) break; \
+        default: CALL((int)Epilogue::Keys) break; \
+    }
     if (pl.reg_table) {
-#define LSH_REG_CASE(SUB_, PF_) \
+#define LSH_REG_CASE(SUB_, PF_, EP_) \
     if (pl.sub == SUB_ && pl.prefetch == PF_) \
-        return launch_kernel(&sampled_reg_kernel<SUB_, PF_>, lds_bytes, a, grid, block, s);
-        LSH_REG_CASE(2, 1) LSH_REG_CASE(2, 2) LSH_REG_CASE(2, 4) LSH_REG_CASE(2, 8)
-        LSH_REG_CASE(1, 1) LSH_REG_CASE(1, 2) LSH_REG_CASE(1, 4) LSH_REG_CASE(1, 8)
+        return launch_kernel(&sampled_reg_kernel<SUB_, PF_, EP_>, lds_bytes, a, grid, block, s);
+#define LSH_REG_ALL(EP_) \
+    LSH_REG_CASE(2, 1, EP_) LSH_REG_CASE(2, 2, EP_) LSH_REG_CASE(2, 4, EP_) LSH_REG_CASE(2, 8, EP_) \
+    LSH_REG_CASE(1, 1, EP_) LSH_REG_CASE(1, 2, EP_) LSH_REG_CASE(1, 4, EP_) LSH_REG_CASE(1, 8, EP_)
+        LSH_EP_CASES(LSH_REG_ALL)
+#undef LSH_REG_ALL
 #undef LSH_REG_CASE
         return LSH_ERR_UNSUPPORTED;
     }
-    if (pl.chunked) return launch_kernel(&sampled_chunked_kernel<4>, lds_bytes, a, grid, block, s);
-    if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8>, lds_bytes, a, grid, block, s);
-    if (pl.rt == 4 && pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4>, lds_bytes, a, grid, block, s);
-    if (pl.rt == 4 && pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2>, lds_bytes, a, grid, block, s);
-    if (pl.rt == 4) return launch_kernel(&sampled_kernel<4, 1>, lds_bytes, a, grid, block, s);
-    if (pl.rt == 2) return launch_kernel(&sampled_kernel<2, 1>, lds_bytes, a, grid, block, s);
-    return launch_kernel(&sampled_kernel<1, 1>, lds_bytes, a, grid, block, s);
+#define LSH_GEN_ALL(EP_) \
+    if (pl.chunked) return launch_kernel(&sampled_chunked_kernel<4, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.rt == 4 && pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.rt == 4 && pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.rt == 4) return launch_kernel(&sampled_kernel<4, 1, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.rt == 2) return launch_kernel(&sampled_kernel<2, 1, EP_>, lds_bytes, a, grid, block, s); \
+    return launch_kernel(&sampled_kernel<1, 1, EP_>, lds_bytes, a, grid, block, s);
+    LSH_EP_CASES(LSH_GEN_ALL)
+#undef LSH_GEN_ALL
+#undef LSH_EP_CASES
+    return LSH_ERR_UNSUPPORTED;
 }
 
 }  // namespace lsh
