@@ -32,6 +32,7 @@ struct SampledPlan {
     bool reg_table = false;  // register-list kernel: (offset, coef) lists live in VGPRs
     bool chunked = false;    // chunked kernel: lists bucketed by coordinate range
     uint32_t chunk = 0, nchunks = 0;  // chunked kernel: coordinates per range, number of ranges
+    uint32_t fpt = 1;        // chunked kernel: functions per lane
     uint32_t prefetch = 0;   // register-list kernel: 64-coordinate chunks fetched per wave and tile
     bool supported = false;
 };

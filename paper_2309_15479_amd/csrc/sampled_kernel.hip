@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <type_traits>
 #include <unordered_map>
 
 #include "lsh_internal.h"
@@ -61,6 +62,14 @@ __device__ __forceinline__ void pin(float (&v)[4]) {
     asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
 }
 
+// Returns v through an empty asm: the compiler can no longer treat values derived from it as
+// loop invariants, so it recomputes cheap per-lane addresses where they are used instead of
+// keeping dozens of them (and spilling) across the gather loops.
+__device__ __forceinline__ uint32_t fresh(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 struct SampledArgs {
     const float *data;   // [N][n]
     uint64_t N;
@@ -92,6 +101,47 @@ __device__ __forceinline__ void quad_transpose(uint32_t (&x)[4]) {
     t0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)t0, kXor2, 0xf, 0xf, true);
     t1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)t1, kXor2, 0xf, 0xf, true);
     if (hi) { x[0] = t0; x[1] = t1; } else { x[2] = t0; x[3] = t1; }
+}
+
+// The LDS slot (one coordinate of four vectors) that lane `lane` of a wave contributes to a
+// 64-coordinate piece: coordinate c_first + lane of vectors row_first .. row_first + 3.
+// With n a multiple of 4 each lane loads 16 contiguous bytes instead of four separate
+// words (coordinates c_first + 4*(lane/4) .. + 3 of vector row_first + lane % 4: a quad of
+// lanes covers 4 vectors x 4 coordinates, a wave reads 256 contiguous bytes of each vector):
+// a quarter of the vector-memory instructions.  The registers then hold the transpose of
+// the slot; slot_from_raw() turns them into the slot just before it is written to LDS.
+// `limit` bounds the coordinates of the piece (exclusive); it is a multiple of 4 when vec4.
+template <bool vec4>
+__device__ __forceinline__ void load_raw(const float *__restrict__ tile_rows, uint32_t rows_valid, uint32_t n,
+                                         uint32_t row_first, uint32_t c_first, uint32_t limit, uint32_t lane,
+                                         float (&x)[4]) {
+    // tile_rows = first vector of the tile (wave-uniform pointer); rows and coordinates are
+    // 32-bit offsets from it.  Rows past the end of the data and coordinates past `limit`
+    // read element 0 of the tile instead (always valid memory): their values are never used.
+    if (vec4) {
+        const uint32_t row = row_first + (lane & 3);
+        const uint32_t c = c_first + (lane & ~3u);
+        const uint32_t off = (c < limit && row < rows_valid) ? row * n + c : 0u;
+        const float4 q = *reinterpret_cast<const float4 *>(tile_rows + off);
+        x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
+    } else {
+        const uint32_t c = c_first + lane;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t off = (c < limit && row_first + r < rows_valid) ? (row_first + r) * n + c : 0u;
+            x[r] = tile_rows[off];
+        }
+    }
+}
+
+template <bool vec4>
+__device__ __forceinline__ void slot_from_raw(float (&x)[4]) {
+    if (vec4) {
+        uint32_t v[4] = {__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+        quad_transpose(v);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = __uint_as_float(v[r]);
+    }
 }
 
 // Sum of a 64-bit value over each aligned group of g consecutive lanes (g a power of two
@@ -261,7 +311,7 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
     }
 }
 
-// Register-list kernel for m_pad == kChunk: a lane's whole list stays in VGPRs while the
+// Register-list kernel for m_pad == MCH * kChunk (MCH = 1 or 2): a lane's whole list stays in VGPRs while the
 // workgroup walks its tiles.  The LDS tile is double buffered: the next tile's vectors are
 // fetched from HBM into registers before the current tile is processed and written to the
 // other buffer afterwards, so one barrier per tile suffices and HBM latency hides behind the
@@ -269,8 +319,8 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
 // with the FMAs of sample i); scheduling barriers keep the compiler from hoisting every LDS
 // read of the tile to the front, which would need more registers than a lane has.
 // PF = 64-coordinate chunks each wave fetches per tile (see launch_sampled).
-template <int SUB, int PF, int EP>
-__global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a) {
+template <int SUB, int PF, int MCH, int EP>
+__global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(const SampledArgs a) {
     constexpr int RT = 4;
     extern __shared__ __align__(16) float tile[];  // 2 x [n + classes][SP][RT]
     constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
@@ -280,9 +330,10 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
     const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
     const uint32_t buf_floats = (n + a.classes) * SP * RT;
 
-    Sample s[kChunk];
+    constexpr int kList = kChunk * MCH;  // list entries kept in registers
+    Sample s[kList];
 #pragma unroll
-    for (int i = 0; i < kChunk; ++i) s[i] = a.tab[(size_t)i * a.kpad + j];
+    for (int i = 0; i < kList; ++i) s[i] = a.tab[(size_t)i * a.kpad + j];
     const float b = a.off[j];
 
     for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x) {
@@ -300,27 +351,37 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t nwaves = blockDim.x >> 6;
     const uint32_t nchunks = SUB * ((n + 63) / 64);
+    const bool vec4 = (n & 3) == 0;
 
     float pre[PF][RT];
-    auto fetch = [&](uint64_t row0) {
+    auto fetch_as = [&](uint64_t row0, auto vec) {
+        constexpr bool V = decltype(vec)::value;
+        const float *rows = a.data + row0 * n;
+        const uint32_t rows_valid = (uint32_t)min((uint64_t)kTileRows, a.N - row0);
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
             const uint32_t q = wave + f * nwaves;
-            const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                const uint64_t row = row0 + (uint64_t)st * RT + r;
-                pre[f][r] = (q < nchunks && c < n && row < a.N) ? a.data[row * n + c] : 0.f;
-            }
+            load_raw<V>(rows, rows_valid, n, (q % SUB) * RT, (q / SUB) * 64, q < nchunks ? n : 0, lane, pre[f]);
         }
     };
-    auto stash = [&](float *buf) {
+    auto stash_as = [&](float *buf, auto vec) {
+        constexpr bool V = decltype(vec)::value;
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
             const uint32_t q = wave + f * nwaves;
             const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
+            slot_from_raw<V>(pre[f]);
             if (q < nchunks && c < n) lds_write_slot<RT>(buf + ((size_t)c * SP + st) * RT, pre[f]);
         }
+    };
+    // the vectorised and the word-by-word variants are separate straight-line code
+    auto fetch = [&](uint64_t row0) {
+        if (vec4) fetch_as(row0, std::true_type{});
+        else fetch_as(row0, std::false_type{});
+    };
+    auto stash = [&](float *buf) {
+        if (vec4) stash_as(buf, std::true_type{});
+        else stash_as(buf, std::false_type{});
     };
 
     uint64_t t = blockIdx.x;
@@ -347,7 +408,7 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
         for (int st = 0; st < SUB; ++st)
             xa[st] = *reinterpret_cast<const float4 *>(base + s[0].lds_byte_offset + st * 16);
 #pragma unroll
-        for (int i = 0; i < kChunk; i += 2) {
+        for (int i = 0; i < kList; i += 2) {
             // region: reads of sample i+1 may interleave with the FMAs of sample i, nothing else
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -362,7 +423,7 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
                 pin(acc[st]);
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (i + 2 < kChunk) {
+            if (i + 2 < kList) {
 #pragma unroll
                 for (int st = 0; st < SUB; ++st)
                     xa[st] = *reinterpret_cast<const float4 *>(base + s[i + 2].lds_byte_offset + st * 16);
@@ -386,90 +447,137 @@ __global__ __launch_bounds__(512, 4) void sampled_reg_kernel(const SampledArgs a
 }
 
 // Chunked kernel for large n (or long lists at large n): the tile holds 4*SUB vectors times a
-// range of `chunk` coordinates, so that enough vectors share one pass over the lists to keep
+// range of `chunk` coordinates (one workgroup per CU with nearly all of its LDS), so that enough vectors share one pass over the lists to keep
 // list traffic (L2 -> registers) well below the LDS gather traffic.  Every function's samples
 // are bucketed by coordinate range on the host; the 64 lists of a wave for one range are
 // padded to a common length (wave-uniform trip count) and bank-scheduled like the flat lists.
 // Accumulators persist across the ranges of a tile.
-template <int SUB, int EP>
-__global__ __launch_bounds__(512, 4) void sampled_chunked_kernel(const SampledArgs a) {
+template <int SUB, int FPT, int EP>
+__global__ __launch_bounds__(1024) void sampled_chunked_kernel(const SampledArgs a) {
     constexpr int RT = 4;
-    constexpr int kStep = 8;  // list entries fetched at a time; list lengths are multiples of it
+    constexpr int kStep = 8;   // list entries fetched at a time; list lengths are multiples of it
+    constexpr int kPre = 8;    // 64-coordinate pieces of the next chunk a wave holds in registers
     extern __shared__ __align__(16) float tile[];  // [chunk + classes][SP][RT]
     constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
     constexpr uint32_t kTileRows = RT * SUB;
     const uint32_t n = a.n;
-    const uint32_t j = blockIdx.y * blockDim.x + threadIdx.x;  // < kpad
+    // a lane owns FPT functions, blockDim.x apart: j0 + f * blockDim.x
+    const uint32_t j0 = blockIdx.y * blockDim.x * FPT + threadIdx.x;
     const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
-    const float b = a.off[j];
+    float b[FPT];
+    uint64_t key_pow[FPT];
+#pragma unroll
+    for (int f = 0; f < FPT; ++f) {
+        const uint32_t j = j0 + f * blockDim.x;  // < kpad
+        b[f] = a.off[j];
+        key_pow[f] = 1;
+        if (EP == (int)Epilogue::Keys) {
+            const uint32_t t = j % a.g;
+            for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow[f] *= kKeyMultiplier;
+        }
+    }
 
     for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x)
         tile[(size_t)a.chunk * SP * RT + e] = 0.f;
 
-    uint64_t key_pow = 1;
-    if (EP == (int)Epilogue::Keys) {
-        const uint32_t t = j % a.g;
-        for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
-    }
-
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t nwaves = blockDim.x >> 6;
-    const uint32_t wave_global = __builtin_amdgcn_readfirstlane(j >> 6);
-    const uint32_t pieces = SUB * ((a.chunk + 63) / 64);  // 64-coordinate pieces of one chunk
+    const uint32_t wave_global = __builtin_amdgcn_readfirstlane(j0 >> 6);
+    const uint32_t pieces = SUB * ((a.chunk + 63) / 64);  // 64-coordinate pieces of one chunk (<= kPre * nwaves)
+    const bool vec4 = (n & 3) == 0;
     const char *base = reinterpret_cast<const char *>(tile);
 
-    for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    // The next chunk (of this tile, or the first of the next tile) travels HBM -> registers
+    // while the current one is gathered from LDS, and is written to LDS between two barriers.
+    float pre[kPre][RT];
+    auto fetch_as = [&](uint64_t row0, uint32_t q, auto vec) {
+        constexpr bool V = decltype(vec)::value;
+        const uint32_t c0 = q * a.chunk;
+        const float *rows = a.data + row0 * n;
+        const uint32_t rows_valid = (uint32_t)min((uint64_t)kTileRows, a.N - row0);
+        const uint32_t end = c0 + a.chunk < n ? c0 + a.chunk : n;  // chunk % 16 == 0
+        const uint32_t ln = fresh(lane);
+#pragma unroll
+        for (int f = 0; f < kPre; ++f) {
+            const uint32_t pc = wave + f * nwaves;
+            load_raw<V>(rows, rows_valid, n, (pc % SUB) * RT, c0 + (pc / SUB) * 64, pc < pieces ? end : 0, ln,
+                        pre[f]);
+        }
+    };
+    auto stash_as = [&](auto vec) {
+        constexpr bool V = decltype(vec)::value;
+        const uint32_t ln = fresh(lane);
+#pragma unroll
+        for (int f = 0; f < kPre; ++f) {
+            const uint32_t pc = wave + f * nwaves;
+            const uint32_t st = pc % SUB, cc = (pc / SUB) * 64 + ln;
+            slot_from_raw<V>(pre[f]);
+            if (pc < pieces && cc < a.chunk) lds_write_slot<RT>(tile + ((size_t)cc * SP + st) * RT, pre[f]);
+        }
+    };
+    auto fetch = [&](uint64_t row0, uint32_t q) {
+        if (vec4) fetch_as(row0, q, std::true_type{});
+        else fetch_as(row0, q, std::false_type{});
+    };
+    auto stash = [&]() {
+        if (vec4) stash_as(std::true_type{});
+        else stash_as(std::false_type{});
+    };
+
+    uint64_t t = blockIdx.x;
+    if (t >= ntiles) return;
+    fetch(t * kTileRows, 0);
+    stash();
+    __syncthreads();
+    for (; t < ntiles; t += gridDim.x) {
         const uint64_t row0 = t * kTileRows;
-        float acc[SUB][RT];
+        float acc[FPT][SUB][RT];
 #pragma unroll
-        for (int st = 0; st < SUB; ++st)
+        for (int f = 0; f < FPT; ++f)
 #pragma unroll
-            for (int r = 0; r < RT; ++r) acc[st][r] = 0.f;
+            for (int st = 0; st < SUB; ++st)
+#pragma unroll
+                for (int r = 0; r < RT; ++r) acc[f][st][r] = 0.f;
 
         for (uint32_t q = 0; q < a.nchunks; ++q) {
-            const uint32_t c0 = q * a.chunk;
-            __syncthreads();  // every lane is done reading the previous chunk
-            for (uint32_t pc = wave; pc < pieces; pc += nwaves) {
-                const uint32_t st = pc % SUB, cc = (pc / SUB) * 64 + lane;
-                if (cc < a.chunk && c0 + cc < n) {
-                    float x[RT];
-#pragma unroll
-                    for (int r = 0; r < RT; ++r) {
-                        const uint64_t row = row0 + (uint64_t)st * RT + r;
-                        x[r] = row < a.N ? a.data[row * n + c0 + cc] : 0.f;
-                    }
-                    lds_write_slot<RT>(tile + ((size_t)cc * SP + st) * RT, x);
-                }
-            }
-            __syncthreads();
+            const bool last = q + 1 == a.nchunks;
+            const uint64_t t_next = t + gridDim.x;
+            const bool more = !last || t_next < ntiles;
+            if (more) fetch((last ? t_next : t) * kTileRows, last ? 0 : q + 1);
 
-            const uint2 info = a.chunk_info[(size_t)wave_global * a.nchunks + q];
-            const Sample *list = a.tab + info.x + lane;
-            for (uint32_t s0 = 0; s0 < info.y; s0 += kStep) {
-                Sample e[kStep];
 #pragma unroll
-                for (int i = 0; i < kStep; ++i) e[i] = list[(size_t)(s0 + i) * 64];
+            for (int f = 0; f < FPT; ++f) {
+                const uint2 info = a.chunk_info[(size_t)(wave_global + f * nwaves) * a.nchunks + q];
+                const Sample *list = a.tab + info.x + lane;
+                for (uint32_t s0 = 0; s0 < info.y; s0 += kStep) {
+                    Sample e[kStep];
 #pragma unroll
-                for (int i = 0; i < kStep; ++i) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    float4 x[SUB];
+                    for (int i = 0; i < kStep; ++i) e[i] = list[(size_t)(s0 + i) * 64];
 #pragma unroll
-                    for (int st = 0; st < SUB; ++st)
-                        x[st] = *reinterpret_cast<const float4 *>(base + e[i].lds_byte_offset + st * 16);
+                    for (int i = 0; i < kStep; ++i) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        float4 x[SUB];
 #pragma unroll
-                    for (int st = 0; st < SUB; ++st) {
-                        acc[st][0] = fmaf(e[i].coef, x[st].x, acc[st][0]);
-                        acc[st][1] = fmaf(e[i].coef, x[st].y, acc[st][1]);
-                        acc[st][2] = fmaf(e[i].coef, x[st].z, acc[st][2]);
-                        acc[st][3] = fmaf(e[i].coef, x[st].w, acc[st][3]);
-                        pin(acc[st]);
+                        for (int st = 0; st < SUB; ++st)
+                            x[st] = *reinterpret_cast<const float4 *>(base + e[i].lds_byte_offset + st * 16);
+#pragma unroll
+                        for (int st = 0; st < SUB; ++st) {
+                            acc[f][st][0] = fmaf(e[i].coef, x[st].x, acc[f][st][0]);
+                            acc[f][st][1] = fmaf(e[i].coef, x[st].y, acc[f][st][1]);
+                            acc[f][st][2] = fmaf(e[i].coef, x[st].z, acc[f][st][2]);
+                            acc[f][st][3] = fmaf(e[i].coef, x[st].w, acc[f][st][3]);
+                            pin(acc[f][st]);
+                        }
                     }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
+                if (last) finish<RT, SUB, EP>(a, row0, fresh(j0) + f * blockDim.x, acc[f], b[f], key_pow[f]);
             }
+            __syncthreads();  // every lane is done reading this chunk
+            if (more) stash();
+            __syncthreads();
         }
-        finish<RT, SUB, EP>(a, row0, j, acc, b, key_pow);
     }
 }
 
@@ -520,39 +628,50 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
     const uint32_t k64 = (k + 63) / 64 * 64;
     // Register-list kernel: lists of one chunk, 16-byte slots, two tile buffers in LDS.  Small
     // tiles (8 or 4 vectors) measured fastest: several workgroups share a CU and one's
-    // epilogue overlaps the others' gathers.  At most 8 prefetch chunks per wave.
+    // epilogue overlaps the others' gathers.  Only while a tile is small (at most 2 prefetch
+    // pieces per wave): with large n one tile's gather is shorter than the latency of the next
+    // tile's loads, and the chunked kernel, which shares a bigger tile among more functions, wins.
     pl.reg_table = false;
-    if (pl.m_pad == (uint32_t)kChunk && pl.rt == 4) {
+    if (pl.m_pad <= 2u * kChunk && pl.rt == 4) {
         const uint32_t block = k64 >= 512 ? 512 : k64;
         for (uint32_t sub : {2u, 1u}) {
             const uint64_t sp = sub == 1 ? 1 : sub + 1;
             const uint64_t bytes = (uint64_t)(n + 16) * sp * 16;
             const uint32_t chunks = sub * ((n + 63) / 64);
             const uint32_t pf = (chunks + block / 64 - 1) / (block / 64);
-            if (2 * bytes > kLdsBudget || pf > 8) continue;
+            if (2 * bytes > kLdsBudget || pf > 2) continue;
             fits(4, sub, 16);
             pl.reg_table = true;
-            pl.prefetch = pf <= 1 ? 1 : (pf <= 2 ? 2 : (pf <= 4 ? 4 : 8));
+            pl.prefetch = pf <= 1 ? 1 : 2;
             break;
         }
     }
     // Chunked kernel: when a full-dimension tile would hold fewer than 16 vectors and the lists
     // do not stay in registers.  16 vectors x `chunk` coordinates, two workgroups per CU.
     pl.chunked = false;
-    if (!pl.reg_table && (pl.rt != 4 || pl.sub < 4)) {
-        const uint32_t slot = 5 * 16;                                // SUB = 4: 5 slots of 16 bytes
-        const uint32_t cmax = (kLdsBudget / 2 / slot - 16) / 16 * 16;
+    if (!pl.reg_table && (pl.rt != 4 || pl.sub < 4) && k64 >= 512) {  // enough waves to prefetch a chunk
+        const uint32_t slot = 5 * 16;  // SUB = 4: 5 slots of 16 bytes per coordinate
+        const uint32_t block = k64 >= 1024 ? 1024 : k64;
+        // the chunk must fit in LDS and its pieces in the waves' prefetch registers (8 pieces
+        // of 64 coordinates x 4 sub-tiles per wave)
+        uint32_t cmax = (kLdsBudget / slot - 16) / 16 * 16;
+        const uint32_t by_regs = 8 * (block / 64) / 4 * 64;
+        if (cmax > by_regs) cmax = by_regs;
         pl.nchunks = (n + cmax - 1) / cmax;
         pl.chunk = ((n + pl.nchunks - 1) / pl.nchunks + 15) / 16 * 16;
         pl.nchunks = (n + pl.chunk - 1) / pl.chunk;
         pl.rt = 4; pl.sub = 4; pl.sp = 5; pl.classes = 16; pl.group = 16;
         pl.lds_bytes = (pl.chunk + 16) * slot;
         pl.chunked = true;
+        // with more than 1024 functions a lane takes two (1024 apart), so that a chunk is
+        // loaded once for 2048 functions
+        pl.fpt = k64 > 1024 ? 2 : 1;
     }
-    const uint32_t max_block = (pl.reg_table || pl.chunked) ? 512 : 1024;
+    const uint32_t max_block = pl.reg_table ? 512 : 1024;
     pl.block = k64 >= max_block ? max_block : k64;
-    pl.kblocks = (k64 + pl.block - 1) / pl.block;
-    pl.kpad = pl.block * pl.kblocks;
+    const uint32_t per_wg = pl.block * (pl.chunked ? pl.fpt : 1);
+    pl.kblocks = (k64 + per_wg - 1) / per_wg;
+    pl.kpad = per_wg * pl.kblocks;
     pl.supported = true;
     return pl;
 }
@@ -588,8 +707,10 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     // a multiple of 8 so that the kblocks workgroups sharing a vector tile land on one XCD
     const uint32_t lds_bytes = pl.reg_table ? 2 * pl.lds_bytes : pl.lds_bytes;
     uint32_t per_cu = kLdsBudget / lds_bytes;
-    // register-list kernel: 4 waves per SIMD (up to 128 VGPRs per lane), else 8
-    const uint32_t by_lanes = ((pl.reg_table || pl.chunked) ? 1024 : 2048) / pl.block;
+    // register-list kernel: 4 waves per SIMD (128 VGPRs per lane; 2 and 256 with two list
+    // chunks), else 8
+    const uint32_t by_lanes =
+        (pl.reg_table ? (pl.m_pad == (uint32_t)kChunk ? 1024 : 512) : 2048) / pl.block;
     if (per_cu > by_lanes) per_cu = by_lanes;
     if (per_cu < 1) per_cu = 1;
     uint64_t gx = (uint64_t)p->num_cus * per_cu / pl.kblocks;
@@ -609,17 +730,19 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     if (pl.reg_table) {
 #define LSH_REG_CASE(SUB_, PF_, EP_) \
     if (pl.sub == SUB_ && pl.prefetch == PF_) \
-        return launch_kernel(&sampled_reg_kernel<SUB_, PF_, EP_>, lds_bytes, a, grid, block, s);
+        return pl.m_pad == (uint32_t)kChunk \
+                   ? launch_kernel(&sampled_reg_kernel<SUB_, PF_, 1, EP_>, lds_bytes, a, grid, block, s) \
+                   : launch_kernel(&sampled_reg_kernel<SUB_, PF_, 2, EP_>, lds_bytes, a, grid, block, s);
 #define LSH_REG_ALL(EP_) \
-    LSH_REG_CASE(2, 1, EP_) LSH_REG_CASE(2, 2, EP_) LSH_REG_CASE(2, 4, EP_) LSH_REG_CASE(2, 8, EP_) \
-    LSH_REG_CASE(1, 1, EP_) LSH_REG_CASE(1, 2, EP_) LSH_REG_CASE(1, 4, EP_) LSH_REG_CASE(1, 8, EP_)
+    LSH_REG_CASE(2, 1, EP_) LSH_REG_CASE(2, 2, EP_) LSH_REG_CASE(1, 1, EP_) LSH_REG_CASE(1, 2, EP_)
         LSH_EP_CASES(LSH_REG_ALL)
 #undef LSH_REG_ALL
 #undef LSH_REG_CASE
         return LSH_ERR_UNSUPPORTED;
     }
 #define LSH_GEN_ALL(EP_) \
-    if (pl.chunked) return launch_kernel(&sampled_chunked_kernel<4, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.chunked && pl.fpt == 2) return launch_kernel(&sampled_chunked_kernel<4, 2, EP_>, lds_bytes, a, grid, block, s); \
+    if (pl.chunked) return launch_kernel(&sampled_chunked_kernel<4, 1, EP_>, lds_bytes, a, grid, block, s); \
     if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8, EP_>, lds_bytes, a, grid, block, s); \
     if (pl.rt == 4 && pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4, EP_>, lds_bytes, a, grid, block, s); \
     if (pl.rt == 4 && pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2, EP_>, lds_bytes, a, grid, block, s); \

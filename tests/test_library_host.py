@@ -88,7 +88,7 @@ def _pass_groups(k, group):
 
 
 @pytest.mark.parametrize("n,k,m,repl", [(128, 512, 32, False), (100, 70, 30, True), (960, 200, 128, False),
-                                        (4096, 520, 30, False)])
+                                        (1024, 520, 30, False)])
 def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
     """The kernel may visit a function's samples in any order (a projection is a sum); the
     schedule must hold every canonical sample exactly once plus padding, and its modelled
@@ -124,7 +124,7 @@ def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
             assert passes / (len(groups) * steps) < 0.75 * naive / (len(groups) * m)
 
 
-@pytest.mark.parametrize("n,k,m,repl", [(16384, 96, 40, False), (30000, 64, 33, True), (4096, 200, 256, False)])
+@pytest.mark.parametrize("n,k,m,repl", [(16384, 520, 40, False), (30000, 512, 33, True), (4096, 600, 256, False)])
 def test_chunked_gather_schedule_is_a_padded_permutation(n, k, m, repl):
     """Large n: the lists are cut by coordinate range and padded per range and per 64
     functions.  Every canonical sample must still appear exactly once, ranges in ascending

@@ -105,6 +105,8 @@ RAGGED = [
     (29, 4096, 192, 64, 8.0, 27, False, 0),      # 8-vector tiles
     (13, 8000, 64, 100, 3.0, 28, True, 0),       # 4-vector tiles
     (9, 16384, 128, 512, 1.0, 29, False, 0),     # 2-vector tiles
+    (40, 16384, 640, 96, 1.0, 33, False, 0),     # coordinate-range chunks, ragged functions
+    (21, 5000, 1100, 40, 2.0, 34, True, 0),      # chunks, two workgroups along the functions
     (5, 30000, 64, 40, 1.0, 30, False, 0),       # 1-vector tiles
     (3, 40384, 64, 33, 1.0, 32, True, 0),        # the largest dimension one LDS tile holds
     (300, 64, 2100, 16, 2.0, 31, False, 0),      # more functions than one workgroup holds
