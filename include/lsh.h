@@ -94,7 +94,11 @@ int lsh_params_get_shape(const lsh_params_t *params, uint32_t *n, uint32_t *k, u
  * functions the passes are: group == 32: functions 0-31 and 32-63; group == 16: the runs of
  * four functions numbered {0,3,5,6}, {1,2,4,7}, {8,11,13,14}, {9,10,12,15} (run q = functions
  * 4q..4q+3), as measured for 16-byte LDS reads on gfx950.
- *   order [k*steps]  entry (j, i) = position in function j's canonical list (0..m-1), or
+ *   order [k*steps]  entry (j, i) = position in function j's canonical list (0..m-1), plus
+ *                    0x40000000 when the sample is read from the second copy of the tile
+ *                    (small n: the tile is kept twice in LDS, the second time with
+ *                    coordinate c in class (c + c / classes) % classes, and every sample is
+ *                    read from the copy that evens out the classes' loads), or
  *                    0x80000000 | class for a padding sample (coefficient 0), or 0xFFFFFFFF
  *                    (unused tail: for large n the lists are cut by coordinate range and
  *                    padded per range and per 64 functions, so rows differ in length; steps

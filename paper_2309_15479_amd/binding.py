@@ -97,7 +97,11 @@ class LshParams:
             load_library().lsh_params_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: module globals may already be gone
+            pass
 
     def __enter__(self):
         return self

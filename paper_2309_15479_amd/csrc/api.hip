@@ -115,8 +115,13 @@ int upload_tables(lsh_params *p) {
                             if (z % pl.classes == want) s.lds_byte_offset = z * slot_bytes;
                         s.coef = 0.f;
                     } else {
-                        s.lds_byte_offset = p->idx[(size_t)j * p->m + e] * slot_bytes;
-                        s.coef = p->coef[(size_t)j * p->m + e];
+                        const uint32_t pos = e & ~kCopyB;
+                        const uint32_t c = p->idx[(size_t)j * p->m + pos];
+                        // second copy: after the first copy and its zero slots
+                        s.lds_byte_offset = (e & kCopyB)
+                                                ? (p->n + pl.classes + copy_b_slot(c, pl.classes)) * slot_bytes
+                                                : c * slot_bytes;
+                        s.coef = p->coef[(size_t)j * p->m + pos];
                     }
                 }
             if (hipMalloc(&p->d_samples, tab.size() * sizeof(Sample)) != hipSuccess) rc = LSH_ERR_ALLOC;
@@ -182,7 +187,8 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
                 p->schedule_cost =
                     pl.chunked ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 8, pl.group, pl.classes,
                                                   p->chunk_steps, p->order)
-                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, p->order);
+                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, pl.copies,
+                                                  p->order);
             } catch (const std::bad_alloc &) {
                 rc = LSH_ERR_ALLOC;
             }

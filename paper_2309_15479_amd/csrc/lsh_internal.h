@@ -28,7 +28,8 @@ struct SampledPlan {
     uint32_t block = 0;      // threads per workgroup = functions per workgroup
     uint32_t kblocks = 0;    // workgroups along the function axis
     uint32_t kpad = 0;       // block * kblocks >= k
-    uint32_t lds_bytes = 0;  // dynamic LDS per workgroup
+    uint32_t lds_bytes = 0;  // LDS bytes of one tile buffer (both copies when copies == 2)
+    uint32_t copies = 1;     // 2: the tile is kept twice, the second copy with rotated bank classes
     bool reg_table = false;  // register-list kernel: (offset, coef) lists live in VGPRs
     bool chunked = false;    // chunked kernel: lists bucketed by coordinate range
     uint32_t chunk = 0, nchunks = 0;  // chunked kernel: coordinates per range, number of ranges
@@ -38,6 +39,14 @@ struct SampledPlan {
 };
 
 constexpr uint32_t kPadSample = 0x80000000u;  // schedule entry: padding sample | bank class
+constexpr uint32_t kCopyB = 0x40000000u;      // schedule entry: read the sample from the second tile copy
+
+// Slot of coordinate c in the second tile copy: inside every run of `classes` coordinates the
+// slots are rotated by the run's number, so coordinates that share a bank class in the first
+// copy (equal c % classes) fall into different classes in the second.
+inline uint32_t copy_b_slot(uint32_t c, uint32_t classes) {
+    return c / classes * classes + (c + c / classes) % classes;
+}
 
 }  // namespace lsh
 
@@ -71,7 +80,7 @@ int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, 
 
 // host: bank-conflict-free visiting order of every function's samples (schedule.cpp)
 uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,
-                          uint32_t group, uint32_t classes, std::vector<uint32_t> &order_out);
+                          uint32_t group, uint32_t classes, uint32_t copies, std::vector<uint32_t> &order_out);
 
 uint64_t schedule_chunked(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t chunk,
                           uint32_t nchunks, uint32_t step_quantum, uint32_t group, uint32_t classes,

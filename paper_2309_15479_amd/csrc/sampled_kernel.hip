@@ -81,6 +81,9 @@ struct SampledArgs {
     int epilogue;        // Epilogue
     void *out;
     uint32_t L, g;       // key groups (Epilogue::Keys)
+    // register-list kernel only: floats per tile buffer; float offset of the second,
+    // class-rotated tile copy inside a buffer (0: single copy)
+    uint32_t buf_floats, copy_b_floats;
     // chunked kernel only
     uint32_t chunk, nchunks;     // coordinates per LDS chunk, number of chunks
     const uint2 *chunk_info;     // [waves][nchunks] {first table entry, steps}
@@ -328,12 +331,21 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
     const uint32_t n = a.n;
     const uint32_t j = blockIdx.y * blockDim.x + threadIdx.x;  // < kpad
     const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
-    const uint32_t buf_floats = (n + a.classes) * SP * RT;
+    const uint32_t buf_floats = a.buf_floats;
 
-    constexpr int kList = kChunk * MCH;  // list entries kept in registers
-    Sample s[kList];
+    // list entries kept in registers: coefficients, and LDS byte offsets (below 64 KB for
+    // the tiles this kernel takes) two to a register
+    constexpr int kList = kChunk * MCH;
+    constexpr int kDepth = 2;  // samples whose LDS reads are in flight or being consumed
+    uint32_t po[kList / 2];
+    float cf[kList];
 #pragma unroll
-    for (int i = 0; i < kList; ++i) s[i] = a.tab[(size_t)i * a.kpad + j];
+    for (int i = 0; i < kList; i += 2) {
+        const Sample s0 = a.tab[(size_t)i * a.kpad + j], s1 = a.tab[(size_t)(i + 1) * a.kpad + j];
+        po[i / 2] = s0.lds_byte_offset | (s1.lds_byte_offset << 16);
+        cf[i] = s0.coef;
+        cf[i + 1] = s1.coef;
+    }
     const float b = a.off[j];
 
     for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x) {
@@ -358,20 +370,27 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
         constexpr bool V = decltype(vec)::value;
         const float *rows = a.data + row0 * n;
         const uint32_t rows_valid = (uint32_t)min((uint64_t)kTileRows, a.N - row0);
+        const uint32_t ln = fresh(lane);
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
             const uint32_t q = wave + f * nwaves;
-            load_raw<V>(rows, rows_valid, n, (q % SUB) * RT, (q / SUB) * 64, q < nchunks ? n : 0, lane, pre[f]);
+            load_raw<V>(rows, rows_valid, n, (q % SUB) * RT, (q / SUB) * 64, q < nchunks ? n : 0, ln, pre[f]);
         }
     };
     auto stash_as = [&](float *buf, auto vec) {
         constexpr bool V = decltype(vec)::value;
+        const uint32_t ln = fresh(lane);
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
             const uint32_t q = wave + f * nwaves;
-            const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
+            const uint32_t st = q % SUB, c = (q / SUB) * 64 + ln;
             slot_from_raw<V>(pre[f]);
-            if (q < nchunks && c < n) lds_write_slot<RT>(buf + ((size_t)c * SP + st) * RT, pre[f]);
+            if (q < nchunks && c < n) {
+                lds_write_slot<RT>(buf + ((size_t)c * SP + st) * RT, pre[f]);
+                if (a.copy_b_floats)  // second copy: slots rotated inside every run of 16 coordinates
+                    lds_write_slot<RT>(buf + a.copy_b_floats + ((size_t)((c & ~15u) | ((c + (c >> 4)) & 15u)) * SP + st) * RT,
+                                       pre[f]);
+            }
         }
     };
     // the vectorised and the word-by-word variants are separate straight-line code
@@ -403,42 +422,36 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
 #pragma unroll
             for (int r = 0; r < RT; ++r) acc[st][r] = 0.f;
 
-        float4 xa[SUB], xb[SUB];
+        // the packed offsets pass through an empty asm every tile, or the compiler would unpack
+        // them once, outside the tile loop, into twice the registers
 #pragma unroll
-        for (int st = 0; st < SUB; ++st)
-            xa[st] = *reinterpret_cast<const float4 *>(base + s[0].lds_byte_offset + st * 16);
+        for (int h = 0; h < kList / 2; ++h) asm volatile("" : "+v"(po[h]));
+        auto read_sample = [&](int i, float4 (&x)[SUB]) {
+            const uint32_t off = (i & 1) ? po[i / 2] >> 16 : po[i / 2] & 0xffffu;
 #pragma unroll
-        for (int i = 0; i < kList; i += 2) {
-            // region: reads of sample i+1 may interleave with the FMAs of sample i, nothing else
+            for (int st = 0; st < SUB; ++st) x[st] = *reinterpret_cast<const float4 *>(base + off + st * 16);
+        };
+        float4 x[kDepth][SUB];
+#pragma unroll
+        for (int i = 0; i < kDepth - 1; ++i) read_sample(i, x[i]);
+#pragma unroll
+        for (int i = 0; i < kList; ++i) {
+            // region: the reads of sample i + kDepth - 1 may interleave with the FMAs of sample i,
+            // nothing else
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int st = 0; st < SUB; ++st)
-                xb[st] = *reinterpret_cast<const float4 *>(base + s[i + 1].lds_byte_offset + st * 16);
+            if (i + kDepth - 1 < kList) read_sample(i + kDepth - 1, x[(i + kDepth - 1) % kDepth]);
 #pragma unroll
             for (int st = 0; st < SUB; ++st) {
-                acc[st][0] = fmaf(s[i].coef, xa[st].x, acc[st][0]);
-                acc[st][1] = fmaf(s[i].coef, xa[st].y, acc[st][1]);
-                acc[st][2] = fmaf(s[i].coef, xa[st].z, acc[st][2]);
-                acc[st][3] = fmaf(s[i].coef, xa[st].w, acc[st][3]);
-                pin(acc[st]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (i + 2 < kList) {
-#pragma unroll
-                for (int st = 0; st < SUB; ++st)
-                    xa[st] = *reinterpret_cast<const float4 *>(base + s[i + 2].lds_byte_offset + st * 16);
-            }
-#pragma unroll
-            for (int st = 0; st < SUB; ++st) {
-                acc[st][0] = fmaf(s[i + 1].coef, xb[st].x, acc[st][0]);
-                acc[st][1] = fmaf(s[i + 1].coef, xb[st].y, acc[st][1]);
-                acc[st][2] = fmaf(s[i + 1].coef, xb[st].z, acc[st][2]);
-                acc[st][3] = fmaf(s[i + 1].coef, xb[st].w, acc[st][3]);
+                const float4 &v = x[i % kDepth][st];
+                acc[st][0] = fmaf(cf[i], v.x, acc[st][0]);
+                acc[st][1] = fmaf(cf[i], v.y, acc[st][1]);
+                acc[st][2] = fmaf(cf[i], v.z, acc[st][2]);
+                acc[st][3] = fmaf(cf[i], v.w, acc[st][3]);
                 pin(acc[st]);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        finish<RT, SUB, EP>(a, row0, j, acc, b, key_pow);
+        finish<RT, SUB, EP>(a, row0, fresh(j), acc, b, key_pow);
 
         if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
         __syncthreads();  // next buffer complete; everyone is done with the current one
@@ -626,15 +639,17 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
         return pl;  // unsupported: one vector does not fit in LDS
     pl.m_pad = (m + kChunk - 1) / kChunk * kChunk;
     const uint32_t k64 = (k + 63) / 64 * 64;
-    // Register-list kernel: lists of one chunk, 16-byte slots, two tile buffers in LDS.  Small
-    // tiles (8 or 4 vectors) measured fastest: several workgroups share a CU and one's
-    // epilogue overlaps the others' gathers.  Only while a tile is small (at most 2 prefetch
+    // Register-list kernel: lists of at most two chunks, 16-byte slots, two tile buffers in LDS.
+    // The kernel is bound by vector-ALU issue (a 64-lane FMA takes a SIMD four cycles), so the
+    // tile is the largest whose accumulators and in-flight reads still fit the 128 registers of
+    // a lane (16 vectors): the per-sample address arithmetic and the per-tile load and barrier
+    // code are then shared by the most FMAs.  Only while a tile stays small (at most 2 prefetch
     // pieces per wave): with large n one tile's gather is shorter than the latency of the next
     // tile's loads, and the chunked kernel, which shares a bigger tile among more functions, wins.
     pl.reg_table = false;
     if (pl.m_pad <= 2u * kChunk && pl.rt == 4) {
         const uint32_t block = k64 >= 512 ? 512 : k64;
-        for (uint32_t sub : {2u, 1u}) {
+        for (uint32_t sub : {4u, 2u, 1u}) {
             const uint64_t sp = sub == 1 ? 1 : sub + 1;
             const uint64_t bytes = (uint64_t)(n + 16) * sp * 16;
             const uint32_t chunks = sub * ((n + 63) / 64);
@@ -643,6 +658,15 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
             fits(4, sub, 16);
             pl.reg_table = true;
             pl.prefetch = pf <= 1 ? 1 : 2;
+            // a second, class-rotated copy of the tile (see schedule.cpp) where it costs no
+            // occupancy and LDS offsets still fit the kernel's 16 bits
+            const uint64_t bytes2 = bytes + (uint64_t)((n + 15) / 16 * 16) * sp * 16;
+            const uint32_t lanes = pl.m_pad == kChunk ? 1024 : 512;
+            const uint32_t wgs = lanes / block < 2 ? lanes / block : 2;
+            if (bytes2 <= 65536 && 2 * bytes2 * wgs <= kLdsBudget) {
+                pl.copies = 2;
+                pl.lds_bytes = (uint32_t)bytes2;
+            }
             break;
         }
     }
@@ -698,6 +722,8 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     a.out = d_out;
     a.L = L;
     a.g = L ? p->k / L : 1;
+    a.buf_floats = pl.lds_bytes / 4;
+    a.copy_b_floats = pl.copies == 2 ? (p->n + pl.classes) * pl.sp * pl.rt : 0;
     a.chunk = pl.chunk;
     a.nchunks = pl.nchunks;
     a.chunk_info = static_cast<const uint2 *>(p->d_chunk_info);
@@ -734,7 +760,8 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
                    ? launch_kernel(&sampled_reg_kernel<SUB_, PF_, 1, EP_>, lds_bytes, a, grid, block, s) \
                    : launch_kernel(&sampled_reg_kernel<SUB_, PF_, 2, EP_>, lds_bytes, a, grid, block, s);
 #define LSH_REG_ALL(EP_) \
-    LSH_REG_CASE(2, 1, EP_) LSH_REG_CASE(2, 2, EP_) LSH_REG_CASE(1, 1, EP_) LSH_REG_CASE(1, 2, EP_)
+    LSH_REG_CASE(4, 1, EP_) LSH_REG_CASE(4, 2, EP_) LSH_REG_CASE(2, 1, EP_) LSH_REG_CASE(2, 2, EP_) \
+    LSH_REG_CASE(1, 1, EP_) LSH_REG_CASE(1, 2, EP_)
         LSH_EP_CASES(LSH_REG_ALL)
 #undef LSH_REG_ALL
 #undef LSH_REG_CASE

@@ -19,6 +19,13 @@
 // Padding samples (coefficient 0) are wildcards: they read one of the tile's zero slots,
 // of whichever class is free.
 //
+// A perfect schedule needs every class to be wanted by at most `steps` samples of a group,
+// which random samples do not grant (with 16 lanes x 32 samples over 16 classes the busiest
+// class is wanted about 42 times).  Where LDS has room the kernel therefore keeps a second
+// copy of the tile whose slots are rotated (copy_b_slot): every sample then has two classes
+// to choose from, the choice is made per group so that the classes are evenly loaded
+// (balance_copies), and the decomposition above comes out conflict-free or nearly so.
+//
 // Two table shapes are built from it: the flat one (every function's m samples, padded to
 // m_pad) and the chunked one (samples bucketed by coordinate range, every wave's bucket
 // padded to the longest list among its 64 lanes).
@@ -121,6 +128,55 @@ struct GroupScheduler {
     }
 };
 
+// Chooses, for every sample of a group, the tile copy to read it from: a[e] / b[e] are the
+// sample's classes in the first / second copy; returns the chosen class per sample with the
+// largest class load as small as possible.  Local search by augmenting paths: while some
+// chain of single-sample moves x0 -> x1 -> ... -> xt leads from a class to one holding at
+// least two samples fewer, shift one sample along every link (only the ends change load).
+std::vector<uint32_t> balance_copies(const std::vector<uint32_t> &a, const std::vector<uint32_t> &b,
+                                     uint32_t classes) {
+    std::vector<uint32_t> cur(a);
+    std::vector<int> load(classes, 0), from_sample(classes), seen(classes);
+    for (uint32_t c : cur) ++load[c];
+    std::vector<uint32_t> by_load(classes), frontier;
+    for (bool moved = true; moved;) {
+        moved = false;
+        std::iota(by_load.begin(), by_load.end(), 0u);
+        std::stable_sort(by_load.begin(), by_load.end(), [&](uint32_t x, uint32_t y) { return load[x] > load[y]; });
+        for (uint32_t src : by_load) {
+            std::fill(seen.begin(), seen.end(), 0);
+            std::fill(from_sample.begin(), from_sample.end(), -1);
+            seen[src] = 1;
+            frontier.assign(1, src);
+            int target = -1;
+            for (size_t f = 0; f < frontier.size() && target < 0; ++f) {
+                const uint32_t x = frontier[f];
+                for (size_t e = 0; e < cur.size() && target < 0; ++e) {
+                    if (cur[e] != x) continue;
+                    const uint32_t y = a[e] == x ? b[e] : a[e];
+                    if (y == x || seen[y]) continue;
+                    seen[y] = 1;
+                    from_sample[y] = (int)e;
+                    if (load[y] + 2 <= load[src]) target = (int)y;
+                    else frontier.push_back(y);
+                }
+            }
+            if (target < 0) continue;
+            for (uint32_t y = (uint32_t)target; y != src;) {  // walk the chain back to src
+                const int e = from_sample[y];
+                const uint32_t x = cur[e];
+                cur[e] = y;
+                y = x;
+            }
+            --load[src];
+            ++load[target];
+            moved = true;
+            break;
+        }
+    }
+    return cur;
+}
+
 // lanes of a wave in pass order: `group` consecutive entries are served together
 void pass_order_of(uint32_t group, uint32_t (&order)[64]) {
     for (uint32_t l = 0; l < 64; ++l) order[l] = l;
@@ -133,17 +189,18 @@ void pass_order_of(uint32_t group, uint32_t (&order)[64]) {
 }  // namespace
 
 // Flat schedule.  idx: canonical [k][m] coordinates.  order_out: [k][m_pad], entry = position
-// in the canonical list (0..m-1) or kPadSample | class for a padding sample that should read
+// in the canonical list (0..m-1), with kCopyB set when the sample is to be read from the
+// second tile copy (copies == 2), or kPadSample | class for a padding sample that should read
 // the zero slot of that class.  Returns the modelled cost: sum over pass groups and steps of
 // the largest number of lanes sharing a class (groups * steps when conflict-free).
 uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,
-                          uint32_t group, uint32_t classes, std::vector<uint32_t> &order_out) {
+                          uint32_t group, uint32_t classes, uint32_t copies, std::vector<uint32_t> &order_out) {
     order_out.assign((size_t)k * m_pad, 0);
     uint32_t pass_order[64];
     pass_order_of(group, pass_order);
     uint64_t cost = 0;
     GroupScheduler g;
-    std::vector<uint32_t> fn;
+    std::vector<uint32_t> fn, class_a, class_b;
     std::vector<std::vector<uint32_t>> cls, out;
     for (uint32_t g0 = 0; g0 < (k + 63) / 64 * 64; g0 += group) {
         fn.clear();
@@ -153,11 +210,24 @@ uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t
         }
         if (fn.empty()) continue;
         cls.assign(fn.size(), std::vector<uint32_t>(m));
+        class_a.clear();
+        class_b.clear();
         for (size_t l = 0; l < fn.size(); ++l)
-            for (uint32_t i = 0; i < m; ++i) cls[l][i] = idx[(size_t)fn[l] * m + i] % classes;
+            for (uint32_t i = 0; i < m; ++i) {
+                const uint32_t c = idx[(size_t)fn[l] * m + i];
+                class_a.push_back(c % classes);
+                class_b.push_back(copies == 2 ? copy_b_slot(c, classes) % classes : c % classes);
+            }
+        const std::vector<uint32_t> chosen = copies == 2 ? balance_copies(class_a, class_b, classes) : class_a;
+        for (size_t l = 0; l < fn.size(); ++l)
+            for (uint32_t i = 0; i < m; ++i) cls[l][i] = chosen[l * m + i];
         cost += g.run(cls, (int)classes, (int)m_pad, out);
         for (size_t l = 0; l < fn.size(); ++l)
-            std::copy(out[l].begin(), out[l].end(), order_out.begin() + (size_t)fn[l] * m_pad);
+            for (uint32_t s = 0; s < m_pad; ++s) {
+                uint32_t e = out[l][s];
+                if (!(e & kPadSample) && chosen[l * m + e] != class_a[l * m + e]) e |= kCopyB;
+                order_out[(size_t)fn[l] * m_pad + s] = e;
+            }
     }
     return cost;
 }

@@ -99,13 +99,16 @@ def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
         steps = order.shape[1]
         assert steps % 32 == 0 and m <= steps < m + 32
         pad = (order & 0x80000000) != 0
+        copy_b = ~pad & ((order & 0x40000000) != 0)      # sample read from the class-rotated tile copy
+        pos = np.where(pad, 0, order & 0x3fffffff).astype(np.int64)
         assert (pad.sum(axis=1) == steps - m).all()
         for j in range(k):
-            assert sorted(order[j][~pad[j]].tolist()) == list(range(m))
+            assert sorted(pos[j][~pad[j]].tolist()) == list(range(m))
         assert ((order[pad] & 0x7fffffff) < classes).all()
         # recompute the modelled cost: per pass group and step, the most popular class
-        cls = np.where(pad, order & 0x7fffffff,
-                       np.take_along_axis(idx, np.where(pad, 0, order).astype(np.int64), axis=1) % classes)
+        coord = np.take_along_axis(idx, pos, axis=1).astype(np.int64)
+        rotated = (coord + coord // classes) % classes
+        cls = np.where(pad, order & 0x7fffffff, np.where(copy_b, rotated, coord % classes))
         groups = _pass_groups(k, group)
         total = 0
         for fn in groups:
@@ -122,6 +125,8 @@ def test_gather_schedule_is_a_padded_permutation(n, k, m, repl):
                 naive += np.bincount(block[:, i], minlength=classes).max()
         if m >= 30 and k >= group:
             assert passes / (len(groups) * steps) < 0.75 * naive / (len(groups) * m)
+        if copy_b.any():    # two tile copies: every sample has two classes to choose from
+            assert passes / (len(groups) * steps) < 1.05
 
 
 @pytest.mark.parametrize("n,k,m,repl", [(16384, 520, 40, False), (30000, 512, 33, True), (4096, 600, 256, False)])
