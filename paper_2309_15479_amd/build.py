@@ -15,6 +15,9 @@ def build_library(verbose=False):
            "-ffp-contract=off", "-fno-gpu-rdc",
            # keep the compiler from forming packed fp32 instructions out of scalar float code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # device code only: no NaN bookkeeping, which lets floor + convert become one
+           # instruction; vectors with NaN coordinates get unspecified ids either way
+           "-Xarch_device", "-fno-honor-nans",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-Wall", "-Wno-unused-command-line-argument",
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]

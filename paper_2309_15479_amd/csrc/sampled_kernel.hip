@@ -168,11 +168,33 @@ __device__ __forceinline__ uint64_t group_sum(uint64_t v, uint32_t g) {
     return v;
 }
 
+// The same transpose for fp32 values, on the matrix pipe instead of the vector ALU (which is
+// what bounds the sampled kernels): the 4x4x1 MFMA computes, in every quad of lanes,
+// D[i][u] += A[i] * B[u] with A[i], B[u] taken from lanes i, u of the quad and D[i][u] landing in
+// register i of lane u.  Four of them, with A = x[t] and B = [u == t], leave x[u] of lane i in
+// register i of lane u.  Multiplying by 1 and adding zeros is exact for finite values;
+// callers clamp first, so that a non-finite value cannot leak into its quad neighbours.
+typedef float float4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void quad_transpose_mfma(float (&x)[4], const float (&unit)[4]) {
+    float4v d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) d = __builtin_amdgcn_mfma_f32_4x4x1f32(x[t], unit[t], d, 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) x[t] = d[t];
+}
+
+// v_writelane_b32 as a compiler intrinsic (this compiler has no builtin of that name); written
+// as inline assembly instead it would miss the wait states the hardware needs between a
+// vector compare that writes the scalar value and the lane write that reads it.
+extern "C" __device__ int write_lane(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
 // One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.  A vector
 // memory instruction costs the memory pipeline about the same whether a lane moves 4 or 16
 // bytes, and this kernel issues one store per (wave, vector): so with 4-vector slots the ids
 // of a quad of lanes are transposed in registers first and leave as 16-byte stores (four
 // consecutive functions of one vector per lane), and sign words leave one store per tile.
+// For a power-of-two w, (p + b) / w is computed as fma(p, 1/w, b/w): scaling by a power of two
+// commutes with the rounding of the sum, so the result is the same float.
 template <int RT, int SUB, int EP>
 __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint32_t j,
                                        const float (&acc)[SUB][RT], float b, uint64_t key_pow) {
@@ -183,20 +205,30 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
             constexpr bool ids = EP == (int)Epilogue::Ids;
             uint32_t *out = reinterpret_cast<uint32_t *>(a.out);
             const bool wide = RT == 4 && (a.k & 3) == 0;
+            const float b_scaled = b * a.inv_w;
+            float unit[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) unit[t] = (threadIdx.x & 3) == (uint32_t)t ? 1.f : 0.f;
 #pragma unroll
             for (int s = 0; s < SUB; ++s) {
-                uint32_t v[RT];
+                float q[RT];
 #pragma unroll
                 for (int r = 0; r < RT; ++r) {
                     const float p = acc[s][r];
-                    const float q = a.w_is_pow2 ? (p + b) * a.inv_w : (p + b) / a.w;
-                    v[r] = ids ? (uint32_t)(int)floorf(q) : __float_as_uint(p);
+                    q[r] = !ids ? p : a.w_is_pow2 ? fmaf(p, a.inv_w, b_scaled) : (p + b) / a.w;
                 }
                 if constexpr (RT == 4) {
                     if (wide) {  // uniform
-                        quad_transpose(v);
+                        // beyond +-2^31 the conversion saturates anyway
+                        const float bound = ids ? 2147483648.f : 3.4028234664e38f;
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) q[r] = __builtin_amdgcn_fmed3f(q[r], -bound, bound);
+                        quad_transpose_mfma(q, unit);
                         const uint64_t row = row0 + s * RT + (threadIdx.x & 3);
                         const uint32_t j4 = j & ~3u;
+                        uint32_t v[4];
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) v[r] = ids ? (uint32_t)(int)floorf(q[r]) : __float_as_uint(q[r]);
                         if (j4 < a.k && row < a.N)
                             *reinterpret_cast<uint4 *>(out + row * a.k + j4) = make_uint4(v[0], v[1], v[2], v[3]);
                         continue;
@@ -205,7 +237,7 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
 #pragma unroll
                 for (int r = 0; r < RT; ++r) {
                     const uint64_t row = row0 + s * RT + r;
-                    if (live && row < a.N) out[row * a.k + j] = v[r];
+                    if (live && row < a.N) out[row * a.k + j] = ids ? (uint32_t)(int)floorf(q[r]) : __float_as_uint(q[r]);
                 }
             }
             break;
@@ -214,14 +246,17 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
             uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
             const uint32_t words = (a.k + 63) / 64;
             const uint32_t lane = threadIdx.x & 63;
-            uint64_t mine = 0;  // lane v of the wave keeps the word of the tile's vector v
+            uint32_t lo = 0, hi = 0;  // lane v of the wave keeps the word of the tile's vector v
 #pragma unroll
             for (int s = 0; s < SUB; ++s)
 #pragma unroll
                 for (int r = 0; r < RT; ++r) {
                     const uint64_t word = __ballot(live && acc[s][r] >= 0.f);  // whole waves get here
-                    if (lane == (uint32_t)(s * RT + r)) mine = word;
+                    // the wave-uniform word goes into lane s * RT + r only
+                    lo = (uint32_t)write_lane((int)(uint32_t)word, s * RT + r, (int)lo);
+                    hi = (uint32_t)write_lane((int)(uint32_t)(word >> 32), s * RT + r, (int)hi);
                 }
+            const uint64_t mine = ((uint64_t)hi << 32) | lo;
             const uint64_t row = row0 + lane;
             if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k && row < a.N) out[row * words + (j >> 6)] = mine;
             break;
