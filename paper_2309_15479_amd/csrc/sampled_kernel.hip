@@ -195,9 +195,13 @@ extern "C" __device__ int write_lane(int value, int lane, int old) __asm("llvm.a
 // consecutive functions of one vector per lane), and sign words leave one store per tile.
 // For a power-of-two w, (p + b) / w is computed as fma(p, 1/w, b/w): scaling by a power of two
 // commutes with the rounding of the sum, so the result is the same float.
-template <int RT, int SUB, int EP>
+// FULL: every vector of the tile exists; the stores then go to a wave-uniform base (scalar
+// arithmetic) plus the per-lane byte offset full_off the caller keeps in a register:
+// ((lane % 4) * k + (j & ~3)) * 4 for ids, (lane % 64 * ceil(k / 64) + j / 64) * 8 for sign words.
+template <int RT, int SUB, int EP, bool FULL = false>
 __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint32_t j,
-                                       const float (&acc)[SUB][RT], float b, uint64_t key_pow) {
+                                       const float (&acc)[SUB][RT], float b, uint64_t key_pow,
+                                       uint32_t full_off = 0) {
     const bool live = j < a.k;
     switch (EP) {
         case (int)Epilogue::Ids:
@@ -229,8 +233,12 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
                         uint32_t v[4];
 #pragma unroll
                         for (int r = 0; r < RT; ++r) v[r] = ids ? (uint32_t)(int)floorf(q[r]) : __float_as_uint(q[r]);
-                        if (j4 < a.k && row < a.N)
+                        if constexpr (FULL) {
+                            char *base = reinterpret_cast<char *>(out + (row0 + s * RT) * a.k);  // uniform
+                            if (j4 < a.k) *reinterpret_cast<uint4 *>(base + full_off) = make_uint4(v[0], v[1], v[2], v[3]);
+                        } else if (j4 < a.k && row < a.N) {
                             *reinterpret_cast<uint4 *>(out + row * a.k + j4) = make_uint4(v[0], v[1], v[2], v[3]);
+                        }
                         continue;
                     }
                 }
@@ -258,7 +266,12 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
                 }
             const uint64_t mine = ((uint64_t)hi << 32) | lo;
             const uint64_t row = row0 + lane;
-            if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k && row < a.N) out[row * words + (j >> 6)] = mine;
+            if constexpr (FULL) {
+                char *base = reinterpret_cast<char *>(out + row0 * words);  // uniform
+                if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k) *reinterpret_cast<uint64_t *>(base + full_off) = mine;
+            } else if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k && row < a.N) {
+                out[row * words + (j >> 6)] = mine;
+            }
             break;
         }
         default: {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64
@@ -357,7 +370,11 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
 // with the FMAs of sample i); scheduling barriers keep the compiler from hoisting every LDS
 // read of the tile to the front, which would need more registers than a lane has.
 // PF = 64-coordinate chunks each wave fetches per tile (see launch_sampled).
-template <int SUB, int PF, int MCH, int EP>
+// REGULAR: the launch covers whole tiles only, n is a multiple of 64 and every wave has PF
+// pieces inside the vector: loads, LDS writes and stores then need no predicates and their
+// addresses are a wave-uniform base plus per-lane constants (the host sends the vectors
+// beyond the last whole tile through the general instantiation).
+template <int SUB, int PF, int MCH, int EP, bool REGULAR>
 __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(const SampledArgs a) {
     constexpr int RT = 4;
     extern __shared__ __align__(16) float tile[];  // 2 x [n + classes][SP][RT]
@@ -428,15 +445,41 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
             }
         }
     };
+    const uint32_t ld_off = (lane & 3) * n + (lane & ~3u);
+    auto fetch_full = [&](uint64_t row0) {
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            const uint32_t q = wave + f * nwaves;
+            const float *src = a.data + (row0 + (q % SUB) * RT) * n + (q / SUB) * 64;  // uniform
+            const float4 v = *reinterpret_cast<const float4 *>(src + ld_off);
+            pre[f][0] = v.x; pre[f][1] = v.y; pre[f][2] = v.z; pre[f][3] = v.w;
+        }
+    };
+    auto stash_full = [&](float *buf) {
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            const uint32_t q = wave + f * nwaves;
+            const uint32_t st = q % SUB, c = (q / SUB) * 64 + lane;
+            slot_from_raw<true>(pre[f]);
+            lds_write_slot<RT>(buf + ((size_t)c * SP + st) * RT, pre[f]);
+            if (a.copy_b_floats)
+                lds_write_slot<RT>(buf + a.copy_b_floats + ((size_t)((c & ~15u) | ((c + (c >> 4)) & 15u)) * SP + st) * RT,
+                                   pre[f]);
+        }
+    };
     // the vectorised and the word-by-word variants are separate straight-line code
     auto fetch = [&](uint64_t row0) {
-        if (vec4) fetch_as(row0, std::true_type{});
+        if constexpr (REGULAR) fetch_full(row0);
+        else if (vec4) fetch_as(row0, std::true_type{});
         else fetch_as(row0, std::false_type{});
     };
     auto stash = [&](float *buf) {
-        if (vec4) stash_as(buf, std::true_type{});
+        if constexpr (REGULAR) stash_full(buf);
+        else if (vec4) stash_as(buf, std::true_type{});
         else stash_as(buf, std::false_type{});
     };
+    const uint32_t full_off = EP == (int)Epilogue::Signs ? (lane * ((a.k + 63) / 64) + (j >> 6)) * 8
+                                                        : ((lane & 3) * a.k + (j & ~3u)) * 4;
 
     uint64_t t = blockIdx.x;
     if (t < ntiles) {
@@ -486,7 +529,7 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        finish<RT, SUB, EP>(a, row0, fresh(j), acc, b, key_pow);
+        finish<RT, SUB, EP, REGULAR>(a, row0, fresh(j), acc, b, key_pow, full_off);
 
         if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
         __syncthreads();  // next buffer complete; everyone is done with the current one
@@ -789,17 +832,44 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
         default: CALL((int)Epilogue::Keys) break; \
     }
     if (pl.reg_table) {
+        // whole tiles of a regular shape go through the predicate-free instantiation, the
+        // vectors after them (fewer than one tile) through the general one
+        const bool regular = pl.sub == 4 && (p->n & 63) == 0 && pl.sub * (p->n / 64) == pl.prefetch * (pl.block / 64) &&
+                             (ep == Epilogue::Signs || ep == Epilogue::Keys || (p->k & 3) == 0);
+        const uint64_t n_whole = regular ? N / tile_rows * tile_rows : 0;
+        SampledArgs tail = a;
+        tail.data = d_data + n_whole * p->n;
+        tail.N = N - n_whole;
+        const uint64_t out_bytes_per_vector = ep == Epilogue::Signs  ? 8ull * ((p->k + 63) / 64)
+                                              : ep == Epilogue::Keys ? 8ull * L
+                                                                     : 4ull * p->k;
+        tail.out = static_cast<char *>(d_out) + n_whole * out_bytes_per_vector;
+        a.N = n_whole;
+        const uint64_t tail_tiles = (tail.N + tile_rows - 1) / tile_rows;
+        dim3 tail_grid((uint32_t)(tail_tiles < gx ? tail_tiles : gx), pl.kblocks);
+        if (n_whole && grid.x > n_whole / tile_rows) grid.x = (uint32_t)(n_whole / tile_rows);
+#define LSH_REG_LAUNCH(SUB_, PF_, MCH_, EP_, REG_, ARGS_, GRID_) \
+    launch_kernel(&sampled_reg_kernel<SUB_, PF_, MCH_, EP_, REG_>, lds_bytes, ARGS_, GRID_, block, s)
 #define LSH_REG_CASE(SUB_, PF_, EP_) \
-    if (pl.sub == SUB_ && pl.prefetch == PF_) \
-        return pl.m_pad == (uint32_t)kChunk \
-                   ? launch_kernel(&sampled_reg_kernel<SUB_, PF_, 1, EP_>, lds_bytes, a, grid, block, s) \
-                   : launch_kernel(&sampled_reg_kernel<SUB_, PF_, 2, EP_>, lds_bytes, a, grid, block, s);
+    if (pl.sub == SUB_ && pl.prefetch == PF_) { \
+        int rc = LSH_OK; \
+        if constexpr (SUB_ == 4) { \
+            if (n_whole) \
+                rc = pl.m_pad == (uint32_t)kChunk ? LSH_REG_LAUNCH(SUB_, PF_, 1, EP_, true, a, grid) \
+                                                  : LSH_REG_LAUNCH(SUB_, PF_, 2, EP_, true, a, grid); \
+        } \
+        if (rc == LSH_OK && tail.N) \
+            rc = pl.m_pad == (uint32_t)kChunk ? LSH_REG_LAUNCH(SUB_, PF_, 1, EP_, false, tail, tail_grid) \
+                                              : LSH_REG_LAUNCH(SUB_, PF_, 2, EP_, false, tail, tail_grid); \
+        return rc; \
+    }
 #define LSH_REG_ALL(EP_) \
     LSH_REG_CASE(4, 1, EP_) LSH_REG_CASE(4, 2, EP_) LSH_REG_CASE(2, 1, EP_) LSH_REG_CASE(2, 2, EP_) \
     LSH_REG_CASE(1, 1, EP_) LSH_REG_CASE(1, 2, EP_)
         LSH_EP_CASES(LSH_REG_ALL)
 #undef LSH_REG_ALL
 #undef LSH_REG_CASE
+#undef LSH_REG_LAUNCH
         return LSH_ERR_UNSUPPORTED;
     }
 #define LSH_GEN_ALL(EP_) \

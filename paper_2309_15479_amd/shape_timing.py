@@ -1,0 +1,70 @@
+"""Kernel times of the hash calls on the paper-shaped workloads, one line per call.
+
+    python -m paper_2309_15479_amd.shape_timing [tiny|sift|gist|highdim|angular ...]
+
+Each call is timed with HIP events around back-to-back launches on the current stream
+(lsh_time_launches), inputs and outputs resident in HBM.  Printed per call: milliseconds per
+launch, the algorithmic HBM rate (4n bytes read + ids / keys / sign words written per
+vector), gather-FMAs per second for the sampled calls and flop/s for the dense call.
+"""
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main(names):
+    import torch
+    import workloads
+    import paper_2309_15479_amd as lsh
+
+    lsh.load_library()
+    for name in names:
+        wl, data = workloads.make_data(name, "cuda")
+        N, n, k = wl.N, wl.n, wl.k
+        for m in wl.m:
+            with lsh.LshParams(n, k, m, wl.w, wl.seed) as p:
+                order, group, classes, passes = p.schedule()
+                used = int((order != 0xFFFFFFFF).sum())
+                conflict = passes / (used / group)
+                if wl.signs:
+                    out = torch.empty((N, (k + 63) // 64), dtype=torch.int64, device="cuda")
+                    which, out_bytes = "signs", 8 * ((k + 63) // 64)
+                else:
+                    out = torch.empty((N, k), dtype=torch.int32, device="cuda")
+                    which, out_bytes = "fastlsh", 4 * k
+                lsh.time_launches(p, which, data, out, reps=3)
+                ms = lsh.time_launches(p, which, data, out, reps=10)
+                print(f"{name} n={n} k={k} m={m} {which}: {ms:.3f} ms  "
+                      f"{N * (4 * n + out_bytes) / ms / 1e6:.0f} GB/s algorithmic  "
+                      f"{N * k * m / ms / 1e9:.2f} T gather-FMA/s  "
+                      f"(schedule: {conflict:.3f} x conflict-free)", flush=True)
+                if wl.L and not wl.signs:
+                    keys = torch.empty((N, wl.L), dtype=torch.int64, device="cuda")
+                    lsh.time_launches(p, "pack_keys", out, keys, L=wl.L, reps=3)
+                    ms = lsh.time_launches(p, "pack_keys", out, keys, L=wl.L, reps=10)
+                    print(f"{name} pack_keys L={wl.L}: {ms:.3f} ms  "
+                          f"{N * (4 * k + 8 * wl.L) / ms / 1e6:.0f} GB/s algorithmic", flush=True)
+                    g = k // wl.L
+                    if g & (g - 1) == 0 and g <= 64:
+                        lsh.time_launches(p, "fastlsh_keys", data, keys, L=wl.L, reps=3)
+                        ms = lsh.time_launches(p, "fastlsh_keys", data, keys, L=wl.L, reps=10)
+                        print(f"{name} m={m} fastlsh_keys L={wl.L}: {ms:.3f} ms  "
+                              f"{N * (4 * n + 8 * wl.L) / ms / 1e6:.0f} GB/s algorithmic", flush=True)
+                del out
+        if not wl.signs:
+            with lsh.LshParams(n, k, n, wl.w, wl.seed) as p:
+                out = torch.empty((N, k), dtype=torch.int32, device="cuda")
+                lsh.time_launches(p, "e2lsh", data, out, reps=2)
+                ms = lsh.time_launches(p, "e2lsh", data, out, reps=5)
+                print(f"{name} n={n} k={k} e2lsh (dense): {ms:.3f} ms  "
+                      f"{2 * N * n * k / ms / 1e9:.1f} TFLOP/s", flush=True)
+                del out
+        del data
+        torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:] or ["tiny", "sift", "gist", "highdim", "angular"])

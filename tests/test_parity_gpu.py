@@ -110,6 +110,9 @@ RAGGED = [
     (5, 30000, 64, 40, 1.0, 30, False, 0),       # 1-vector tiles
     (3, 40384, 64, 33, 1.0, 32, True, 0),        # the largest dimension one LDS tile holds
     (300, 64, 2100, 16, 2.0, 31, False, 0),      # more functions than one workgroup holds
+    (100, 256, 512, 64, 4.0, 35, False, 16),     # register lists of two chunks, two pieces per wave, whole tiles + tail
+    (50, 128, 514, 20, 2.0, 36, True, 0),        # padded register lists, k not a multiple of 4
+    (16, 128, 512, 32, 16.0, 37, False, 32),     # exactly one whole tile, no tail
 ]
 
 
