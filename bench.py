@@ -22,9 +22,22 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
-# fp32 vector peak: 256 CUs x 128 FMA lanes/clk x 2 flop x 2.4 GHz (plain v_fma_f32 measured at
-# 109 of those 128 lanes/clk/CU on this part, no packed instructions involved)
+# fp32 vector peak with packed instructions: 256 CUs x 128 FMA lanes/clk x 2 flop x 2.4 GHz.
+# This library is compiled without packed fp32 operations; a plain 64-lane v_fma_f32 occupies a
+# SIMD for four cycles, i.e. 64 lanes/clk/CU, half of that peak.
 VALU_FP32_PEAK_TFLOPS = 157.3
+VALU_FP32_UNPACKED_TFLOPS = 78.6
+
+# HBM bytes per launch on this workload from rocprofv3's FETCH_SIZE and WRITE_SIZE counters
+# (two runs, each scaled by what the same counter reads for a 1 GiB device copy: 2 KiB and
+# 1 KiB per count), taken on the kernels as they stand; the summary and its commands are in
+# profiles/sift_step_hbm_traffic.md.  Set an entry to None when its kernel changes.
+MEASURED_TRAFFIC_BYTES = {
+    "fastlsh": 250656 * 2048 + 2000000 * 1024,    # 0.513 GB read + 2.048 GB written
+    "pack_keys": 1000021 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
+    "e2lsh": 301706 * 2048 + 2090870 * 1024,      # 0.618 GB + 2.141 GB
+    "signs": 250567 * 2048 + 62500 * 1024,        # 0.513 GB + 0.064 GB
+}
 
 
 def cpu_baseline(wl, data, p_fast, p_dense, budget_s=12.0):
@@ -55,8 +68,9 @@ def cpu_baseline(wl, data, p_fast, p_dense, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    # the GPU's clocks ramp up over the first ~100 ms of load: warm up for about that long
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device-to-device copies (a kernel of known HBM traffic, "
@@ -126,25 +140,26 @@ def main():
             ms[s] += ev[i].elapsed_time(ev[i + 1])
     ms = {s: v / args.steps for s, v in ms.items()}
 
-    def hbm(bytes_per_launch, t_ms):
-        a = bytes_per_launch / (t_ms * 1e-3) / 1e9
+    def hbm(stage, bytes_per_launch):
+        a = bytes_per_launch / (ms[stage] * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": a / HBM_PEAK_GBS, "traffic": None}
+                "frac": a / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES[stage]}
 
     rooflines = {
         # algorithmic bytes per vector: 4n read + 4k written (ids) / 8 per 64 functions (signs)
-        "fastlsh": hbm(N * (4 * n + 4 * k), ms["fastlsh"]),
-        "pack_keys": hbm(N * (4 * k + 8 * L), ms["pack_keys"]),
-        "signs": hbm(N * (4 * n + 8 * ((k + 63) // 64)), ms["signs"]),
+        "fastlsh": hbm("fastlsh", N * (4 * n + 4 * k)),
+        "pack_keys": hbm("pack_keys", N * (4 * k + 8 * L)),
+        "signs": hbm("signs", N * (4 * n + 8 * ((k + 63) // 64))),
     }
     tf = 2.0 * N * n * k / (ms["e2lsh"] * 1e-3) / 1e12
     rooflines["e2lsh"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                          "frac": tf / MFMA_FP32_PEAK_TFLOPS, "traffic": None}
+                          "frac": tf / MFMA_FP32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES["e2lsh"]}
     # the sampled kernels' arithmetic against the plain fp32 vector ceiling, for context
     for s in ("fastlsh", "signs"):
         alu = 2.0 * N * k * m / (ms[s] * 1e-3) / 1e12
         rooflines[s]["alu_tflops"] = alu
         rooflines[s]["alu_frac_of_fp32_vector_peak"] = alu / VALU_FP32_PEAK_TFLOPS
+        rooflines[s]["alu_frac_of_unpacked_fp32_issue_rate"] = alu / VALU_FP32_UNPACKED_TFLOPS
     dominant = max(stages, key=lambda s: ms[s])
 
     hashes_per_step = 3.0 * N * k

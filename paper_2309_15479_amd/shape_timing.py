@@ -3,7 +3,8 @@
     python -m paper_2309_15479_amd.shape_timing [tiny|sift|gist|highdim|angular ...]
 
 Each call is timed with HIP events around back-to-back launches on the current stream
-(lsh_time_launches), inputs and outputs resident in HBM.  Printed per call: milliseconds per
+(lsh_time_launches), inputs and outputs resident in HBM, after enough untimed launches for
+the GPU's clocks to settle (they ramp up over the first ~100 ms of load).  Printed per call: milliseconds per
 launch, the algorithmic HBM rate (4n bytes read + ids / keys / sign words written per
 vector), gather-FMAs per second for the sampled calls and flop/s for the dense call.
 """
@@ -13,6 +14,12 @@ import sys
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+
+
+def settle(launch, busy_ms=150.0):
+    """Untimed launches for about busy_ms of GPU time."""
+    ms = launch(2)
+    launch(max(1, min(200, int(busy_ms / max(ms, 1e-3)))))
 
 
 def main(names):
@@ -35,7 +42,7 @@ def main(names):
                 else:
                     out = torch.empty((N, k), dtype=torch.int32, device="cuda")
                     which, out_bytes = "fastlsh", 4 * k
-                lsh.time_launches(p, which, data, out, reps=3)
+                settle(lambda reps: lsh.time_launches(p, which, data, out, reps=reps))
                 ms = lsh.time_launches(p, which, data, out, reps=10)
                 print(f"{name} n={n} k={k} m={m} {which}: {ms:.3f} ms  "
                       f"{N * (4 * n + out_bytes) / ms / 1e6:.0f} GB/s algorithmic  "
@@ -43,13 +50,13 @@ def main(names):
                       f"(schedule: {conflict:.3f} x conflict-free)", flush=True)
                 if wl.L and not wl.signs:
                     keys = torch.empty((N, wl.L), dtype=torch.int64, device="cuda")
-                    lsh.time_launches(p, "pack_keys", out, keys, L=wl.L, reps=3)
+                    settle(lambda reps: lsh.time_launches(p, "pack_keys", out, keys, L=wl.L, reps=reps))
                     ms = lsh.time_launches(p, "pack_keys", out, keys, L=wl.L, reps=10)
                     print(f"{name} pack_keys L={wl.L}: {ms:.3f} ms  "
                           f"{N * (4 * k + 8 * wl.L) / ms / 1e6:.0f} GB/s algorithmic", flush=True)
                     g = k // wl.L
                     if g & (g - 1) == 0 and g <= 64:
-                        lsh.time_launches(p, "fastlsh_keys", data, keys, L=wl.L, reps=3)
+                        settle(lambda reps: lsh.time_launches(p, "fastlsh_keys", data, keys, L=wl.L, reps=reps))
                         ms = lsh.time_launches(p, "fastlsh_keys", data, keys, L=wl.L, reps=10)
                         print(f"{name} m={m} fastlsh_keys L={wl.L}: {ms:.3f} ms  "
                               f"{N * (4 * n + 8 * wl.L) / ms / 1e6:.0f} GB/s algorithmic", flush=True)
@@ -57,7 +64,7 @@ def main(names):
         if not wl.signs:
             with lsh.LshParams(n, k, n, wl.w, wl.seed) as p:
                 out = torch.empty((N, k), dtype=torch.int32, device="cuda")
-                lsh.time_launches(p, "e2lsh", data, out, reps=2)
+                settle(lambda reps: lsh.time_launches(p, "e2lsh", data, out, reps=reps))
                 ms = lsh.time_launches(p, "e2lsh", data, out, reps=5)
                 print(f"{name} n={n} k={k} e2lsh (dense): {ms:.3f} ms  "
                       f"{2 * N * n * k / ms / 1e9:.1f} TFLOP/s", flush=True)
