@@ -45,6 +45,7 @@ def _load():
         lib.oracle_philox4x64_10.argtypes = [p, p, p]
         lib.oracle_philox4x64_10.restype = None
         lib.oracle_params.argtypes = [u32, u32, u32, f32, u64, u32, p, p, p]
+        lib.oracle_params_shared.argtypes = [u32, u32, u32, f32, u64, u32, u32, p, p, p]
         lib.oracle_fastlsh.argtypes = [p, u64, u32, u32, u32, p, p, p, f32, p, p, p, p, i32]
         lib.oracle_e2lsh.argtypes = [p, u64, u32, u32, p, p, f32, p, p, p, p, i32]
         lib.oracle_signs.argtypes = [p, u64, u32, u32, u32, p, p, p, p, p, i32]
@@ -89,6 +90,17 @@ def params(n, k, m, w, seed, with_replacement=False):
     off = np.empty(k, np.float32)
     _check(_load().oracle_params(n, k, m, w, seed, int(bool(with_replacement)),
                                  _ptr(idx), _ptr(coef), _ptr(off)), "params")
+    return idx, coef, off
+
+
+def params_shared(n, k, m, w, seed, L, with_replacement=False):
+    """The same tables with one sample S per table of k/L functions (the table's first
+    function's S); coefficients and offsets stay per function."""
+    idx = np.empty((k, m), np.uint32)
+    coef = np.empty((k, m), np.float32)
+    off = np.empty(k, np.float32)
+    _check(_load().oracle_params_shared(n, k, m, w, seed, int(bool(with_replacement)), L,
+                                        _ptr(idx), _ptr(coef), _ptr(off)), "params_shared")
     return idx, coef, off
 
 

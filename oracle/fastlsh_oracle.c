@@ -28,7 +28,11 @@
  *     kept) as the default, with replacement (the paper's i.i.d. multiset) as
  *     the alternative; m == n means "no sampling": S_j = (0, 1, ..., n-1);
  *   - 64-bit key of a group of g bucket ids: Horner polynomial in a fixed odd
- *     multiplier, arithmetic mod 2^64.
+ *     multiplier, arithmetic mod 2^64;
+ *   - whether the k functions share their sample S: Sec. 3.1 draws "a multiset S" once,
+ *     Sec. 3.2 draws k functions independently from the family.  Default: every function its
+ *     own S_j.  Alternative (oracle_params_shared): the g = k/L functions of one table share
+ *     one S (that of the table's first function), with their own a~_j and b~_j.
  *
  * Parity status: the arithmetic (gather, projection, floor, signs, keys) is
  * pinned by the tests under tests/ (paper's worked sampling example, exact
@@ -112,8 +116,9 @@ static double uniform53(uint64_t word) { return (double)(word >> 11) * 0x1.0p-53
  *   coef [k*m]  a~_j[i] ~ N(0,1), fp32
  *   off  [k]    b~_j ~ U[0,w), fp32
  */
-int oracle_params(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
-                  uint32_t with_replacement, uint32_t *idx, float *coef, float *off)
+static int params_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
+                         uint32_t with_replacement, uint32_t group, uint32_t *idx, float *coef,
+                         float *off)
 {
     if (!n || !k || !m || m > n || !(w > 0.0f) || !isfinite(w) || !idx || !coef || !off)
         return ORACLE_ERR_ARG;
@@ -124,15 +129,17 @@ int oracle_params(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
     }
     for (uint32_t j = 0; j < k; ++j) {
         uint32_t *S = idx + (size_t)j * m;
+        /* the function whose draws give S: j itself, or the first function of j's table */
+        const uint32_t js = j - j % group;
         if (m == n) {
             for (uint32_t i = 0; i < m; ++i) S[i] = i;              /* no sampling */
         } else if (with_replacement) {
             for (uint32_t i = 0; i < m; ++i)                          /* i.i.d. multiset */
-                S[i] = (uint32_t)draw_below(seed, j, i, n);
+                S[i] = (uint32_t)draw_below(seed, js, i, n);
         } else {
             for (uint32_t c = 0; c < n; ++c) perm[c] = c;             /* Fisher-Yates, m steps */
             for (uint32_t i = 0; i < m; ++i) {
-                uint32_t r = i + (uint32_t)draw_below(seed, j, i, n - i);
+                uint32_t r = i + (uint32_t)draw_below(seed, js, i, n - i);
                 uint32_t tmp = perm[i]; perm[i] = perm[r]; perm[r] = tmp;
                 S[i] = perm[i];
             }
@@ -155,6 +162,25 @@ int oracle_params(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
     }
     free(perm);
     return ORACLE_OK;
+}
+
+int oracle_params(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
+                  uint32_t with_replacement, uint32_t *idx, float *coef, float *off)
+{
+    return params_tables(n, k, m, w, seed, with_replacement, 1, idx, coef, off);
+}
+
+/*
+ * The same tables with one sample S per table of g = k / L functions (Sec. 3.1 read
+ * literally: one multiset S, then the projection vectors): functions l*g .. l*g + g - 1 all
+ * get the S that function l*g has in oracle_params; a~ and b~ stay per function.
+ */
+int oracle_params_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
+                         uint32_t with_replacement, uint32_t L, uint32_t *idx, float *coef,
+                         float *off)
+{
+    if (!L || !k || k % L) return ORACLE_ERR_ARG;
+    return params_tables(n, k, m, w, seed, with_replacement, k / L, idx, coef, off);
 }
 
 /* ------------------------------------------------------------------------ */

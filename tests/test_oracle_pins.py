@@ -311,6 +311,65 @@ def test_fastlsh_collision_rate_conditional_law_and_monotone():
         assert all(a > b for a, b in zip(rates, rates[1:])), rates
 
 
+# --------------------------------------------------------------------------
+# One sample S per table (Sec. 3.1 read literally: one multiset S for the family).
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("repl", [False, True])
+def test_shared_sample_tables_structure(repl):
+    n, k, m, w, L = 50, 48, 7, 2.0, 6
+    g = k // L
+    idx_i, coef_i, off_i = oracle.params(n, k, m, w, seed=9, with_replacement=repl)
+    idx_s, coef_s, off_s = oracle.params_shared(n, k, m, w, seed=9, L=L, with_replacement=repl)
+    # a~ and b~ stay per function; S of table l is the S of its first function, for all g
+    assert np.array_equal(coef_s.view(np.uint32), coef_i.view(np.uint32))
+    assert np.array_equal(off_s.view(np.uint32), off_i.view(np.uint32))
+    for l in range(L):
+        for t in range(g):
+            assert np.array_equal(idx_s[l * g + t], idx_i[l * g])
+    # tables differ from one another (the draws of different tables are independent)
+    assert len({tuple(idx_s[l * g]) for l in range(L)}) == L
+    # L = k is the per-function case, L = 1 one sample for everything
+    assert np.array_equal(oracle.params_shared(n, k, m, w, 9, L=k, with_replacement=repl)[0], idx_i)
+    assert (oracle.params_shared(n, k, m, w, 9, L=1, with_replacement=repl)[0] == idx_i[0]).all()
+    with pytest.raises(Exception):
+        oracle.params_shared(n, k, m, w, 9, L=5)          # k % L != 0
+
+
+def test_shared_sample_key_collision_law():
+    # With one S per table the g functions of a table are independent E2LSH functions on the
+    # same sub-vector, so a whole key collides with probability p_w(s~_l)^g given S_l, and the
+    # rate over many tables is the mean of that: not the g-th power of the mean collision
+    # rate, which is what per-function samples give.  A sparse difference vector makes the
+    # two laws differ widely (s~ is 0 for most samples).
+    n, m, w, g, L = 40, 4, 4.0, 4, 6000
+    k = g * L
+    v = np.random.default_rng(5).normal(size=n)
+    diff = np.zeros(n)
+    diff[:4] = 6.0                                       # only 4 of the 40 coordinates differ
+    pair = np.stack([v, v + diff]).astype(np.float32)
+    d64 = pair[0].astype(np.float64) - pair[1].astype(np.float64)
+
+    def p_of(s_tilde):
+        return 1.0 if s_tilde == 0 else _p_closed(s_tilde, w)
+
+    idx, coef, off = oracle.params_shared(n, k, m, w, seed=77, L=L)
+    ids = oracle.fastlsh(pair, idx, coef, off, w)["ids"].reshape(2, L, g)
+    rate_shared = (ids[0] == ids[1]).all(axis=1).mean()
+    s_tab = np.sqrt((d64[idx[::g].astype(np.int64)] ** 2).sum(axis=1))               # [L]
+    expect_shared = np.mean([p_of(x) ** g for x in s_tab])
+    assert abs(rate_shared - expect_shared) < 4 * math.sqrt(expect_shared * (1 - expect_shared) / L)
+
+    idx, coef, off = oracle.params(n, k, m, w, seed=77)
+    ids = oracle.fastlsh(pair, idx, coef, off, w)["ids"].reshape(2, L, g)
+    rate_indep = (ids[0] == ids[1]).all(axis=1).mean()
+    s_fn = np.sqrt((d64[idx.astype(np.int64)] ** 2).sum(axis=1)).reshape(L, g)
+    expect_indep = np.mean([np.prod([p_of(x) for x in row]) for row in s_fn])
+    assert abs(rate_indep - expect_indep) < 4 * math.sqrt(expect_indep * (1 - expect_indep) / L)
+    # and the two readings are far apart here, so the test separates them
+    assert rate_shared > rate_indep + 0.1
+
+
 def test_fastlsh_tends_to_e2lsh_at_scaled_distance_for_large_m():
     # Corollary of Sec. 4.2: s~X -> N(0, m s^2 / n); so with the same w the FastLSH
     # collision rate approaches the E2LSH law at distance s*sqrt(m/n)
