@@ -70,6 +70,21 @@ int lsh_params_create(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed
                       lsh_params_t **out);
 int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
                          uint32_t flags, lsh_params_t **out);
+/*
+ * The same with ONE sample per table (Sec. 3.1 read literally: a single multiset S is drawn,
+ * then the projection vectors): with L > 0 (k % L == 0) the g = k / L functions of table l,
+ * j = l*g .. l*g + g - 1, all use the sample S that function l*g gets from
+ * lsh_params_create_ex; a~_j and b~_j stay per function.  Given S, the functions of a table
+ * are independent E2LSH functions on the same sub-vector (Sec. 4.1), so a table's key collides
+ * with probability p_w(s~)^g given S instead of the product over g independent samples.
+ * Every hash call accepts such an object; lsh_hash_fastlsh and lsh_project_fastlsh then gather
+ * each table's sub-vector once and contract it with the g coefficient vectors on the matrix
+ * cores when the shape allows (n % 4 == 0, n <= 304, m <= 64, g % 4 == 0), and fall back to
+ * the per-function gather kernels otherwise.  L == 0 is lsh_params_create_ex.
+ * Errors: as lsh_params_create, and INVALID_ARG when k % L != 0.
+ */
+int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
+                             uint32_t flags, uint32_t L, lsh_params_t **out);
 void lsh_params_destroy(lsh_params_t *params);
 
 /*
@@ -85,6 +100,9 @@ int lsh_params_get_offsets(const lsh_params_t *params, float *out);
 /* the six scalars: n, k, m, flags as uint32; w; seed.  Any out pointer may be NULL. */
 int lsh_params_get_shape(const lsh_params_t *params, uint32_t *n, uint32_t *k, uint32_t *m,
                          uint32_t *flags, float *w, uint64_t *seed);
+
+/* L of lsh_params_create_shared (0: every function has its own sample). */
+int lsh_params_get_tables(const lsh_params_t *params, uint32_t *shared_tables);
 
 /*
  * The order in which the sampled kernel visits each function's samples.  A projection is a

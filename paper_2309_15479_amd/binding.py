@@ -18,8 +18,9 @@ SAMPLE_WITHOUT_REPLACEMENT = 0
 SAMPLE_WITH_REPLACEMENT = 1
 
 EXPORTS = [
-    "lsh_params_create", "lsh_params_create_ex", "lsh_params_destroy", "lsh_params_get_indices",
-    "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape", "lsh_params_get_schedule",
+    "lsh_params_create", "lsh_params_create_ex", "lsh_params_create_shared", "lsh_params_destroy",
+    "lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape",
+    "lsh_params_get_tables", "lsh_params_get_schedule",
     "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
@@ -53,6 +54,8 @@ def load_library():
     u32, u64, f32, p, i = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int
     lib.lsh_params_create.argtypes = [u32, u32, u32, f32, u64, ctypes.POINTER(p)]
     lib.lsh_params_create_ex.argtypes = [u32, u32, u32, f32, u64, u32, ctypes.POINTER(p)]
+    lib.lsh_params_create_shared.argtypes = [u32, u32, u32, f32, u64, u32, u32, ctypes.POINTER(p)]
+    lib.lsh_params_get_tables.argtypes = [p, p]
     lib.lsh_params_destroy.argtypes = [p]
     lib.lsh_params_destroy.restype = None
     for name in ("lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets"):
@@ -83,12 +86,13 @@ def _check(status, what):
 class LshParams:
     """Owns one lsh_params_t (the k hash functions and their device tables)."""
 
-    def __init__(self, n, k, m, w, seed, with_replacement=False):
+    def __init__(self, n, k, m, w, seed, with_replacement=False, shared_tables=0):
+        """shared_tables = L > 0: the k/L functions of each table share one sample S."""
         lib = load_library()
         handle = ctypes.c_void_p()
         flags = SAMPLE_WITH_REPLACEMENT if with_replacement else SAMPLE_WITHOUT_REPLACEMENT
-        _check(lib.lsh_params_create_ex(n, k, m, w, seed, flags, ctypes.byref(handle)),
-               "lsh_params_create_ex")
+        _check(lib.lsh_params_create_shared(n, k, m, w, seed, flags, shared_tables, ctypes.byref(handle)),
+               "lsh_params_create_shared")
         self._h = handle
         self.n, self.k, self.m, self.w, self.seed = int(n), int(k), int(m), float(w), int(seed)
 
@@ -140,6 +144,11 @@ class LshParams:
         order = np.empty((self.k, steps.value), np.uint32)
         _check(lib.lsh_params_get_schedule(self.handle, order.ctypes.data, None, None, None, None), "get_schedule")
         return order, group.value, classes.value, passes.value
+
+    def shared_tables(self):
+        L = ctypes.c_uint32()
+        _check(load_library().lsh_params_get_tables(self.handle, ctypes.addressof(L)), "get_tables")
+        return L.value
 
     def shape(self):
         n, k, m, fl = (ctypes.c_uint32() for _ in range(4))

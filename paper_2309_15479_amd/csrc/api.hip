@@ -168,17 +168,19 @@ using namespace lsh;
 
 extern "C" {
 
-int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
-                         lsh_params_t **out) {
+int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
+                             uint32_t L, lsh_params_t **out) {
     if (!out) return LSH_ERR_INVALID_ARG;
     *out = nullptr;
     if (!n || !k || !m || m > n || !(w > 0.f) || !std::isfinite(w)) return LSH_ERR_INVALID_ARG;
     if (flags & ~LSH_SAMPLE_WITH_REPLACEMENT) return LSH_ERR_INVALID_ARG;
     if ((uint64_t)k * m > (1ull << 31)) return LSH_ERR_INVALID_ARG;
+    if (L && k % L) return LSH_ERR_INVALID_ARG;
     lsh_params *p = new (std::nothrow) lsh_params;
     if (!p) return LSH_ERR_ALLOC;
     p->n = n; p->k = k; p->m = m; p->w = w; p->seed = seed; p->flags = flags;
-    int rc = generate_tables(n, k, m, w, seed, flags, p->idx, p->coef, p->off);
+    p->shared_tables = L;
+    int rc = generate_tables(n, k, m, w, seed, flags, L ? k / L : 1, p->idx, p->coef, p->off);
     if (rc == LSH_OK) {
         p->plan = plan_sampled(n, k, m);
         if (p->plan.supported) {
@@ -201,6 +203,11 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
     }
     *out = p;
     return LSH_OK;
+}
+
+int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
+                         lsh_params_t **out) {
+    return lsh_params_create_shared(n, k, m, w, seed, flags, 0, out);
 }
 
 int lsh_params_create(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, lsh_params_t **out) {
@@ -240,6 +247,12 @@ int lsh_params_get_shape(const lsh_params_t *p, uint32_t *n, uint32_t *k, uint32
     if (flags) *flags = p->flags;
     if (w) *w = p->w;
     if (seed) *seed = p->seed;
+    return LSH_OK;
+}
+
+int lsh_params_get_tables(const lsh_params_t *p, uint32_t *shared_tables) {
+    if (!p || !shared_tables) return LSH_ERR_INVALID_ARG;
+    *shared_tables = p->shared_tables;
     return LSH_OK;
 }
 

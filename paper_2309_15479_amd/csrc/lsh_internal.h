@@ -52,6 +52,7 @@ inline uint32_t copy_b_slot(uint32_t c, uint32_t classes) {
 
 struct lsh_params {
     uint32_t n = 0, k = 0, m = 0, flags = 0;
+    uint32_t shared_tables = 0;  // L when the k/L functions of a table share one sample S, else 0
     float w = 0.f;
     uint64_t seed = 0;
     // canonical host tables
@@ -75,8 +76,11 @@ struct lsh_params {
 namespace lsh {
 
 // host: draws the canonical tables (returns LSH_OK / LSH_ERR_*)
+// (sample_group consecutive functions share the sample S of the first of them; 1 = every
+// function its own)
 int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
-                    std::vector<uint32_t> &idx, std::vector<float> &coef, std::vector<float> &off);
+                    uint32_t sample_group, std::vector<uint32_t> &idx, std::vector<float> &coef,
+                    std::vector<float> &off);
 
 // host: bank-conflict-free visiting order of every function's samples (schedule.cpp)
 uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,

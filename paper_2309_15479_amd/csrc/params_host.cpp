@@ -65,7 +65,8 @@ inline double top53(uint64_t word) { return std::ldexp(static_cast<double>(word 
 }  // namespace
 
 int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
-                    std::vector<uint32_t> &idx, std::vector<float> &coef, std::vector<float> &off) {
+                    uint32_t sample_group, std::vector<uint32_t> &idx, std::vector<float> &coef,
+                    std::vector<float> &off) {
     try {
         idx.assign(static_cast<size_t>(k) * m, 0);
         coef.assign(static_cast<size_t>(k) * m, 0.f);
@@ -88,13 +89,15 @@ int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, 
     for (uint32_t j = 0; j < k; ++j) {
         uint32_t *S = &idx[static_cast<size_t>(j) * m];
         float *a = &coef[static_cast<size_t>(j) * m];
+        // sample_group consecutive functions use the draws of the first of them for S
+        const uint32_t owner = j / sample_group * sample_group;
         if (m == n) {
             for (uint32_t i = 0; i < m; ++i) S[i] = i;
         } else if (replace) {
-            for (uint32_t i = 0; i < m; ++i) S[i] = uniform_below(seed, j, i, n);
+            for (uint32_t i = 0; i < m; ++i) S[i] = uniform_below(seed, owner, i, n);
         } else {
             for (uint32_t i = 0; i < m; ++i) {
-                const uint32_t pick = i + uniform_below(seed, j, i, n - i);
+                const uint32_t pick = i + uniform_below(seed, owner, i, n - i);
                 swapped_with[i] = pick;
                 std::swap(deck[i], deck[pick]);
                 S[i] = deck[i];

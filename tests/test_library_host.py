@@ -74,6 +74,27 @@ def test_tables_bit_identical_to_oracle(n, k, m, w, seed, repl):
         assert s["w"] == np.float32(w)
 
 
+@pytest.mark.parametrize("n,k,m,w,seed,repl,L", [
+    (128, 512, 32, 16.0, 2, False, 32), (128, 64, 32, 4.0, 1, False, 8), (100, 72, 30, 2.5, 11, True, 6),
+    (960, 1024, 128, 1.0, 3, False, 64), (64, 60, 64, 1.0, 4, False, 5), (50, 48, 7, 2.0, 9, False, 48),
+])
+def test_shared_sample_tables_bit_identical_to_oracle(n, k, m, w, seed, repl, L):
+    with binding.LshParams(n, k, m, w, seed, with_replacement=repl, shared_tables=L) as p:
+        idx, coef, off = oracle.params_shared(n, k, m, w, seed, L, with_replacement=repl)
+        assert np.array_equal(p.indices(), idx)
+        assert np.array_equal(p.coeffs().view(np.uint32), coef.view(np.uint32))
+        assert np.array_equal(p.offsets().view(np.uint32), off.view(np.uint32))
+        assert p.shared_tables() == L
+    with binding.LshParams(n, k, m, w, seed, with_replacement=repl) as p:
+        assert p.shared_tables() == 0
+
+
+def test_shared_sample_rejects_bad_table_count():
+    with pytest.raises(binding.LshError) as e:
+        binding.LshParams(128, 64, 32, 4.0, 1, shared_tables=7)
+    assert e.value.status == -1
+
+
 def _pass_groups(k, group):
     """Functions served by one pass of an LDS read, as the header documents them."""
     quads = {32: [list(range(8)), list(range(8, 16))],
