@@ -18,6 +18,12 @@ void free_tables(lsh_params *p) {
     if (p->d_off) (void)hipFree(p->d_off);
     if (p->d_dense) (void)hipFree(p->d_dense);
     if (p->d_chunk_info) (void)hipFree(p->d_chunk_info);
+    if (p->d_shared_coef) (void)hipFree(p->d_shared_coef);
+    if (p->d_shared_sample_off) (void)hipFree(p->d_shared_sample_off);
+    if (p->d_shared_offset) (void)hipFree(p->d_shared_offset);
+    p->d_shared_coef = nullptr;
+    p->d_shared_sample_off = nullptr;
+    p->d_shared_offset = nullptr;
     p->d_samples = nullptr;
     p->d_off = nullptr;
     p->d_dense = nullptr;
@@ -129,6 +135,19 @@ int upload_tables(lsh_params *p) {
                                           hipMemcpyHostToDevice) != hipSuccess)
                 rc = LSH_ERR_HIP;
         }
+        if (rc == LSH_OK && p->shared_plan.supported) {
+            std::vector<float> coef, offset;
+            std::vector<uint32_t> sample_off;
+            build_shared_tables(p, coef, sample_off, offset);
+            auto upload = [&](void **dst, const void *src, size_t bytes) {
+                if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
+                if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
+            };
+            upload(reinterpret_cast<void **>(&p->d_shared_coef), coef.data(), coef.size() * sizeof(float));
+            upload(reinterpret_cast<void **>(&p->d_shared_sample_off), sample_off.data(),
+                   sample_off.size() * sizeof(uint32_t));
+            upload(reinterpret_cast<void **>(&p->d_shared_offset), offset.data(), offset.size() * sizeof(float));
+        }
         if (rc == LSH_OK && p->kpad_dense) {
             // m == n: S_j is the identity, so the canonical coefficient table IS the dense
             // matrix A [k][n]; rows up to the tile grid are zero
@@ -183,6 +202,7 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
     int rc = generate_tables(n, k, m, w, seed, flags, L ? k / L : 1, p->idx, p->coef, p->off);
     if (rc == LSH_OK) {
         p->plan = plan_sampled(n, k, m);
+        p->shared_plan = plan_shared(n, k, m, L);
         if (p->plan.supported) {
             try {
                 const SampledPlan &pl = p->plan;
@@ -298,12 +318,14 @@ int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *st
 int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
+    if (p->shared_plan.supported) return launch_shared(p, false, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
 }
 
 int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, float *d_out, void *stream) {
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
+    if (p->shared_plan.supported) return launch_shared(p, true, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);
 }
 

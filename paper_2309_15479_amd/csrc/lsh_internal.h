@@ -38,6 +38,20 @@ struct SampledPlan {
     bool supported = false;
 };
 
+// Plan of the shared-sample kernel (shared_kernel.hip): one sample S per table of g functions.
+struct SharedPlan {
+    uint32_t g = 0;                 // functions per table
+    uint32_t rows = 0;              // vectors per LDS tile
+    uint32_t stride = 0;            // floats per tile row
+    uint32_t ksteps = 0;            // MFMA steps of 4 samples: 8 (m <= 32) or 16 (m <= 64)
+    uint32_t blocks_per_table = 0;  // blocks of 16 functions per table
+    uint32_t nblocks = 0;           // L * blocks_per_table
+    uint32_t rb = 0;                // blocks per wave
+    uint32_t kblocks = 0;           // workgroups along the function axis
+    uint32_t lds_bytes = 0;
+    bool supported = false;
+};
+
 constexpr uint32_t kPadSample = 0x80000000u;  // schedule entry: padding sample | bank class
 constexpr uint32_t kCopyB = 0x40000000u;      // schedule entry: read the sample from the second tile copy
 
@@ -71,6 +85,11 @@ struct lsh_params {
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n] when m == n (row j = a_j), else null
     uint32_t kpad_dense = 0;
+    // one sample per table: operand tables of the shared-sample kernel (null when unsupported)
+    lsh::SharedPlan shared_plan;
+    float *d_shared_coef = nullptr;
+    uint32_t *d_shared_sample_off = nullptr;
+    float *d_shared_offset = nullptr;
 };
 
 namespace lsh {
@@ -98,6 +117,12 @@ void free_tables(lsh_params *p);
 enum class Epilogue : int { Ids = 0, Proj = 1, Signs = 2, Keys = 3 };
 int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                    uint32_t L, void *stream);
+SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
+void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
+                         std::vector<float> &offset);
+int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out, void *stream);
+// raises a kernel's dynamic LDS limit once (per kernel and size)
+int ensure_lds_limit(const void *fn, uint32_t lds_bytes);
 int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
                  void *stream);
 int launch_pack(const lsh_params *p, const int32_t *d_ids, uint64_t N, uint32_t L,

@@ -672,6 +672,16 @@ __global__ __launch_bounds__(1024) void sampled_chunked_kernel(const SampledArgs
     }
 }
 
+template <typename Kernel>
+int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 grid, dim3 block,
+                  hipStream_t stream) {
+    if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP;
+    hipLaunchKernelGGL(fn, grid, block, lds_bytes, stream, args);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+}  // namespace
+
 // hipFuncSetAttribute costs about a millisecond of host time: raise a kernel's dynamic LDS
 // limit once (per kernel and size), not per launch.
 int ensure_lds_limit(const void *fn, uint32_t lds_bytes) {
@@ -685,16 +695,6 @@ int ensure_lds_limit(const void *fn, uint32_t lds_bytes) {
     granted[fn] = lds_bytes;
     return LSH_OK;
 }
-
-template <typename Kernel>
-int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 grid, dim3 block,
-                  hipStream_t stream) {
-    if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP;
-    hipLaunchKernelGGL(fn, grid, block, lds_bytes, stream, args);
-    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
-}
-
-}  // namespace
 
 uint32_t sampled_chunk() { return kChunk; }
 

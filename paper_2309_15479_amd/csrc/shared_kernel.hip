@@ -1,0 +1,280 @@
+// FastLSH with one sample per table (Sec. 3.1 read literally: one multiset S; Sec. 3.2: tables
+// of g = k / L functions) for gfx950:
+//
+//   p_j(v) = sum_{i<m} a~_j[i] * v[S_l[i]],   l = j / g,   h_j(v) = floor((p_j(v) + b~_j) / w)
+//
+// When the g functions of a table share S_l, the table's projections are a small dense
+// product [g x m] . [m x vectors] of the coefficient vectors with the gathered sub-vectors
+// S_l(v): the gather is done once per (vector, table) instead of once per (vector, function),
+// and the multiply-adds move from the vector ALU to the matrix cores.
+//
+// Mapping.  A workgroup of 16 waves walks tiles of `rows` vectors (persistent, double-buffered
+// in LDS as [vector][n + 4] floats, next tile prefetched HBM -> registers during the
+// contraction).  A wave owns RB blocks of 16 consecutive functions (a block lies inside one
+// table) and keeps their coefficients in registers for the whole launch.  Per block and 16
+// vectors it issues KS = ceil(m / 4) `v_mfma_f32_16x16x4_f32`:
+//   row operand    A[i][kq] = a~_{block*16 + i}[4*kk + kq]        lane = i + 16*kq   (registers)
+//   column operand B[kq][c] = v_{vector c}[S_l[4*kk + kq]]         lane = c + 16*kq   (one 4-byte LDS read)
+//   result         D[4*q + r][c] in register r of lane c + 16*q: four consecutive functions
+//                  of one vector per lane, so ids leave as 16-byte stores.
+// The tile's row stride n + 4 puts the 16 vectors of a read 4 banks apart (conflict-free for
+// one coordinate; the two coordinates of a half-wave pass collide only when they are equal
+// modulo 4).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "lsh_internal.h"
+
+namespace lsh {
+namespace {
+
+constexpr uint32_t kLdsBudget = 158u * 1024u;
+constexpr int kPre = 5;           // float4 prefetch registers per lane: rows * n / 4 <= kPre * 1024
+constexpr uint32_t kWaves = 16;   // waves per workgroup
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+struct SharedArgs {
+    const float *data;  // [N][n]
+    uint64_t N;
+    uint32_t n, k, g;
+    uint32_t rows;               // vectors per tile, a multiple of 32
+    uint32_t stride;             // floats per tile row in LDS
+    uint32_t n4_magic;           // floor(2^32 / (n / 4)) + 1: e / (n / 4) = mulhi(e, n4_magic) for e * n / 4 < 2^32
+    uint32_t blocks_per_table;   // ceil(g / 16)
+    uint32_t nblocks;            // L * blocks_per_table
+    const float *coef;           // [blocks][KS][64]   row operands, one float per lane
+    const uint32_t *sample_off;  // [blocks][KS][4]    4 * S_l[4*kk + kq]: byte offset inside a tile row
+    const float *offset;         // [blocks][16]       b~ of the block's functions
+    float w, inv_w;
+    int w_is_pow2;
+    void *out;
+};
+
+template <int KS, int RB, bool PROJ>
+__global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
+    extern __shared__ __align__(16) float tile[];  // 2 x [rows][stride]
+    const uint32_t n = a.n, n4 = n >> 2, rows = a.rows, stride = a.stride;
+    const uint32_t lane = threadIdx.x & 63, c16 = lane & 15, q = lane >> 4;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t block0 = (blockIdx.y * kWaves + wave) * RB;
+    const uint64_t ntiles = (a.N + rows - 1) / rows;
+    const uint32_t buf_floats = rows * stride;
+
+    // this wave's blocks: coefficients, per-lane LDS offsets of the sampled coordinates, b~
+    float cf[RB][KS];
+    uint32_t xo[RB][KS];
+    float bq[RB][4];
+    uint32_t fn0[RB];  // first of the lane's four functions, or >= k when it has none
+#pragma unroll
+    for (int e = 0; e < RB; ++e) {
+        const uint32_t blk = block0 + e;
+        const bool have = blk < a.nblocks;
+        const uint32_t table = blk / a.blocks_per_table, in_table = (blk % a.blocks_per_table) * 16 + q * 4;
+        fn0[e] = have && in_table < a.g ? table * a.g + in_table : a.k;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            cf[e][kk] = have ? a.coef[((size_t)blk * KS + kk) * 64 + lane] : 0.f;
+            xo[e][kk] = (have ? a.sample_off[((size_t)blk * KS + kk) * 4 + q] : 0u) + c16 * stride * 4;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bq[e][r] = have ? a.offset[(size_t)blk * 16 + q * 4 + r] : 0.f;
+    }
+
+    // tile transfer: element e of the tile's float4 sequence = (vector e / n4, coordinates
+    // 4 * (e % n4) ..); the slot arithmetic is redone at every use (it is cheap, and kept in
+    // registers across the contraction it would push the coefficient registers out)
+    float4 pre[kPre];
+    auto opaque = [](uint32_t v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    };
+    auto fetch = [&](uint64_t row0) {
+        const uint32_t tid = opaque(threadIdx.x);
+#pragma unroll
+        for (int f = 0; f < kPre; ++f) {
+            const uint32_t e = tid + f * 1024;
+            const uint32_t r = __umulhi(e, a.n4_magic), c4 = e - r * n4;
+            const bool ok = r < rows && row0 + r < a.N;
+            pre[f] = ok ? *reinterpret_cast<const float4 *>(a.data + (row0 + r) * n + c4 * 4)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto stash = [&](float *buf) {
+        const uint32_t tid = opaque(threadIdx.x);
+#pragma unroll
+        for (int f = 0; f < kPre; ++f) {
+            const uint32_t e = tid + f * 1024;
+            const uint32_t r = __umulhi(e, a.n4_magic), c4 = e - r * n4;
+            if (r < rows) *reinterpret_cast<float4 *>(buf + r * stride + c4 * 4) = pre[f];
+        }
+    };
+
+    uint64_t t = blockIdx.x;
+    if (t >= ntiles) return;
+    fetch(t * rows);
+    stash(tile);
+    __syncthreads();
+    uint32_t cur = 0;
+    for (; t < ntiles; t += gridDim.x) {
+        const uint64_t row0 = t * rows;
+        const uint64_t t_next = t + gridDim.x;
+        if (t_next < ntiles) fetch(t_next * rows);
+
+        const char *base = reinterpret_cast<const char *>(tile + cur * buf_floats);
+        for (uint32_t vb = 0; vb < rows / 16; vb += 2) {  // two blocks of 16 vectors at a time
+            float4v acc[2][RB];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < RB; ++e) acc[u][e] = float4v{0.f, 0.f, 0.f, 0.f};
+            // byte offsets of the two vector blocks (wave-uniform; opaque so that the compiler
+            // adds them at each read instead of keeping xo + offset for both blocks in registers)
+            uint32_t voff[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                voff[u] = (vb + u) * 16 * stride * 4;
+                asm volatile("" : "+s"(voff[u]));
+            }
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e = 0; e < RB; ++e) {
+                        const float x = *reinterpret_cast<const float *>(base + (voff[u] + xo[e][kk]));
+                        acc[u][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(cf[e][kk], x, acc[u][e], 0, 0, 0);
+                    }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint64_t row = row0 + (vb + u) * 16 + opaque(c16);
+#pragma unroll
+                for (int e = 0; e < RB; ++e) {
+                    uint32_t v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float p = acc[u][e][r];
+                        if (PROJ) {
+                            v[r] = __float_as_uint(p);
+                        } else {
+                            const float s = a.w_is_pow2 ? fmaf(p, a.inv_w, bq[e][r] * a.inv_w) : (p + bq[e][r]) / a.w;
+                            v[r] = (uint32_t)(int)floorf(s);
+                        }
+                    }
+                    if (fn0[e] < a.k && row < a.N)
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint32_t *>(a.out) + row * a.k + fn0[e]) =
+                            make_uint4(v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
+
+        if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
+        __syncthreads();  // next buffer complete; everyone is done with the current one
+        cur ^= 1;
+    }
+}
+
+template <typename Kernel>
+int launch(Kernel fn, uint32_t lds_bytes, const SharedArgs &args, dim3 grid, hipStream_t stream) {
+    if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP;
+    hipLaunchKernelGGL(fn, grid, dim3(1024), lds_bytes, stream, args);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+}  // namespace
+
+// Shapes the kernel takes: n a multiple of 4 whose tile of >= 32 vectors fits LDS twice, lists
+// of at most 64 samples, tables of a multiple of 4 functions.
+SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
+    SharedPlan pl;
+    if (!L || k % L || (n & 3) || m > 64 || m == n) return pl;
+    const uint32_t g = k / L;
+    if (g & 3) return pl;
+    pl.stride = n + 4;
+    for (uint32_t rows : {128u, 64u, 32u}) {
+        if (2ull * rows * pl.stride * 4 > kLdsBudget || (uint64_t)rows * (n / 4) > (uint64_t)kPre * 1024) continue;
+        pl.rows = rows;
+        break;
+    }
+    if (!pl.rows) return pl;
+    pl.g = g;
+    pl.ksteps = m <= 32 ? 8 : 16;
+    pl.blocks_per_table = (g + 15) / 16;
+    pl.nblocks = L * pl.blocks_per_table;
+    const uint32_t rb_max = 16 / pl.ksteps;  // coefficients + offsets of a wave's blocks: 2 * rb * ksteps registers
+    pl.rb = 1;
+    while (pl.rb < rb_max && kWaves * pl.rb < pl.nblocks) pl.rb *= 2;
+    pl.kblocks = (pl.nblocks + kWaves * pl.rb - 1) / (kWaves * pl.rb);
+    pl.lds_bytes = 2 * pl.rows * pl.stride * 4;
+    pl.supported = true;
+    return pl;
+}
+
+// Device tables in the kernel's operand layout (see the file comment).
+void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
+                         std::vector<float> &offset) {
+    const SharedPlan &pl = p->shared_plan;
+    const uint32_t ks = pl.ksteps, blocks = pl.kblocks * kWaves * pl.rb;
+    coef.assign((size_t)blocks * ks * 64, 0.f);
+    sample_off.assign((size_t)blocks * ks * 4, 0u);
+    offset.assign((size_t)blocks * 16, 0.f);
+    for (uint32_t blk = 0; blk < pl.nblocks; ++blk) {
+        const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
+        for (uint32_t kk = 0; kk < ks; ++kk)
+            for (uint32_t kq = 0; kq < 4; ++kq) {
+                const uint32_t s = kk * 4 + kq;  // sample number; beyond m: coefficient 0, coordinate 0
+                if (s < p->m)
+                    sample_off[((size_t)blk * ks + kk) * 4 + kq] = 4u * p->idx[(size_t)table * pl.g * p->m + s];
+                for (uint32_t i = 0; i < 16; ++i) {
+                    const uint32_t in_table = first + i;
+                    if (s < p->m && in_table < pl.g)
+                        coef[((size_t)blk * ks + kk) * 64 + kq * 16 + i] =
+                            p->coef[(size_t)(table * pl.g + in_table) * p->m + s];
+                }
+            }
+        for (uint32_t i = 0; i < 16; ++i)
+            if (first + i < pl.g) offset[(size_t)blk * 16 + i] = p->off[table * pl.g + first + i];
+    }
+}
+
+int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out, void *stream) {
+    const SharedPlan &pl = p->shared_plan;
+    if (!pl.supported) return LSH_ERR_UNSUPPORTED;
+    SharedArgs a;
+    a.data = d_data;
+    a.N = N;
+    a.n = p->n;
+    a.k = p->k;
+    a.g = pl.g;
+    a.rows = pl.rows;
+    a.stride = pl.stride;
+    a.n4_magic = (uint32_t)((1ull << 32) / (p->n / 4)) + 1;
+    a.blocks_per_table = pl.blocks_per_table;
+    a.nblocks = pl.nblocks;
+    a.coef = p->d_shared_coef;
+    a.sample_off = p->d_shared_sample_off;
+    a.offset = p->d_shared_offset;
+    a.w = p->w;
+    a.inv_w = 1.0f / p->w;
+    int exp2 = 0;
+    a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
+    a.out = d_out;
+    const uint64_t ntiles = (N + pl.rows - 1) / pl.rows;
+    // one workgroup per CU (the tile buffers take most of its LDS); a multiple of 8 along x, so
+    // that the kblocks workgroups sharing a vector tile land on one XCD
+    uint64_t gx = (uint64_t)p->num_cus / pl.kblocks;
+    gx = gx < 8 ? 8 : gx / 8 * 8;
+    if (gx > ntiles) gx = ntiles;
+    dim3 grid((uint32_t)gx, pl.kblocks);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+#define LSH_SHARED_CASE(KS_, RB_) \
+    if (pl.ksteps == KS_ && pl.rb == RB_) \
+        return proj ? launch(&shared_kernel<KS_, RB_, true>, pl.lds_bytes, a, grid, s) \
+                    : launch(&shared_kernel<KS_, RB_, false>, pl.lds_bytes, a, grid, s);
+    LSH_SHARED_CASE(8, 1) LSH_SHARED_CASE(8, 2) LSH_SHARED_CASE(16, 1)
+#undef LSH_SHARED_CASE
+    return LSH_ERR_UNSUPPORTED;
+}
+
+}  // namespace lsh

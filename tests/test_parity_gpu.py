@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 import workloads
-from parity import check_ids, check_proj, check_signs
+from parity import BAND, check_ids, check_proj, check_signs
 
 pytestmark = pytest.mark.gpu
 
@@ -71,9 +71,16 @@ def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=Tr
         assert np.array_equal(keys[rows_t].cpu().numpy().view(np.uint64), want), label + " keys"
         g = p.k // L
         if g & (g - 1) == 0 and g <= 64:
+            # fused hashing + packing: the oracle's keys, except for keys that hold an id inside
+            # the boundary band (the fused kernel may sum in another order than the ids kernel)
             fused = lsh.hash_fastlsh_keys(p, data_gpu, L)
             torch.cuda.synchronize()
-            assert torch.equal(fused, keys), label + " fused keys"
+            got = fused[rows_t].cpu().numpy().view(np.uint64)
+            near = (ora["frac"] < BAND) | (ora["frac"] > 1.0 - BAND)
+            key_near = near.reshape(len(rows_t), L, g).any(axis=2)
+            bad = (got != oracle.pack_keys(ora["ids"], L)) & ~key_near
+            assert not bad.any(), f"{label} fused keys: {int(bad.sum())} keys differ outside the boundary band"
+            stats["fused_keys_excluded"] = float(key_near.mean())
     return stats
 
 
@@ -124,6 +131,37 @@ def test_ragged_shapes(lsh, N, n, k, m, w, seed, repl, L):
     data = torch.randn((N, n), generator=g, device="cuda") * 3.0
     with lsh.LshParams(n, k, m, w, seed, with_replacement=repl) as p:
         say(_compare_all(lsh, p, data, np.arange(N), L=L, label=f"ragged{seed}", dense=(m == n)))
+
+
+# ---------------------------------------------------------------------------------------
+# one sample per table: the matrix-core kernel and the shapes that fall back to the gather kernels
+# ---------------------------------------------------------------------------------------
+
+SHARED = [
+    # N, n, k, m, w, seed, with_replacement, L
+    (1000, 128, 64, 32, 4.0, 41, False, 8),      # tables of 8 functions: half-empty 16-function blocks
+    (1003, 128, 512, 32, 16.0, 42, False, 32),   # the benchmark shape: two blocks per wave, ragged tail
+    (77, 100, 72, 30, 2.5, 43, True, 6),         # tables of 12, duplicates in S, w not a power of two
+    (300, 256, 512, 64, 4.0, 44, False, 16),     # tables of 32 (two blocks each), 16 MFMA steps, 64-vector tiles
+    (50, 612, 64, 20, 2.0, 45, False, 4),        # 32-vector tiles
+    (200, 64, 2048, 8, 1.0, 46, False, 128),     # several workgroups along the functions
+    (1, 128, 16, 4, 1.0, 47, False, 1),          # one vector, one table
+    (40, 130, 64, 16, 1.0, 48, False, 8),        # n not a multiple of 4: gather kernels
+    (40, 960, 128, 128, 1.0, 49, False, 8),      # m > 64: gather kernels
+    (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
+]
+
+
+@pytest.mark.parametrize("N,n,k,m,w,seed,repl,L", SHARED)
+def test_shared_sample_shapes(lsh, N, n, k, m, w, seed, repl, L):
+    say(f"shared case N={N} n={n} k={k} m={m} w={w} seed={seed} repl={repl} L={L}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    data = torch.randn((N, n), generator=g, device="cuda") * 3.0
+    with lsh.LshParams(n, k, m, w, seed, with_replacement=repl, shared_tables=L) as p:
+        idx, coef, off = oracle.params_shared(n, k, m, w, seed, L, with_replacement=repl)
+        assert np.array_equal(p.indices(), idx) and np.array_equal(p.coeffs().view(np.uint32), coef.view(np.uint32))
+        say(_compare_all(lsh, p, data, np.arange(N), L=L, label=f"shared{seed}"))
 
 
 @pytest.mark.parametrize("N,n,k", [(130, 128, 128), (129, 100, 200), (1, 37, 5), (515, 36, 257), (64, 4096, 64)])
@@ -214,6 +252,13 @@ def test_sift_full_size(lsh):
         say("sift fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="sift"))
     with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
         say("sift e2lsh", _compare_all(lsh, p, data, rows, label="sift-dense", dense=True, signs=False))
+
+
+def test_sift_full_size_shared_sample(lsh):
+    wl, data = workloads.make_data("sift", "cuda")
+    rows = _sampled(wl.N, 4096)
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
+        say("sift shared-sample fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="sift-shared"))
 
 
 def test_gist_full_size(lsh):
