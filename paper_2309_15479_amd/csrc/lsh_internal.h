@@ -42,6 +42,8 @@ struct SampledPlan {
 struct SharedPlan {
     uint32_t g = 0;                 // functions per table
     uint32_t rows = 0;              // vectors per LDS tile
+    uint32_t waves = 0;             // waves per workgroup (16 or 8)
+    uint32_t per_cu = 0;            // workgroups per CU
     uint32_t stride = 0;            // floats per tile row
     uint32_t ksteps = 0;            // MFMA steps of 4 samples: 8 (m <= 32) or 16 (m <= 64)
     uint32_t blocks_per_table = 0;  // blocks of 16 functions per table

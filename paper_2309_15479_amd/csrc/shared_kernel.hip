@@ -30,8 +30,7 @@ namespace lsh {
 namespace {
 
 constexpr uint32_t kLdsBudget = 158u * 1024u;
-constexpr int kPre = 5;           // float4 prefetch registers per lane: rows * n / 4 <= kPre * 1024
-constexpr uint32_t kWaves = 16;   // waves per workgroup
+constexpr int kPre = 5;           // float4 prefetch registers per lane: rows * n / 4 <= kPre * lanes
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
@@ -52,8 +51,10 @@ struct SharedArgs {
     void *out;
 };
 
-template <int KS, int RB, bool PROJ>
-__global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
+template <int KS, int RB, int WAVES, bool PROJ>
+__global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs a) {
+    constexpr uint32_t kWaves = WAVES, kLanes = WAVES * 64;
+    constexpr int VB = RB >= 4 ? 1 : 2;  // blocks of 16 vectors in flight: VB * RB independent accumulators
     extern __shared__ __align__(16) float tile[];  // 2 x [rows][stride]
     const uint32_t n = a.n, n4 = n >> 2, rows = a.rows, stride = a.stride;
     const uint32_t lane = threadIdx.x & 63, c16 = lane & 15, q = lane >> 4;
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
             xo[e][kk] = (have ? a.sample_off[((size_t)blk * KS + kk) * 4 + q] : 0u) + c16 * stride * 4;
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bq[e][r] = have ? a.offset[(size_t)blk * 16 + q * 4 + r] : 0.f;
+        for (int r = 0; r < 4; ++r) bq[e][r] = a.offset[(size_t)blk * 16 + q * 4 + r];  // padded to every wave's blocks
     }
 
     // tile transfer: element e of the tile's float4 sequence = (vector e / n4, coordinates
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
         const uint32_t tid = opaque(threadIdx.x);
 #pragma unroll
         for (int f = 0; f < kPre; ++f) {
-            const uint32_t e = tid + f * 1024;
+            const uint32_t e = tid + f * kLanes;
             const uint32_t r = __umulhi(e, a.n4_magic), c4 = e - r * n4;
             const bool ok = r < rows && row0 + r < a.N;
             pre[f] = ok ? *reinterpret_cast<const float4 *>(a.data + (row0 + r) * n + c4 * 4)
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
         const uint32_t tid = opaque(threadIdx.x);
 #pragma unroll
         for (int f = 0; f < kPre; ++f) {
-            const uint32_t e = tid + f * 1024;
+            const uint32_t e = tid + f * kLanes;
             const uint32_t r = __umulhi(e, a.n4_magic), c4 = e - r * n4;
             if (r < rows) *reinterpret_cast<float4 *>(buf + r * stride + c4 * 4) = pre[f];
         }
@@ -123,31 +124,46 @@ __global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
         if (t_next < ntiles) fetch(t_next * rows);
 
         const char *base = reinterpret_cast<const char *>(tile + cur * buf_floats);
-        for (uint32_t vb = 0; vb < rows / 16; vb += 2) {  // two blocks of 16 vectors at a time
-            float4v acc[2][RB];
+        for (uint32_t vb = 0; vb < rows / 16; vb += VB) {
+            float4v acc[VB][RB];
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < VB; ++u)
 #pragma unroll
                 for (int e = 0; e < RB; ++e) acc[u][e] = float4v{0.f, 0.f, 0.f, 0.f};
-            // byte offsets of the two vector blocks (wave-uniform; opaque so that the compiler
+            // byte offsets of the vector blocks (wave-uniform; opaque so that the compiler
             // adds them at each read instead of keeping xo + offset for both blocks in registers)
-            uint32_t voff[2];
+            uint32_t voff[VB];
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < VB; ++u) {
                 voff[u] = (vb + u) * 16 * stride * 4;
                 asm volatile("" : "+s"(voff[u]));
             }
+            // software pipeline: the LDS reads of step kk + kAhead are issued before the MFMAs of
+            // step kk (scheduling barriers keep the compiler from batching reads and MFMAs apart)
+            constexpr int kAhead = 2;
+            float x[kAhead + 1][VB][RB];
+            auto read_step = [&](int kk) {
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
+                for (int u = 0; u < VB; ++u)
 #pragma unroll
-                for (int u = 0; u < 2; ++u)
+                    for (int e = 0; e < RB; ++e)
+                        x[kk % (kAhead + 1)][u][e] = *reinterpret_cast<const float *>(base + (voff[u] + xo[e][kk]));
+            };
 #pragma unroll
-                    for (int e = 0; e < RB; ++e) {
-                        const float x = *reinterpret_cast<const float *>(base + (voff[u] + xo[e][kk]));
-                        acc[u][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(cf[e][kk], x, acc[u][e], 0, 0, 0);
-                    }
+            for (int kk = 0; kk < kAhead; ++kk) read_step(kk);
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int kk = 0; kk < KS; ++kk) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (kk + kAhead < KS) read_step(kk + kAhead);
+#pragma unroll
+                for (int u = 0; u < VB; ++u)
+#pragma unroll
+                    for (int e = 0; e < RB; ++e)
+                        acc[u][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(cf[e][kk], x[kk % (kAhead + 1)][u][e], acc[u][e], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < VB; ++u) {
                 const uint64_t row = row0 + (vb + u) * 16 + opaque(c16);
 #pragma unroll
                 for (int e = 0; e < RB; ++e) {
@@ -176,9 +192,9 @@ __global__ __launch_bounds__(1024) void shared_kernel(const SharedArgs a) {
 }
 
 template <typename Kernel>
-int launch(Kernel fn, uint32_t lds_bytes, const SharedArgs &args, dim3 grid, hipStream_t stream) {
+int launch(Kernel fn, uint32_t lds_bytes, const SharedArgs &args, dim3 grid, uint32_t lanes, hipStream_t stream) {
     if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP;
-    hipLaunchKernelGGL(fn, grid, dim3(1024), lds_bytes, stream, args);
+    hipLaunchKernelGGL(fn, grid, dim3(lanes), lds_bytes, stream, args);
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
 
@@ -192,20 +208,27 @@ SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
     const uint32_t g = k / L;
     if (g & 3) return pl;
     pl.stride = n + 4;
-    for (uint32_t rows : {128u, 64u, 32u}) {
-        if (2ull * rows * pl.stride * 4 > kLdsBudget || (uint64_t)rows * (n / 4) > (uint64_t)kPre * 1024) continue;
-        pl.rows = rows;
-        break;
-    }
-    if (!pl.rows) return pl;
     pl.g = g;
     pl.ksteps = m <= 32 ? 8 : 16;
     pl.blocks_per_table = (g + 15) / 16;
     pl.nblocks = L * pl.blocks_per_table;
-    const uint32_t rb_max = 16 / pl.ksteps;  // coefficients + offsets of a wave's blocks: 2 * rb * ksteps registers
+    // One workgroup of 16 waves per CU with the largest tile that fits LDS twice (two
+    // workgroups of 8 waves on 64-vector tiles measured slower).  A wave keeps 2 * rb * ksteps
+    // coefficient and offset registers: at most 32 of a lane's 128.
+    struct Shape { uint32_t waves, rows, per_cu; };
+    for (const Shape sh : {Shape{16, 128, 1}, Shape{16, 64, 1}, Shape{16, 32, 1}}) {
+        if (2ull * sh.rows * pl.stride * 4 * sh.per_cu > kLdsBudget) continue;
+        if ((uint64_t)sh.rows * (n / 4) > (uint64_t)kPre * sh.waves * 64) continue;
+        pl.waves = sh.waves;
+        pl.rows = sh.rows;
+        pl.per_cu = sh.per_cu;
+        break;
+    }
+    if (!pl.rows) return pl;
+    const uint32_t rb_max = (pl.waves == 8 ? 32 : 16) / pl.ksteps;
     pl.rb = 1;
-    while (pl.rb < rb_max && kWaves * pl.rb < pl.nblocks) pl.rb *= 2;
-    pl.kblocks = (pl.nblocks + kWaves * pl.rb - 1) / (kWaves * pl.rb);
+    while (pl.rb < rb_max && pl.waves * pl.rb < pl.nblocks) pl.rb *= 2;
+    pl.kblocks = (pl.nblocks + pl.waves * pl.rb - 1) / (pl.waves * pl.rb);
     pl.lds_bytes = 2 * pl.rows * pl.stride * 4;
     pl.supported = true;
     return pl;
@@ -215,7 +238,7 @@ SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
                          std::vector<float> &offset) {
     const SharedPlan &pl = p->shared_plan;
-    const uint32_t ks = pl.ksteps, blocks = pl.kblocks * kWaves * pl.rb;
+    const uint32_t ks = pl.ksteps, blocks = pl.kblocks * pl.waves * pl.rb;
     coef.assign((size_t)blocks * ks * 64, 0.f);
     sample_off.assign((size_t)blocks * ks * 4, 0u);
     offset.assign((size_t)blocks * 16, 0.f);
@@ -261,18 +284,18 @@ int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t 
     a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
     a.out = d_out;
     const uint64_t ntiles = (N + pl.rows - 1) / pl.rows;
-    // one workgroup per CU (the tile buffers take most of its LDS); a multiple of 8 along x, so
-    // that the kblocks workgroups sharing a vector tile land on one XCD
-    uint64_t gx = (uint64_t)p->num_cus / pl.kblocks;
+    // persistent workgroups, as many as fit the CUs; a multiple of 8 along x, so that the
+    // kblocks workgroups sharing a vector tile land on one XCD
+    uint64_t gx = (uint64_t)p->num_cus * pl.per_cu / pl.kblocks;
     gx = gx < 8 ? 8 : gx / 8 * 8;
     if (gx > ntiles) gx = ntiles;
     dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-#define LSH_SHARED_CASE(KS_, RB_) \
-    if (pl.ksteps == KS_ && pl.rb == RB_) \
-        return proj ? launch(&shared_kernel<KS_, RB_, true>, pl.lds_bytes, a, grid, s) \
-                    : launch(&shared_kernel<KS_, RB_, false>, pl.lds_bytes, a, grid, s);
-    LSH_SHARED_CASE(8, 1) LSH_SHARED_CASE(8, 2) LSH_SHARED_CASE(16, 1)
+#define LSH_SHARED_CASE(KS_, RB_, WAVES_) \
+    if (pl.ksteps == KS_ && pl.rb == RB_ && pl.waves == WAVES_) \
+        return proj ? launch(&shared_kernel<KS_, RB_, WAVES_, true>, pl.lds_bytes, a, grid, WAVES_ * 64, s) \
+                    : launch(&shared_kernel<KS_, RB_, WAVES_, false>, pl.lds_bytes, a, grid, WAVES_ * 64, s);
+    LSH_SHARED_CASE(8, 1, 16) LSH_SHARED_CASE(8, 2, 16) LSH_SHARED_CASE(16, 1, 16)
 #undef LSH_SHARED_CASE
     return LSH_ERR_UNSUPPORTED;
 }
