@@ -51,6 +51,7 @@ struct SharedPlan {
     uint32_t rb = 0;                // blocks per wave
     uint32_t kblocks = 0;           // workgroups along the function axis
     uint32_t lds_bytes = 0;
+    bool staged = false;            // ids leave as whole 128-byte lines (lanes pair up their 16-byte pieces)
     bool supported = false;
 };
 

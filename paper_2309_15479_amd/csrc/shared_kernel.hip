@@ -48,6 +48,7 @@ struct SharedArgs {
     const float *offset;         // [blocks][16]       b~ of the block's functions
     float w, inv_w;
     int w_is_pow2;
+    int staged;                  // two-block waves pair up their pieces into whole 128-byte lines (needs g % 16 == 0)
     void *out;
 };
 
@@ -164,24 +165,57 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < VB; ++u) {
-                const uint64_t row = row0 + (vb + u) * 16 + opaque(c16);
+                uint4 v[RB];
 #pragma unroll
                 for (int e = 0; e < RB; ++e) {
-                    uint32_t v[4];
+                    uint32_t w4[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float p = acc[u][e][r];
                         if (PROJ) {
-                            v[r] = __float_as_uint(p);
+                            w4[r] = __float_as_uint(p);
                         } else {
                             const float s = a.w_is_pow2 ? fmaf(p, a.inv_w, bq[e][r] * a.inv_w) : (p + bq[e][r]) / a.w;
-                            v[r] = (uint32_t)(int)floorf(s);
+                            w4[r] = (uint32_t)(int)floorf(s);
                         }
                     }
-                    if (fn0[e] < a.k && row < a.N)
-                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint32_t *>(a.out) + row * a.k + fn0[e]) =
-                            make_uint4(v[0], v[1], v[2], v[3]);
+                    v[e] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
                 }
+                if constexpr (RB == 2) {
+                    if (a.staged) {  // uniform
+                        // The wave's two blocks are 32 consecutive functions = 128 bytes of a
+                        // vector's ids, held as 16-byte pieces by 8 lanes: lanes (c, q), q = 0..3,
+                        // hold piece q (block 0) and piece 4 + q (block 1) of vector c.  Lanes c
+                        // and c ^ 8 swap one piece each (a rotation by 8 inside the row of 16
+                        // lanes, DPP), after which one store covers vectors 0..7 and another
+                        // vectors 8..15 with whole 128-byte lines (a store that leaves 64-byte
+                        // halves of 16 lines is a fifth slower on this memory system).
+                        const uint32_t lane_o = opaque(lane);
+                        const bool upper = lane_o & 8;
+                        const uint4 give = upper ? v[0] : v[1];
+                        uint4 got;
+                        got.x = (uint32_t)__builtin_amdgcn_mov_dpp((int)give.x, 0x128, 0xf, 0xf, true);  // row_ror:8
+                        got.y = (uint32_t)__builtin_amdgcn_mov_dpp((int)give.y, 0x128, 0xf, 0xf, true);
+                        got.z = (uint32_t)__builtin_amdgcn_mov_dpp((int)give.z, 0x128, 0xf, 0xf, true);
+                        got.w = (uint32_t)__builtin_amdgcn_mov_dpp((int)give.w, 0x128, 0xf, 0xf, true);
+                        // lane (c, q): piece q of vector c % 8 (+ 8 for the second store) when c < 8,
+                        // piece 4 + q when c >= 8
+                        const uint4 first = upper ? got : v[0], second = upper ? v[1] : got;
+                        const uint64_t row = row0 + (vb + u) * 16 + (lane_o & 7);
+                        uint32_t *dst = reinterpret_cast<uint32_t *>(a.out) + row * a.k + block0 * 16 +
+                                        ((upper ? 4u : 0u) + (lane_o >> 4)) * 4;
+                        if (block0 < a.nblocks) {
+                            if (row < a.N) *reinterpret_cast<uint4 *>(dst) = first;
+                            if (row + 8 < a.N) *reinterpret_cast<uint4 *>(dst + 8 * (size_t)a.k) = second;
+                        }
+                        continue;
+                    }
+                }
+                const uint64_t row = row0 + (vb + u) * 16 + opaque(c16);
+#pragma unroll
+                for (int e = 0; e < RB; ++e)
+                    if (fn0[e] < a.k && row < a.N)
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint32_t *>(a.out) + row * a.k + fn0[e]) = v[e];
             }
         }
 
@@ -230,6 +264,8 @@ SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
     while (pl.rb < rb_max && pl.waves * pl.rb < pl.nblocks) pl.rb *= 2;
     pl.kblocks = (pl.nblocks + pl.waves * pl.rb - 1) / (pl.waves * pl.rb);
     pl.lds_bytes = 2 * pl.rows * pl.stride * 4;
+    // whole-line stores when a wave's two blocks are 32 consecutive functions and every block is full
+    pl.staged = pl.rb == 2 && g % 16 == 0 && pl.nblocks % 2 == 0;
     pl.supported = true;
     return pl;
 }
@@ -283,6 +319,7 @@ int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t 
     int exp2 = 0;
     a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
     a.out = d_out;
+    a.staged = pl.staged ? 1 : 0;
     const uint64_t ntiles = (N + pl.rows - 1) / pl.rows;
     // persistent workgroups, as many as fit the CUs; a multiple of 8 along x, so that the
     // kblocks workgroups sharing a vector tile land on one XCD
