@@ -162,6 +162,24 @@ def main():
         rooflines[s]["alu_frac_of_unpacked_fp32_issue_rate"] = alu / VALU_FP32_UNPACKED_TFLOPS
     dominant = max(stages, key=lambda s: ms[s])
 
+    # Outside the timed step: the same FastLSH shape with one sample per table (L = 32 tables
+    # of 16 functions), which runs on the matrix cores; reported beside the step's kernels.
+    p_shared = lsh.LshParams(n, k, m, wl.w, wl.seed, shared_tables=L)
+    for _ in range(args.warmup):
+        lsh.hash_fastlsh(p_shared, data, out=ids_f)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        lsh.hash_fastlsh(p_shared, data, out=ids_f)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_shared = e0.elapsed_time(e1) / args.steps
+    a = N * (4 * n + 4 * k) / (ms_shared * 1e-3) / 1e9
+    shared_sample = {"ms": ms_shared, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": a / HBM_PEAK_GBS, "traffic": None,
+                     "mfma_tflops": 2.0 * N * k * m / (ms_shared * 1e-3) / 1e12,
+                     "hashes_per_s": N * k / (ms_shared * 1e-3)}
+
     hashes_per_step = 3.0 * N * k
     out = {
         "metric": "hashes/sec (N*k per sec), FastLSH vs E2LSH, 1 GPU",
@@ -187,6 +205,7 @@ def main():
         "dominant_kernel": dominant,
         "roofline": rooflines[dominant],
         "rooflines": rooflines,
+        "fastlsh_shared_sample_per_table": shared_sample,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, data, p_fast, p_dense)

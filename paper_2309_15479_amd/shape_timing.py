@@ -61,6 +61,16 @@ def main(names):
                         print(f"{name} m={m} fastlsh_keys L={wl.L}: {ms:.3f} ms  "
                               f"{N * (4 * n + 8 * wl.L) / ms / 1e6:.0f} GB/s algorithmic", flush=True)
                 del out
+            if wl.L and not wl.signs:
+                # one sample per table (matrix-core kernel where the shape allows)
+                with lsh.LshParams(n, k, m, wl.w, wl.seed, shared_tables=wl.L) as p:
+                    out = torch.empty((N, k), dtype=torch.int32, device="cuda")
+                    settle(lambda reps: lsh.time_launches(p, "fastlsh", data, out, reps=reps))
+                    ms = lsh.time_launches(p, "fastlsh", data, out, reps=10)
+                    print(f"{name} n={n} k={k} m={m} fastlsh, one sample per table (L={wl.L}): {ms:.3f} ms  "
+                          f"{N * (4 * n + 4 * k) / ms / 1e6:.0f} GB/s algorithmic  "
+                          f"{2 * N * k * m / ms / 1e9:.1f} TFLOP/s", flush=True)
+                    del out
         if not wl.signs:
             with lsh.LshParams(n, k, n, wl.w, wl.seed) as p:
                 out = torch.empty((N, k), dtype=torch.int32, device="cuda")
