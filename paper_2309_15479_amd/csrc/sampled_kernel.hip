@@ -31,6 +31,9 @@ namespace {
 
 constexpr int kChunk = 32;                     // samples held in registers at a time
 constexpr uint32_t kLdsBudget = 158u * 1024u;  // of the CU's 160 KB
+// chunked kernel: 64-coordinate pieces of the next chunk a wave prefetches into registers
+// (6 x 16 waves cover the 1376 coordinates x 4 sub-tiles that fill LDS)
+constexpr int kChunkPre = 6;
 
 template <int RT>
 __device__ __forceinline__ void lds_read_slot(const char *slot, float (&x)[RT]) {
@@ -531,7 +534,7 @@ template <int SUB, int FPT, int EP>
 __global__ __launch_bounds__(1024) void sampled_chunked_kernel(const SampledArgs a) {
     constexpr int RT = 4;
     constexpr int kStep = 8;   // list entries fetched at a time; list lengths are multiples of it
-    constexpr int kPre = 8;    // 64-coordinate pieces of the next chunk a wave holds in registers
+    constexpr int kPre = kChunkPre;  // 64-coordinate pieces of the next chunk a wave holds in registers
     extern __shared__ __align__(16) float tile[];  // [chunk + classes][SP][RT]
     constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
     constexpr uint32_t kTileRows = RT * SUB;
@@ -738,10 +741,10 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
     if (!pl.reg_table && (pl.rt != 4 || pl.sub < 4) && k64 >= 512) {  // enough waves to prefetch a chunk
         const uint32_t slot = 5 * 16;  // SUB = 4: 5 slots of 16 bytes per coordinate
         const uint32_t block = k64 >= 1024 ? 1024 : k64;
-        // the chunk must fit in LDS and its pieces in the waves' prefetch registers (8 pieces
+        // the chunk must fit in LDS and its pieces in the waves' prefetch registers (kChunkPre pieces
         // of 64 coordinates x 4 sub-tiles per wave)
         uint32_t cmax = (kLdsBudget / slot - 16) / 16 * 16;
-        const uint32_t by_regs = 8 * (block / 64) / 4 * 64;
+        const uint32_t by_regs = (uint32_t)kChunkPre * (block / 64) / 4 * 64;
         if (cmax > by_regs) cmax = by_regs;
         pl.nchunks = (n + cmax - 1) / cmax;
         pl.chunk = ((n + pl.nchunks - 1) / pl.nchunks + 15) / 16 * 16;
