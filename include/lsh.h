@@ -77,10 +77,11 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
  * lsh_params_create_ex; a~_j and b~_j stay per function.  Given S, the functions of a table
  * are independent E2LSH functions on the same sub-vector (Sec. 4.1), so a table's key collides
  * with probability p_w(s~)^g given S instead of the product over g independent samples.
- * Every hash call accepts such an object; lsh_hash_fastlsh and lsh_project_fastlsh then gather
- * each table's sub-vector once and contract it with the g coefficient vectors on the matrix
- * cores when the shape allows (n % 4 == 0, n <= 304, m <= 64, g % 4 == 0), and fall back to
- * the per-function gather kernels otherwise.  L == 0 is lsh_params_create_ex.
+ * Every hash call accepts such an object; lsh_hash_fastlsh, lsh_project_fastlsh and (called
+ * with the same L, g <= 32) lsh_hash_fastlsh_keys then gather each table's sub-vector once and
+ * contract it with the g coefficient vectors on the matrix cores when the shape allows
+ * (n % 4 == 0, n <= 612, m <= 64, g % 4 == 0), and fall back to the per-function gather
+ * kernels otherwise.  L == 0 is lsh_params_create_ex.
  * Errors: as lsh_params_create, and INVALID_ARG when k % L != 0.
  */
 int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,

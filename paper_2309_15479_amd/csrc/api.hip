@@ -318,14 +318,14 @@ int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *st
 int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
-    if (p->shared_plan.supported) return launch_shared(p, false, d_data, N, d_out, stream);
+    if (p->shared_plan.supported) return launch_shared(p, 0, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
 }
 
 int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, float *d_out, void *stream) {
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
-    if (p->shared_plan.supported) return launch_shared(p, true, d_data, N, d_out, stream);
+    if (p->shared_plan.supported) return launch_shared(p, 1, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);
 }
 
@@ -343,6 +343,7 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
     const uint32_t g = p->k / L;
     if (!is_pow2(g) || g > 64) return LSH_ERR_UNSUPPORTED;
     if (N == 0) return LSH_OK;
+    if (shared_keys_ok(p, L)) return launch_shared(p, 2, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
 }
 

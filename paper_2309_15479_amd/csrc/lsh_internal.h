@@ -123,7 +123,10 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
                          std::vector<float> &offset);
-int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out, void *stream);
+// ep: 0 bucket ids, 1 raw projections, 2 one key per table (needs shared_keys_ok)
+int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out, void *stream);
+// the shared-sample kernel can fold keys when a table lies inside one wave's blocks
+bool shared_keys_ok(const lsh_params *p, uint32_t L);
 // raises a kernel's dynamic LDS limit once (per kernel and size)
 int ensure_lds_limit(const void *fn, uint32_t lds_bytes);
 int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,

@@ -52,7 +52,8 @@ struct SharedArgs {
     void *out;
 };
 
-template <int KS, int RB, int WAVES, bool PROJ>
+// EP: 0 bucket ids, 1 raw projections, 2 one 64-bit key per table (Sec. 3.2; the fold of pack_kernel.hip)
+template <int KS, int RB, int WAVES, int EP>
 __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs a) {
     constexpr uint32_t kWaves = WAVES, kLanes = WAVES * 64;
     constexpr int VB = RB >= 4 ? 1 : 2;  // blocks of 16 vectors in flight: VB * RB independent accumulators
@@ -67,8 +68,10 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
     // this wave's blocks: coefficients, per-lane LDS offsets of the sampled coordinates, b~
     float cf[RB][KS];
     uint32_t xo[RB][KS];
+    constexpr bool PROJ = EP == 1, KEYS = EP == 2;
     float bq[RB][4];
     uint32_t fn0[RB];  // first of the lane's four functions, or >= k when it has none
+    uint64_t pw[KEYS ? RB : 1];  // keys: C^(g - 4 - position in the table of the lane's first function), 0 for none
 #pragma unroll
     for (int e = 0; e < RB; ++e) {
         const uint32_t blk = block0 + e;
@@ -82,6 +85,11 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) bq[e][r] = a.offset[(size_t)blk * 16 + q * 4 + r];  // padded to every wave's blocks
+        if constexpr (KEYS) {
+            uint64_t c = have && in_table < a.g ? 1 : 0;  // g % 4 == 0: a lane has four functions or none
+            for (uint32_t i = in_table + 4; i < a.g; ++i) c *= kKeyMultiplier;
+            pw[e] = c;
+        }
     }
 
     // tile transfer: element e of the tile's float4 sequence = (vector e / n4, coordinates
@@ -180,6 +188,40 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
                         }
                     }
                     v[e] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+                }
+                if constexpr (KEYS) {
+                    // Horner fold of the lane's four ids of each block, times the lane's power of
+                    // C, summed over the four lanes (c, q = 0..3) that hold a block; a table of 32
+                    // functions is the wave's two blocks
+                    uint64_t part[RB];
+#pragma unroll
+                    for (int e = 0; e < RB; ++e) {
+                        uint64_t h = v[e].x;
+                        h = h * kKeyMultiplier + v[e].y;
+                        h = h * kKeyMultiplier + v[e].z;
+                        h = h * kKeyMultiplier + v[e].w;
+                        part[e] = h * pw[e];
+                    }
+                    if (RB == 2 && a.blocks_per_table == 2) part[0] += part[1];
+#pragma unroll
+                    for (int e = 0; e < RB; ++e) {
+                        part[e] += __shfl_xor(part[e], 16);
+                        part[e] += __shfl_xor(part[e], 32);
+                    }
+                    const uint64_t row = row0 + (vb + u) * 16 + opaque(c16);
+                    uint64_t *keys = reinterpret_cast<uint64_t *>(a.out) + row * (a.nblocks / a.blocks_per_table);
+                    if (opaque(q) == 0 && row < a.N && block0 < a.nblocks) {
+                        if (RB == 2 && a.blocks_per_table == 1) {
+                            if (block0 + 1 < a.nblocks) {
+                                *reinterpret_cast<ulonglong2 *>(keys + block0) = make_ulonglong2(part[0], part[1]);
+                            } else {
+                                keys[block0] = part[0];
+                            }
+                        } else {
+                            keys[block0 / a.blocks_per_table] = part[0];
+                        }
+                    }
+                    continue;
                 }
                 if constexpr (RB == 2) {
                     if (a.staged) {  // uniform
@@ -297,7 +339,14 @@ void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vec
     }
 }
 
-int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out, void *stream) {
+// Keys come out of the kernel when the key groups are the tables and a table is one block or
+// the two blocks of one wave.
+bool shared_keys_ok(const lsh_params *p, uint32_t L) {
+    const SharedPlan &pl = p->shared_plan;
+    return pl.supported && L == p->shared_tables && (pl.blocks_per_table == 1 || (pl.blocks_per_table == 2 && pl.rb == 2));
+}
+
+int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out, void *stream) {
     const SharedPlan &pl = p->shared_plan;
     if (!pl.supported) return LSH_ERR_UNSUPPORTED;
     SharedArgs a;
@@ -329,9 +378,11 @@ int launch_shared(const lsh_params *p, bool proj, const float *d_data, uint64_t 
     dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 #define LSH_SHARED_CASE(KS_, RB_, WAVES_) \
-    if (pl.ksteps == KS_ && pl.rb == RB_ && pl.waves == WAVES_) \
-        return proj ? launch(&shared_kernel<KS_, RB_, WAVES_, true>, pl.lds_bytes, a, grid, WAVES_ * 64, s) \
-                    : launch(&shared_kernel<KS_, RB_, WAVES_, false>, pl.lds_bytes, a, grid, WAVES_ * 64, s);
+    if (pl.ksteps == KS_ && pl.rb == RB_ && pl.waves == WAVES_) { \
+        if (ep == 0) return launch(&shared_kernel<KS_, RB_, WAVES_, 0>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        if (ep == 1) return launch(&shared_kernel<KS_, RB_, WAVES_, 1>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        return launch(&shared_kernel<KS_, RB_, WAVES_, 2>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+    }
     LSH_SHARED_CASE(8, 1, 16) LSH_SHARED_CASE(8, 2, 16) LSH_SHARED_CASE(16, 1, 16)
 #undef LSH_SHARED_CASE
     return LSH_ERR_UNSUPPORTED;

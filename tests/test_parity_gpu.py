@@ -146,7 +146,8 @@ SHARED = [
     (50, 612, 64, 20, 2.0, 45, False, 4),        # 32-vector tiles
     (200, 64, 2048, 8, 1.0, 46, False, 128),     # several workgroups along the functions
     (1, 128, 16, 4, 1.0, 47, False, 1),          # one vector, one table
-    (333, 128, 384, 32, 8.0, 51, False, 24),     # two blocks per wave with idle waves: staged stores
+    (333, 128, 384, 32, 8.0, 51, False, 24),     # two blocks per wave with idle waves: whole-line stores
+    (150, 128, 1024, 16, 2.0, 52, False, 32),    # tables of 32 = a wave's two blocks; two workgroups along the functions
     (40, 130, 64, 16, 1.0, 48, False, 8),        # n not a multiple of 4: gather kernels
     (40, 960, 128, 128, 1.0, 49, False, 8),      # m > 64: gather kernels
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
