@@ -9,14 +9,21 @@
 // sample differ only in their immediate offset.  Each lane walks its own list of
 // (LDS offset, coefficient) pairs; there is no cross-lane reduction.
 //
-// The gather is LDS-bandwidth bound, so the order in which a lane visits its samples is
-// chosen on the host (schedule.cpp) such that the lanes served together by one pass of an
-// LDS read (16 consecutive lanes for 16-byte reads) hit distinct bank classes.  With more
-// than one sub-tile the coordinate stride is padded to an odd number of 16-byte slots, which
-// keeps "distinct coordinates mod 16" equivalent to "distinct bank classes" for every
-// sub-tile.  The lists are stored step-major ([step][function]) so that a wave reads them
-// coalesced.  Two kernels: sampled_reg_kernel keeps a list of one chunk in VGPRs for the
-// whole launch; sampled_kernel streams longer lists through registers for every tile.
+// Every gather-FMA costs one 64-lane vector-ALU slot (4 cycles of a SIMD: packed fp32 is off
+// in this build) and 4 bytes of LDS bandwidth, and the two ceilings are close, so both are
+// kept lean.  LDS: the order in which a lane visits its samples is chosen on the host
+// (schedule.cpp) such that the lanes served together by one pass of an LDS read (four quads
+// of lanes for 16-byte reads) hit distinct bank classes; with more than one sub-tile the
+// coordinate stride is padded to an odd number of 16-byte slots, which keeps "distinct
+// coordinates mod 16" equivalent to "distinct bank classes" for every sub-tile.  Vector ALU:
+// 16-vector tiles share each address computation among 16 FMAs, and the epilogues move what
+// they can to the matrix pipe, the scalar ALU and single instructions (see finish()).  The
+// lists are stored step-major ([step][function]) so that a wave reads them coalesced.
+//
+// Three kernels: sampled_reg_kernel keeps lists of up to 64 samples in registers for the whole
+// launch (small n); sampled_kernel streams longer lists through registers for every
+// full-dimension tile; sampled_chunked_kernel cuts large vectors into coordinate ranges that
+// fill LDS and walks per-range lists.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
