@@ -194,6 +194,32 @@ int lsh_project_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t 
 int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, uint64_t N,
                       uint32_t L, void *d_out, void *stream, int reps, float *ms_per_launch);
 
+/*
+ * Collision probabilities (host functions, no GPU involved): what one needs to choose m and
+ * the bucket width.  All pointers are host pointers.
+ *
+ * lsh_e2lsh_collision_probability: p_w(s) of Eq. 2 (Sec. 2.2) for two vectors at distance
+ *   s >= 0 under bucket width w, in closed form.
+ * lsh_pair_statistics: for a vector pair (v, u) of dimension n and sample size m, mu~ = m * mean
+ *   and sigma~ = sqrt(m * variance) of the n squared coordinate differences (v_i - u_i)^2
+ *   (Sec. 4.1, first paragraph).
+ * lsh_fastlsh_collision_probability: p(s, sigma) of Eq. 9 (Sec. 4.1) under the paper's model
+ *   s~^2 ~ N(mu~, sigma~^2) truncated to [0, inf), computed as the mixture of Eq. 2 over that
+ *   distribution (absolute error below 1e-10).
+ * lsh_fastlsh_moment_factors: epsilon and lambda of the moment lemma of Sec. 4.2:
+ *   E[(s~X)^2] = mu~ (1 + epsilon), E[(s~X)^4] = 3 mu~^2 (1 + lambda).
+ * lsh_equivalent_width: the FastLSH width w * sqrt(m / n) under which, for large m, the
+ *   collision law equals E2LSH's with width w (corollary of Sec. 4.2; the variance of the
+ *   sampled projection difference is m s^2 / n).
+ * Errors: INVALID_ARG (null pointer, non-positive or non-finite mu~ or w, negative sigma~).
+ */
+int lsh_e2lsh_collision_probability(double s, double w, double *p);
+int lsh_pair_statistics(const float *v, const float *u, uint32_t n, uint32_t m, double *mu_tilde,
+                        double *sigma_tilde);
+int lsh_fastlsh_collision_probability(double mu_tilde, double sigma_tilde, double w, double *p);
+int lsh_fastlsh_moment_factors(double mu_tilde, double sigma_tilde, double *epsilon, double *lambda);
+double lsh_equivalent_width(uint32_t n, uint32_t m, double w);
+
 const char *lsh_status_string(int status);
 
 #ifdef __cplusplus

@@ -24,6 +24,8 @@ EXPORTS = [
     "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
+    "lsh_e2lsh_collision_probability", "lsh_pair_statistics", "lsh_fastlsh_collision_probability",
+    "lsh_fastlsh_moment_factors", "lsh_equivalent_width",
 ]
 
 
@@ -68,6 +70,13 @@ def load_library():
     lib.lsh_pack_keys.argtypes = [p, p, u64, u32, p, p]
     lib.lsh_hash_fastlsh_keys.argtypes = [p, p, u64, u32, p, p]
     lib.lsh_time_launches.argtypes = [p, i, p, u64, u32, p, p, i, ctypes.POINTER(f32)]
+    f64 = ctypes.c_double
+    lib.lsh_e2lsh_collision_probability.argtypes = [f64, f64, p]
+    lib.lsh_pair_statistics.argtypes = [p, p, u32, u32, p, p]
+    lib.lsh_fastlsh_collision_probability.argtypes = [f64, f64, f64, p]
+    lib.lsh_fastlsh_moment_factors.argtypes = [f64, f64, p, p]
+    lib.lsh_equivalent_width.argtypes = [u32, u32, f64]
+    lib.lsh_equivalent_width.restype = f64
     lib.lsh_status_string.argtypes = [i]
     lib.lsh_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -241,6 +250,42 @@ def hash_fastlsh_keys(params, data, L, out=None, stream=None):
 
 
 _WHICH = {"fastlsh": 0, "e2lsh": 1, "signs": 2, "pack_keys": 3, "fastlsh_keys": 4}
+
+
+def e2lsh_collision_probability(s, w):
+    out = ctypes.c_double()
+    _check(load_library().lsh_e2lsh_collision_probability(s, w, ctypes.addressof(out)),
+           "lsh_e2lsh_collision_probability")
+    return out.value
+
+
+def pair_statistics(v, u, m):
+    """(mu~, sigma~) of a pair of host float32 vectors for sample size m."""
+    v = np.ascontiguousarray(v, np.float32)
+    u = np.ascontiguousarray(u, np.float32)
+    assert v.shape == u.shape and v.ndim == 1
+    mu, sigma = ctypes.c_double(), ctypes.c_double()
+    _check(load_library().lsh_pair_statistics(v.ctypes.data, u.ctypes.data, v.size, m, ctypes.addressof(mu),
+                                              ctypes.addressof(sigma)), "lsh_pair_statistics")
+    return mu.value, sigma.value
+
+
+def fastlsh_collision_probability(mu_tilde, sigma_tilde, w):
+    out = ctypes.c_double()
+    _check(load_library().lsh_fastlsh_collision_probability(mu_tilde, sigma_tilde, w, ctypes.addressof(out)),
+           "lsh_fastlsh_collision_probability")
+    return out.value
+
+
+def fastlsh_moment_factors(mu_tilde, sigma_tilde):
+    eps, lam = ctypes.c_double(), ctypes.c_double()
+    _check(load_library().lsh_fastlsh_moment_factors(mu_tilde, sigma_tilde, ctypes.addressof(eps),
+                                                     ctypes.addressof(lam)), "lsh_fastlsh_moment_factors")
+    return eps.value, lam.value
+
+
+def equivalent_width(n, m, w):
+    return load_library().lsh_equivalent_width(n, m, w)
 
 
 def time_launches(params, which, d_in, d_out, L=0, reps=10, stream=None):

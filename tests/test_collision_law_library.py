@@ -1,0 +1,69 @@
+"""The library's collision-probability calculator (host code, mixture route) against the
+oracle's (characteristic function and inverse Fourier transform, the paper's route)."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import collision_law as law
+from paper_2309_15479_amd import binding
+
+
+@pytest.mark.parametrize("mu_t,sigma_t,w", [(4.0, 1.0, 4.0), (9.0, 6.0, 4.0), (1.0, 1.4, 1.5), (30.0, 12.0, 8.0),
+                                            (0.25, 0.02, 1.0), (100.0, 300.0, 16.0)])
+def test_fastlsh_collision_probability_matches_oracle(mu_t, sigma_t, w):
+    got = binding.fastlsh_collision_probability(mu_t, sigma_t, w)
+    want = law.fastlsh_collision_probability(mu_t, sigma_t, w)
+    assert abs(got - want) < 2e-8, (got, want)
+
+
+def test_e2lsh_collision_probability_matches_oracle_and_golden(golden_dir):
+    rows = [ln.split() for ln in open(os.path.join(golden_dir, "e2lsh_collision_law.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    for w, s, p in rows:
+        assert abs(binding.e2lsh_collision_probability(float(s), float(w)) - float(p)) < 1e-9
+    for s, w in [(0.3, 1.0), (7.0, 2.0), (50.0, 4.0)]:
+        assert abs(binding.e2lsh_collision_probability(s, w) - law.e2lsh_collision_probability(s, w)) < 1e-11
+    assert binding.e2lsh_collision_probability(0.0, 3.0) == 1.0
+
+
+def test_moment_factors_and_pair_statistics_match_oracle(golden_dir):
+    for ratio in (0.05, 0.3, 0.7, 1.4, 3.0):
+        got = binding.fastlsh_moment_factors(2.0, 2.0 * ratio)
+        want = law.moment_factors(2.0, 2.0 * ratio)
+        assert got == pytest.approx(want, rel=1e-12, abs=1e-300)
+    assert binding.fastlsh_moment_factors(3.0, 0.0) == (0.0, 0.0)
+    rng = np.random.default_rng(3)
+    v = rng.normal(size=257).astype(np.float32)
+    u = rng.normal(size=257).astype(np.float32)
+    assert binding.pair_statistics(v, u, 30) == pytest.approx(law.pair_statistics(v, u, 30), rel=1e-12)
+
+
+def test_zero_spread_and_large_m_limits():
+    # sigma~ = 0: the E2LSH law at the sampled distance; width helper: w * sqrt(m / n)
+    assert binding.fastlsh_collision_probability(4.0, 0.0, 4.0) == pytest.approx(
+        binding.e2lsh_collision_probability(2.0, 4.0), abs=1e-15)
+    assert binding.equivalent_width(128, 32, 16.0) == pytest.approx(8.0)
+    # large m: p(s, sigma) at width w * sqrt(m / n) approaches E2LSH's p_w(s)  (Sec. 4.2)
+    n, s, w = 4096, 3.0, 4.0
+    rng = np.random.default_rng(4)
+    d = rng.normal(size=n)
+    d *= s / np.linalg.norm(d)
+    v = np.zeros(n, np.float32)
+    u = d.astype(np.float32)
+    errs = []
+    for m in (16, 256, 4096):
+        mu_t, sigma_t = binding.pair_statistics(v, u, m)
+        p_fast = binding.fastlsh_collision_probability(mu_t, sigma_t, binding.equivalent_width(n, m, w))
+        errs.append(abs(p_fast - binding.e2lsh_collision_probability(s, w)))
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 1e-3
+
+
+def test_argument_errors():
+    lib = binding.load_library()
+    for args in [(-1.0, 1.0, 1.0), (1.0, -1.0, 1.0), (1.0, 1.0, 0.0), (float("nan"), 1.0, 1.0)]:
+        with pytest.raises(binding.LshError):
+            binding.fastlsh_collision_probability(*args)
+    assert lib.lsh_fastlsh_collision_probability(1.0, 1.0, 1.0, None) == -1
+    assert lib.lsh_e2lsh_collision_probability(1.0, 1.0, None) == -1
