@@ -37,6 +37,7 @@ MEASURED_TRAFFIC_BYTES = {
     "pack_keys": 1000021 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
     "e2lsh": 301706 * 2048 + 2090870 * 1024,      # 0.618 GB + 2.141 GB
     "signs": 250567 * 2048 + 62500 * 1024,        # 0.513 GB + 0.064 GB
+    "fastlsh_shared_sample": 250361 * 2048 + 2000000 * 1024,  # 0.513 GB + 2.048 GB
 }
 
 
@@ -176,7 +177,7 @@ def main():
     ms_shared = e0.elapsed_time(e1) / args.steps
     a = N * (4 * n + 4 * k) / (ms_shared * 1e-3) / 1e9
     shared_sample = {"ms": ms_shared, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": a / HBM_PEAK_GBS, "traffic": None,
+                     "frac": a / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["fastlsh_shared_sample"],
                      "mfma_tflops": 2.0 * N * k * m / (ms_shared * 1e-3) / 1e12,
                      "hashes_per_s": N * k / (ms_shared * 1e-3)}
 
