@@ -195,6 +195,46 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
                       uint32_t L, void *d_out, void *stream, int reps, float *ms_per_launch);
 
 /*
+ * LSH index (Sec. 3.2): L hash tables of <key, id> pairs and the lookup of a query's L buckets.
+ * A table is the vector ids sorted by key (stable: ids ascending inside a bucket), a bucket a
+ * contiguous run of them found by binary search; 12 bytes per vector and table of device
+ * memory, owned by the index object.
+ *
+ * lsh_index_build: d_keys [N][L] (device, as written by lsh_pack_keys or
+ *   lsh_hash_fastlsh_keys), N < 2^32.  Sorts the L columns on `stream` and WAITS for them
+ *   (temporary buffers are released before returning).
+ * lsh_index_tables: N, L and the device arrays sorted keys [L][N], ids in key order [L][N]
+ *   (owned by the index; any out pointer may be NULL).
+ * lsh_index_probe: d_qkeys [Q][L] -> d_start [Q][L], d_count [Q][L]: the bucket of query q in
+ *   table l is ids[l][start .. start + count).  count 0 = empty bucket.  Asynchronous.
+ * lsh_index_candidate_offsets: exclusive prefix sum of `items` counts into d_offsets
+ *   [items + 1] (the last entry is the total); waits for the stream.
+ * lsh_index_candidates: the buckets of every (query, table) item copied to
+ *   d_out[offsets[item] ..): a query's combined candidate list is its L runs one after the
+ *   other (an id met in several tables appears once per table).  Asynchronous.
+ * lsh_index_nearest: exact processing of the candidates (Sec. 3.2, last paragraph): for every
+ *   query the candidate with the smallest squared l2 distance over the full n-dimensional
+ *   vectors (fp32; ties to the smaller id) -> d_best_id [Q] (0xFFFFFFFF when all L buckets
+ *   are empty), d_best_dist [Q] (squared distance, +inf when none).  d_data [N][n] must be the
+ *   indexed vectors, d_queries [Q][n].  Asynchronous.
+ * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^32, called on another device than the one
+ * the index was built on), ALLOC, HIP, NO_DEVICE, UNSUPPORTED (lsh_index_nearest: n > 16368).
+ */
+typedef struct lsh_index lsh_index_t; /* opaque */
+int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream, lsh_index_t **out);
+void lsh_index_destroy(lsh_index_t *index);
+int lsh_index_tables(const lsh_index_t *index, uint64_t *N, uint32_t *L, const uint64_t **d_sorted_keys,
+                     const uint32_t **d_sorted_ids);
+int lsh_index_probe(const lsh_index_t *index, const uint64_t *d_qkeys, uint64_t Q, uint32_t *d_start,
+                    uint32_t *d_count, void *stream);
+int lsh_index_candidate_offsets(const uint32_t *d_count, uint64_t items, uint64_t *d_offsets, void *stream);
+int lsh_index_candidates(const lsh_index_t *index, const uint32_t *d_start, const uint32_t *d_count,
+                         const uint64_t *d_offsets, uint64_t Q, uint32_t *d_out, void *stream);
+int lsh_index_nearest(const lsh_index_t *index, const float *d_data, const float *d_queries, uint32_t n,
+                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t *d_best_id,
+                      float *d_best_dist, void *stream);
+
+/*
  * Collision probabilities (host functions, no GPU involved): what one needs to choose m and
  * the bucket width.  All pointers are host pointers.
  *

@@ -3,12 +3,12 @@ E2LSH on the fp32 matrix cores, sign hashes and compound-key packing, behind the
 ``include/lsh.h``.  This package is only the Python binding (argument marshalling); all
 hash arithmetic runs in the HIP kernels of ``liblsh.so`` (the collision-probability helpers
 are host functions of the same library)."""
-from .binding import (LshError, LshParams, e2lsh_collision_probability, equivalent_width,
+from .binding import (LshError, LshIndex, LshParams, e2lsh_collision_probability, equivalent_width,
                       fastlsh_collision_probability, fastlsh_moment_factors, hash_e2lsh, hash_fastlsh,
                       hash_fastlsh_keys, hash_signs, library_path, load_library, pack_keys, pair_statistics,
                       project_e2lsh, project_fastlsh, time_launches)
 
-__all__ = ["LshError", "LshParams", "hash_e2lsh", "hash_fastlsh", "hash_fastlsh_keys", "hash_signs",
+__all__ = ["LshError", "LshIndex", "LshParams", "hash_e2lsh", "hash_fastlsh", "hash_fastlsh_keys", "hash_signs",
            "library_path", "load_library", "pack_keys", "project_e2lsh", "project_fastlsh",
            "time_launches", "e2lsh_collision_probability", "equivalent_width",
            "fastlsh_collision_probability", "fastlsh_moment_factors", "pair_statistics"]

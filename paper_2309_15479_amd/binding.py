@@ -26,6 +26,8 @@ EXPORTS = [
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
     "lsh_e2lsh_collision_probability", "lsh_pair_statistics", "lsh_fastlsh_collision_probability",
     "lsh_fastlsh_moment_factors", "lsh_equivalent_width",
+    "lsh_index_build", "lsh_index_destroy", "lsh_index_tables", "lsh_index_probe",
+    "lsh_index_candidate_offsets", "lsh_index_candidates", "lsh_index_nearest",
 ]
 
 
@@ -77,6 +79,14 @@ def load_library():
     lib.lsh_fastlsh_moment_factors.argtypes = [f64, f64, p, p]
     lib.lsh_equivalent_width.argtypes = [u32, u32, f64]
     lib.lsh_equivalent_width.restype = f64
+    lib.lsh_index_build.argtypes = [p, u64, u32, p, ctypes.POINTER(p)]
+    lib.lsh_index_destroy.argtypes = [p]
+    lib.lsh_index_destroy.restype = None
+    lib.lsh_index_tables.argtypes = [p, p, p, p, p]
+    lib.lsh_index_probe.argtypes = [p, p, u64, p, p, p]
+    lib.lsh_index_candidate_offsets.argtypes = [p, u64, p, p]
+    lib.lsh_index_candidates.argtypes = [p, p, p, p, u64, p, p]
+    lib.lsh_index_nearest.argtypes = [p, p, p, u32, p, p, u64, p, p, p]
     lib.lsh_status_string.argtypes = [i]
     lib.lsh_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -250,6 +260,83 @@ def hash_fastlsh_keys(params, data, L, out=None, stream=None):
 
 
 _WHICH = {"fastlsh": 0, "e2lsh": 1, "signs": 2, "pack_keys": 3, "fastlsh_keys": 4}
+
+
+class LshIndex:
+    """Owns one lsh_index_t: L hash tables built from the keys [N, L] of the indexed vectors."""
+
+    def __init__(self, keys, stream=None):
+        import torch
+        assert keys.is_cuda and keys.dtype == torch.int64 and keys.dim() == 2 and keys.is_contiguous()
+        handle = ctypes.c_void_p()
+        _check(load_library().lsh_index_build(keys.data_ptr(), keys.shape[0], keys.shape[1], _stream(stream),
+                                              ctypes.byref(handle)), "lsh_index_build")
+        self._h = handle
+        self.N, self.L, self.device = int(keys.shape[0]), int(keys.shape[1]), keys.device
+
+    @property
+    def handle(self):
+        if not getattr(self, "_h", None):
+            raise ValueError("LshIndex is closed")
+        return self._h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().lsh_index_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def probe(self, qkeys, stream=None):
+        """Bucket of every (query, table): (start [Q, L], count [Q, L]) int32 tensors (uint32 bits)."""
+        import torch
+        assert qkeys.is_cuda and qkeys.dtype == torch.int64 and qkeys.is_contiguous() and qkeys.shape[1] == self.L
+        Q = qkeys.shape[0]
+        start = torch.empty((Q, self.L), dtype=torch.int32, device=qkeys.device)
+        count = torch.empty((Q, self.L), dtype=torch.int32, device=qkeys.device)
+        _check(load_library().lsh_index_probe(self.handle, qkeys.data_ptr(), Q, start.data_ptr(), count.data_ptr(),
+                                              _stream(stream)), "lsh_index_probe")
+        return start, count
+
+    def candidates(self, start, count, stream=None):
+        """(offsets [Q*L + 1] int64, ids [total] int32): the bucket of item q*L + l is
+        ids[offsets[item] : offsets[item + 1]]."""
+        import torch
+        items = start.numel()
+        offsets = torch.empty(items + 1, dtype=torch.int64, device=start.device)
+        _check(load_library().lsh_index_candidate_offsets(count.data_ptr(), items, offsets.data_ptr(),
+                                                          _stream(stream)), "lsh_index_candidate_offsets")
+        total = int(offsets[-1].item())
+        ids = torch.empty(total, dtype=torch.int32, device=start.device)
+        if total:
+            _check(load_library().lsh_index_candidates(self.handle, start.data_ptr(), count.data_ptr(),
+                                                       offsets.data_ptr(), start.shape[0], ids.data_ptr(),
+                                                       _stream(stream)), "lsh_index_candidates")
+        return offsets, ids
+
+    def nearest(self, data, queries, start, count, stream=None):
+        """Exact processing: (best id [Q] int32 with -1 for none, squared distance [Q] float32)."""
+        import torch
+        assert data.is_cuda and data.dtype == torch.float32 and data.is_contiguous() and data.shape[0] == self.N
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        Q, n = queries.shape
+        assert data.shape[1] == n and start.shape == (Q, self.L)
+        best = torch.empty(Q, dtype=torch.int32, device=data.device)
+        dist = torch.empty(Q, dtype=torch.float32, device=data.device)
+        _check(load_library().lsh_index_nearest(self.handle, data.data_ptr(), queries.data_ptr(), n,
+                                                start.data_ptr(), count.data_ptr(), Q, best.data_ptr(),
+                                                dist.data_ptr(), _stream(stream)), "lsh_index_nearest")
+        return best, dist
 
 
 def e2lsh_collision_probability(s, w):

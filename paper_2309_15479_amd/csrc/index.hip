@@ -1,0 +1,281 @@
+// LSH index (Sec. 3.2): L hash tables of <key, id> pairs and the lookup of a query's L
+// buckets, for gfx950.
+//
+// The paper fixes what a table holds (every vector's id under its key H_l(v)) and how a query
+// uses it (fetch the L buckets H_1(u) .. H_L(u), evaluate the candidates), not a layout.  Here a
+// table is the vector ids sorted by key (a stable radix sort of N <key, id> pairs, ids
+// ascending inside a bucket): a bucket is a contiguous run of the sorted ids, found by binary
+// search of the sorted keys.  No chains, no resizing, 12 bytes per vector and table.
+//
+//   build      keys [N][L] -> per table: sorted keys [N], ids in key order [N]
+//   probe      query keys [Q][L] -> per (query, table): first position and length of the bucket
+//   candidates concatenation of a query's L buckets, all queries, at given offsets
+//   nearest    exact processing (Sec. 3.2, last paragraph): the candidate closest to the query
+//              in l2, distances in fp32 over the full vectors
+#include <hip/hip_runtime.h>
+#include <hipcub/hipcub.hpp>
+
+#include <new>
+
+#include "lsh.h"
+
+struct lsh_index {
+    uint64_t N = 0;
+    uint32_t L = 0;
+    int device = -1;
+    uint64_t *d_keys = nullptr;  // [L][N] ascending per table
+    uint32_t *d_ids = nullptr;   // [L][N] vector ids in key order (ascending within equal keys)
+};
+
+namespace {
+
+__global__ void take_column(const uint64_t *__restrict__ keys, uint64_t N, uint32_t L, uint32_t l,
+                            uint64_t *__restrict__ column, uint32_t *__restrict__ ids) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < N; i += (uint64_t)gridDim.x * blockDim.x) {
+        column[i] = keys[i * L + l];
+        ids[i] = (uint32_t)i;
+    }
+}
+
+// one thread per (query, table): lower and upper bound of the query's key in the table
+__global__ void probe_kernel(const uint64_t *__restrict__ sorted_keys, uint64_t N, uint32_t L,
+                             const uint64_t *__restrict__ qkeys, uint64_t items, uint32_t *__restrict__ start,
+                             uint32_t *__restrict__ count) {
+    const uint64_t item = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (item >= items) return;
+    const uint32_t l = (uint32_t)(item % L);
+    const uint64_t key = qkeys[item];
+    const uint64_t *table = sorted_keys + (uint64_t)l * N;
+    uint64_t lo = 0, hi = N;  // first position with table[pos] >= key
+    while (lo < hi) {
+        const uint64_t mid = (lo + hi) / 2;
+        if (table[mid] < key) lo = mid + 1;
+        else hi = mid;
+    }
+    const uint64_t first = lo;
+    hi = N;  // first position with table[pos] > key
+    while (lo < hi) {
+        const uint64_t mid = (lo + hi) / 2;
+        if (table[mid] <= key) lo = mid + 1;
+        else hi = mid;
+    }
+    start[item] = (uint32_t)first;
+    count[item] = (uint32_t)(lo - first);
+}
+
+__global__ void widen_counts(const uint32_t *__restrict__ count, uint64_t items, uint64_t *__restrict__ wide) {
+    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (i < items) wide[i] = count[i];
+    if (i == items) wide[i] = 0;  // the extra element turns the exclusive scan's last entry into the total
+}
+
+// one wave per (query, table): copies the bucket's ids to the output run of that item
+__global__ void candidates_kernel(const uint32_t *__restrict__ sorted_ids, uint64_t N, uint32_t L,
+                                  const uint32_t *__restrict__ start, const uint32_t *__restrict__ count,
+                                  const uint64_t *__restrict__ offsets, uint64_t items, uint32_t *__restrict__ out) {
+    const uint64_t item = (blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6;
+    if (item >= items) return;
+    const uint32_t lane = threadIdx.x & 63, l = (uint32_t)(item % L);
+    const uint32_t *src = sorted_ids + (uint64_t)l * N + start[item];
+    uint32_t *dst = out + offsets[item];
+    for (uint32_t i = lane; i < count[item]; i += 64) dst[i] = src[i];
+}
+
+// one workgroup per query: squared l2 distance of every candidate of its L buckets (a candidate
+// met in several tables is simply evaluated again), minimum with ties to the smaller id
+__global__ __launch_bounds__(256) void nearest_kernel(const uint32_t *__restrict__ sorted_ids, uint64_t N, uint32_t L,
+                                                      const float *__restrict__ data, const float *__restrict__ queries,
+                                                      uint32_t n, const uint32_t *__restrict__ start,
+                                                      const uint32_t *__restrict__ count, uint32_t *__restrict__ best_id,
+                                                      float *__restrict__ best_dist) {
+    extern __shared__ float query[];  // [n], then per-wave results
+    const uint64_t q = blockIdx.x;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    for (uint32_t c = threadIdx.x; c < n; c += blockDim.x) query[c] = queries[q * n + c];
+    __syncthreads();
+    float mine_d = INFINITY;
+    uint32_t mine_id = 0xFFFFFFFFu;
+    uint32_t seen = 0;  // candidates are dealt to the waves round-robin over all L buckets
+    for (uint32_t l = 0; l < L; ++l) {
+        const uint32_t first = start[q * L + l], len = count[q * L + l];
+        const uint32_t *bucket = sorted_ids + (uint64_t)l * N + first;
+        for (uint32_t i = (wave + waves - seen % waves) % waves; i < len; i += waves) {
+            const uint32_t id = bucket[i];
+            const float *v = data + (uint64_t)id * n;
+            float acc = 0.f;
+            for (uint32_t c = lane; c < n; c += 64) {
+                const float d = v[c] - query[c];
+                acc = fmaf(d, d, acc);
+            }
+            for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+            if (acc < mine_d || (acc == mine_d && id < mine_id)) {
+                mine_d = acc;
+                mine_id = id;
+            }
+        }
+        seen += len;
+    }
+    float *wave_d = query + n;
+    uint32_t *wave_id = reinterpret_cast<uint32_t *>(wave_d + waves);
+    if (lane == 0) {
+        wave_d[wave] = mine_d;
+        wave_id[wave] = mine_id;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (uint32_t w = 1; w < waves; ++w)
+            if (wave_d[w] < mine_d || (wave_d[w] == mine_d && wave_id[w] < mine_id)) {
+                mine_d = wave_d[w];
+                mine_id = wave_id[w];
+            }
+        best_id[q] = mine_id;
+        best_dist[q] = mine_d;
+    }
+}
+
+int on_index_device(const lsh_index *ix) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return LSH_ERR_HIP;
+    return dev == ix->device ? LSH_OK : LSH_ERR_INVALID_ARG;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream, lsh_index_t **out) {
+    if (!out) return LSH_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!d_keys || !N || !L || N >= (1ull << 32)) return LSH_ERR_INVALID_ARG;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
+        (void)hipGetLastError();
+        return LSH_ERR_NO_DEVICE;
+    }
+    lsh_index *ix = new (std::nothrow) lsh_index;
+    if (!ix) return LSH_ERR_ALLOC;
+    ix->N = N;
+    ix->L = L;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    uint64_t *column = nullptr;
+    uint32_t *iota = nullptr;
+    void *temp = nullptr;
+    size_t temp_bytes = 0;
+    int rc = LSH_OK;
+    if (hipGetDevice(&ix->device) != hipSuccess) rc = LSH_ERR_HIP;
+    if (rc == LSH_OK && hipMalloc(&ix->d_keys, (size_t)L * N * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK && hipMalloc(&ix->d_ids, (size_t)L * N * sizeof(uint32_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK && hipMalloc(&column, N * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK && hipMalloc(&iota, N * sizeof(uint32_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK &&
+        hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, column, ix->d_keys, iota, ix->d_ids, (int)N, 0, 64, s) !=
+            hipSuccess)
+        rc = LSH_ERR_HIP;
+    if (rc == LSH_OK && hipMalloc(&temp, temp_bytes ? temp_bytes : 1) != hipSuccess) rc = LSH_ERR_ALLOC;
+    const uint32_t blocks = (uint32_t)((N + 255) / 256 < 4096 ? (N + 255) / 256 : 4096);
+    for (uint32_t l = 0; rc == LSH_OK && l < L; ++l) {
+        hipLaunchKernelGGL(take_column, dim3(blocks), dim3(256), 0, s, d_keys, N, L, l, column, iota);
+        // stable least-significant-digit radix sort: equal keys keep ascending ids
+        if (hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, column, ix->d_keys + (size_t)l * N, iota,
+                                               ix->d_ids + (size_t)l * N, (int)N, 0, 64, s) != hipSuccess)
+            rc = LSH_ERR_HIP;
+    }
+    if (rc == LSH_OK && hipStreamSynchronize(s) != hipSuccess) rc = LSH_ERR_HIP;
+    if (rc == LSH_OK && hipGetLastError() != hipSuccess) rc = LSH_ERR_HIP;
+    if (column) (void)hipFree(column);
+    if (iota) (void)hipFree(iota);
+    if (temp) (void)hipFree(temp);
+    if (rc != LSH_OK) {
+        (void)hipGetLastError();
+        lsh_index_destroy(ix);
+        return rc;
+    }
+    *out = ix;
+    return LSH_OK;
+}
+
+void lsh_index_destroy(lsh_index_t *ix) {
+    if (!ix) return;
+    if (ix->d_keys) (void)hipFree(ix->d_keys);
+    if (ix->d_ids) (void)hipFree(ix->d_ids);
+    delete ix;
+}
+
+int lsh_index_tables(const lsh_index_t *ix, uint64_t *N, uint32_t *L, const uint64_t **d_sorted_keys,
+                     const uint32_t **d_sorted_ids) {
+    if (!ix) return LSH_ERR_INVALID_ARG;
+    if (N) *N = ix->N;
+    if (L) *L = ix->L;
+    if (d_sorted_keys) *d_sorted_keys = ix->d_keys;
+    if (d_sorted_ids) *d_sorted_ids = ix->d_ids;
+    return LSH_OK;
+}
+
+int lsh_index_probe(const lsh_index_t *ix, const uint64_t *d_qkeys, uint64_t Q, uint32_t *d_start, uint32_t *d_count,
+                    void *stream) {
+    if (!ix) return LSH_ERR_INVALID_ARG;
+    if (Q == 0) return LSH_OK;
+    if (!d_qkeys || !d_start || !d_count) return LSH_ERR_INVALID_ARG;
+    int rc = on_index_device(ix);
+    if (rc != LSH_OK) return rc;
+    const uint64_t items = Q * ix->L;
+    hipLaunchKernelGGL(probe_kernel, dim3((uint32_t)((items + 255) / 256)), dim3(256), 0,
+                       reinterpret_cast<hipStream_t>(stream), ix->d_keys, ix->N, ix->L, d_qkeys, items, d_start, d_count);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+int lsh_index_candidate_offsets(const uint32_t *d_count, uint64_t items, uint64_t *d_offsets, void *stream) {
+    if (!d_count || !d_offsets || items >= (1ull << 31)) return LSH_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    uint64_t *wide = nullptr;
+    void *temp = nullptr;
+    size_t temp_bytes = 0;
+    int rc = LSH_OK;
+    if (hipMalloc(&wide, (items + 1) * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK) {
+        hipLaunchKernelGGL(widen_counts, dim3((uint32_t)((items + 256) / 256)), dim3(256), 0, s, d_count, items, wide);
+        if (hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, wide, d_offsets, (int)(items + 1), s) != hipSuccess)
+            rc = LSH_ERR_HIP;
+    }
+    if (rc == LSH_OK && hipMalloc(&temp, temp_bytes ? temp_bytes : 1) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK &&
+        hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, wide, d_offsets, (int)(items + 1), s) != hipSuccess)
+        rc = LSH_ERR_HIP;
+    if (rc == LSH_OK && hipStreamSynchronize(s) != hipSuccess) rc = LSH_ERR_HIP;
+    if (wide) (void)hipFree(wide);
+    if (temp) (void)hipFree(temp);
+    if (rc == LSH_OK && hipGetLastError() != hipSuccess) rc = LSH_ERR_HIP;
+    return rc;
+}
+
+int lsh_index_candidates(const lsh_index_t *ix, const uint32_t *d_start, const uint32_t *d_count,
+                         const uint64_t *d_offsets, uint64_t Q, uint32_t *d_out, void *stream) {
+    if (!ix) return LSH_ERR_INVALID_ARG;
+    if (Q == 0) return LSH_OK;
+    if (!d_start || !d_count || !d_offsets || !d_out) return LSH_ERR_INVALID_ARG;
+    int rc = on_index_device(ix);
+    if (rc != LSH_OK) return rc;
+    const uint64_t items = Q * ix->L;
+    hipLaunchKernelGGL(candidates_kernel, dim3((uint32_t)((items * 64 + 255) / 256)), dim3(256), 0,
+                       reinterpret_cast<hipStream_t>(stream), ix->d_ids, ix->N, ix->L, d_start, d_count, d_offsets, items,
+                       d_out);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+int lsh_index_nearest(const lsh_index_t *ix, const float *d_data, const float *d_queries, uint32_t n,
+                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t *d_best_id,
+                      float *d_best_dist, void *stream) {
+    if (!ix || !n) return LSH_ERR_INVALID_ARG;
+    if (Q == 0) return LSH_OK;
+    if (!d_data || !d_queries || !d_start || !d_count || !d_best_id || !d_best_dist) return LSH_ERR_INVALID_ARG;
+    if (Q >= (1ull << 31)) return LSH_ERR_INVALID_ARG;
+    if ((uint64_t)n * 4 + 64 > 64 * 1024) return LSH_ERR_UNSUPPORTED;  // the query is kept in LDS
+    int rc = on_index_device(ix);
+    if (rc != LSH_OK) return rc;
+    const uint32_t lds = n * 4 + 4 * 8;
+    hipLaunchKernelGGL(nearest_kernel, dim3((uint32_t)Q), dim3(256), lds, reinterpret_cast<hipStream_t>(stream), ix->d_ids,
+                       ix->N, ix->L, d_data, d_queries, n, d_start, d_count, d_best_id, d_best_dist);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+}  // extern "C"
