@@ -71,6 +71,34 @@ def main(names):
                           f"{N * (4 * n + 4 * k) / ms / 1e6:.0f} GB/s algorithmic  "
                           f"{2 * N * k * m / ms / 1e9:.1f} TFLOP/s", flush=True)
                     del out
+        if wl.L and not wl.signs:
+            # index: build the L tables from the keys, probe 4096 of the vectors as queries
+            import time
+            with lsh.LshParams(n, k, wl.m[0], wl.w, wl.seed) as p:
+                keys = lsh.hash_fastlsh_keys(p, data, wl.L)
+            torch.cuda.synchronize()
+            lsh.LshIndex(keys).close()                       # warm-up (first launches, allocator)
+            t0 = time.perf_counter()
+            ix = lsh.LshIndex(keys)                          # waits for the sorts
+            build_ms = (time.perf_counter() - t0) * 1e3
+            qkeys = keys[:4096].contiguous()
+            queries = data[:4096].contiguous()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            start, count = ix.probe(qkeys)
+            ix.nearest(data, queries, start, count)
+            torch.cuda.synchronize()
+            ev[0].record()
+            start, count = ix.probe(qkeys)
+            ev[1].record()
+            best, dist = ix.nearest(data, queries, start, count)
+            ev[2].record()
+            torch.cuda.synchronize()
+            cands = int(count.to(torch.int64).sum().item())
+            print(f"{name} index L={wl.L}: build {build_ms:.1f} ms ({N * wl.L / build_ms / 1e3:.0f} M pairs/s)  "
+                  f"probe of 4096 queries {ev[0].elapsed_time(ev[1]):.3f} ms  exact nearest over {cands} candidates "
+                  f"{ev[1].elapsed_time(ev[2]):.3f} ms", flush=True)
+            ix.close()
+            del keys, qkeys, queries
         if not wl.signs:
             with lsh.LshParams(n, k, n, wl.w, wl.seed) as p:
                 out = torch.empty((N, k), dtype=torch.int32, device="cuda")
