@@ -212,11 +212,13 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
  * lsh_index_candidates: the buckets of every (query, table) item copied to
  *   d_out[offsets[item] ..): a query's combined candidate list is its L runs one after the
  *   other (an id met in several tables appears once per table).  Asynchronous.
- * lsh_index_nearest: exact processing of the candidates (Sec. 3.2, last paragraph): for every
+ * lsh_index_nearest: processing of the candidates (Sec. 3.2, last paragraph): for every
  *   query the candidate with the smallest squared l2 distance over the full n-dimensional
  *   vectors (fp32; ties to the smaller id) -> d_best_id [Q] (0xFFFFFFFF when all L buckets
- *   are empty), d_best_dist [Q] (squared distance, +inf when none).  d_data [N][n] must be the
- *   indexed vectors, d_queries [Q][n].  Asynchronous.
+ *   are empty), d_best_dist [Q] (squared distance, +inf when none).  max_candidates = 0
+ *   evaluates every candidate (the exact version); otherwise only the first max_candidates
+ *   entries of the query's combined list are evaluated (the approximate version of the paper
+ *   uses 3L).  d_data [N][n] must be the indexed vectors, d_queries [Q][n].  Asynchronous.
  * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^32, called on another device than the one
  * the index was built on), ALLOC, HIP, NO_DEVICE, UNSUPPORTED (lsh_index_nearest: n > 16368).
  */
@@ -231,8 +233,8 @@ int lsh_index_candidate_offsets(const uint32_t *d_count, uint64_t items, uint64_
 int lsh_index_candidates(const lsh_index_t *index, const uint32_t *d_start, const uint32_t *d_count,
                          const uint64_t *d_offsets, uint64_t Q, uint32_t *d_out, void *stream);
 int lsh_index_nearest(const lsh_index_t *index, const float *d_data, const float *d_queries, uint32_t n,
-                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t *d_best_id,
-                      float *d_best_dist, void *stream);
+                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t max_candidates,
+                      uint32_t *d_best_id, float *d_best_dist, void *stream);
 
 /*
  * Collision probabilities (host functions, no GPU involved): what one needs to choose m and

@@ -39,9 +39,13 @@ def candidates(buckets_of_query):
     return [i for bucket in buckets_of_query for i in bucket]
 
 
-def nearest(data, query, cand):
-    """Exact processing: the distinct candidate nearest to the query in l2 (ties: the smaller
-    id), or -1 when there is none.  Distances in fp64."""
+def nearest(data, query, cand, max_candidates=0):
+    """Processing of the candidates: the distinct candidate nearest to the query in l2 (ties:
+    the smaller id), or -1 when there is none.  Distances in fp64.  max_candidates = 0: all of
+    them (the exact version); otherwise only the first max_candidates entries of the combined
+    list (the approximate version evaluates no more than 3L points)."""
+    if max_candidates:
+        cand = cand[:max_candidates]
     best, best_d = -1, np.inf
     for i in sorted(set(cand)):
         d = float(((data[i].astype(np.float64) - query.astype(np.float64)) ** 2).sum())

@@ -86,7 +86,7 @@ def load_library():
     lib.lsh_index_probe.argtypes = [p, p, u64, p, p, p]
     lib.lsh_index_candidate_offsets.argtypes = [p, u64, p, p]
     lib.lsh_index_candidates.argtypes = [p, p, p, p, u64, p, p]
-    lib.lsh_index_nearest.argtypes = [p, p, p, u32, p, p, u64, p, p, p]
+    lib.lsh_index_nearest.argtypes = [p, p, p, u32, p, p, u64, u32, p, p, p]
     lib.lsh_status_string.argtypes = [i]
     lib.lsh_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -324,8 +324,10 @@ class LshIndex:
                                                        _stream(stream)), "lsh_index_candidates")
         return offsets, ids
 
-    def nearest(self, data, queries, start, count, stream=None):
-        """Exact processing: (best id [Q] int32 with -1 for none, squared distance [Q] float32)."""
+    def nearest(self, data, queries, start, count, max_candidates=0, stream=None):
+        """Nearest candidate: (best id [Q] int32 with -1 for none, squared distance [Q] float32).
+        max_candidates = 0: every candidate (exact version); else only the first max_candidates
+        of each query's combined list (the paper's approximate version uses 3 * L)."""
         import torch
         assert data.is_cuda and data.dtype == torch.float32 and data.is_contiguous() and data.shape[0] == self.N
         assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
@@ -334,8 +336,9 @@ class LshIndex:
         best = torch.empty(Q, dtype=torch.int32, device=data.device)
         dist = torch.empty(Q, dtype=torch.float32, device=data.device)
         _check(load_library().lsh_index_nearest(self.handle, data.data_ptr(), queries.data_ptr(), n,
-                                                start.data_ptr(), count.data_ptr(), Q, best.data_ptr(),
-                                                dist.data_ptr(), _stream(stream)), "lsh_index_nearest")
+                                                start.data_ptr(), count.data_ptr(), Q, max_candidates,
+                                                best.data_ptr(), dist.data_ptr(), _stream(stream)),
+               "lsh_index_nearest")
         return best, dist
 
 

@@ -175,6 +175,9 @@ int check_hash_args(const lsh_params *p, const void *d_in, const void *d_out, ui
     if (!p) return LSH_ERR_INVALID_ARG;
     if (N && (!d_in || !d_out)) return LSH_ERR_INVALID_ARG;
     if (p->device < 0) return LSH_ERR_NO_DEVICE;
+    int dev = -1;  // the tables live on the device that was current at create time
+    if (hipGetDevice(&dev) != hipSuccess) return LSH_ERR_HIP;
+    if (dev != p->device) return LSH_ERR_INVALID_ARG;
     return LSH_OK;
 }
 

@@ -10,8 +10,10 @@
 //   build      keys [N][L] -> per table: sorted keys [N], ids in key order [N]
 //   probe      query keys [Q][L] -> per (query, table): first position and length of the bucket
 //   candidates concatenation of a query's L buckets, all queries, at given offsets
-//   nearest    exact processing (Sec. 3.2, last paragraph): the candidate closest to the query
-//              in l2, distances in fp32 over the full vectors
+//   nearest    processing of the candidates (Sec. 3.2, last paragraph): the candidate closest to
+//              the query in l2, distances in fp32 over the full vectors; all candidates (the
+//              exact version) or only the first max_candidates of the combined list (the
+//              approximate version evaluates no more than 3L points)
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
@@ -86,8 +88,8 @@ __global__ void candidates_kernel(const uint32_t *__restrict__ sorted_ids, uint6
 __global__ __launch_bounds__(256) void nearest_kernel(const uint32_t *__restrict__ sorted_ids, uint64_t N, uint32_t L,
                                                       const float *__restrict__ data, const float *__restrict__ queries,
                                                       uint32_t n, const uint32_t *__restrict__ start,
-                                                      const uint32_t *__restrict__ count, uint32_t *__restrict__ best_id,
-                                                      float *__restrict__ best_dist) {
+                                                      const uint32_t *__restrict__ count, uint32_t max_candidates,
+                                                      uint32_t *__restrict__ best_id, float *__restrict__ best_dist) {
     extern __shared__ float query[];  // [n], then per-wave results
     const uint64_t q = blockIdx.x;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
@@ -96,8 +98,10 @@ __global__ __launch_bounds__(256) void nearest_kernel(const uint32_t *__restrict
     float mine_d = INFINITY;
     uint32_t mine_id = 0xFFFFFFFFu;
     uint32_t seen = 0;  // candidates are dealt to the waves round-robin over all L buckets
-    for (uint32_t l = 0; l < L; ++l) {
-        const uint32_t first = start[q * L + l], len = count[q * L + l];
+    for (uint32_t l = 0; l < L && seen < max_candidates; ++l) {
+        const uint32_t first = start[q * L + l];
+        uint32_t len = count[q * L + l];
+        if (len > max_candidates - seen) len = max_candidates - seen;  // only the first max_candidates of the list
         const uint32_t *bucket = sorted_ids + (uint64_t)l * N + first;
         for (uint32_t i = (wave + waves - seen % waves) % waves; i < len; i += waves) {
             const uint32_t id = bucket[i];
@@ -263,8 +267,8 @@ int lsh_index_candidates(const lsh_index_t *ix, const uint32_t *d_start, const u
 }
 
 int lsh_index_nearest(const lsh_index_t *ix, const float *d_data, const float *d_queries, uint32_t n,
-                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t *d_best_id,
-                      float *d_best_dist, void *stream) {
+                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t max_candidates,
+                      uint32_t *d_best_id, float *d_best_dist, void *stream) {
     if (!ix || !n) return LSH_ERR_INVALID_ARG;
     if (Q == 0) return LSH_OK;
     if (!d_data || !d_queries || !d_start || !d_count || !d_best_id || !d_best_dist) return LSH_ERR_INVALID_ARG;
@@ -274,7 +278,8 @@ int lsh_index_nearest(const lsh_index_t *ix, const float *d_data, const float *d
     if (rc != LSH_OK) return rc;
     const uint32_t lds = n * 4 + 4 * 8;
     hipLaunchKernelGGL(nearest_kernel, dim3((uint32_t)Q), dim3(256), lds, reinterpret_cast<hipStream_t>(stream), ix->d_ids,
-                       ix->N, ix->L, d_data, d_queries, n, d_start, d_count, d_best_id, d_best_dist);
+                       ix->N, ix->L, d_data, d_queries, n, d_start, d_count, max_candidates ? max_candidates : 0xFFFFFFFFu,
+                       d_best_id, d_best_dist);
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
 

@@ -103,6 +103,19 @@ def test_index_end_to_end_with_fastlsh_keys_and_exact_nearest(lsh):
         found += int(best_h[q] == src[q])
     say(f"planted neighbours found: {found} of {Q - 4}")
     assert found >= (Q - 4) * 0.8
+    # approximate version: only the first 3 candidates of the combined list
+    with lsh.LshIndex(keys) as ix:
+        start, count = ix.probe(qkeys)
+        best3, dist3 = ix.nearest(data, queries, start, count, max_candidates=3)
+        torch.cuda.synchronize()
+    best3_h = best3.cpu().numpy()
+    for q in range(Q):
+        cand = oindex.candidates(want[q])
+        expect = oindex.nearest(data_h, queries_h[q], cand, max_candidates=3)
+        if best3_h[q] != expect:
+            d_e = ((data_h[expect].astype(np.float64) - queries_h[q].astype(np.float64)) ** 2).sum()
+            d_g = ((data_h[best3_h[q]].astype(np.float64) - queries_h[q].astype(np.float64)) ** 2).sum()
+            assert best3_h[q] in cand[:3] and abs(d_g - d_e) <= 1e-5 * d_e
 
 
 def test_index_sift_shape_build_and_probe(lsh):
