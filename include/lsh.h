@@ -104,6 +104,10 @@ int lsh_params_get_shape(const lsh_params_t *params, uint32_t *n, uint32_t *k, u
 
 /* L of lsh_params_create_shared (0: every function has its own sample). */
 int lsh_params_get_tables(const lsh_params_t *params, uint32_t *shared_tables);
+/* a0 [k] of the maximum-inner-product transform (see lsh_hash_mips_data); host array of the
+ * caller.  Errors: INVALID_ARG, UNSUPPORTED (the object was not made by lsh_params_create_shared
+ * with L > 0). */
+int lsh_params_get_mips_coeffs(const lsh_params_t *params, float *out);
 
 /*
  * The order in which the sampled kernel visits each function's samples.  A projection is a
@@ -237,6 +241,45 @@ int lsh_index_nearest(const lsh_index_t *index, const float *d_data, const float
                       uint32_t *d_best_id, float *d_best_dist, void *stream);
 
 /*
+ * Maximum inner product search (appendix "Extension to Maximum Inner Product Search").  With one
+ * sample S_l per table (lsh_params_create_shared, L > 0; the appendix' "sample operator S" and
+ * its constant kappa~ are per table here), data and queries are transformed as
+ *     P~_l(v) = ( sqrt(kappa~_l^2 - ||S_l(v)||^2), S_l(v) ),   kappa~_l = max_i ||S_l(v_i)||
+ *     Q~_l(u) = ( 0, S_l(u) / ||S_l(u)|| )            (the appendix asks for ||S(u)|| = 1)
+ * and hashed with the l2 hash (Eq. 1) whose coefficient vector is (a0_j, a~_j), a0_j ~ N(0,1)
+ * one more draw per function (generator table 3):
+ *     data   h_j(v) = floor((a0_j sqrt(kappa~_l^2 - ||S_l(v)||^2) + a~_j . S_l(v) + b~_j) / w)
+ *     query  h_j(u) = floor((a~_j . S_l(u) / ||S_l(u)|| + b~_j) / w),        l = j div (k / L)
+ * The nearest transformed data vector of a transformed query is the data vector with the
+ * largest inner product with the query on the sampled coordinates.
+ *
+ * lsh_mips_kappa      d_kappa2 [L] float (device) <- max over the N vectors of ||S_l(v)||^2;
+ *                     accumulate != 0 keeps what d_kappa2 holds and only raises it (data that
+ *                     arrives in batches), 0 starts from zero.  NaN coordinates are ignored.
+ * lsh_hash_mips_data  d_out [N][k] int32 bucket ids of the data; d_kappa2 from lsh_mips_kappa
+ *                     over ALL data vectors (a vector whose norm exceeds kappa~_l is hashed as
+ *                     if it attained it).
+ * lsh_hash_mips_query d_out [Q][k] int32 bucket ids of the queries (a query whose sub-vector is
+ *                     all zero projects to 0).
+ * lsh_project_mips_*  the value before "+ b~_j) / w" as float, for parity checks.
+ * All arithmetic is fp32; norms are summed in sample order, four partial sums.  The ids feed
+ * lsh_pack_keys and the index like any others.  Pointers are device pointers, outputs are the
+ * caller's; asynchronous on `stream`.
+ * Errors: as lsh_hash_fastlsh; UNSUPPORTED when the object has no shared samples or its shape
+ * is outside the matrix-core kernel's (see lsh_params_create_shared).
+ */
+int lsh_mips_kappa(const lsh_params_t *params, const float *d_data, uint64_t N, int accumulate,
+                   float *d_kappa2, void *stream);
+int lsh_hash_mips_data(const lsh_params_t *params, const float *d_data, uint64_t N,
+                       const float *d_kappa2, int32_t *d_out, void *stream);
+int lsh_hash_mips_query(const lsh_params_t *params, const float *d_queries, uint64_t Q,
+                        int32_t *d_out, void *stream);
+int lsh_project_mips_data(const lsh_params_t *params, const float *d_data, uint64_t N,
+                          const float *d_kappa2, float *d_out, void *stream);
+int lsh_project_mips_query(const lsh_params_t *params, const float *d_queries, uint64_t Q,
+                           float *d_out, void *stream);
+
+/*
  * Collision probabilities (host functions, no GPU involved): what one needs to choose m and
  * the bucket width.  All pointers are host pointers.
  *
@@ -253,7 +296,10 @@ int lsh_index_nearest(const lsh_index_t *index, const float *d_data, const float
  * lsh_equivalent_width: the FastLSH width w * sqrt(m / n) under which, for large m, the
  *   collision law equals E2LSH's with width w (corollary of Sec. 4.2; the variance of the
  *   sampled projection difference is m s^2 / n).
- * Errors: INVALID_ARG (null pointer, non-positive or non-finite mu~ or w, negative sigma~).
+ * lsh_mips_collision_probability: the last equation of the appendix on maximum inner product
+ *   search: the transformed pair's squared distance is s~^2 + delta with
+ *   delta = kappa~^2 - ||S(v)||^2 >= 0, so the law of Eq. 9 applies with mean mu~ + delta.
+ * Errors: INVALID_ARG (null pointer, non-positive or non-finite mu~ or w, negative sigma~ or delta).
  */
 int lsh_e2lsh_collision_probability(double s, double w, double *p);
 int lsh_pair_statistics(const float *v, const float *u, uint32_t n, uint32_t m, double *mu_tilde,
@@ -261,6 +307,7 @@ int lsh_pair_statistics(const float *v, const float *u, uint32_t n, uint32_t m, 
 int lsh_fastlsh_collision_probability(double mu_tilde, double sigma_tilde, double w, double *p);
 int lsh_fastlsh_moment_factors(double mu_tilde, double sigma_tilde, double *epsilon, double *lambda);
 double lsh_equivalent_width(uint32_t n, uint32_t m, double w);
+int lsh_mips_collision_probability(double mu_tilde, double sigma_tilde, double delta, double w, double *p);
 
 const char *lsh_status_string(int status);
 

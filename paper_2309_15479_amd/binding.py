@@ -20,12 +20,14 @@ SAMPLE_WITH_REPLACEMENT = 1
 EXPORTS = [
     "lsh_params_create", "lsh_params_create_ex", "lsh_params_create_shared", "lsh_params_destroy",
     "lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape",
-    "lsh_params_get_tables", "lsh_params_get_schedule",
+    "lsh_params_get_tables", "lsh_params_get_mips_coeffs", "lsh_params_get_schedule",
     "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
     "lsh_e2lsh_collision_probability", "lsh_pair_statistics", "lsh_fastlsh_collision_probability",
-    "lsh_fastlsh_moment_factors", "lsh_equivalent_width",
+    "lsh_fastlsh_moment_factors", "lsh_equivalent_width", "lsh_mips_collision_probability",
+    "lsh_mips_kappa", "lsh_hash_mips_data", "lsh_hash_mips_query", "lsh_project_mips_data",
+    "lsh_project_mips_query",
     "lsh_index_build", "lsh_index_destroy", "lsh_index_tables", "lsh_index_probe",
     "lsh_index_candidate_offsets", "lsh_index_candidates", "lsh_index_nearest",
 ]
@@ -62,13 +64,19 @@ def load_library():
     lib.lsh_params_get_tables.argtypes = [p, p]
     lib.lsh_params_destroy.argtypes = [p]
     lib.lsh_params_destroy.restype = None
-    for name in ("lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets"):
+    for name in ("lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets",
+                 "lsh_params_get_mips_coeffs"):
         getattr(lib, name).argtypes = [p, p]
     lib.lsh_params_get_shape.argtypes = [p, p, p, p, p, p, p]
     lib.lsh_params_get_schedule.argtypes = [p, p, p, p, p, p]
     for name in ("lsh_hash_fastlsh", "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_project_fastlsh",
                  "lsh_project_e2lsh"):
         getattr(lib, name).argtypes = [p, p, u64, p, p]
+    for name in ("lsh_hash_mips_query", "lsh_project_mips_query"):
+        getattr(lib, name).argtypes = [p, p, u64, p, p]
+    for name in ("lsh_hash_mips_data", "lsh_project_mips_data"):
+        getattr(lib, name).argtypes = [p, p, u64, p, p, p]
+    lib.lsh_mips_kappa.argtypes = [p, p, u64, i, p, p]
     lib.lsh_pack_keys.argtypes = [p, p, u64, u32, p, p]
     lib.lsh_hash_fastlsh_keys.argtypes = [p, p, u64, u32, p, p]
     lib.lsh_time_launches.argtypes = [p, i, p, u64, u32, p, p, i, ctypes.POINTER(f32)]
@@ -79,6 +87,7 @@ def load_library():
     lib.lsh_fastlsh_moment_factors.argtypes = [f64, f64, p, p]
     lib.lsh_equivalent_width.argtypes = [u32, u32, f64]
     lib.lsh_equivalent_width.restype = f64
+    lib.lsh_mips_collision_probability.argtypes = [f64, f64, f64, f64, p]
     lib.lsh_index_build.argtypes = [p, u64, u32, p, ctypes.POINTER(p)]
     lib.lsh_index_destroy.argtypes = [p]
     lib.lsh_index_destroy.restype = None
@@ -151,6 +160,12 @@ class LshParams:
     def offsets(self):
         out = np.empty(self.k, np.float32)
         _check(load_library().lsh_params_get_offsets(self.handle, out.ctypes.data), "get_offsets")
+        return out
+
+    def mips_coeffs(self):
+        """a0 [k] of the maximum-inner-product transform (objects with shared_tables > 0)."""
+        out = np.empty(self.k, np.float32)
+        _check(load_library().lsh_params_get_mips_coeffs(self.handle, out.ctypes.data), "get_mips_coeffs")
         return out
 
     def schedule(self):
@@ -236,6 +251,55 @@ def project_fastlsh(params, data, out=None, stream=None):
 def project_e2lsh(params, data, out=None, stream=None):
     import torch
     return _hash_call("lsh_project_e2lsh", params, data, params.k, torch.float32, out, stream)
+
+
+def mips_kappa(params, data, out=None, accumulate=False, stream=None):
+    """kappa~_l^2 = max_i ||S_l(v_i)||^2, float32 [L]; accumulate=True only raises what `out` holds."""
+    import torch
+    _dev_in(data, torch.float32, params.n)
+    L = params.shared_tables()
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs the array to raise")
+        out = torch.empty(L, dtype=torch.float32, device=data.device)
+    if not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == L):
+        raise ValueError(f"expected a contiguous CUDA float32 tensor of {L} elements")
+    _check(load_library().lsh_mips_kappa(params.handle, data.data_ptr(), data.shape[0], int(bool(accumulate)),
+                                         out.data_ptr(), _stream(stream)), "lsh_mips_kappa")
+    return out
+
+
+def _mips_data_call(name, params, data, kappa2, dtype, out, stream):
+    import torch
+    _dev_in(data, torch.float32, params.n)
+    if not (kappa2.is_cuda and kappa2.dtype == torch.float32 and kappa2.is_contiguous()
+            and kappa2.numel() == params.shared_tables()):
+        raise ValueError("kappa2: expected the float32 CUDA tensor [L] of mips_kappa")
+    N = data.shape[0]
+    out = _out(data, N, params.k, dtype, out)
+    _check(getattr(load_library(), name)(params.handle, data.data_ptr(), N, kappa2.data_ptr(), out.data_ptr(),
+                                         _stream(stream)), name)
+    return out
+
+
+def hash_mips_data(params, data, kappa2, out=None, stream=None):
+    import torch
+    return _mips_data_call("lsh_hash_mips_data", params, data, kappa2, torch.int32, out, stream)
+
+
+def project_mips_data(params, data, kappa2, out=None, stream=None):
+    import torch
+    return _mips_data_call("lsh_project_mips_data", params, data, kappa2, torch.float32, out, stream)
+
+
+def hash_mips_query(params, queries, out=None, stream=None):
+    import torch
+    return _hash_call("lsh_hash_mips_query", params, queries, params.k, torch.int32, out, stream)
+
+
+def project_mips_query(params, queries, out=None, stream=None):
+    import torch
+    return _hash_call("lsh_project_mips_query", params, queries, params.k, torch.float32, out, stream)
 
 
 def pack_keys(params, buckets, L, out=None, stream=None):
@@ -364,6 +428,13 @@ def fastlsh_collision_probability(mu_tilde, sigma_tilde, w):
     out = ctypes.c_double()
     _check(load_library().lsh_fastlsh_collision_probability(mu_tilde, sigma_tilde, w, ctypes.addressof(out)),
            "lsh_fastlsh_collision_probability")
+    return out.value
+
+
+def mips_collision_probability(mu_tilde, sigma_tilde, delta, w):
+    out = ctypes.c_double()
+    _check(load_library().lsh_mips_collision_probability(mu_tilde, sigma_tilde, delta, w, ctypes.addressof(out)),
+           "lsh_mips_collision_probability")
     return out.value
 
 

@@ -21,6 +21,8 @@ void free_tables(lsh_params *p) {
     if (p->d_shared_coef) (void)hipFree(p->d_shared_coef);
     if (p->d_shared_sample_off) (void)hipFree(p->d_shared_sample_off);
     if (p->d_shared_offset) (void)hipFree(p->d_shared_offset);
+    if (p->d_shared_extra) (void)hipFree(p->d_shared_extra);
+    p->d_shared_extra = nullptr;
     p->d_shared_coef = nullptr;
     p->d_shared_sample_off = nullptr;
     p->d_shared_offset = nullptr;
@@ -136,9 +138,9 @@ int upload_tables(lsh_params *p) {
                 rc = LSH_ERR_HIP;
         }
         if (rc == LSH_OK && p->shared_plan.supported) {
-            std::vector<float> coef, offset;
+            std::vector<float> coef, offset, extra;
             std::vector<uint32_t> sample_off;
-            build_shared_tables(p, coef, sample_off, offset);
+            build_shared_tables(p, coef, sample_off, offset, extra);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
@@ -147,6 +149,7 @@ int upload_tables(lsh_params *p) {
             upload(reinterpret_cast<void **>(&p->d_shared_sample_off), sample_off.data(),
                    sample_off.size() * sizeof(uint32_t));
             upload(reinterpret_cast<void **>(&p->d_shared_offset), offset.data(), offset.size() * sizeof(float));
+            upload(reinterpret_cast<void **>(&p->d_shared_extra), extra.data(), extra.size() * sizeof(float));
         }
         if (rc == LSH_OK && p->kpad_dense) {
             // m == n: S_j is the identity, so the canonical coefficient table IS the dense
@@ -203,6 +206,7 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
     p->n = n; p->k = k; p->m = m; p->w = w; p->seed = seed; p->flags = flags;
     p->shared_tables = L;
     int rc = generate_tables(n, k, m, w, seed, flags, L ? k / L : 1, p->idx, p->coef, p->off);
+    if (rc == LSH_OK && L) rc = generate_extra_coefficients(k, seed, p->extra);
     if (rc == LSH_OK) {
         p->plan = plan_sampled(n, k, m);
         p->shared_plan = plan_shared(n, k, m, L);
@@ -279,6 +283,13 @@ int lsh_params_get_tables(const lsh_params_t *p, uint32_t *shared_tables) {
     return LSH_OK;
 }
 
+int lsh_params_get_mips_coeffs(const lsh_params_t *p, float *out) {
+    if (!p || !out) return LSH_ERR_INVALID_ARG;
+    if (p->extra.empty()) return LSH_ERR_UNSUPPORTED;
+    std::copy(p->extra.begin(), p->extra.end(), out);
+    return LSH_OK;
+}
+
 int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *steps, uint32_t *group,
                             uint32_t *classes, uint64_t *modelled_passes) {
     if (!p) return LSH_ERR_INVALID_ARG;
@@ -348,6 +359,54 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
     if (N == 0) return LSH_OK;
     if (shared_keys_ok(p, L)) return launch_shared(p, 2, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
+}
+
+int lsh_mips_kappa(const lsh_params_t *p, const float *d_data, uint64_t N, int accumulate, float *d_kappa2,
+                   void *stream) {
+    if (!d_kappa2) return LSH_ERR_INVALID_ARG;
+    int rc = check_hash_args(p, d_data, d_kappa2, N);
+    if (rc != LSH_OK) return rc;
+    if (!p->shared_plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (!accumulate) rc = clear_floats(d_kappa2, p->shared_tables, stream);
+    if (rc != LSH_OK || N == 0) return rc;
+    return launch_shared(p, 3, d_data, N, d_kappa2, stream);
+}
+
+static int mips_data(const lsh_params_t *p, const float *d_data, uint64_t N, const float *d_kappa2, void *d_out,
+                     void *stream, int raw) {
+    int rc = check_hash_args(p, d_data, d_out, N);
+    if (rc != LSH_OK) return rc;
+    if (N && !d_kappa2) return LSH_ERR_INVALID_ARG;
+    if (!p->shared_plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (N == 0) return LSH_OK;
+    return launch_shared(p, 4, d_data, N, d_out, stream, d_kappa2, raw);
+}
+
+static int mips_query(const lsh_params_t *p, const float *d_queries, uint64_t Q, void *d_out, void *stream, int raw) {
+    int rc = check_hash_args(p, d_queries, d_out, Q);
+    if (rc != LSH_OK) return rc;
+    if (!p->shared_plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (Q == 0) return LSH_OK;
+    return launch_shared(p, 5, d_queries, Q, d_out, stream, nullptr, raw);
+}
+
+int lsh_hash_mips_data(const lsh_params_t *p, const float *d_data, uint64_t N, const float *d_kappa2,
+                       int32_t *d_out, void *stream) {
+    return mips_data(p, d_data, N, d_kappa2, d_out, stream, 0);
+}
+
+int lsh_project_mips_data(const lsh_params_t *p, const float *d_data, uint64_t N, const float *d_kappa2,
+                          float *d_out, void *stream) {
+    return mips_data(p, d_data, N, d_kappa2, d_out, stream, 1);
+}
+
+int lsh_hash_mips_query(const lsh_params_t *p, const float *d_queries, uint64_t Q, int32_t *d_out, void *stream) {
+    return mips_query(p, d_queries, Q, d_out, stream, 0);
+}
+
+int lsh_project_mips_query(const lsh_params_t *p, const float *d_queries, uint64_t Q, float *d_out,
+                           void *stream) {
+    return mips_query(p, d_queries, Q, d_out, stream, 1);
 }
 
 int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32_t *d_out, void *stream) {

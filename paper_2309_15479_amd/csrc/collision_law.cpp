@@ -118,4 +118,9 @@ int lsh_fastlsh_collision_probability(double mu_tilde, double sigma_tilde, doubl
     return LSH_OK;
 }
 
+int lsh_mips_collision_probability(double mu_tilde, double sigma_tilde, double delta, double w, double *p) {
+    if (!(delta >= 0.0) || !std::isfinite(delta)) return LSH_ERR_INVALID_ARG;
+    return lsh_fastlsh_collision_probability(mu_tilde + delta, sigma_tilde, w, p);
+}
+
 }  // extern "C"

@@ -76,6 +76,7 @@ struct lsh_params {
     std::vector<uint32_t> idx;  // [k][m]
     std::vector<float> coef;    // [k][m]
     std::vector<float> off;     // [k]
+    std::vector<float> extra;   // [k] a0 of the maximum-inner-product transform (one sample per table only)
     // device side
     int device = -1;  // -1: no device tables
     int num_cus = 0;
@@ -93,6 +94,7 @@ struct lsh_params {
     float *d_shared_coef = nullptr;
     uint32_t *d_shared_sample_off = nullptr;
     float *d_shared_offset = nullptr;
+    float *d_shared_extra = nullptr;
 };
 
 namespace lsh {
@@ -103,6 +105,7 @@ namespace lsh {
 int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, uint32_t flags,
                     uint32_t sample_group, std::vector<uint32_t> &idx, std::vector<float> &coef,
                     std::vector<float> &off);
+int generate_extra_coefficients(uint32_t k, uint64_t seed, std::vector<float> &extra);
 
 // host: bank-conflict-free visiting order of every function's samples (schedule.cpp)
 uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,
@@ -122,9 +125,14 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
                    uint32_t L, void *stream);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
-                         std::vector<float> &offset);
-// ep: 0 bucket ids, 1 raw projections, 2 one key per table (needs shared_keys_ok)
-int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out, void *stream);
+                         std::vector<float> &offset, std::vector<float> &extra);
+// ep: 0 bucket ids, 1 raw projections, 2 one key per table (needs shared_keys_ok);
+// maximum-inner-product transform: 3 max of ||S_l(v)||^2 per table into d_out (float [L], atomic
+// max: cleared by the caller), 4 data hash (needs d_kappa2, float [L]), 5 query hash; raw != 0
+// makes 4 and 5 write the projections instead of the ids
+int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out, void *stream,
+                  const float *d_kappa2 = nullptr, int raw = 0);
+int clear_floats(float *d, uint32_t count, void *stream);
 // the shared-sample kernel can fold keys when a table lies inside one wave's blocks
 bool shared_keys_ok(const lsh_params *p, uint32_t L);
 // raises a kernel's dynamic LDS limit once (per kernel and size)

@@ -43,7 +43,7 @@ struct Philox4x64 {
     }
 };
 
-enum TableId : uint64_t { kIndexTable = 0, kCoefTable = 1, kOffsetTable = 2 };
+enum TableId : uint64_t { kIndexTable = 0, kCoefTable = 1, kOffsetTable = 2, kExtraTable = 3 };
 
 inline Block element_block(uint64_t seed, TableId table, uint64_t j, uint64_t i, uint64_t attempt) {
     return Philox4x64::run(Block{{i, j, static_cast<uint64_t>(table), attempt}}, seed, 0);
@@ -115,6 +115,24 @@ int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, 
         float b = static_cast<float>(top53(r.v[0]) * static_cast<double>(w));
         if (b >= w) b = std::nextafterf(w, 0.f);
         off[j] = b;
+    }
+    return LSH_OK;
+}
+
+// a0_j of the maximum-inner-product transform (appendix on maximum inner product search): one
+// more N(0,1) coefficient per function, for the extra leading component of the transformed
+// vectors.  Table 3 of the generator, element 0 of function j, drawn like the coefficients.
+int generate_extra_coefficients(uint32_t k, uint64_t seed, std::vector<float> &extra) {
+    try {
+        extra.assign(k, 0.f);
+    } catch (const std::bad_alloc &) {
+        return LSH_ERR_ALLOC;
+    }
+    const double two_pi = 6.283185307179586476925286766559;
+    for (uint32_t j = 0; j < k; ++j) {
+        const Block r = element_block(seed, kExtraTable, j, 0, 0);
+        const double radius_u = std::ldexp(static_cast<double>(r.v[0] >> 11) + 1.0, -53);
+        extra[j] = static_cast<float>(std::sqrt(-2.0 * std::log(radius_u)) * std::cos(two_pi * top53(r.v[1])));
     }
     return LSH_OK;
 }

@@ -19,7 +19,18 @@
 //                  of one vector per lane, so ids leave as 16-byte stores.
 // The tile's row stride n + 4 puts the 16 vectors of a read 4 banks apart (conflict-free for
 // one coordinate; the two coordinates of a half-wave pass collide only when they are equal
-// modulo 4).
+// modulo 4).  The 4 pad floats of a row are kept zero: samples beyond m read them.
+//
+// Maximum inner product search (appendix): the transformed vectors are
+// P~(v) = (sqrt(kappa~^2 - ||S(v)||^2), S(v)) for data and Q~(u) = (0, S(u) / ||S(u)||) for
+// queries, hashed with the l2 hash whose coefficient vector is (a0_j, a~_j).  The lanes
+// already hold the sampled coordinates as column operands, so ||S_l(v)||^2 is their sum of
+// squares over the steps and over the four lanes of a vector; the data hash adds
+// a0_j * sqrt(kappa~_l^2 - ||S_l(v)||^2) to the projection, the query hash divides it by
+// ||S_l(u)||, and a first pass takes kappa~_l^2 = max_v ||S_l(v)||^2 with the same arithmetic
+// (so the difference is exactly 0 for the vector that attains it).  The extra component and
+// the offset enter as one more MFMA step, row operand (a0_j, b~_j, 0, 0), column operand
+// (sqrt(kappa~^2 - ||S(v)||^2), 1, 0, 0): one register per block instead of eight.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -46,13 +57,17 @@ struct SharedArgs {
     const float *coef;           // [blocks][KS][64]   row operands, one float per lane
     const uint32_t *sample_off;  // [blocks][KS][4]    4 * S_l[4*kk + kq]: byte offset inside a tile row
     const float *offset;         // [blocks][16]       b~ of the block's functions
+    const float *extra;          // [blocks][64]       row operand (a0, b~, 0, 0) of the extra step (maximum inner product)
+    const float *kappa2;         // [L]                kappa~_l^2, input of the data hash
+    int raw;                     // maximum inner product hashes: write the projections, not the ids
     float w, inv_w;
     int w_is_pow2;
     int staged;                  // two-block waves pair up their pieces into whole 128-byte lines (needs g % 16 == 0)
     void *out;
 };
 
-// EP: 0 bucket ids, 1 raw projections, 2 one 64-bit key per table (Sec. 3.2; the fold of pack_kernel.hip)
+// EP: 0 bucket ids, 1 raw projections, 2 one 64-bit key per table (Sec. 3.2; the fold of pack_kernel.hip),
+//     3 kappa~_l^2 (atomic max into out, float [L]), 4 maximum-inner-product data hash, 5 query hash
 template <int KS, int RB, int WAVES, int EP>
 __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs a) {
     constexpr uint32_t kWaves = WAVES, kLanes = WAVES * 64;
@@ -68,10 +83,14 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
     // this wave's blocks: coefficients, per-lane LDS offsets of the sampled coordinates, b~
     float cf[RB][KS];
     uint32_t xo[RB][KS];
-    constexpr bool PROJ = EP == 1, KEYS = EP == 2;
+    constexpr bool PROJ = EP == 1, KEYS = EP == 2, KAPPA = EP == 3, MDATA = EP == 4, MQUERY = EP == 5;
+    constexpr bool NORMS = EP >= 3;
     float bq[RB][4];
     uint32_t fn0[RB];  // first of the lane's four functions, or >= k when it has none
     uint64_t pw[KEYS ? RB : 1];  // keys: C^(g - 4 - position in the table of the lane's first function), 0 for none
+    float cfx[MDATA || MQUERY ? RB : 1];  // row operand of the extra step
+    float kap[MDATA ? RB : 1];            // kappa~^2 of the block's table
+    float kmax[KAPPA ? RB : 1];    // running max of ||S_l(v)||^2 over the vectors this lane has seen
 #pragma unroll
     for (int e = 0; e < RB; ++e) {
         const uint32_t blk = block0 + e;
@@ -83,14 +102,21 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
             cf[e][kk] = have ? a.coef[((size_t)blk * KS + kk) * 64 + lane] : 0.f;
             xo[e][kk] = (have ? a.sample_off[((size_t)blk * KS + kk) * 4 + q] : 0u) + c16 * stride * 4;
         }
+        if constexpr (EP < 3) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bq[e][r] = a.offset[(size_t)blk * 16 + q * 4 + r];  // padded to every wave's blocks
+            for (int r = 0; r < 4; ++r) bq[e][r] = a.offset[(size_t)blk * 16 + q * 4 + r];  // padded to every wave's blocks
+        }
         if constexpr (KEYS) {
             uint64_t c = have && in_table < a.g ? 1 : 0;  // g % 4 == 0: a lane has four functions or none
             for (uint32_t i = in_table + 4; i < a.g; ++i) c *= kKeyMultiplier;
             pw[e] = c;
         }
+        if constexpr (MDATA || MQUERY) cfx[e] = a.extra[(size_t)blk * 64 + lane];
+        if constexpr (MDATA) kap[e] = have ? a.kappa2[table] : 0.f;
+        if constexpr (KAPPA) kmax[e] = 0.f;
     }
+    // the pad floats of every tile row (both buffers) stay zero for the whole launch
+    for (uint32_t i = threadIdx.x; i < 2 * rows * 4; i += kLanes) tile[(i >> 2) * stride + n + (i & 3)] = 0.f;
 
     // tile transfer: element e of the tile's float4 sequence = (vector e / n4, coordinates
     // 4 * (e % n4) ..); the slot arithmetic is redone at every use (it is cheap, and kept in
@@ -160,6 +186,13 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
             };
 #pragma unroll
             for (int kk = 0; kk < kAhead; ++kk) read_step(kk);
+            float nrm[NORMS ? VB : 1][NORMS ? RB : 1];  // ||S_l(v)||^2: this lane's coordinates, then the vector's
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int u = 0; u < VB; ++u)
+#pragma unroll
+                    for (int e = 0; e < RB; ++e) nrm[u][e] = 0.f;
+            }
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
                 __builtin_amdgcn_sched_barrier(0);
@@ -167,21 +200,55 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
 #pragma unroll
                 for (int u = 0; u < VB; ++u)
 #pragma unroll
-                    for (int e = 0; e < RB; ++e)
-                        acc[u][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(cf[e][kk], x[kk % (kAhead + 1)][u][e], acc[u][e], 0, 0, 0);
+                    for (int e = 0; e < RB; ++e) {
+                        const float xv = x[kk % (kAhead + 1)][u][e];
+                        if constexpr (!KAPPA) acc[u][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(cf[e][kk], xv, acc[u][e], 0, 0, 0);
+                        if constexpr (NORMS) nrm[u][e] = fmaf(xv, xv, nrm[u][e]);
+                    }
             }
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NORMS) {
+                // lanes c, c + 16, c + 32, c + 48 hold the partial sums of vector c: one more MFMA
+                // with an all-ones row operand adds them, D[i][c] = sum_kq partial[kq][c] in every
+                // row i, so every lane of the vector gets the same bits (the same instruction on
+                // the same operands in the kappa~ pass and in the data hash)
+#pragma unroll
+                for (int u = 0; u < VB; ++u)
+#pragma unroll
+                    for (int e = 0; e < RB; ++e) {
+                        const float4v sum = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, nrm[u][e], float4v{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                        nrm[u][e] = sum[0];
+                        if constexpr (KAPPA) kmax[e] = fmaxf(kmax[e], nrm[u][e]);  // vectors beyond N are zero rows
+                    }
+            }
+            if constexpr (KAPPA) continue;
 #pragma unroll
             for (int u = 0; u < VB; ++u) {
                 uint4 v[RB];
 #pragma unroll
                 for (int e = 0; e < RB; ++e) {
                     uint32_t w4[4];
+                    if constexpr (MDATA || MQUERY) {
+                        // data: sqrt(kappa~^2 - ||S(v)||^2) (0 when the norm exceeds kappa~); query: 1 / ||S(u)||
+                        float scale;
+                        if constexpr (MDATA) {
+                            scale = __builtin_amdgcn_sqrtf(fmaxf(kap[e] - nrm[u][e], 0.f));  // 1 ulp; sqrt(0) = 0
+                        } else {
+                            scale = nrm[u][e] > 0.f ? __builtin_amdgcn_rsqf(nrm[u][e]) : 0.f;
+                            acc[u][e] *= scale;
+                        }
+                        // extra step: + a0_j * scale (data) + b~_j (ids)
+                        const float one = a.raw ? 0.f : 1.f;
+                        const float colx = q == 0 ? (MDATA ? scale : 0.f) : (q == 1 ? one : 0.f);
+                        acc[u][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(cfx[e], colx, acc[u][e], 0, 0, 0);
+                    }
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float p = acc[u][e][r];
-                        if (PROJ) {
+                        if (PROJ || (NORMS && a.raw)) {
                             w4[r] = __float_as_uint(p);
+                        } else if constexpr (NORMS) {
+                            w4[r] = (uint32_t)(int)floorf(a.w_is_pow2 ? p * a.inv_w : p / a.w);  // b~ is in p already
                         } else {
                             const float s = a.w_is_pow2 ? fmaf(p, a.inv_w, bq[e][r] * a.inv_w) : (p + bq[e][r]) / a.w;
                             w4[r] = (uint32_t)(int)floorf(s);
@@ -265,6 +332,23 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
         __syncthreads();  // next buffer complete; everyone is done with the current one
         cur ^= 1;
     }
+    if constexpr (KAPPA) {
+        // max over the wave's 16 vector columns, then one atomic per block; norms are >= 0, so
+        // their bit patterns order like the values
+#pragma unroll
+        for (int e = 0; e < RB; ++e) {
+            float v = kmax[e];
+#pragma unroll
+            for (int s = 1; s < 16; s *= 2) v = fmaxf(v, __shfl_xor(v, s));
+            if (lane == 0 && block0 + e < a.nblocks)
+                atomicMax(reinterpret_cast<unsigned int *>(a.out) + (block0 + e) / a.blocks_per_table, __float_as_uint(v));
+        }
+    }
+}
+
+__global__ void clear_kernel(float *d, uint32_t count) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) d[i] = 0.f;
 }
 
 template <typename Kernel>
@@ -314,17 +398,18 @@ SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
 
 // Device tables in the kernel's operand layout (see the file comment).
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
-                         std::vector<float> &offset) {
+                         std::vector<float> &offset, std::vector<float> &extra) {
     const SharedPlan &pl = p->shared_plan;
     const uint32_t ks = pl.ksteps, blocks = pl.kblocks * pl.waves * pl.rb;
     coef.assign((size_t)blocks * ks * 64, 0.f);
-    sample_off.assign((size_t)blocks * ks * 4, 0u);
+    sample_off.assign((size_t)blocks * ks * 4, 4u * p->n);  // default: the row's zero pad
     offset.assign((size_t)blocks * 16, 0.f);
+    extra.assign((size_t)blocks * 64, 0.f);
     for (uint32_t blk = 0; blk < pl.nblocks; ++blk) {
         const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
         for (uint32_t kk = 0; kk < ks; ++kk)
             for (uint32_t kq = 0; kq < 4; ++kq) {
-                const uint32_t s = kk * 4 + kq;  // sample number; beyond m: coefficient 0, coordinate 0
+                const uint32_t s = kk * 4 + kq;  // sample number; beyond m: coefficient 0, the zero pad
                 if (s < p->m)
                     sample_off[((size_t)blk * ks + kk) * 4 + kq] = 4u * p->idx[(size_t)table * pl.g * p->m + s];
                 for (uint32_t i = 0; i < 16; ++i) {
@@ -335,7 +420,11 @@ void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vec
                 }
             }
         for (uint32_t i = 0; i < 16; ++i)
-            if (first + i < pl.g) offset[(size_t)blk * 16 + i] = p->off[table * pl.g + first + i];
+            if (first + i < pl.g) {
+                offset[(size_t)blk * 16 + i] = p->off[table * pl.g + first + i];
+                extra[(size_t)blk * 64 + i] = p->extra[table * pl.g + first + i];       // row operand, sample lane 0
+                extra[(size_t)blk * 64 + 16 + i] = p->off[table * pl.g + first + i];    // sample lane 1
+            }
     }
 }
 
@@ -346,7 +435,14 @@ bool shared_keys_ok(const lsh_params *p, uint32_t L) {
     return pl.supported && L == p->shared_tables && (pl.blocks_per_table == 1 || (pl.blocks_per_table == 2 && pl.rb == 2));
 }
 
-int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out, void *stream) {
+int clear_floats(float *d, uint32_t count, void *stream) {
+    if (!count) return LSH_OK;
+    hipLaunchKernelGGL(clear_kernel, dim3((count + 255) / 256), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), d, count);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out, void *stream,
+                  const float *d_kappa2, int raw) {
     const SharedPlan &pl = p->shared_plan;
     if (!pl.supported) return LSH_ERR_UNSUPPORTED;
     SharedArgs a;
@@ -363,6 +459,9 @@ int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, 
     a.coef = p->d_shared_coef;
     a.sample_off = p->d_shared_sample_off;
     a.offset = p->d_shared_offset;
+    a.extra = p->d_shared_extra;
+    a.kappa2 = d_kappa2;
+    a.raw = raw;
     a.w = p->w;
     a.inv_w = 1.0f / p->w;
     int exp2 = 0;
@@ -381,7 +480,11 @@ int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, 
     if (pl.ksteps == KS_ && pl.rb == RB_ && pl.waves == WAVES_) { \
         if (ep == 0) return launch(&shared_kernel<KS_, RB_, WAVES_, 0>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
         if (ep == 1) return launch(&shared_kernel<KS_, RB_, WAVES_, 1>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
-        return launch(&shared_kernel<KS_, RB_, WAVES_, 2>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        if (ep == 2) return launch(&shared_kernel<KS_, RB_, WAVES_, 2>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        if (ep == 3) return launch(&shared_kernel<KS_, RB_, WAVES_, 3>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        if (ep == 4) return launch(&shared_kernel<KS_, RB_, WAVES_, 4>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        if (ep == 5) return launch(&shared_kernel<KS_, RB_, WAVES_, 5>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+        return LSH_ERR_INVALID_ARG; \
     }
     LSH_SHARED_CASE(8, 1, 16) LSH_SHARED_CASE(8, 2, 16) LSH_SHARED_CASE(16, 1, 16)
 #undef LSH_SHARED_CASE

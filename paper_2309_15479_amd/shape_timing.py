@@ -70,6 +70,33 @@ def main(names):
                     print(f"{name} n={n} k={k} m={m} fastlsh, one sample per table (L={wl.L}): {ms:.3f} ms  "
                           f"{N * (4 * n + 4 * k) / ms / 1e6:.0f} GB/s algorithmic  "
                           f"{2 * N * k * m / ms / 1e9:.1f} TFLOP/s", flush=True)
+                    # maximum-inner-product transform (appendix): kappa~ pass, data hash, query hash
+                    try:
+                        kap = lsh.mips_kappa(p, data)
+                    except lsh.LshError:
+                        kap = None           # shape outside the matrix-core kernel
+                    if kap is not None:
+                        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                        for _ in range(3):
+                            lsh.mips_kappa(p, data, out=kap)
+                            lsh.hash_mips_data(p, data, kap, out=out)
+                            lsh.hash_mips_query(p, data, out=out)
+                        reps = 10
+                        ev[0].record()
+                        for _ in range(reps):
+                            lsh.mips_kappa(p, data, out=kap)
+                        ev[1].record()
+                        for _ in range(reps):
+                            lsh.hash_mips_data(p, data, kap, out=out)
+                        ev[2].record()
+                        for _ in range(reps):
+                            lsh.hash_mips_query(p, data, out=out)
+                        ev[3].record()
+                        torch.cuda.synchronize()
+                        t = [ev[i].elapsed_time(ev[i + 1]) / reps for i in range(3)]
+                        print(f"{name} n={n} k={k} m={m} maximum inner product: kappa {t[0]:.3f} ms "
+                              f"({N * 4 * n / t[0] / 1e6:.0f} GB/s), data hash {t[1]:.3f} ms "
+                              f"({N * (4 * n + 4 * k) / t[1] / 1e6:.0f} GB/s), query hash {t[2]:.3f} ms", flush=True)
                     del out
         if wl.L and not wl.signs:
             # index: build the L tables from the keys, probe 4096 of the vectors as queries

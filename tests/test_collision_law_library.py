@@ -60,6 +60,17 @@ def test_zero_spread_and_large_m_limits():
     assert errs[0] > errs[1] > errs[2] and errs[2] < 1e-3
 
 
+def test_mips_collision_probability_matches_oracle():
+    from oracle import mips
+    for mu_t, sigma_t, delta, w in [(3.0, 1.5, 2.0, 4.0), (9.0, 6.0, 0.0, 4.0), (1.0, 0.5, 10.0, 2.0)]:
+        got = binding.mips_collision_probability(mu_t, sigma_t, delta, w)
+        assert abs(got - mips.collision_probability(mu_t, sigma_t, delta, w)) < 2e-8
+    with pytest.raises(binding.LshError):
+        binding.mips_collision_probability(1.0, 1.0, -0.5, 1.0)
+    # a larger gap to kappa~ (a shorter data vector) lowers the collision probability
+    assert binding.mips_collision_probability(3.0, 1.0, 0.0, 4.0) > binding.mips_collision_probability(3.0, 1.0, 5.0, 4.0)
+
+
 def test_argument_errors():
     lib = binding.load_library()
     for args in [(-1.0, 1.0, 1.0), (1.0, -1.0, 1.0), (1.0, 1.0, 0.0), (float("nan"), 1.0, 1.0)]:

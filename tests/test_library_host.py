@@ -85,8 +85,13 @@ def test_shared_sample_tables_bit_identical_to_oracle(n, k, m, w, seed, repl, L)
         assert np.array_equal(p.coeffs().view(np.uint32), coef.view(np.uint32))
         assert np.array_equal(p.offsets().view(np.uint32), off.view(np.uint32))
         assert p.shared_tables() == L
+        # a0 of the maximum-inner-product transform (appendix): the generator's table 3
+        from oracle import mips
+        assert np.array_equal(p.mips_coeffs().view(np.uint32), mips.extra_coefficients(k, seed).view(np.uint32))
     with binding.LshParams(n, k, m, w, seed, with_replacement=repl) as p:
         assert p.shared_tables() == 0
+        with pytest.raises(binding.LshError):
+            p.mips_coeffs()
 
 
 def test_shared_sample_rejects_bad_table_count():

@@ -1,0 +1,194 @@
+"""GPU parity of the maximum-inner-product extension (appendix) against oracle/mips.py.
+
+Tolerances.  kappa~^2 and the norms are fp32 sums of m <= 64 squares in four partial sums:
+relative error below (m / 4 + 3) * 2^-24 < 2e-6, so |delta_gpu - delta| <= DELTA_ERR * kappa~^2
+with DELTA_ERR = 4e-6 for delta = kappa~^2 - ||S(v)||^2 (both terms carry the error).  The data
+projection a0 * sqrt(delta) + a~ . S(v) is then within
+    1e-5 * (sum_i |a~_i S(v)_i| + |a0| sqrt(delta)) + |a0| * (sqrt(delta + e) - sqrt(max(delta - e, 0)))
+of the oracle's, e = DELTA_ERR * kappa~^2; the query projection within 1e-5 * sum_i |a~_i S(u)_i| / ||S(u)||.
+Bucket ids: identical, except where the oracle's value lies within max(1e-4, 2 * tol / w) of a
+boundary (tol the element's projection tolerance), where either neighbour is accepted."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from oracle import mips
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+DELTA_ERR = 4e-6
+
+
+@pytest.fixture(scope="module")
+def lsh():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2309_15479_amd as lib
+    lib.load_library()
+    return lib
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def _check_ids(got, val, tol, w, label):
+    ids = np.floor(val)
+    frac = val - ids
+    band = np.maximum(1e-4, 2.0 * tol / w)
+    near = (frac < band) | (frac > 1.0 - band)
+    diff = got.astype(np.int64) - ids.astype(np.int64)
+    bad = (diff != 0) & ~near
+    assert not bad.any(), f"{label}: {int(bad.sum())} ids differ outside the band, first {np.argwhere(bad)[0].tolist()}"
+    assert (np.abs(diff) <= 1).all(), f"{label}: id off by more than one bucket"
+    return float(near.mean())
+
+
+def _compare(lsh, p, data_gpu, queries_gpu, rows, L, label):
+    """kappa over all of data_gpu; data hash checked on `rows`; query hash on all queries."""
+    n, k, m, w = p.n, p.k, p.m, p.w
+    g = k // L
+    idx, coef, off = p.indices(), p.coeffs(), p.offsets()
+    a0 = p.mips_coeffs()
+    assert np.array_equal(a0.view(np.uint32), mips.extra_coefficients(k, p.seed).view(np.uint32))
+    data = data_gpu.cpu().numpy()
+    kappa2_gpu = lsh.mips_kappa(p, data_gpu)
+    torch.cuda.synchronize()
+    kappa2 = mips.kappa_squared(data, idx, L)
+    kg = kappa2_gpu.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(kg - kappa2) <= 2e-6 * kappa2), f"{label}: kappa^2 off by {np.abs(kg / kappa2 - 1).max():.2e}"
+
+    sub_rows = data[rows]
+    proj_gpu = lsh.project_mips_data(p, data_gpu, kappa2_gpu)
+    ids_gpu = lsh.hash_mips_data(p, data_gpu, kappa2_gpu)
+    torch.cuda.synchronize()
+    val, _, _ = mips.hash_data(sub_rows, idx, coef, a0, off, w, L, kappa2)
+    want = val * np.float64(w) - off.astype(np.float64)[None, :]
+    tol = np.empty_like(want)
+    for l in range(L):
+        s = sub_rows.astype(np.float64)[:, idx[l * g].astype(np.int64)]
+        delta = np.maximum(kappa2[l] - (s ** 2).sum(axis=1), 0.0)
+        e = DELTA_ERR * kappa2[l]
+        root_err = np.sqrt(delta + e) - np.sqrt(np.maximum(delta - e, 0.0))
+        for j in range(l * g, (l + 1) * g):
+            abs_sum = np.abs(s * coef[j].astype(np.float64)).sum(axis=1) + abs(float(a0[j])) * np.sqrt(delta)
+            tol[:, j] = 1e-5 * abs_sum + abs(float(a0[j])) * root_err + 1e-30
+    err = np.abs(proj_gpu.cpu().numpy()[rows].astype(np.float64) - want)
+    worst = float((err / tol).max())
+    assert worst <= 1.0, f"{label}: data projection error {worst:.3f} x tolerance"
+    excl = _check_ids(ids_gpu.cpu().numpy()[rows], val, tol, w, label + " data")
+
+    worst_q = excl_q = 0.0
+    if queries_gpu is not None and queries_gpu.shape[0]:
+        queries = queries_gpu.cpu().numpy()
+        qproj = lsh.project_mips_query(p, queries_gpu)
+        qids = lsh.hash_mips_query(p, queries_gpu)
+        torch.cuda.synchronize()
+        qval, _, _ = mips.hash_queries(queries, idx, coef, a0, off, w, L)
+        qwant = qval * np.float64(w) - off.astype(np.float64)[None, :]
+        Q = mips.transformed_queries(queries, idx, L)
+        qtol = np.empty_like(qwant)
+        for j in range(k):
+            qtol[:, j] = 1e-5 * np.abs(Q[j // g][:, 1:] * coef[j].astype(np.float64)).sum(axis=1) + 1e-30
+        qerr = np.abs(qproj.cpu().numpy().astype(np.float64) - qwant)
+        worst_q = float((qerr / qtol).max())
+        assert worst_q <= 1.0, f"{label}: query projection error {worst_q:.3f} x tolerance"
+        excl_q = _check_ids(qids.cpu().numpy(), qval, qtol, w, label + " query")
+    return dict(proj=round(worst, 3), qproj=round(worst_q, 3), excluded=excl, qexcluded=excl_q)
+
+
+CASES = [
+    # N, Q, n, k, m, w, seed, with_replacement, L
+    (1003, 37, 128, 512, 32, 16.0, 61, False, 32),   # the benchmark shape: two blocks per wave, whole-line stores
+    (1000, 20, 128, 64, 32, 4.0, 62, False, 8),      # tables of 8 functions: half-empty blocks
+    (77, 9, 100, 72, 30, 2.5, 63, True, 6),          # samples padded to the MFMA step, duplicates, w not a power of two
+    (300, 40, 256, 512, 64, 4.0, 64, False, 16),     # 16 MFMA steps, two blocks per table
+    (50, 5, 612, 64, 20, 2.0, 65, False, 4),         # 32-vector tiles
+    (200, 16, 64, 2048, 8, 1.0, 66, False, 128),     # several workgroups along the functions
+    (1, 1, 128, 16, 4, 1.0, 67, False, 1),           # one vector: it attains kappa~ in the only table
+    (150, 10, 128, 1024, 16, 2.0, 68, False, 32),    # tables of 32 = a wave's two blocks
+]
+
+
+@pytest.mark.parametrize("N,Q,n,k,m,w,seed,repl,L", CASES)
+def test_mips_shapes(lsh, N, Q, n, k, m, w, seed, repl, L):
+    say(f"mips case N={N} Q={Q} n={n} k={k} m={m} w={w} seed={seed} repl={repl} L={L}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    # norms spread over an order of magnitude, as maximum inner product search expects
+    data = torch.randn((N, n), generator=g, device="cuda") * (0.3 + 3.0 * torch.rand((N, 1), generator=g, device="cuda"))
+    queries = torch.randn((Q, n), generator=g, device="cuda")
+    with lsh.LshParams(n, k, m, w, seed, with_replacement=repl, shared_tables=L) as p:
+        say(_compare(lsh, p, data, queries, np.arange(N), L, f"mips{seed}"))
+
+
+def test_vector_that_attains_kappa_and_accumulation(lsh):
+    N, n, k, m, w, L = 500, 128, 256, 32, 8.0, 16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(71)
+    data = torch.randn((N, n), generator=g, device="cuda") * (0.5 + torch.rand((N, 1), generator=g, device="cuda"))
+    with lsh.LshParams(n, k, m, w, 71, shared_tables=L) as p:
+        kap = lsh.mips_kappa(p, data)
+        # in batches: the same maxima, bit for bit
+        acc = lsh.mips_kappa(p, data[:123].contiguous())
+        lsh.mips_kappa(p, data[123:].contiguous(), out=acc, accumulate=True)
+        torch.cuda.synchronize()
+        assert torch.equal(kap, acc)
+        # the vector with the largest sampled norm of a table has delta = 0 exactly there: its data
+        # projection is the plain projection, bit for bit
+        idx = p.indices()
+        plain = lsh.project_fastlsh(p, data).cpu().numpy()
+        trans = lsh.project_mips_data(p, data, kap).cpu().numpy()
+        kappa2 = mips.kappa_squared(data.cpu().numpy(), idx, L)
+        gsz = k // L
+        for l in range(L):
+            s = data.cpu().numpy().astype(np.float64)[:, idx[l * gsz].astype(np.int64)]
+            top = int((s ** 2).sum(axis=1).argmax())
+            cols = slice(l * gsz, (l + 1) * gsz)
+            assert np.array_equal(trans[top, cols].view(np.uint32), plain[top, cols].view(np.uint32)), l
+            others = np.delete(np.arange(N), top)
+            assert (trans[others, cols] != plain[others, cols]).mean() > 0.9
+        # a vector beyond kappa~ (hashed with another set's kappa~) is treated as attaining it
+        big = (data[:4] * 100.0).contiguous()
+        assert np.array_equal(lsh.project_mips_data(p, big, kap).cpu().numpy().view(np.uint32),
+                              lsh.project_fastlsh(p, big).cpu().numpy().view(np.uint32))
+
+
+def test_mips_empty_zero_query_and_errors(lsh):
+    with lsh.LshParams(128, 64, 16, 2.0, 3, shared_tables=4) as p:
+        empty = torch.empty((0, 128), device="cuda")
+        kap = lsh.mips_kappa(p, empty)
+        torch.cuda.synchronize()
+        assert kap.shape == (4,) and (kap == 0).all()
+        assert lsh.hash_mips_data(p, empty, kap).shape == (0, 64)
+        assert lsh.hash_mips_query(p, empty).shape == (0, 64)
+        # an all-zero query projects to 0: its ids are floor(b / w) = 0 (b < w)
+        z = torch.zeros((3, 128), device="cuda")
+        assert (lsh.project_mips_query(p, z) == 0).all() and (lsh.hash_mips_query(p, z) == 0).all()
+        # all-zero data: kappa~ = 0, projection 0
+        kz = lsh.mips_kappa(p, z)
+        assert (kz == 0).all() and (lsh.project_mips_data(p, z, kz) == 0).all()
+    with lsh.LshParams(128, 64, 16, 2.0, 3) as p:          # no shared samples
+        with pytest.raises(lsh.LshError) as e:
+            lsh.hash_mips_query(p, torch.zeros((2, 128), device="cuda"))
+        assert "unsupported" in str(e.value).lower()
+        with pytest.raises(lsh.LshError):
+            p.mips_coeffs()
+    with lsh.LshParams(130, 64, 16, 2.0, 3, shared_tables=4) as p:   # shape outside the matrix-core kernel
+        with pytest.raises(lsh.LshError):
+            lsh.hash_mips_query(p, torch.zeros((2, 130), device="cuda"))
+
+
+def test_mips_sift_full_size(lsh):
+    wl, data = workloads.make_data("sift", "cuda")
+    rows = workloads.sample_rows(wl.N, 2048).numpy()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    queries = data[torch.randint(0, wl.N, (256,), generator=g, device="cuda")].contiguous()
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
+        say("sift mips", _compare(lsh, p, data, queries, rows, wl.L, "sift-mips"))
