@@ -323,13 +323,19 @@ __global__ __launch_bounds__(kSmallThreads) void dense_short_kernel(const DenseA
     // One quad of the epilogue: registers 4q..4q+3 of the accumulator are functions
     // 8q + 4*lh .. + 3 of the wave's 32, for vector lr; one 16-byte store.
     const bool k_vec = (a.k & 3) == 0 && col0 + BN <= a.k;
+    // The offsets of the lane's 16 functions stay in registers: a load inside the tile loop
+    // would have to be waited for with vmcnt(0), which also waits for the id stores issued
+    // just before it, i.e. for a full trip to HBM, four times per tile.
+    float4 bq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        bq[q] = *reinterpret_cast<const float4 *>(a.off + col0 + wn + 8 * q + 4 * lh);  // padded
     auto finish_quad = [&](const floatx16 &acc, int q, uint64_t tile) {
         const uint64_t row0 = tile * BM;
         const uint64_t row = row0 + wm + lr;
         OutT *dst_row = reinterpret_cast<OutT *>(a.out) + row * a.k;
         const uint32_t col = col0 + wn + 8 * q + 4 * lh;
-        const float4 b = *reinterpret_cast<const float4 *>(a.off + col);  // padded
-        const float bb[4] = {b.x, b.y, b.z, b.w};
+        const float bb[4] = {bq[q].x, bq[q].y, bq[q].z, bq[q].w};
         OutT v[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -398,6 +404,197 @@ __global__ __launch_bounds__(kSmallThreads) void dense_short_kernel(const DenseA
     }
 }
 
+
+// The same persistent scheme for the plain case n == 128, k a multiple of 128, stripped of
+// per-tile vector-ALU work.  On this part a vector-ALU instruction and an MFMA of the same SIMD
+// do not overlap (the co-execution counter reads 0), so every address computation, predicate
+// or register copy in the tile loop is taken from the matrix pipe: the 120 such instructions
+// per wave and tile of the general kernel cost it a tenth of its time.  Here the loads and
+// stores use a uniform tile pointer (scalar registers) plus a per-lane byte offset that never
+// changes, LDS accesses use immediate offsets, and the epilogue is one FMA and one
+// floor-convert per output (b~ / w is folded into the FMA's addend).  Only the last, partial
+// row tile takes predicated accesses.
+template <bool PROJ, bool POW2>
+__global__ __launch_bounds__(kSmallThreads) void dense_lean_kernel(const DenseArgs a) {
+    using OutT = typename std::conditional<PROJ, float, int32_t>::type;
+    using Vec4 = typename std::conditional<PROJ, float4, int4>::type;
+    static_assert(sizeof(OutT) == 4, "ids and projections are 4 bytes");
+    extern __shared__ __align__(16) float lds[];
+    float *lds_b = lds;                 // [128 functions][SSTRIDE]
+    float *lds_a = lds + BN * SSTRIDE;  // [128 vectors][SSTRIDE]
+
+    const uint32_t ntile_n = a.k / BN;
+    const uint64_t ntile_m = (a.N + BM - 1) / BM, full_m = a.N / BM;
+    const uint32_t xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
+    const uint32_t ct = slot % ntile_n;
+    const uint64_t stream = slot / ntile_n, streams = slots / ntile_n;
+    if (stream >= streams) return;
+    const uint32_t col0 = ct * BN;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave / (BN / 32)) * 32, wn = (wave % (BN / 32)) * 32;
+    const int lr = lane & 31, lh = lane >> 5;
+
+    // per-lane byte offsets, constant for the whole launch
+    const uint32_t ld_off = (threadIdx.x >> 5) * (SK * 4) + (threadIdx.x & 31) * 16;   // in a 128 x 128 block of floats
+    float *const lw = lds_a + (threadIdx.x >> 5) * SSTRIDE + (threadIdx.x & 31) * 4;     // + q * 32 rows
+    const uint32_t st_off = ((uint32_t)(wm + lr) * a.k + col0 + wn + 4 * lh) * 4;        // in a 128 x k block of outputs; + 32 q
+    const float *la = lds_a + (wm + lr) * SSTRIDE + lh * 4;
+    const float *lb = lds_b + (wn + lr) * SSTRIDE + lh * 4;
+    const char *const data = reinterpret_cast<const char *>(a.data);
+    char *const out = reinterpret_cast<char *>(a.out);
+
+    float4 r[kBlockRegs];
+    // One 16-byte piece of a block of vectors.  FULL: the tile has all its 128 rows, the address
+    // is the uniform tile pointer plus the lane's constant offset; otherwise rows beyond N read
+    // row N - 1 (computed, never stored).
+    auto fetch = [&](auto full_tag, uint64_t tile, int q) -> float4 {
+        if constexpr (decltype(full_tag)::value) {
+            return *reinterpret_cast<const float4 *>(data + tile * (uint64_t)(BM * SK * 4) + (ld_off + q * 32 * SK * 4));
+        } else {
+            uint64_t row = tile * BM + (threadIdx.x >> 5) + q * 32;
+            row = row < a.N ? row : a.N - 1;
+            return *reinterpret_cast<const float4 *>(data + row * (SK * 4) + (threadIdx.x & 31) * 16);
+        }
+    };
+
+    // coefficient tile, resident for the whole launch (rows padded to the tile grid)
+#pragma unroll
+    for (int q = 0; q < kBlockRegs; ++q)
+        r[q] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(a.a) + (uint64_t)col0 * (SK * 4) +
+                                                 (ld_off + q * 32 * SK * 4));
+#pragma unroll
+    for (int q = 0; q < kBlockRegs; ++q)
+        *reinterpret_cast<float4 *>(lds_b + (threadIdx.x >> 5) * SSTRIDE + (threadIdx.x & 31) * 4 + q * 32 * SSTRIDE) = r[q];
+
+    // epilogue constants: accumulator register 4q + t is function col0 + wn + 8q + 4 lh + t
+    float bs[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float4 b = *reinterpret_cast<const float4 *>(a.off + col0 + wn + 8 * q + 4 * lh);
+        bs[4 * q + 0] = POW2 ? b.x * a.inv_w : b.x;
+        bs[4 * q + 1] = POW2 ? b.y * a.inv_w : b.y;
+        bs[4 * q + 2] = POW2 ? b.z * a.inv_w : b.z;
+        bs[4 * q + 3] = POW2 ? b.w * a.inv_w : b.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bs[i]));  // held in registers, not recomputed per tile
+
+    const uint64_t stride = 8 * streams;
+    uint64_t rt = xcd + 8 * stream;
+    if (rt < full_m) {
+#pragma unroll
+        for (int q = 0; q < kBlockRegs; ++q) r[q] = fetch(std::true_type{}, rt, q);
+    }
+
+    OutT res[16];  // finished outputs of the previous tile; their stores go out during the next tile
+    uint64_t done_tile = 0;
+    auto store_quad = [&](auto full_tag, int q) {
+        Vec4 w4;
+        w4.x = res[4 * q + 0]; w4.y = res[4 * q + 1]; w4.z = res[4 * q + 2]; w4.w = res[4 * q + 3];
+        char *dst = out + done_tile * ((uint64_t)BM * 4) * a.k + (st_off + 32 * q);
+        if (decltype(full_tag)::value || done_tile * BM + wm + lr < a.N) *reinterpret_cast<Vec4 *>(dst) = w4;
+    };
+
+    // LDS hand-over: the block of vectors in `r` replaces the one in LDS.
+    auto hand_over = [&]() {
+        __syncthreads();  // everyone is done with the previous block of vectors
+#pragma unroll
+        for (int q = 0; q < kBlockRegs; ++q) *reinterpret_cast<float4 *>(lw + q * 32 * SSTRIDE) = r[q];
+        __syncthreads();
+    };
+
+    // One tile: 16 contraction steps with the memory work spread between them, then the epilogue
+    // arithmetic into `res`.  The next block's four loads go out during steps 0..3 (they have the
+    // rest of the tile to arrive), the previous tile's four stores during steps 5, 7, 9, 11; the
+    // hand-over that follows waits for the loads only (the counter of outstanding memory
+    // operations is in order, and the stores were issued after them).  FULL: a tile of the main
+    // loop, which has all its rows and prefetches full tiles only; the partial last tile runs
+    // the other instantiation once, after the loop.  STORE: there is a previous tile to store.
+    auto run_tile = [&](auto full_tag, auto store_tag) {
+        constexpr bool FULL = decltype(full_tag)::value, STORE = decltype(store_tag)::value;
+        const uint64_t next = rt + stride;
+        const bool more = FULL && next < full_m;
+        floatx16 acc;
+        // The operands of step kg + 1 are read from LDS before the MFMAs of step kg are issued:
+        // the four waves of a SIMD run in step, so a read issued only after a wave's MFMAs
+        // would find all of them waiting for LDS at the same time, with the matrix pipe idle.
+        float4 fa[2], fb[2];
+        fa[0] = *reinterpret_cast<const float4 *>(la);
+        fb[0] = *reinterpret_cast<const float4 *>(lb);
+#pragma unroll
+        for (int kg = 0; kg < SK / 8; ++kg) {
+            if (kg + 1 < SK / 8) {
+                fa[(kg + 1) & 1] = *reinterpret_cast<const float4 *>(la + (kg + 1) * 8);
+                fb[(kg + 1) & 1] = *reinterpret_cast<const float4 *>(lb + (kg + 1) * 8);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const float4 xa = fa[kg & 1], xb = fb[kg & 1];
+            if (kg == 0) {
+                const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xb.x, xa.x, zero, 0, 0, 0);
+            } else {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xb.x, xa.x, acc, 0, 0, 0);
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xb.y, xa.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xb.z, xa.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xb.w, xa.w, acc, 0, 0, 0);
+            if constexpr (FULL) {
+                if (more && kg == 0) r[0] = fetch(full_tag, next, 0);
+                if (more && kg == 1) r[1] = fetch(full_tag, next, 1);
+                if (more && kg == 2) r[2] = fetch(full_tag, next, 2);
+                if (more && kg == 3) r[3] = fetch(full_tag, next, 3);
+            }
+            if constexpr (STORE) {
+                if (kg >= 5 && kg <= 11 && (kg & 1)) store_quad(full_tag, (kg - 5) >> 1);  // in a FULL pass the previous tile was a full one
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keeps the memory instructions at their steps
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if constexpr (PROJ) {
+                res[i] = acc[i];
+            } else if constexpr (POW2) {
+                res[i] = (int)floorf(fmaf(acc[i], a.inv_w, bs[i]));
+            } else {
+                res[i] = (int)floorf((acc[i] + bs[i]) / a.w);
+            }
+        }
+        done_tile = rt;
+    };
+
+    bool have_done = false;
+    if (rt < full_m) {
+        hand_over();
+        run_tile(std::true_type{}, std::false_type{});  // first tile: nothing to store yet
+        have_done = true;
+        rt += stride;
+        if (rt < full_m) {
+            hand_over();
+            // the hand-over sits at the end of the loop body, after the body's loads and stores in
+            // straight-line code: at the top of the loop it would also be reached from the first
+            // tile, which has no stores after its loads, and would have to wait for everything
+            while (true) {
+                run_tile(std::true_type{}, std::true_type{});
+                rt += stride;
+                if (rt >= full_m) break;
+                hand_over();
+            }
+        }
+    }
+    if (rt < ntile_m) {  // the partial tile, if it is this workgroup's
+#pragma unroll
+        for (int q = 0; q < kBlockRegs; ++q) r[q] = fetch(std::false_type{}, rt, q);
+        hand_over();
+        if (have_done) run_tile(std::false_type{}, std::true_type{}); else run_tile(std::false_type{}, std::false_type{});
+        have_done = true;
+    }
+    if (have_done) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) store_quad(std::false_type{}, q);
+    }
+}
+
 }  // namespace
 
 uint32_t dense_col_tile() { return BN; }
@@ -433,6 +630,23 @@ int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N
         while (wgs / 8 < tiles_n) wgs += 8;
         const dim3 g2(wgs), b2(kSmallThreads);
         const bool pw = a.w_is_pow2 != 0;
+        if (p->n == (uint32_t)SK && p->k % BN == 0 && (uint64_t)p->k * BM * 4 < (1ull << 32)) {
+#define LSH_LEAN_CASE(P_, W_) \
+    if (proj == P_ && pw == W_) { \
+        auto fn = &dense_lean_kernel<P_, W_>; \
+        static std::atomic<bool> granted{false}; \
+        if (!granted.load(std::memory_order_acquire)) { \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
+                return LSH_ERR_HIP; \
+            granted.store(true, std::memory_order_release); \
+        } \
+        hipLaunchKernelGGL(fn, g2, b2, lds_bytes, s, a); \
+    }
+            LSH_LEAN_CASE(false, true) LSH_LEAN_CASE(false, false) LSH_LEAN_CASE(true, true) LSH_LEAN_CASE(true, false)
+#undef LSH_LEAN_CASE
+            return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+        }
 #define LSH_SHORT_CASE(V_, P_, W_) \
     if (vec4 == V_ && proj == P_ && pw == W_) { \
         auto fn = &dense_short_kernel<V_, P_, W_>; \

@@ -17,9 +17,10 @@
 //   column operand B[kq][c] = v_{vector c}[S_l[4*kk + kq]]         lane = c + 16*kq   (one 4-byte LDS read)
 //   result         D[4*q + r][c] in register r of lane c + 16*q: four consecutive functions
 //                  of one vector per lane, so ids leave as 16-byte stores.
-// The tile's row stride n + 4 puts the 16 vectors of a read 4 banks apart (conflict-free for
-// one coordinate; the two coordinates of a half-wave pass collide only when they are equal
-// modulo 4).  The 4 pad floats of a row are kept zero: samples beyond m read them.
+// The tile's row stride n + 4 puts the 16 vectors of a read 4 banks apart when n is a multiple
+// of 64 (conflict-free for one coordinate; two coordinates of a step collide when they are
+// equal modulo 4, which the host avoids by choosing which samples share a step).  The 4 pad
+// floats of a row are kept zero: samples beyond m read them.
 //
 // Maximum inner product search (appendix): the transformed vectors are
 // P~(v) = (sqrt(kappa~^2 - ||S(v)||^2), S(v)) for data and Q~(u) = (0, S(u) / ||S(u)||) for
@@ -405,11 +406,39 @@ void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vec
     sample_off.assign((size_t)blocks * ks * 4, 4u * p->n);  // default: the row's zero pad
     offset.assign((size_t)blocks * 16, 0.f);
     extra.assign((size_t)blocks * 64, 0.f);
+    // Which sample sits in which slot (step kk, lane group kq) is free: a projection is a sum.
+    // The 64 lanes of a column-operand read address banks 4 * vector + coordinate (mod 64), so
+    // the four coordinates of a step hit distinct banks iff they differ modulo 4.  Per table,
+    // deal the samples (and the pads, which read coordinate n = 0 mod 4) to the steps from the
+    // residue classes with the most left, one per class where four classes are left.
+    constexpr uint32_t kPad = 0xFFFFFFFFu;
+    std::vector<uint32_t> slot_sample((size_t)(pl.nblocks / pl.blocks_per_table) * ks * 4, kPad);
+    for (uint32_t table = 0; table < pl.nblocks / pl.blocks_per_table; ++table) {
+        std::vector<uint32_t> cls[4];
+        for (uint32_t smp = p->m; smp-- > 0;) cls[p->idx[(size_t)table * pl.g * p->m + smp] & 3].push_back(smp);
+        for (uint32_t pad = p->m; pad < ks * 4; ++pad) cls[0].insert(cls[0].begin(), kPad);  // pads leave last
+        for (uint32_t kk = 0; kk < ks; ++kk) {
+            uint32_t taken[4] = {0, 0, 0, 0};
+            for (uint32_t kq = 0; kq < 4; ++kq) {
+                // the class with the most left among those not used in this step, else the fullest
+                int best = -1;
+                for (int pass = 0; pass < 2 && best < 0; ++pass)
+                    for (int c = 0; c < 4; ++c)
+                        if (!cls[c].empty() && (pass == 1 || !taken[c]) &&
+                            (best < 0 || cls[c].size() > cls[best].size()))
+                            best = c;
+                slot_sample[((size_t)table * ks + kk) * 4 + kq] = cls[best].back();
+                cls[best].pop_back();
+                taken[best] = 1;
+            }
+        }
+    }
     for (uint32_t blk = 0; blk < pl.nblocks; ++blk) {
         const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
         for (uint32_t kk = 0; kk < ks; ++kk)
             for (uint32_t kq = 0; kq < 4; ++kq) {
-                const uint32_t s = kk * 4 + kq;  // sample number; beyond m: coefficient 0, the zero pad
+                // sample number; a pad slot keeps coefficient 0 and reads the row's zero pad
+                const uint32_t s = slot_sample[((size_t)table * ks + kk) * 4 + kq];
                 if (s < p->m)
                     sample_off[((size_t)blk * ks + kk) * 4 + kq] = 4u * p->idx[(size_t)table * pl.g * p->m + s];
                 for (uint32_t i = 0; i < 16; ++i) {

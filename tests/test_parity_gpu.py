@@ -176,6 +176,20 @@ def test_dense_shapes(lsh, N, n, k):
         say(_compare_all(lsh, p, data, np.arange(N), label=f"dense{N}x{n}x{k}", dense=True, signs=False))
 
 
+@pytest.mark.parametrize("N,k,w", [(1, 128, 2.0), (128, 128, 4.0), (127, 256, 1.5), (3000, 384, 2.0), (40000, 512, 0.5),
+                                   (2049, 1152, 3.0)])
+def test_dense_n128_shapes(lsh, N, k, w):
+    """n = 128 with k a multiple of 128 has a kernel of its own: single partial tile, exactly one
+    full tile, several column tiles, more row tiles than workgroups, w a power of two or not."""
+    say(f"dense n=128 case N={N} k={k} w={w}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(N * 3 + k)
+    data = torch.randn((N, 128), generator=g, device="cuda") * 2.0
+    with lsh.LshParams(128, k, 128, w, N + k) as p:
+        say(_compare_all(lsh, p, data, np.arange(N) if N <= 4096 else workloads.sample_rows(N, 2048).numpy(),
+                         label=f"dense128-{N}x{k}", dense=True, signs=False))
+
+
 @pytest.mark.parametrize("k,L", [(64, 16), (64, 1), (512, 2), (1024, 2), (96, 8), (60, 60), (256, 32), (100, 5)])
 def test_pack_keys_group_sizes(lsh, k, L):
     """Key packing is exact integer work: bit-exact against the oracle for every group size
