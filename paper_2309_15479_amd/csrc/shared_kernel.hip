@@ -69,12 +69,16 @@ struct SharedArgs {
 
 // EP: 0 bucket ids, 1 raw projections, 2 one 64-bit key per table (Sec. 3.2; the fold of pack_kernel.hip),
 //     3 kappa~_l^2 (atomic max into out, float [L]), 4 maximum-inner-product data hash, 5 query hash
-template <int KS, int RB, int WAVES, int EP>
+// GEOM: the tile geometry of n = 128 (128-vector tiles, row stride 132) as compile-time
+// constants: the loop over the tile's vector blocks is then unrolled and a block's LDS offset is
+// an immediate of the read instead of a vector add per read (a sixth of the kernel's
+// vector-ALU instructions, which do not overlap with its MFMAs).
+template <int KS, int RB, int WAVES, int EP, bool GEOM>
 __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs a) {
     constexpr uint32_t kWaves = WAVES, kLanes = WAVES * 64;
     constexpr int VB = RB >= 4 ? 1 : 2;  // blocks of 16 vectors in flight: VB * RB independent accumulators
     extern __shared__ __align__(16) float tile[];  // 2 x [rows][stride]
-    const uint32_t n = a.n, n4 = n >> 2, rows = a.rows, stride = a.stride;
+    const uint32_t n = GEOM ? 128u : a.n, n4 = n >> 2, rows = GEOM ? 128u : a.rows, stride = GEOM ? 132u : a.stride;
     const uint32_t lane = threadIdx.x & 63, c16 = lane & 15, q = lane >> 4;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t block0 = (blockIdx.y * kWaves + wave) * RB;
@@ -160,6 +164,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
         if (t_next < ntiles) fetch(t_next * rows);
 
         const char *base = reinterpret_cast<const char *>(tile + cur * buf_floats);
+#pragma unroll(GEOM ? 8 : 1)
         for (uint32_t vb = 0; vb < rows / 16; vb += VB) {
             float4v acc[VB][RB];
 #pragma unroll
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
 #pragma unroll
             for (int u = 0; u < VB; ++u) {
                 voff[u] = (vb + u) * 16 * stride * 4;
-                asm volatile("" : "+s"(voff[u]));
+                if constexpr (!GEOM) asm volatile("" : "+s"(voff[u]));
             }
             // software pipeline: the LDS reads of step kk + kAhead are issued before the MFMAs of
             // step kk (scheduling barriers keep the compiler from batching reads and MFMAs apart)
@@ -505,18 +510,19 @@ int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, 
     if (gx > ntiles) gx = ntiles;
     dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-#define LSH_SHARED_CASE(KS_, RB_, WAVES_) \
-    if (pl.ksteps == KS_ && pl.rb == RB_ && pl.waves == WAVES_) { \
-        if (ep == 0) return launch(&shared_kernel<KS_, RB_, WAVES_, 0>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
-        if (ep == 1) return launch(&shared_kernel<KS_, RB_, WAVES_, 1>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
-        if (ep == 2) return launch(&shared_kernel<KS_, RB_, WAVES_, 2>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
-        if (ep == 3) return launch(&shared_kernel<KS_, RB_, WAVES_, 3>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
-        if (ep == 4) return launch(&shared_kernel<KS_, RB_, WAVES_, 4>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
-        if (ep == 5) return launch(&shared_kernel<KS_, RB_, WAVES_, 5>, pl.lds_bytes, a, grid, WAVES_ * 64, s); \
+    const bool geom = p->n == 128 && pl.rows == 128 && pl.stride == 132;
+#define LSH_SHARED_EP(KS_, RB_, WAVES_, G_, EP_) \
+    if (ep == EP_) return launch(&shared_kernel<KS_, RB_, WAVES_, EP_, G_>, pl.lds_bytes, a, grid, WAVES_ * 64, s);
+#define LSH_SHARED_CASE(KS_, RB_, WAVES_, G_) \
+    if (pl.ksteps == KS_ && pl.rb == RB_ && pl.waves == WAVES_ && geom == G_) { \
+        LSH_SHARED_EP(KS_, RB_, WAVES_, G_, 0) LSH_SHARED_EP(KS_, RB_, WAVES_, G_, 1) LSH_SHARED_EP(KS_, RB_, WAVES_, G_, 2) \
+        LSH_SHARED_EP(KS_, RB_, WAVES_, G_, 3) LSH_SHARED_EP(KS_, RB_, WAVES_, G_, 4) LSH_SHARED_EP(KS_, RB_, WAVES_, G_, 5) \
         return LSH_ERR_INVALID_ARG; \
     }
-    LSH_SHARED_CASE(8, 1, 16) LSH_SHARED_CASE(8, 2, 16) LSH_SHARED_CASE(16, 1, 16)
+    LSH_SHARED_CASE(8, 1, 16, false) LSH_SHARED_CASE(8, 2, 16, false) LSH_SHARED_CASE(16, 1, 16, false)
+    LSH_SHARED_CASE(8, 1, 16, true) LSH_SHARED_CASE(8, 2, 16, true) LSH_SHARED_CASE(16, 1, 16, true)
 #undef LSH_SHARED_CASE
+#undef LSH_SHARED_EP
     return LSH_ERR_UNSUPPORTED;
 }
 
