@@ -78,7 +78,7 @@ def main():
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (rows shard trivially, but no "
+        sys.exit("bench.py: this library runs on one GPU only (rows shard trivially, but no "
                  "multi-GPU path exists); use --gpus 1")
 
     import torch

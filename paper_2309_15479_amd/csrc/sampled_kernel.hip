@@ -9,8 +9,8 @@
 // sample differ only in their immediate offset.  Each lane walks its own list of
 // (LDS offset, coefficient) pairs; there is no cross-lane reduction.
 //
-// Every gather-FMA costs one 64-lane vector-ALU slot (4 cycles of a SIMD: packed fp32 is off
-// in this build) and 4 bytes of LDS bandwidth, and the two ceilings are close, so both are
+// Every gather-FMA costs one 64-lane vector-ALU slot (4 cycles of a SIMD: the library is
+// compiled without packed fp32) and 4 bytes of LDS bandwidth, and the two ceilings are close, so both are
 // kept lean.  LDS: the order in which a lane visits its samples is chosen on the host
 // (schedule.cpp) such that the lanes served together by one pass of an LDS read (four quads
 // of lanes for 16-byte reads) hit distinct bank classes; with more than one sub-tile the

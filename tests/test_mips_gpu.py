@@ -192,3 +192,39 @@ def test_mips_sift_full_size(lsh):
     queries = data[torch.randint(0, wl.N, (256,), generator=g, device="cuda")].contiguous()
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
         say("sift mips", _compare(lsh, p, data, queries, rows, wl.L, "sift-mips"))
+
+
+def test_mips_retrieval_end_to_end(lsh):
+    """Data hashed with P~, queries with Q~, the index of Sec. 3.2 in between: the planted vector
+    with the largest inner product is among the candidates of almost every query, and the
+    candidate lists are a small part of the data (rates checked on the CPU oracle first:
+    0.98 and 1 % for these parameters)."""
+    n, N, Q, k, L, m, w, seed = 128, 20000, 64, 512, 64, 64, 1.25, 7
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    queries = torch.randn((Q, n), generator=g, device="cuda")
+    queries = (queries / torch.linalg.vector_norm(queries, dim=1, keepdim=True)).contiguous()
+    data = torch.randn((N, n), generator=g, device="cuda") / n ** 0.5 * (0.2 + 0.6 * torch.rand((N, 1), generator=g, device="cuda"))
+    data[:Q] = 0.97 * queries + 0.03 * torch.randn((Q, n), generator=g, device="cuda") / n ** 0.5
+    data = data.contiguous()
+    assert ((data @ queries.T).argmax(dim=0).cpu() == torch.arange(Q)).all()       # the planted vector is the answer
+    with lsh.LshParams(n, k, m, w, seed, shared_tables=L) as p:
+        kap = lsh.mips_kappa(p, data)
+        keys = lsh.pack_keys(p, lsh.hash_mips_data(p, data, kap), L)
+        qkeys = lsh.pack_keys(p, lsh.hash_mips_query(p, queries), L)
+        with lsh.LshIndex(keys) as ix:
+            start, count = ix.probe(qkeys)
+            offsets, ids = ix.candidates(start, count)
+            torch.cuda.synchronize()
+            offsets, ids = offsets.cpu().numpy(), ids.cpu().numpy()
+            found = best = 0
+            sizes = []
+            dcpu, qcpu = data.cpu().numpy(), queries.cpu().numpy()
+            for q in range(Q):
+                cand = np.unique(ids[offsets[q * L]:offsets[(q + 1) * L]])
+                sizes.append(cand.size)
+                found += int(q in cand)
+                if cand.size:
+                    best += int(cand[(dcpu[cand] @ qcpu[q]).argmax()] == q)
+    say(f"mips retrieval: planted found {found}/{Q}, best candidate is the answer {best}/{Q}, mean candidates {np.mean(sizes):.0f} of {N}")
+    assert found >= 0.9 * Q and best == found and np.mean(sizes) < 0.05 * N
