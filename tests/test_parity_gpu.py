@@ -263,7 +263,7 @@ def _sampled(N, count):
 
 def test_sift_full_size(lsh):
     wl, data = workloads.make_data("sift", "cuda")
-    rows = _sampled(wl.N, 4096)
+    rows = _sampled(wl.N, 32768)
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
         say("sift fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="sift"))
     with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
@@ -272,14 +272,14 @@ def test_sift_full_size(lsh):
 
 def test_sift_full_size_shared_sample(lsh):
     wl, data = workloads.make_data("sift", "cuda")
-    rows = _sampled(wl.N, 4096)
+    rows = _sampled(wl.N, 32768)
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
         say("sift shared-sample fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="sift-shared"))
 
 
 def test_gist_full_size(lsh):
     wl, data = workloads.make_data("gist", "cuda")
-    rows = _sampled(wl.N, 2048)
+    rows = _sampled(wl.N, 8192)
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
         say("gist fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="gist", signs=False))
     with lsh.LshParams(wl.n, wl.k, wl.n, wl.w, wl.seed) as p:
@@ -288,7 +288,7 @@ def test_gist_full_size(lsh):
 
 def test_highdim_full_size(lsh):
     wl, data = workloads.make_data("highdim", "cuda")
-    rows = _sampled(wl.N, 1024)
+    rows = _sampled(wl.N, 4096)
     # planted near-duplicates and their sources: collision counts must separate them from random pairs
     src = wl.extra["planted_src"].numpy()
     planted_rows = np.arange(wl.N - wl.planted, wl.N)
@@ -309,7 +309,7 @@ def test_highdim_full_size(lsh):
 
 def test_angular_full_size(lsh):
     wl, data = workloads.make_data("angular", "cuda")
-    rows = _sampled(wl.N, 1024)
+    rows = _sampled(wl.N, 4096)
     idxs = torch.as_tensor(rows, device="cuda")
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed) as p:
         idx, coef, _ = _tables(p)
