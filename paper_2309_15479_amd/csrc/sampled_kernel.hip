@@ -523,9 +523,12 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        finish<RT, SUB, EP, REGULAR>(a, row0, fresh(j), acc, b, key_pow, full_off);
-
+        // The next tile goes to LDS before this tile's results are stored: the counter of
+        // outstanding memory operations is in order, so a wait for the prefetched registers that
+        // came after the stores would also wait for them, a trip to HBM per tile.
         if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
+        __builtin_amdgcn_sched_barrier(0);
+        finish<RT, SUB, EP, REGULAR>(a, row0, fresh(j), acc, b, key_pow, full_off);
         __syncthreads();  // next buffer complete; everyone is done with the current one
         cur ^= 1;
     }

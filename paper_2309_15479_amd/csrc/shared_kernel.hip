@@ -90,6 +90,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
     uint32_t xo[RB][KS];
     constexpr bool PROJ = EP == 1, KEYS = EP == 2, KAPPA = EP == 3, MDATA = EP == 4, MQUERY = EP == 5;
     constexpr bool NORMS = EP >= 3;
+    constexpr bool kEarlyStash = EP < 3;
     float bq[RB][4];
     uint32_t fn0[RB];  // first of the lane's four functions, or >= k when it has none
     uint64_t pw[KEYS ? RB : 1];  // keys: C^(g - 4 - position in the table of the lane's first function), 0 for none
@@ -213,6 +214,15 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
                     }
             }
             __builtin_amdgcn_sched_barrier(0);
+            // The prefetched tile goes to the other LDS buffer after the first block's MFMAs and
+            // before any of this tile's stores: the counter of outstanding memory operations is
+            // in order, so a wait for the prefetch registers issued after stores would wait for
+            // those stores too (a trip to HBM per tile).  By now the loads have had a quarter
+            // of the tile's time to arrive.  (The maximum-inner-product hashes have no registers
+            // left for it at this point and keep the hand-over at the end of the tile.)
+            if constexpr (kEarlyStash) {
+                if (vb == 0 && t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
+            }
             if constexpr (NORMS) {
                 // lanes c, c + 16, c + 32, c + 48 hold the partial sums of vector c: one more MFMA
                 // with an all-ones row operand adds them, D[i][c] = sum_kq partial[kq][c] in every
@@ -334,7 +344,9 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
             }
         }
 
-        if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
+        if constexpr (!kEarlyStash) {
+            if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
+        }
         __syncthreads();  // next buffer complete; everyone is done with the current one
         cur ^= 1;
     }
