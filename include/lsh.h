@@ -80,8 +80,8 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
  * Every hash call accepts such an object; lsh_hash_fastlsh, lsh_project_fastlsh and (called
  * with the same L, g <= 32) lsh_hash_fastlsh_keys then gather each table's sub-vector once and
  * contract it with the g coefficient vectors on the matrix cores when the shape allows
- * (n % 4 == 0, n <= 612, m <= 64, g % 4 == 0), and fall back to the per-function gather
- * kernels otherwise.  L == 0 is lsh_params_create_ex.
+ * (n % 4 == 0, g % 4 == 0, and m <= 64 with n <= 612 or 64 < m <= 128 with n <= 1260), and
+ * fall back to the per-function gather kernels otherwise.  L == 0 is lsh_params_create_ex.
  * Errors: as lsh_params_create, and INVALID_ARG when k % L != 0.
  */
 int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,

@@ -50,7 +50,7 @@ struct SharedArgs {
     const float *data;  // [N][n]
     uint64_t N;
     uint32_t n, k, g;
-    uint32_t rows;               // vectors per tile, a multiple of 32
+    uint32_t rows;               // vectors per tile, a multiple of 32 (of 16 for the 32-step kernel)
     uint32_t stride;             // floats per tile row in LDS
     uint32_t n4_magic;           // floor(2^32 / (n / 4)) + 1: e / (n / 4) = mulhi(e, n4_magic) for e * n / 4 < 2^32
     uint32_t blocks_per_table;   // ceil(g / 16)
@@ -76,7 +76,9 @@ struct SharedArgs {
 template <int KS, int RB, int WAVES, int EP, bool GEOM>
 __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs a) {
     constexpr uint32_t kWaves = WAVES, kLanes = WAVES * 64;
-    constexpr int VB = RB >= 4 ? 1 : 2;  // blocks of 16 vectors in flight: VB * RB independent accumulators
+    // blocks of 16 vectors in flight: VB * RB independent accumulators (one with 32 steps of
+    // coefficients in registers, and so that 16-vector tiles are possible)
+    constexpr int VB = (RB >= 4 || KS >= 32) ? 1 : 2;
     extern __shared__ __align__(16) float tile[];  // 2 x [rows][stride]
     const uint32_t n = GEOM ? 128u : a.n, n4 = n >> 2, rows = GEOM ? 128u : a.rows, stride = GEOM ? 132u : a.stride;
     const uint32_t lane = threadIdx.x & 63, c16 = lane & 15, q = lane >> 4;
@@ -87,7 +89,12 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
 
     // this wave's blocks: coefficients, per-lane LDS offsets of the sampled coordinates, b~
     float cf[RB][KS];
-    uint32_t xo[RB][KS];
+    // per-lane LDS byte offsets of the sampled coordinates: one register per step, or (32 steps:
+    // the registers are needed for the coefficients) the offsets inside a tile row packed two to
+    // a register, with the lane's row offset added at each read
+    constexpr bool kPacked = KS >= 32;
+    uint32_t xo[RB][kPacked ? KS / 2 : KS];
+    const uint32_t lane_row = c16 * stride * 4;
     constexpr bool PROJ = EP == 1, KEYS = EP == 2, KAPPA = EP == 3, MDATA = EP == 4, MQUERY = EP == 5;
     constexpr bool NORMS = EP >= 3;
     constexpr bool kEarlyStash = EP < 3;
@@ -106,7 +113,12 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
             cf[e][kk] = have ? a.coef[((size_t)blk * KS + kk) * 64 + lane] : 0.f;
-            xo[e][kk] = (have ? a.sample_off[((size_t)blk * KS + kk) * 4 + q] : 0u) + c16 * stride * 4;
+            const uint32_t off = have ? a.sample_off[((size_t)blk * KS + kk) * 4 + q] : 0u;  // < 4 n + 16 < 65536
+            if constexpr (kPacked) {
+                if (kk & 1) xo[e][kk / 2] |= off << 16; else xo[e][kk / 2] = off;
+            } else {
+                xo[e][kk] = off + lane_row;
+            }
         }
         if constexpr (EP < 3) {
 #pragma unroll
@@ -165,6 +177,13 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
         if (t_next < ntiles) fetch(t_next * rows);
 
         const char *base = reinterpret_cast<const char *>(tile + cur * buf_floats);
+        if constexpr (kPacked) {
+            // or the compiler would unpack them once, outside the tile loop, into twice the registers
+#pragma unroll
+            for (int e = 0; e < RB; ++e)
+#pragma unroll
+                for (int h = 0; h < KS / 2; ++h) asm volatile("" : "+v"(xo[e][h]));
+        }
 #pragma unroll(GEOM ? 8 : 1)
         for (uint32_t vb = 0; vb < rows / 16; vb += VB) {
             float4v acc[VB][RB];
@@ -189,7 +208,15 @@ __global__ __launch_bounds__(WAVES * 64, 4) void shared_kernel(const SharedArgs 
                 for (int u = 0; u < VB; ++u)
 #pragma unroll
                     for (int e = 0; e < RB; ++e)
-                        x[kk % (kAhead + 1)][u][e] = *reinterpret_cast<const float *>(base + (voff[u] + xo[e][kk]));
+                    {
+                        uint32_t off;
+                        if constexpr (kPacked) {
+                            off = lane_row + ((kk & 1) ? xo[e][kk / 2] >> 16 : xo[e][kk / 2] & 0xffffu);
+                        } else {
+                            off = xo[e][kk];
+                        }
+                        x[kk % (kAhead + 1)][u][e] = *reinterpret_cast<const float *>(base + (voff[u] + off));
+                    }
             };
 #pragma unroll
             for (int kk = 0; kk < kAhead; ++kk) read_step(kk);
@@ -378,23 +405,24 @@ int launch(Kernel fn, uint32_t lds_bytes, const SharedArgs &args, dim3 grid, uin
 
 }  // namespace
 
-// Shapes the kernel takes: n a multiple of 4 whose tile of >= 32 vectors fits LDS twice, lists
-// of at most 64 samples, tables of a multiple of 4 functions.
+// Shapes the kernel takes: n a multiple of 4 whose tile of >= 32 vectors (>= 16 for lists of more
+// than 64 samples) fits LDS twice, lists of at most 128 samples, tables of a multiple of 4 functions.
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
     SharedPlan pl;
-    if (!L || k % L || (n & 3) || m > 64 || m == n) return pl;
+    if (!L || k % L || (n & 3) || m > 128 || m == n) return pl;
     const uint32_t g = k / L;
     if (g & 3) return pl;
     pl.stride = n + 4;
     pl.g = g;
-    pl.ksteps = m <= 32 ? 8 : 16;
+    pl.ksteps = m <= 32 ? 8 : m <= 64 ? 16 : 32;
     pl.blocks_per_table = (g + 15) / 16;
     pl.nblocks = L * pl.blocks_per_table;
     // One workgroup of 16 waves per CU with the largest tile that fits LDS twice (two
     // workgroups of 8 waves on 64-vector tiles measured slower).  A wave keeps 2 * rb * ksteps
     // coefficient and offset registers: at most 32 of a lane's 128.
     struct Shape { uint32_t waves, rows, per_cu; };
-    for (const Shape sh : {Shape{16, 128, 1}, Shape{16, 64, 1}, Shape{16, 32, 1}}) {
+    for (const Shape sh : {Shape{16, 128, 1}, Shape{16, 64, 1}, Shape{16, 32, 1}, Shape{16, 16, 1}}) {
+        if (sh.rows == 16 && pl.ksteps != 32) continue;  // only the 32-step kernel walks single 16-vector blocks
         if (2ull * sh.rows * pl.stride * 4 * sh.per_cu > kLdsBudget) continue;
         if ((uint64_t)sh.rows * (n / 4) > (uint64_t)kPre * sh.waves * 64) continue;
         pl.waves = sh.waves;
@@ -403,7 +431,7 @@ SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L) {
         break;
     }
     if (!pl.rows) return pl;
-    const uint32_t rb_max = (pl.waves == 8 ? 32 : 16) / pl.ksteps;
+    const uint32_t rb_max = pl.ksteps >= 32 ? 1 : (pl.waves == 8 ? 32 : 16) / pl.ksteps;
     pl.rb = 1;
     while (pl.rb < rb_max && pl.waves * pl.rb < pl.nblocks) pl.rb *= 2;
     pl.kblocks = (pl.nblocks + pl.waves * pl.rb - 1) / (pl.waves * pl.rb);
@@ -532,6 +560,7 @@ int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, 
         return LSH_ERR_INVALID_ARG; \
     }
     LSH_SHARED_CASE(8, 1, 16, false) LSH_SHARED_CASE(8, 2, 16, false) LSH_SHARED_CASE(16, 1, 16, false)
+    LSH_SHARED_CASE(32, 1, 16, false)
     LSH_SHARED_CASE(8, 1, 16, true) LSH_SHARED_CASE(8, 2, 16, true) LSH_SHARED_CASE(16, 1, 16, true)
 #undef LSH_SHARED_CASE
 #undef LSH_SHARED_EP

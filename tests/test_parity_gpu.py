@@ -149,7 +149,11 @@ SHARED = [
     (333, 128, 384, 32, 8.0, 51, False, 24),     # two blocks per wave with idle waves: whole-line stores
     (150, 128, 1024, 16, 2.0, 52, False, 32),    # tables of 32 = a wave's two blocks; two workgroups along the functions
     (40, 130, 64, 16, 1.0, 48, False, 8),        # n not a multiple of 4: gather kernels
-    (40, 960, 128, 128, 1.0, 49, False, 8),      # m > 64: gather kernels
+    (90, 960, 128, 128, 1.0, 49, False, 8),      # 64 < m <= 128: 32 MFMA steps, 16-vector tiles (the GIST shape's geometry)
+    (300, 256, 512, 100, 4.0, 53, True, 32),     # 32 steps with padded samples, 64-vector tiles
+    (33, 1260, 64, 65, 2.0, 54, False, 4),       # the widest n the 32-step kernel takes
+    (40, 1264, 64, 65, 2.0, 55, False, 4),       # one more: gather kernels
+    (40, 960, 128, 160, 1.0, 56, False, 8),      # m > 128: gather kernels
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
 ]
 
@@ -275,6 +279,13 @@ def test_sift_full_size_shared_sample(lsh):
     rows = _sampled(wl.N, 32768)
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
         say("sift shared-sample fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="sift-shared"))
+
+
+def test_gist_full_size_shared_sample(lsh):
+    wl, data = workloads.make_data("gist", "cuda")
+    rows = _sampled(wl.N, 8192)
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
+        say("gist shared-sample fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="gist-shared", signs=False))
 
 
 def test_gist_full_size(lsh):
