@@ -330,3 +330,29 @@ def test_angular_full_size(lsh):
         torch.cuda.synchronize()
         ex = check_signs(w_gpu[idxs].cpu().numpy().view(np.uint64), w_ora, pr, npd, p.k, "angular")
         say("angular signs excluded fraction", ex)
+
+
+def test_bucket_ids_saturate_outside_int32(lsh):
+    """Projections beyond +-2^31 buckets come out as INT32_MAX / INT32_MIN on every path (the
+    conversion saturates); the oracle's fp64 value says which elements those are."""
+    N, n, k, L = 300, 128, 128, 8
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    data = torch.randn((N, n), generator=g, device="cuda") * 3.0e10
+    data[::7] *= 1e-9                                   # some vectors stay in range
+    host = data.cpu().numpy()
+    lo, hi = -2 ** 31, 2 ** 31 - 1
+    for m, shared in ((32, 0), (32, L), (n, 0)):
+        with lsh.LshParams(n, k, m, 1.0, 5, shared_tables=shared) as p:
+            idx, coef, off = _tables(p)
+            val = (host.astype(np.float64)[:, idx.astype(np.int64)] * coef.astype(np.float64)[None]).sum(axis=2) + off
+            want = np.clip(np.floor(val), lo, hi)
+            sure = (np.abs(val) > 2.0 ** 31 * 1.001) | (np.abs(val) < 2.0 ** 31 * 0.999)
+            calls = [lsh.hash_fastlsh] + ([lsh.hash_e2lsh] if m == n else [])
+            for call in calls:
+                got = call(p, data).cpu().numpy().astype(np.float64)
+                big = np.abs(val) > 2.0 ** 31 * 1.001
+                assert big.any() and (~big).any()
+                assert np.array_equal(got[big], want[big]), f"{call.__name__} m={m} shared={shared}: saturation"
+                inside = sure & ~big          # in range: the id within fp32 accuracy of the projection
+                assert (np.abs(got[inside] - want[inside]) <= np.maximum(1.0, np.abs(val[inside]) * 1e-5)).all()
