@@ -34,8 +34,8 @@ VALU_FP32_UNPACKED_TFLOPS = 78.6
 # profiles/sift_step_hbm_traffic.md.  Set an entry to None when its kernel changes.
 MEASURED_TRAFFIC_BYTES = {
     "fastlsh": 250656 * 2048 + 2000000 * 1024,    # 0.513 GB read + 2.048 GB written
-    "pack_keys": 1000021 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
-    "e2lsh": 251090 * 2048 + 2020563 * 1024,      # 0.514 GB + 2.069 GB
+    "pack_keys": 1000044 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
+    "e2lsh": 251088 * 2048 + 2019286 * 1024,      # 0.514 GB + 2.068 GB
     "signs": 250574 * 2048 + 62500 * 1024,        # 0.513 GB + 0.064 GB
     "fastlsh_shared_sample": 250422 * 2048 + 2000000 * 1024,  # 0.513 GB + 2.048 GB
 }
