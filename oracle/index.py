@@ -52,3 +52,18 @@ def nearest(data, query, cand, max_candidates=0):
         if d < best_d:
             best, best_d = i, d
     return best
+
+
+def best_inner_product(data, query, cand, max_candidates=0):
+    """Processing of the candidates for maximum inner product search (the appendix on maximum
+    inner product search ranks the transformed vectors by distance, which is the order of the
+    inner products v . u): the distinct candidate with the largest inner product with the query
+    (ties: the smaller id), or -1 when there is none.  fp64."""
+    if max_candidates:
+        cand = cand[:max_candidates]
+    best, best_ip = -1, -np.inf
+    for i in sorted(set(cand)):
+        ip = float((data[i].astype(np.float64) * query.astype(np.float64)).sum())
+        if ip > best_ip:
+            best, best_ip = i, ip
+    return best

@@ -48,3 +48,22 @@ def test_near_duplicates_are_found_through_real_hashes():
     cand = oindex.candidates(buckets)
     assert cand.count(123) >= L // 2
     assert oindex.nearest(data, query, cand) == 123
+
+
+def test_best_inner_product_is_the_brute_force_argmax():
+    import numpy as np
+    from oracle import index as ix
+    rng = np.random.default_rng(3)
+    data = rng.normal(size=(50, 7)).astype(np.float32)
+    q = rng.normal(size=7).astype(np.float32)
+    cand = [4, 9, 9, 30, 2, 41, 4]
+    ips = data.astype(np.float64) @ q.astype(np.float64)
+    assert ix.best_inner_product(data, q, cand) == max(set(cand), key=lambda i: ips[i])
+    assert ix.best_inner_product(data, q, cand, max_candidates=3) == max({4, 9}, key=lambda i: ips[i])
+    assert ix.best_inner_product(data, q, []) == -1
+    # ties go to the smaller id; and it is NOT the nearest vector in general
+    data[9] = data[4]
+    assert ix.best_inner_product(data, q, [9, 4]) == 4
+    far = np.array([[10.0, 0.0], [0.9, 0.0]], np.float32)
+    u = np.array([1.0, 0.0], np.float32)
+    assert ix.best_inner_product(far, u, [0, 1]) == 0 and ix.nearest(far, u, [0, 1]) == 1
