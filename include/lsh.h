@@ -223,8 +223,13 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
  *   evaluates every candidate (the exact version); otherwise only the first max_candidates
  *   entries of the query's combined list are evaluated (the approximate version of the paper
  *   uses 3L).  d_data [N][n] must be the indexed vectors, d_queries [Q][n].  Asynchronous.
+ * lsh_index_best_inner_product: the same walk for maximum inner product search (appendix): the
+ *   candidate with the largest inner product v . u with the query (fp32; ties to the smaller
+ *   id) -> d_best_id, d_best_ip [Q] (-inf when there is no candidate).  The index is then built
+ *   from the keys of lsh_hash_mips_data and probed with those of lsh_hash_mips_query.
  * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^32, called on another device than the one
- * the index was built on), ALLOC, HIP, NO_DEVICE, UNSUPPORTED (lsh_index_nearest: n > 16368).
+ * the index was built on), ALLOC, HIP, NO_DEVICE, UNSUPPORTED (lsh_index_nearest and
+ * lsh_index_best_inner_product: n > 16368).
  */
 typedef struct lsh_index lsh_index_t; /* opaque */
 int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream, lsh_index_t **out);
@@ -239,6 +244,9 @@ int lsh_index_candidates(const lsh_index_t *index, const uint32_t *d_start, cons
 int lsh_index_nearest(const lsh_index_t *index, const float *d_data, const float *d_queries, uint32_t n,
                       const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t max_candidates,
                       uint32_t *d_best_id, float *d_best_dist, void *stream);
+int lsh_index_best_inner_product(const lsh_index_t *index, const float *d_data, const float *d_queries, uint32_t n,
+                                 const uint32_t *d_start, const uint32_t *d_count, uint64_t Q,
+                                 uint32_t max_candidates, uint32_t *d_best_id, float *d_best_ip, void *stream);
 
 /*
  * Maximum inner product search (appendix "Extension to Maximum Inner Product Search").  With one

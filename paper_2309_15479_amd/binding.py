@@ -29,7 +29,7 @@ EXPORTS = [
     "lsh_mips_kappa", "lsh_hash_mips_data", "lsh_hash_mips_query", "lsh_project_mips_data",
     "lsh_project_mips_query",
     "lsh_index_build", "lsh_index_destroy", "lsh_index_tables", "lsh_index_probe",
-    "lsh_index_candidate_offsets", "lsh_index_candidates", "lsh_index_nearest",
+    "lsh_index_candidate_offsets", "lsh_index_candidates", "lsh_index_nearest", "lsh_index_best_inner_product",
 ]
 
 
@@ -96,6 +96,7 @@ def load_library():
     lib.lsh_index_candidate_offsets.argtypes = [p, u64, p, p]
     lib.lsh_index_candidates.argtypes = [p, p, p, p, u64, p, p]
     lib.lsh_index_nearest.argtypes = [p, p, p, u32, p, p, u64, u32, p, p, p]
+    lib.lsh_index_best_inner_product.argtypes = [p, p, p, u32, p, p, u64, u32, p, p, p]
     lib.lsh_status_string.argtypes = [i]
     lib.lsh_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -388,10 +389,18 @@ class LshIndex:
                                                        _stream(stream)), "lsh_index_candidates")
         return offsets, ids
 
+    def best_inner_product(self, data, queries, start, count, max_candidates=0, stream=None):
+        """Candidate with the largest inner product: (best id [Q] int32 with -1 for none, inner
+        product [Q] float32, -inf for none)."""
+        return self._best("lsh_index_best_inner_product", data, queries, start, count, max_candidates, stream)
+
     def nearest(self, data, queries, start, count, max_candidates=0, stream=None):
         """Nearest candidate: (best id [Q] int32 with -1 for none, squared distance [Q] float32).
         max_candidates = 0: every candidate (exact version); else only the first max_candidates
         of each query's combined list (the paper's approximate version uses 3 * L)."""
+        return self._best("lsh_index_nearest", data, queries, start, count, max_candidates, stream)
+
+    def _best(self, name, data, queries, start, count, max_candidates, stream):
         import torch
         assert data.is_cuda and data.dtype == torch.float32 and data.is_contiguous() and data.shape[0] == self.N
         assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
@@ -399,10 +408,9 @@ class LshIndex:
         assert data.shape[1] == n and start.shape == (Q, self.L)
         best = torch.empty(Q, dtype=torch.int32, device=data.device)
         dist = torch.empty(Q, dtype=torch.float32, device=data.device)
-        _check(load_library().lsh_index_nearest(self.handle, data.data_ptr(), queries.data_ptr(), n,
-                                                start.data_ptr(), count.data_ptr(), Q, max_candidates,
-                                                best.data_ptr(), dist.data_ptr(), _stream(stream)),
-               "lsh_index_nearest")
+        _check(getattr(load_library(), name)(self.handle, data.data_ptr(), queries.data_ptr(), n,
+                                             start.data_ptr(), count.data_ptr(), Q, max_candidates,
+                                             best.data_ptr(), dist.data_ptr(), _stream(stream)), name)
         return best, dist
 
 

@@ -84,7 +84,10 @@ __global__ void candidates_kernel(const uint32_t *__restrict__ sorted_ids, uint6
 }
 
 // one workgroup per query: squared l2 distance of every candidate of its L buckets (a candidate
-// met in several tables is simply evaluated again), minimum with ties to the smaller id
+// met in several tables is simply evaluated again), minimum with ties to the smaller id.
+// INNER: the score is the inner product with the query instead and the largest one wins
+// (maximum inner product search; internally the negated product is minimised).
+template <bool INNER>
 __global__ __launch_bounds__(256) void nearest_kernel(const uint32_t *__restrict__ sorted_ids, uint64_t N, uint32_t L,
                                                       const float *__restrict__ data, const float *__restrict__ queries,
                                                       uint32_t n, const uint32_t *__restrict__ start,
@@ -108,8 +111,12 @@ __global__ __launch_bounds__(256) void nearest_kernel(const uint32_t *__restrict
             const float *v = data + (uint64_t)id * n;
             float acc = 0.f;
             for (uint32_t c = lane; c < n; c += 64) {
-                const float d = v[c] - query[c];
-                acc = fmaf(d, d, acc);
+                if constexpr (INNER) {
+                    acc = fmaf(-v[c], query[c], acc);
+                } else {
+                    const float d = v[c] - query[c];
+                    acc = fmaf(d, d, acc);
+                }
             }
             for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
             if (acc < mine_d || (acc == mine_d && id < mine_id)) {
@@ -133,7 +140,7 @@ __global__ __launch_bounds__(256) void nearest_kernel(const uint32_t *__restrict
                 mine_id = wave_id[w];
             }
         best_id[q] = mine_id;
-        best_dist[q] = mine_d;
+        best_dist[q] = INNER ? -mine_d : mine_d;  // no candidate: +inf distance, -inf inner product
     }
 }
 
@@ -266,21 +273,40 @@ int lsh_index_candidates(const lsh_index_t *ix, const uint32_t *d_start, const u
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
 
-int lsh_index_nearest(const lsh_index_t *ix, const float *d_data, const float *d_queries, uint32_t n,
-                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t max_candidates,
-                      uint32_t *d_best_id, float *d_best_dist, void *stream) {
+static int best_candidate(bool inner, const lsh_index_t *ix, const float *d_data, const float *d_queries, uint32_t n,
+                          const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t max_candidates,
+                          uint32_t *d_best_id, float *d_best_score, void *stream) {
     if (!ix || !n) return LSH_ERR_INVALID_ARG;
     if (Q == 0) return LSH_OK;
-    if (!d_data || !d_queries || !d_start || !d_count || !d_best_id || !d_best_dist) return LSH_ERR_INVALID_ARG;
+    if (!d_data || !d_queries || !d_start || !d_count || !d_best_id || !d_best_score) return LSH_ERR_INVALID_ARG;
     if (Q >= (1ull << 31)) return LSH_ERR_INVALID_ARG;
     if ((uint64_t)n * 4 + 64 > 64 * 1024) return LSH_ERR_UNSUPPORTED;  // the query is kept in LDS
     int rc = on_index_device(ix);
     if (rc != LSH_OK) return rc;
     const uint32_t lds = n * 4 + 4 * 8;
-    hipLaunchKernelGGL(nearest_kernel, dim3((uint32_t)Q), dim3(256), lds, reinterpret_cast<hipStream_t>(stream), ix->d_ids,
-                       ix->N, ix->L, d_data, d_queries, n, d_start, d_count, max_candidates ? max_candidates : 0xFFFFFFFFu,
-                       d_best_id, d_best_dist);
+    const uint32_t limit = max_candidates ? max_candidates : 0xFFFFFFFFu;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (inner)
+        hipLaunchKernelGGL(nearest_kernel<true>, dim3((uint32_t)Q), dim3(256), lds, s, ix->d_ids, ix->N, ix->L, d_data,
+                           d_queries, n, d_start, d_count, limit, d_best_id, d_best_score);
+    else
+        hipLaunchKernelGGL(nearest_kernel<false>, dim3((uint32_t)Q), dim3(256), lds, s, ix->d_ids, ix->N, ix->L, d_data,
+                           d_queries, n, d_start, d_count, limit, d_best_id, d_best_score);
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+int lsh_index_nearest(const lsh_index_t *ix, const float *d_data, const float *d_queries, uint32_t n,
+                      const uint32_t *d_start, const uint32_t *d_count, uint64_t Q, uint32_t max_candidates,
+                      uint32_t *d_best_id, float *d_best_dist, void *stream) {
+    return best_candidate(false, ix, d_data, d_queries, n, d_start, d_count, Q, max_candidates, d_best_id, d_best_dist,
+                          stream);
+}
+
+int lsh_index_best_inner_product(const lsh_index_t *ix, const float *d_data, const float *d_queries, uint32_t n,
+                                 const uint32_t *d_start, const uint32_t *d_count, uint64_t Q,
+                                 uint32_t max_candidates, uint32_t *d_best_id, float *d_best_ip, void *stream) {
+    return best_candidate(true, ix, d_data, d_queries, n, d_start, d_count, Q, max_candidates, d_best_id, d_best_ip,
+                          stream);
 }
 
 }  // extern "C"

@@ -103,6 +103,25 @@ def test_index_end_to_end_with_fastlsh_keys_and_exact_nearest(lsh):
         found += int(best_h[q] == src[q])
     say(f"planted neighbours found: {found} of {Q - 4}")
     assert found >= (Q - 4) * 0.8
+    # the same candidates ranked by inner product (maximum inner product search), all and first 5
+    with lsh.LshIndex(keys) as ix:
+        start, count = ix.probe(qkeys)
+        for limit in (0, 5):
+            bip, ip = ix.best_inner_product(data, queries, start, count, max_candidates=limit)
+            torch.cuda.synchronize()
+            bip_h, ip_h = bip.cpu().numpy(), ip.cpu().numpy()
+            for q in range(Q):
+                cand = oindex.candidates(want[q])
+                expect = oindex.best_inner_product(data_h, queries_h[q], cand, max_candidates=limit)
+                if expect < 0:
+                    assert bip_h[q] == -1 and np.isneginf(ip_h[q])
+                    continue
+                scale = float(np.abs(data_h[expect].astype(np.float64) * queries_h[q].astype(np.float64)).sum())
+                e_ip = float((data_h[expect].astype(np.float64) * queries_h[q].astype(np.float64)).sum())
+                assert abs(ip_h[q] - e_ip) <= 1e-5 * scale + 1e-12
+                if bip_h[q] != expect:   # only a near-tie in fp32 may pick another candidate
+                    o_ip = float((data_h[bip_h[q]].astype(np.float64) * queries_h[q].astype(np.float64)).sum())
+                    assert bip_h[q] in (cand[:limit] if limit else cand) and abs(o_ip - e_ip) <= 1e-5 * scale
     # approximate version: only the first 3 candidates of the combined list
     with lsh.LshIndex(keys) as ix:
         start, count = ix.probe(qkeys)

@@ -221,7 +221,9 @@ def test_mips_retrieval_end_to_end(lsh):
         with lsh.LshIndex(keys) as ix:
             start, count = ix.probe(qkeys)
             offsets, ids = ix.candidates(start, count)
+            gpu_best, gpu_ip = ix.best_inner_product(data, queries, start, count)
             torch.cuda.synchronize()
+            gpu_best = gpu_best.cpu().numpy()
             offsets, ids = offsets.cpu().numpy(), ids.cpu().numpy()
             found = best = 0
             sizes = []
@@ -231,6 +233,10 @@ def test_mips_retrieval_end_to_end(lsh):
                 sizes.append(cand.size)
                 found += int(q in cand)
                 if cand.size:
-                    best += int(cand[(dcpu[cand] @ qcpu[q]).argmax()] == q)
+                    top = cand[(dcpu[cand] @ qcpu[q]).argmax()]
+                    best += int(top == q)
+                    assert gpu_best[q] == top          # the library's ranking of the same candidates
+                else:
+                    assert gpu_best[q] == -1
     say(f"mips retrieval: planted found {found}/{Q}, best candidate is the answer {best}/{Q}, mean candidates {np.mean(sizes):.0f} of {N}")
     assert found >= 0.9 * Q and best == found and np.mean(sizes) < 0.05 * N
