@@ -170,7 +170,8 @@ def test_shared_sample_shapes(lsh, N, n, k, m, w, seed, repl, L):
         say(_compare_all(lsh, p, data, np.arange(N), L=L, label=f"shared{seed}"))
 
 
-@pytest.mark.parametrize("N,n,k", [(130, 128, 128), (129, 100, 200), (1, 37, 5), (515, 36, 257), (64, 4096, 64)])
+@pytest.mark.parametrize("N,n,k", [(130, 128, 128), (129, 100, 200), (1, 37, 5), (515, 36, 257), (64, 4096, 64),
+                                   (300, 128, 192), (257, 128, 70), (400, 124, 256)])
 def test_dense_shapes(lsh, N, n, k):
     say(f"dense case N={N} n={n} k={k}")
     g = torch.Generator(device="cuda")
