@@ -270,6 +270,47 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
         }
         default: {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64
             uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
+            if constexpr (RT == 4) {
+                if (a.g >= 4) {  // uniform
+                    // As for ids, the quads are transposed first: a lane then holds the ids of the
+                    // quad's four consecutive functions for ONE vector, folds them by Horner's rule
+                    // (three multiplications by C and one by its power of C, instead of one 64-bit
+                    // multiplication per id and vector), and only the g / 4 partials of a vector are
+                    // left to add across lanes: those of the lanes i, i + 4, i + 8, ... of the key
+                    // group, by DPP shifts inside a row of 16 lanes and exchanges across rows.
+                    // (for g >= 4 the kernels pass key_pow = C^(g-1-(t|3)), the power of the quad's last function)
+                    // everything per lane is derived from j, which the register-list kernels pass
+                    // through an empty asm every tile: derived from threadIdx.x it would be hoisted
+                    // out of the tile loop and held in registers across the gather
+                    const uint32_t g_log2 = 31 - __builtin_clz(a.g), t = j & (a.g - 1), u_mine = j & 3;  // workgroup sizes are multiples of 4
+                    float unit[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) unit[u] = u_mine == (uint32_t)u ? 1.f : 0.f;
+                    const float b_scaled = b * a.inv_w;
+#pragma unroll
+                    for (int s = 0; s < SUB; ++s) {
+                        float q[RT];
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) {
+                            const float v = a.w_is_pow2 ? fmaf(acc[s][r], a.inv_w, b_scaled) : (acc[s][r] + b) / a.w;
+                            q[r] = __builtin_amdgcn_fmed3f(v, -2147483648.f, 2147483648.f);
+                        }
+                        quad_transpose_mfma(q, unit);
+                        uint64_t part = (uint32_t)(int)floorf(q[0]);
+                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[1]);
+                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[2]);
+                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[3]);
+                        part *= key_pow;
+                        if (a.g >= 8) part += dpp_u64<0x104>(part);   // row_shl:4: lane i takes lane i + 4 (0 past the row)
+                        if (a.g >= 16) part += dpp_u64<0x108>(part);  // row_shl:8
+                        if (a.g >= 32) part += __shfl_down(part, 16);
+                        if (a.g >= 64) part += __shfl_down(part, 32);
+                        const uint64_t row = row0 + s * RT + u_mine;
+                        if (live && row < a.N && t < 4) out[row * a.L + (j >> g_log2)] = part;
+                    }
+                    break;
+                }
+            }
 #pragma unroll
             for (int s = 0; s < SUB; ++s)
 #pragma unroll
@@ -301,7 +342,8 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
 
     uint64_t key_pow = 1;  // C^(g-1-t) for this lane's position t in its key group
     if (EP == (int)Epilogue::Keys) {
-        const uint32_t t = j % a.g;
+        uint32_t t = j % a.g;
+        if (RT == 4 && a.g >= 4) t |= 3;  // the transposed fold multiplies by the power of the quad's last function
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
     }
 
@@ -401,7 +443,8 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
 
     uint64_t key_pow = 1;
     if (EP == (int)Epilogue::Keys) {
-        const uint32_t t = j % a.g;
+        uint32_t t = j % a.g;
+        if (RT == 4 && a.g >= 4) t |= 3;  // the transposed fold multiplies by the power of the quad's last function
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
     }
 
@@ -528,7 +571,15 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
         // came after the stores would also wait for them, a trip to HBM per tile.
         if (t_next < ntiles) stash(tile + (cur ^ 1) * buf_floats);
         __builtin_amdgcn_sched_barrier(0);
-        finish<RT, SUB, EP, REGULAR>(a, row0, fresh(j), acc, b, key_pow, full_off);
+        if constexpr (EP == (int)Epilogue::Keys) {
+            // the key fold needs a few registers more than the other epilogues: the offset is read
+            // again every tile (an L2 hit, issued after the wait for the prefetched tile) rather
+            // than held across the gather
+            const uint32_t jt = fresh(j);
+            finish<RT, SUB, EP, REGULAR>(a, row0, jt, acc, a.off[jt], key_pow, full_off);
+        } else {
+            finish<RT, SUB, EP, REGULAR>(a, row0, fresh(j), acc, b, key_pow, full_off);
+        }
         __syncthreads();  // next buffer complete; everyone is done with the current one
         cur ^= 1;
     }
@@ -560,7 +611,8 @@ __global__ __launch_bounds__(1024) void sampled_chunked_kernel(const SampledArgs
         b[f] = a.off[j];
         key_pow[f] = 1;
         if (EP == (int)Epilogue::Keys) {
-            const uint32_t t = j % a.g;
+            uint32_t t = j % a.g;
+            if (RT == 4 && a.g >= 4) t |= 3;  // the transposed fold multiplies by the power of the quad's last function
             for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow[f] *= kKeyMultiplier;
         }
     }

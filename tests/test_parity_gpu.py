@@ -195,6 +195,35 @@ def test_dense_n128_shapes(lsh, N, k, w):
                          label=f"dense128-{N}x{k}", dense=True, signs=False))
 
 
+@pytest.mark.parametrize("N,n,k,m,seed", [(203, 128, 512, 32, 51),     # register lists, whole tiles + tail
+                                          (19, 128, 64, 32, 52),       # one small workgroup
+                                          (77, 960, 1024, 128, 53),    # streamed lists
+                                          (45, 16384, 640, 96, 54),    # coordinate-range chunks
+                                          (30, 4096, 192, 64, 55)])    # 8-vector tiles
+def test_fused_key_group_sizes(lsh, N, n, k, m, seed):
+    """Fused hashing + packing for every supported group size g = k / L (1 ... 64): the keys equal
+    the oracle's packing of the oracle's ids wherever no id of the key lies in the boundary band."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    data = torch.randn((N, n), generator=g, device="cuda") * 3.0
+    with lsh.LshParams(n, k, m, 4.0, seed) as p:
+        idx, coef, off = _tables(p)
+        ora = oracle.fastlsh(data.cpu().numpy(), idx, coef, off, p.w, nthreads=THREADS, want=("ids", "frac"))
+        near = (ora["frac"] < BAND) | (ora["frac"] > 1.0 - BAND)
+        for gs in (1, 2, 4, 8, 16, 32, 64):
+            if k % gs:
+                continue
+            L = k // gs
+            say(f"fused keys N={N} n={n} k={k} m={m} g={gs}")
+            fused = lsh.hash_fastlsh_keys(p, data, L)
+            torch.cuda.synchronize()
+            got = fused.cpu().numpy().view(np.uint64)
+            key_near = near.reshape(N, L, gs).any(axis=2)
+            bad = (got != oracle.pack_keys(ora["ids"], L)) & ~key_near
+            assert not bad.any(), f"g={gs}: {int(bad.sum())} keys differ outside the boundary band"
+            assert key_near.mean() < 0.05
+
+
 @pytest.mark.parametrize("k,L", [(64, 16), (64, 1), (512, 2), (1024, 2), (96, 8), (60, 60), (256, 32), (100, 5)])
 def test_pack_keys_group_sizes(lsh, k, L):
     """Key packing is exact integer work: bit-exact against the oracle for every group size
