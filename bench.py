@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix peak
 # fp32 vector peak with packed instructions: 256 CUs x 128 FMA lanes/clk x 2 flop x 2.4 GHz.
 # This library is compiled without packed fp32 operations; a plain 64-lane v_fma_f32 occupies a
 # SIMD for four cycles, i.e. 64 lanes/clk/CU, half of that peak.
@@ -33,11 +34,12 @@ VALU_FP32_UNPACKED_TFLOPS = 78.6
 # 1 KiB per count), taken on the kernels as they stand; the summary and its commands are in
 # profiles/sift_step_hbm_traffic.md.  Set an entry to None when its kernel changes.
 MEASURED_TRAFFIC_BYTES = {
-    "fastlsh": 250656 * 2048 + 2000000 * 1024,    # 0.513 GB read + 2.048 GB written
-    "pack_keys": 1000044 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
-    "e2lsh": 251088 * 2048 + 2019286 * 1024,      # 0.514 GB + 2.068 GB
+    "fastlsh": 250604 * 2048 + 2000000 * 1024,    # 0.513 GB read + 2.048 GB written
+    "pack_keys": 1000042 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
+    "e2lsh": 251131 * 2048 + 2135488 * 1024,      # 0.514 GB + 2.187 GB (bf16 x 3 kernel)
+    "e2lsh_fp32": 251082 * 2048 + 2017484 * 1024,  # 0.514 GB + 2.066 GB (fp32 MFMA kernel)
     "signs": 250574 * 2048 + 62500 * 1024,        # 0.513 GB + 0.064 GB
-    "fastlsh_shared_sample": 250422 * 2048 + 2000000 * 1024,  # 0.513 GB + 2.048 GB
+    "fastlsh_shared_sample": 250411 * 2048 + 2000000 * 1024,  # 0.513 GB + 2.048 GB
 }
 
 
@@ -152,9 +154,17 @@ def main():
         "pack_keys": hbm("pack_keys", N * (4 * k + 8 * L)),
         "signs": hbm("signs", N * (4 * n + 8 * ((k + 63) // 64))),
     }
+    # The dense product runs as six bf16 MFMA products of exact three-way splits (fp32 accuracy):
+    # 12 n k bf16 flop per vector against the bf16 matrix peak; the same launch moves 4n + 4k
+    # bytes per vector, which bounds it just as tightly (0.32 ms either way on this shape).
     tf = 2.0 * N * n * k / (ms["e2lsh"] * 1e-3) / 1e12
-    rooflines["e2lsh"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                          "frac": tf / MFMA_FP32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES["e2lsh"]}
+    gbs = N * (4 * n + 4 * k) / (ms["e2lsh"] * 1e-3) / 1e9
+    rooflines["e2lsh"] = {"bound": "mfma", "achieved": 6.0 * tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": 6.0 * tf / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES["e2lsh"],
+                          "arithmetic": "bf16 x 3 splits, 6 MFMA products, fp32 accumulation",
+                          "fp32_equivalent_tflops": tf,
+                          "fp32_equivalent_frac_of_fp32_mfma_peak": tf / MFMA_FP32_PEAK_TFLOPS,
+                          "hbm_gbs": gbs, "hbm_frac": gbs / HBM_PEAK_GBS}
     # the sampled kernels' arithmetic against the plain fp32 vector ceiling, for context
     for s in ("fastlsh", "signs"):
         alu = 2.0 * N * k * m / (ms[s] * 1e-3) / 1e12
@@ -181,6 +191,22 @@ def main():
                      "mfma_tflops": 2.0 * N * k * m / (ms_shared * 1e-3) / 1e12,
                      "hashes_per_s": N * k / (ms_shared * 1e-3)}
 
+    # and the dense product on the fp32 matrix cores (the library's other dense arithmetic)
+    p_dense.set_dense_arithmetic(lsh.DENSE_FP32)
+    for _ in range(args.warmup):
+        lsh.hash_e2lsh(p_dense, data, out=ids_d)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        lsh.hash_e2lsh(p_dense, data, out=ids_d)
+    e1.record()
+    torch.cuda.synchronize()
+    p_dense.set_dense_arithmetic(lsh.DENSE_AUTO)
+    ms_fp32 = e0.elapsed_time(e1) / args.steps
+    tf32 = 2.0 * N * n * k / (ms_fp32 * 1e-3) / 1e12
+    e2lsh_fp32 = {"ms": ms_fp32, "bound": "mfma", "achieved": tf32, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                  "frac": tf32 / MFMA_FP32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES["e2lsh_fp32"]}
+
     hashes_per_step = 3.0 * N * k
     out = {
         "metric": "hashes/sec (N*k per sec), FastLSH vs E2LSH, 1 GPU",
@@ -197,7 +223,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "sift-shaped: N=1000000 n=128 k=512 m=32 w=16 L=32, 100-cluster mixture in [0,255]",
                    "step": "fastlsh ids + key packing + dense e2lsh ids (m=n) + sign hashes",
-                   "hashes_per_step": hashes_per_step},
+                   "hashes_per_step": hashes_per_step,
+                   "dense_arithmetic": "bf16 x 3 exact splits on the bf16 matrix cores, fp32 accumulation"},
         "vectors_per_s": N * args.steps / elapsed,
         "kernel_ms": ms,
         "fastlsh_hashes_per_s": N * k / (ms["fastlsh"] * 1e-3),
@@ -207,6 +234,7 @@ def main():
         "roofline": rooflines[dominant],
         "rooflines": rooflines,
         "fastlsh_shared_sample_per_table": shared_sample,
+        "e2lsh_fp32_mfma": e2lsh_fp32,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, data, p_fast, p_dense)

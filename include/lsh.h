@@ -154,6 +154,21 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
                    int32_t *d_out_buckets, void *stream);
 
 /*
+ * Arithmetic of the dense contraction (lsh_hash_e2lsh, lsh_project_e2lsh) of this object.
+ * LSH_DENSE_AUTO (the default): for n == 128 and k a multiple of 32 every fp32 operand is
+ * split exactly into three bf16 terms and the product is formed from the six bf16 MFMA
+ * products of weight >= 2^-16, accumulated in fp32; what is left out is below 2^-23 of each
+ * term |a_i v_i|, one fp32 rounding, and the projections stay within the same
+ * 1e-5 * sum_i |a_i v_i| of the exact value as the fp32 path.  (Operands whose bf16 rounding
+ * overflows, |x| > 3.39e38, give NaN there.)  Other shapes use fp32 MFMA.
+ * LSH_DENSE_FP32: fp32 MFMA for every shape.
+ * Errors: INVALID_ARG (null, unknown mode).
+ */
+#define LSH_DENSE_AUTO 0
+#define LSH_DENSE_FP32 1
+int lsh_params_set_dense_arithmetic(lsh_params_t *params, int mode);
+
+/*
  * Sign hashes for angular similarity (Sec. 5: FastLSH on normalised data; the sign form
  * of the sampled projection): bit j = [a~_j^T S_j(v) >= 0]; function j is bit j % 64
  * (bit 0 least significant) of d_out_words[v * ceil(k/64) + j / 64]; unused high bits of

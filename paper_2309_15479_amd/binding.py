@@ -16,11 +16,14 @@ _lib = None
 LSH_OK = 0
 SAMPLE_WITHOUT_REPLACEMENT = 0
 SAMPLE_WITH_REPLACEMENT = 1
+DENSE_AUTO = 0
+DENSE_FP32 = 1
 
 EXPORTS = [
     "lsh_params_create", "lsh_params_create_ex", "lsh_params_create_shared", "lsh_params_destroy",
     "lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape",
     "lsh_params_get_tables", "lsh_params_get_mips_coeffs", "lsh_params_get_schedule",
+    "lsh_params_set_dense_arithmetic",
     "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
@@ -62,6 +65,7 @@ def load_library():
     lib.lsh_params_create_ex.argtypes = [u32, u32, u32, f32, u64, u32, ctypes.POINTER(p)]
     lib.lsh_params_create_shared.argtypes = [u32, u32, u32, f32, u64, u32, u32, ctypes.POINTER(p)]
     lib.lsh_params_get_tables.argtypes = [p, p]
+    lib.lsh_params_set_dense_arithmetic.argtypes = [p, i]
     lib.lsh_params_destroy.argtypes = [p]
     lib.lsh_params_destroy.restype = None
     for name in ("lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets",
@@ -162,6 +166,10 @@ class LshParams:
         out = np.empty(self.k, np.float32)
         _check(load_library().lsh_params_get_offsets(self.handle, out.ctypes.data), "get_offsets")
         return out
+
+    def set_dense_arithmetic(self, mode):
+        """DENSE_AUTO: bf16 x 3 matrix-core product where the shape allows; DENSE_FP32: fp32 MFMA."""
+        _check(load_library().lsh_params_set_dense_arithmetic(self.handle, int(mode)), "set_dense_arithmetic")
 
     def mips_coeffs(self):
         """a0 [k] of the maximum-inner-product transform (objects with shared_tables > 0)."""

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblsh.so")
-SOURCES = ["api.hip", "sampled_kernel.hip", "shared_kernel.hip", "dense_kernel.hip", "pack_kernel.hip", "index.hip", "params_host.cpp", "schedule.cpp", "collision_law.cpp"]
+SOURCES = ["api.hip", "sampled_kernel.hip", "shared_kernel.hip", "dense_kernel.hip", "dense_split_kernel.hip", "pack_kernel.hip", "index.hip", "params_host.cpp", "schedule.cpp", "collision_law.cpp"]
 
 
 def build_library(verbose=False):

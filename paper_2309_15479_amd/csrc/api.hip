@@ -414,6 +414,8 @@ int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32
     if (rc != LSH_OK) return rc;
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+        return launch_dense_split(p, false, d_data, N, d_out, stream);
     return launch_dense(p, false, d_data, N, d_out, stream);
 }
 
@@ -422,7 +424,15 @@ int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, fl
     if (rc != LSH_OK) return rc;
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+        return launch_dense_split(p, true, d_data, N, d_out, stream);
     return launch_dense(p, true, d_data, N, d_out, stream);
+}
+
+int lsh_params_set_dense_arithmetic(lsh_params_t *p, int mode) {
+    if (!p || (mode != LSH_DENSE_AUTO && mode != LSH_DENSE_FP32)) return LSH_ERR_INVALID_ARG;
+    p->dense_arithmetic = mode;
+    return LSH_OK;
 }
 
 int lsh_pack_keys(const lsh_params_t *p, const int32_t *d_ids, uint64_t N, uint32_t L, uint64_t *d_keys,

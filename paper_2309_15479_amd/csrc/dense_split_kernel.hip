@@ -1,0 +1,311 @@
+// Dense E2LSH (Sec. 2.2, Eq. 1) for n = 128 on the bf16 matrix cores, with fp32 accuracy.
+//
+// The fp32 MFMA of this part runs at a sixteenth of the bf16 rate, so the product is computed
+// from three-way bf16 splits instead: an fp32 value x is EXACTLY x1 + x2 + x3 with
+// x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2) under round-to-nearest (each step
+// leaves at most the bits below the previous term's last place: 8 + 8 + 8 significant bits),
+// and a . v = sum over splits of a_p v_q.  The six products with p + q <= 4 are formed (exact in
+// the fp32 accumulator's inputs: an 8 x 8 bit product); the three left out are below
+// 2^-23 |a v| together, the size of one fp32 rounding.  Six bf16 MFMAs do the work of one fp32
+// product at 16 / 6 of its speed.
+//
+//   V [N][128] row-major (vectors), A [kpad][128] row-major (row j = a_j, fp32).
+//
+// Workgroup = 512 threads (8 waves), persistent, one per CU.  A wave owns 32 functions and keeps
+// their coefficients, already split, in 96 registers for the whole launch (the row operand of
+// v_mfma_f32_32x32x16_bf16: lane l holds row l % 32, contraction indices 16 s + 8 (l / 32) ...
+// + 7 of step s).  A workgroup therefore covers 256 functions; a tile is 64 vectors, split on
+// the way into LDS (three planes of bf16, rows padded to 272 bytes so that the 16-byte operand
+// reads of 16 consecutive rows cover all banks once) and shared by the 8 waves.  The column
+// operand uses the same contraction indices per lane, so any lane layout of them that is the
+// same for both operands gives the same sums.  As in the fp32 kernels a lane ends up with runs
+// of four consecutive functions of one vector (accumulator register i = function
+// 8 (i / 4) + 4 (l / 32) + i % 4, vector l % 32) and the results leave as 16-byte stores.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <type_traits>
+
+#include "lsh_internal.h"
+
+namespace lsh {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int SN = 128;            // contraction length
+constexpr int KSTEPS = SN / 16;    // MFMA steps
+constexpr int TV = 64;             // vectors per tile (two column blocks of 32)
+constexpr int ROWB = SN * 2 + 16;  // bytes per vector and plane in LDS
+constexpr int PLANE = TV * ROWB;
+constexpr int BUF = 3 * PLANE;     // one tile: 52224 bytes
+constexpr int kThreadsS = 512;
+constexpr int kFuncsPerWave = 32, kFuncsPerBlock = 8 * kFuncsPerWave;
+constexpr int kQuads = TV * (SN / 4) / kThreadsS;  // 16-byte pieces of a tile per thread: 4
+
+struct SplitArgs {
+    const float *data;  // [N][128]
+    const float *a;     // [>= k rows][128]
+    const float *off;   // [>= k]
+    uint64_t N;
+    uint32_t k;         // multiple of 32
+    float w, inv_w;
+    void *out;          // [N][k]
+};
+
+__device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &x3) {
+    x1 = (__bf16)x;
+    const float r1 = x - (float)x1;
+    x2 = (__bf16)r1;
+    x3 = (__bf16)(r1 - (float)x2);
+}
+
+template <bool PROJ, bool POW2>
+__global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitArgs a) {
+    using Vec4 = typename std::conditional<PROJ, float4, int4>::type;
+    extern __shared__ __align__(16) char lds_s[];  // 2 x [3 planes][64 vectors][272 bytes]
+
+    const uint32_t slices = (a.k + kFuncsPerBlock - 1) / kFuncsPerBlock;
+    const uint64_t ntiles = (a.N + TV - 1) / TV;
+    // workgroups i, i + 8, ... share an XCD (and its L2): the slices of one row tile run there
+    // side by side
+    const uint32_t slot = blockIdx.x / 8, slots = gridDim.x / 8;
+    const uint32_t slice = slot % slices;
+    const uint64_t stream = (uint64_t)(slot / slices) * 8 + blockIdx.x % 8, streams = (uint64_t)(slots / slices) * 8;
+    if (slot / slices >= slots / slices) return;
+
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lr = lane & 31, lh = lane >> 5;
+    const uint32_t wf = slice * kFuncsPerBlock + wave * kFuncsPerWave;  // first function of the wave
+    const bool active = wf < a.k;                                     // whole wave
+
+    // coefficients of the wave's 32 functions, split, resident: c[s][p]
+    bf16x8 c[KSTEPS][3];
+    float bs[16];
+    if (active) {
+        const float *row = a.a + (size_t)(wf + lr) * SN + 8 * lh;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const float4 u0 = *reinterpret_cast<const float4 *>(row + 16 * s);
+            const float4 u1 = *reinterpret_cast<const float4 *>(row + 16 * s + 4);
+            const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                __bf16 x1, x2, x3;
+                split3(u[e], x1, x2, x3);
+                c[s][0][e] = x1;
+                c[s][1][e] = x2;
+                c[s][2][e] = x3;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
+            bs[i] = PROJ ? 0.f : POW2 ? b * a.inv_w : b;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c[s][p][e] = (__bf16)0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) bs[i] = 0.f;
+    }
+
+    // loader: thread t takes the 16-byte pieces t, t + 512, ... of the tile (32 pieces per vector);
+    // rows beyond the last vector read the last vector (computed, never stored), so a fetch is in
+    // bounds for any tile number
+    const uint32_t ld_vec = threadIdx.x >> 5, ld_piece = threadIdx.x & 31;
+    float4 raw[kQuads];
+    auto fetch = [&](uint64_t tile) {
+#pragma unroll
+        for (int q = 0; q < kQuads; ++q) {
+            uint64_t vec = tile * TV + ld_vec + 16 * q;
+            vec = vec < a.N ? vec : a.N - 1;
+            raw[q] = *reinterpret_cast<const float4 *>(a.data + vec * SN + ld_piece * 4);
+        }
+    };
+    auto stash_quad = [&](char *buf, int q) {
+        {
+            const float u[4] = {raw[q].x, raw[q].y, raw[q].z, raw[q].w};
+            bf16x4 h[3];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                __bf16 x1, x2, x3;
+                split3(u[e], x1, x2, x3);
+                h[0][e] = x1;
+                h[1][e] = x2;
+                h[2][e] = x3;
+            }
+            char *dst = buf + (ld_vec + 16 * q) * ROWB + ld_piece * 8;
+#pragma unroll
+            for (int p = 0; p < 3; ++p) *reinterpret_cast<bf16x4 *>(dst + p * PLANE) = h[p];
+        }
+    };
+    auto stash = [&](char *buf) {
+#pragma unroll
+        for (int q = 0; q < kQuads; ++q) stash_quad(buf, q);
+    };
+
+    uint64_t t = stream;
+    fetch(t);
+    stash(lds_s);
+    __syncthreads();
+    fetch(t + streams);
+    uint32_t cur = 0;
+
+    if (!active) {
+        // waves beyond the last function only help to load: same barriers as the others
+        for (; t < ntiles; t += streams) {
+            stash(lds_s + (cur ^ 1) * BUF);
+            fetch(t + 2 * streams);
+            __syncthreads();
+            cur ^= 1;
+        }
+        return;
+    }
+
+    const uint32_t rd_off = lr * ROWB + lh * 16;  // + column block * 32 rows + plane + 32 bytes per step
+    // one contraction step (16 indices) for both column blocks of 32 vectors: 12 MFMAs
+    auto step = [&](const char *base, int s, floatx16 (&acc)[2]) {
+        bf16x8 d[2][3];
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                d[vb][p] = *reinterpret_cast<const bf16x8 *>(base + vb * 32 * ROWB + s * 32 + p * PLANE);
+        // smallest terms first; the two column blocks alternate, so that an MFMA never waits for
+        // the one just issued
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][2], d[vb][0], acc[vb], 0, 0, 0);
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][1], acc[vb], 0, 0, 0);
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][2], acc[vb], 0, 0, 0);
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][0], acc[vb], 0, 0, 0);
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][1], acc[vb], 0, 0, 0);
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][0], acc[vb], 0, 0, 0);
+    };
+    // Epilogue in two parts.  `settle` turns the accumulators of a tile into the 2 x 16 results
+    // a lane keeps (bucket ids or raw projections); `store_piece` writes one 16-byte piece of
+    // them.  The 8 pieces of a tile leave one per contraction step of the NEXT tile: a burst of
+    // 64 store instructions per workgroup at the end of a tile holds the waves (and with them the
+    // matrix pipe) until the memory pipeline has taken them.
+    const uint32_t st_off = (lr * a.k + wf + 4 * lh) * 4;  // in a block of 32 x k outputs; below 2^32 (host)
+    Vec4 res[2][4];
+    auto settle = [&](const floatx16 (&acc)[2]) {
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if constexpr (PROJ) {
+                    res[vb][q] = make_float4(acc[vb][4 * q], acc[vb][4 * q + 1], acc[vb][4 * q + 2], acc[vb][4 * q + 3]);
+                } else {
+                    int r[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p = acc[vb][4 * q + e];
+                        const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
+                        r[e] = (int)floorf(h);
+                    }
+                    res[vb][q] = make_int4(r[0], r[1], r[2], r[3]);
+                }
+            }
+    };
+    auto store_piece = [&](auto full_tag, uint64_t tile, int piece) {
+        const int vb = piece / 4, q = piece % 4;
+        const uint64_t vec0 = tile * TV + vb * 32;
+        if constexpr (!decltype(full_tag)::value) {
+            if (vec0 + lr >= a.N) return;
+        }
+        char *dst = reinterpret_cast<char *>(a.out) + vec0 * a.k * 4 + st_off;
+        *reinterpret_cast<Vec4 *>(dst + q * 32) = res[vb][q];
+    };
+    // One tile.  The vector-ALU and memory work shares the scheduling regions of the contraction
+    // steps, so that the matrix pipe runs in its background (and in that of the other wave of the
+    // SIMD): step s stores piece s of the previous tile, and the last four steps each split one
+    // 16-byte piece of the next tile on its way to LDS.  The loads these consume were issued a
+    // tile earlier and have the first steps to arrive; the loads of the tile after the next are
+    // issued last.
+    uint64_t t_prev = 0;
+    auto run_tile = [&](auto have_prev) {
+        const char *base = lds_s + cur * BUF + rd_off;
+        char *next = lds_s + (cur ^ 1) * BUF;
+        floatx16 acc[2];
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[vb][i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            step(base, s, acc);
+            if constexpr (decltype(have_prev)::value) store_piece(std::true_type{}, t_prev, s);  // a tile with a successor is whole
+            if (s >= KSTEPS - kQuads) stash_quad(next, s - (KSTEPS - kQuads));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        settle(acc);
+        t_prev = t;
+        fetch(t + 2 * streams);
+        __syncthreads();  // next buffer complete; everyone is done with the current one
+        cur ^= 1;
+    };
+    static_assert(KSTEPS == 8, "one stored piece per contraction step");
+    if (t >= ntiles) return;
+    run_tile(std::false_type{});
+    for (t += streams; t < ntiles; t += streams) run_tile(std::true_type{});
+#pragma unroll
+    for (int piece = 0; piece < 8; ++piece) store_piece(std::false_type{}, t_prev, piece);
+}
+
+}  // namespace
+
+bool dense_split_supported(const lsh_params *p) {
+    return p->m == p->n && p->n == (uint32_t)SN && p->k % kFuncsPerWave == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
+}
+
+int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
+                       void *stream) {
+    SplitArgs a;
+    a.data = d_data;
+    a.a = p->d_dense;
+    a.off = p->d_off;
+    a.N = N;
+    a.k = p->k;
+    a.w = p->w;
+    a.inv_w = 1.0f / p->w;
+    a.out = d_out;
+    int exp2 = 0;
+    const bool pw = std::frexp(p->w, &exp2) == 0.5f;
+    const uint32_t slices = (p->k + kFuncsPerBlock - 1) / kFuncsPerBlock;
+    // one workgroup per CU (102 KB of LDS); every XCD needs a workgroup per slice of functions
+    uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
+    if (wgs < 8) wgs = 8;
+    while (wgs / 8 < slices) wgs += 8;
+    const uint32_t lds_bytes = 2 * BUF;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+#define LSH_SPLIT_CASE(P_, W_) \
+    if (proj == P_ && pw == W_) { \
+        auto fn = &dense_split_kernel<P_, W_>; \
+        static std::atomic<bool> granted{false};  /* the attribute call costs ~1 ms: once per kernel */ \
+        if (!granted.load(std::memory_order_acquire)) { \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
+                return LSH_ERR_HIP; \
+            granted.store(true, std::memory_order_release); \
+        } \
+        hipLaunchKernelGGL(fn, dim3(wgs), dim3(kThreadsS), lds_bytes, s, a); \
+    }
+    LSH_SPLIT_CASE(false, true) LSH_SPLIT_CASE(false, false) LSH_SPLIT_CASE(true, true) LSH_SPLIT_CASE(true, false)
+#undef LSH_SPLIT_CASE
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+}  // namespace lsh

@@ -89,6 +89,7 @@ struct lsh_params {
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n] when m == n (row j = a_j), else null
     uint32_t kpad_dense = 0;
+    int dense_arithmetic = LSH_DENSE_AUTO;  // see lsh_params_set_dense_arithmetic
     // one sample per table: operand tables of the shared-sample kernel (null when unsupported)
     lsh::SharedPlan shared_plan;
     float *d_shared_coef = nullptr;
@@ -139,6 +140,10 @@ bool shared_keys_ok(const lsh_params *p, uint32_t L);
 int ensure_lds_limit(const void *fn, uint32_t lds_bytes);
 int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
                  void *stream);
+// bf16 x 3 matrix-core version of the dense product (n = 128, k a multiple of 32)
+bool dense_split_supported(const lsh_params *p);
+int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
+                       void *stream);
 int launch_pack(const lsh_params *p, const int32_t *d_ids, uint64_t N, uint32_t L,
                 uint64_t *d_keys, void *stream);
 

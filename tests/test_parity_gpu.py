@@ -181,18 +181,44 @@ def test_dense_shapes(lsh, N, n, k):
         say(_compare_all(lsh, p, data, np.arange(N), label=f"dense{N}x{n}x{k}", dense=True, signs=False))
 
 
+@pytest.mark.parametrize("fp32_only", [False, True])
 @pytest.mark.parametrize("N,k,w", [(1, 128, 2.0), (128, 128, 4.0), (127, 256, 1.5), (3000, 384, 2.0), (40000, 512, 0.5),
-                                   (2049, 1152, 3.0)])
-def test_dense_n128_shapes(lsh, N, k, w):
-    """n = 128 with k a multiple of 128 has a kernel of its own: single partial tile, exactly one
-    full tile, several column tiles, more row tiles than workgroups, w a power of two or not."""
-    say(f"dense n=128 case N={N} k={k} w={w}")
+                                   (2049, 1152, 3.0), (65, 32, 1.0), (64, 96, 2.5), (1000, 288, 8.0), (333, 544, 1.0)])
+def test_dense_n128_shapes(lsh, N, k, w, fp32_only):
+    """n = 128 has kernels of its own, in both arithmetics (bf16 x 3 for k a multiple of 32, fp32
+    MFMA with a lean variant for k a multiple of 128): single partial tile, exactly one full tile,
+    several slices of functions, idle waves, more row tiles than workgroups, w a power of two or
+    not.  The tolerances are the same for both."""
+    say(f"dense n=128 case N={N} k={k} w={w} fp32_only={fp32_only}")
     g = torch.Generator(device="cuda")
     g.manual_seed(N * 3 + k)
     data = torch.randn((N, 128), generator=g, device="cuda") * 2.0
     with lsh.LshParams(128, k, 128, w, N + k) as p:
+        if fp32_only:
+            p.set_dense_arithmetic(lsh.DENSE_FP32)
         say(_compare_all(lsh, p, data, np.arange(N) if N <= 4096 else workloads.sample_rows(N, 2048).numpy(),
                          label=f"dense128-{N}x{k}", dense=True, signs=False))
+
+
+def test_dense_split_products_error(lsh):
+    """The bf16 x 3 product against the fp64 oracle on data with a wide range of magnitudes in
+    one vector: the error stays at the level of fp32 rounding (a few 2^-24 of sum |a_i v_i|),
+    far inside the 1e-5 bound, and no worse than twice the fp32 MFMA path's."""
+    N, k = 512, 256
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    data = torch.randn((N, 128), generator=g, device="cuda") * torch.exp(
+        6.0 * torch.randn((N, 128), generator=g, device="cuda"))
+    with lsh.LshParams(128, k, 128, 4.0, 99) as p:
+        _, coef, off = _tables(p)
+        ora = oracle.e2lsh(data.cpu().numpy(), coef, off, p.w, nthreads=THREADS, want=("proj", "abs_sum"))
+        split = lsh.project_e2lsh(p, data).cpu().numpy()
+        p.set_dense_arithmetic(lsh.DENSE_FP32)
+        plain = lsh.project_e2lsh(p, data).cpu().numpy()
+    err_split = float((np.abs(split - ora["proj"]) / ora["abs_sum"]).max())
+    err_plain = float((np.abs(plain - ora["proj"]) / ora["abs_sum"]).max())
+    say(f"worst |error| / sum|a v|: bf16 x 3 {err_split:.3e}, fp32 MFMA {err_plain:.3e}")
+    assert err_split < 2e-6 and err_split < 2.0 * err_plain + 2.0 ** -22
 
 
 @pytest.mark.parametrize("N,n,k,m,seed", [(203, 128, 512, 32, 51),     # register lists, whole tiles + tail
