@@ -145,8 +145,8 @@ int lsh_hash_fastlsh(const lsh_params_t *params, const float *d_data, uint64_t N
                      int32_t *d_out_buckets, void *stream);
 
 /*
- * E2LSH bucket ids (Eq. 1) by a dense [N x n] . [n x k] fp32 MFMA contraction with the
- * floor((. + b) / w) epilogue fused.  Requires params created with m == n
+ * E2LSH bucket ids (Eq. 1) by a dense [N x n] . [n x k] matrix-core contraction (arithmetic:
+ * see lsh_params_set_dense_arithmetic) with the floor((. + b) / w) epilogue fused.  Requires params created with m == n
  * (INVALID_ARG otherwise).  Same output layout as lsh_hash_fastlsh, and the two agree
  * on such params up to fp32 summation order.
  */
@@ -154,14 +154,20 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
                    int32_t *d_out_buckets, void *stream);
 
 /*
- * Arithmetic of the dense contraction (lsh_hash_e2lsh, lsh_project_e2lsh) of this object.
+ * Arithmetic of the matrix-core kernels (lsh_hash_e2lsh, lsh_project_e2lsh, and lsh_hash_signs
+ * at n == 128) of this object.
  * LSH_DENSE_AUTO (the default): for n == 128 and k a multiple of 32 every fp32 operand is
  * split exactly into three bf16 terms and the product is formed from the six bf16 MFMA
  * products of weight >= 2^-16, accumulated in fp32; what is left out is below 2^-23 of each
  * term |a_i v_i|, one fp32 rounding, and the projections stay within the same
  * 1e-5 * sum_i |a_i v_i| of the exact value as the fp32 path.  (Operands whose bf16 rounding
- * overflows, |x| > 3.39e38, give NaN there.)  Other shapes use fp32 MFMA.
- * LSH_DENSE_FP32: fp32 MFMA for every shape.
+ * overflows, |x| > 3.39e38, give NaN there.)  Other shapes use fp32 MFMA.  With n == 128 and k
+ * a multiple of 64, lsh_hash_signs of ANY object (m <= n) runs on the matrix cores too, on the
+ * coefficients written out over all n coordinates (zeros where a function does not sample, sums
+ * where it samples a coordinate more than once), with two-way splits and three products: what
+ * they leave out is below 3 * 2^-16 * sum_i |a_i v_i|, under half of the 1e-4 * |a| * |S(v)| around
+ * zero inside which a sign bit is unspecified.
+ * LSH_DENSE_FP32: fp32 MFMA for every shape, and the gathered fp32 kernel for the signs.
  * Errors: INVALID_ARG (null, unknown mode).
  */
 #define LSH_DENSE_AUTO 0
@@ -172,7 +178,8 @@ int lsh_params_set_dense_arithmetic(lsh_params_t *params, int mode);
  * Sign hashes for angular similarity (Sec. 5: FastLSH on normalised data; the sign form
  * of the sampled projection): bit j = [a~_j^T S_j(v) >= 0]; function j is bit j % 64
  * (bit 0 least significant) of d_out_words[v * ceil(k/64) + j / 64]; unused high bits of
- * the last word are 0.  b~ and w are not used.
+ * the last word are 0.  b~ and w are not used.  A bit whose projection lies within
+ * 1e-4 * |a~_j| * |S_j(v)| of zero is unspecified (see lsh_params_set_dense_arithmetic).
  */
 int lsh_hash_signs(const lsh_params_t *params, const float *d_data, uint64_t N,
                    uint64_t *d_out_words, void *stream);

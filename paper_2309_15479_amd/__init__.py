@@ -1,5 +1,5 @@
 """MI355X (gfx950) batched l2 LSH hash evaluation: FastLSH (sampled projection), dense
-E2LSH on the fp32 matrix cores, sign hashes and compound-key packing, behind the C ABI of
+E2LSH on the matrix cores, sign hashes and compound-key packing, behind the C ABI of
 ``include/lsh.h``.  This package is only the Python binding (argument marshalling); all
 hash arithmetic runs in the HIP kernels of ``liblsh.so`` (the collision-probability helpers
 are host functions of the same library)."""

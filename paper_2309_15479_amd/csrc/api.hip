@@ -52,7 +52,8 @@ int upload_tables(lsh_params *p) {
     const uint32_t m_pad = p->plan.m_pad;
     const uint32_t kpad = p->plan.supported ? p->plan.kpad : (p->k + 63) / 64 * 64;
     p->kpad_dense = 0;
-    if (p->m == p->n) p->kpad_dense = (p->k + dense_col_tile() - 1) / dense_col_tile() * dense_col_tile();
+    // n == 128: the matrix-core sign kernel takes any object's coefficients written out densely
+    if (p->m == p->n || p->n == 128) p->kpad_dense = (p->k + dense_col_tile() - 1) / dense_col_tile() * dense_col_tile();
     const uint32_t off_len = kpad > p->kpad_dense ? kpad : p->kpad_dense;
 
     int rc = LSH_OK;
@@ -153,9 +154,16 @@ int upload_tables(lsh_params *p) {
         }
         if (rc == LSH_OK && p->kpad_dense) {
             // m == n: S_j is the identity, so the canonical coefficient table IS the dense
-            // matrix A [k][n]; rows up to the tile grid are zero
+            // matrix A [k][n]; rows up to the tile grid are zero.  m < n: zeros at the coordinates
+            // a function does not sample; a coordinate drawn more than once gets the sum
             std::vector<float> dense((size_t)p->kpad_dense * p->n, 0.f);
-            std::copy(p->coef.begin(), p->coef.end(), dense.begin());
+            if (p->m == p->n) {
+                std::copy(p->coef.begin(), p->coef.end(), dense.begin());
+            } else {
+                for (uint32_t j = 0; j < p->k; ++j)
+                    for (uint32_t i = 0; i < p->m; ++i)
+                        dense[(size_t)j * p->n + p->idx[(size_t)j * p->m + i]] += p->coef[(size_t)j * p->m + i];
+            }
             if (hipMalloc(&p->d_dense, dense.size() * sizeof(float)) != hipSuccess) rc = LSH_ERR_ALLOC;
             if (rc == LSH_OK && hipMemcpy(p->d_dense, dense.data(), dense.size() * sizeof(float),
                                           hipMemcpyHostToDevice) != hipSuccess)
@@ -346,6 +354,8 @@ int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, 
 int lsh_hash_signs(const lsh_params_t *p, const float *d_data, uint64_t N, uint64_t *d_out, void *stream) {
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_signs_supported(p))
+        return launch_dense_split(p, 2, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Signs, d_data, N, d_out, 0, stream);
 }
 
@@ -415,7 +425,7 @@ int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
     if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
-        return launch_dense_split(p, false, d_data, N, d_out, stream);
+        return launch_dense_split(p, 0, d_data, N, d_out, stream);
     return launch_dense(p, false, d_data, N, d_out, stream);
 }
 
@@ -425,7 +435,7 @@ int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, fl
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
     if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
-        return launch_dense_split(p, true, d_data, N, d_out, stream);
+        return launch_dense_split(p, 1, d_data, N, d_out, stream);
     return launch_dense(p, true, d_data, N, d_out, stream);
 }
 

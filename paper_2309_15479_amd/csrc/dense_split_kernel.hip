@@ -9,6 +9,14 @@
 // 2^-23 |a v| together, the size of one fp32 rounding.  Six bf16 MFMAs do the work of one fp32
 // product at 16 / 6 of its speed.
 //
+// Sign hashes (Sec. 5, angular similarity) need the sign of the projection only, and are
+// compared away from zero: with two-way splits and the three products a1 v1 + a1 v2 + a2 v1 the
+// terms left out are below 3 * 2^-16 |a v| per coordinate, under half of the 1e-4 |a| |S(v)|
+// inside which a sign may differ from the exact one.  For these the coefficient matrix may be a
+// FastLSH object's, written out densely (zeros at the coordinates a function does not sample):
+// at n = 128 three bf16 MFMA products over all coordinates cost less than the gathered fp32
+// multiply-adds of a quarter of them.
+//
 //   V [N][128] row-major (vectors), A [kpad][128] row-major (row j = a_j, fp32).
 //
 // Workgroup = 512 threads (8 waves), persistent, one per CU.  A wave owns 32 functions and keeps
@@ -49,9 +57,9 @@ constexpr int kQuads = TV * (SN / 4) / kThreadsS;  // 16-byte pieces of a tile p
 struct SplitArgs {
     const float *data;  // [N][128]
     const float *a;     // [>= k rows][128]
-    const float *off;   // [>= k]
+    const float *off;   // [>= k]; not read for signs
     uint64_t N;
-    uint32_t k;         // multiple of 32
+    uint32_t k;         // multiple of 32 (signs: of 64)
     float w, inv_w;
     void *out;          // [N][k]
 };
@@ -63,8 +71,13 @@ __device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &
     x3 = (__bf16)(r1 - (float)x2);
 }
 
-template <bool PROJ, bool POW2>
+enum : int { kIds = 0, kProj = 1, kSigns = 2 };
+
+// EP: bucket ids, raw projections (both [N][k], 4 bytes each), or sign words ([N][k / 64] of 64 bits)
+template <int EP, bool POW2>
 __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitArgs a) {
+    constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns;
+    constexpr int NSPLIT = SIGNS ? 2 : 3;
     using Vec4 = typename std::conditional<PROJ, float4, int4>::type;
     extern __shared__ __align__(16) char lds_s[];  // 2 x [3 planes][64 vectors][272 bytes]
 
@@ -83,7 +96,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const bool active = wf < a.k;                                     // whole wave
 
     // coefficients of the wave's 32 functions, split, resident: c[s][p]
-    bf16x8 c[KSTEPS][3];
+    bf16x8 c[KSTEPS][NSPLIT];
     float bs[16];
     if (active) {
         const float *row = a.a + (size_t)(wf + lr) * SN + 8 * lh;
@@ -98,19 +111,23 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                 split3(u[e], x1, x2, x3);
                 c[s][0][e] = x1;
                 c[s][1][e] = x2;
-                c[s][2][e] = x3;
+                if constexpr (NSPLIT == 3) c[s][2][e] = x3;
             }
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
-            bs[i] = PROJ ? 0.f : POW2 ? b * a.inv_w : b;
+            if constexpr (EP == kIds) {
+                const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
+                bs[i] = POW2 ? b * a.inv_w : b;
+            } else {
+                bs[i] = 0.f;
+            }
         }
     } else {
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
-            for (int p = 0; p < 3; ++p)
+            for (int p = 0; p < NSPLIT; ++p)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) c[s][p][e] = (__bf16)0.f;
 #pragma unroll
@@ -144,7 +161,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             }
             char *dst = buf + (ld_vec + 16 * q) * ROWB + ld_piece * 8;
 #pragma unroll
-            for (int p = 0; p < 3; ++p) *reinterpret_cast<bf16x4 *>(dst + p * PLANE) = h[p];
+            for (int p = 0; p < NSPLIT; ++p) *reinterpret_cast<bf16x4 *>(dst + p * PLANE) = h[p];
         }
     };
     auto stash = [&](char *buf) {
@@ -173,20 +190,22 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t rd_off = lr * ROWB + lh * 16;  // + column block * 32 rows + plane + 32 bytes per step
     // one contraction step (16 indices) for both column blocks of 32 vectors: 12 MFMAs
     auto step = [&](const char *base, int s, floatx16 (&acc)[2]) {
-        bf16x8 d[2][3];
+        bf16x8 d[2][NSPLIT];
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
-            for (int p = 0; p < 3; ++p)
+            for (int p = 0; p < NSPLIT; ++p)
                 d[vb][p] = *reinterpret_cast<const bf16x8 *>(base + vb * 32 * ROWB + s * 32 + p * PLANE);
         // smallest terms first; the two column blocks alternate, so that an MFMA never waits for
         // the one just issued
+        if constexpr (NSPLIT == 3) {
 #pragma unroll
-        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][2], d[vb][0], acc[vb], 0, 0, 0);
+            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][2], d[vb][0], acc[vb], 0, 0, 0);
 #pragma unroll
-        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][1], acc[vb], 0, 0, 0);
+            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][1], acc[vb], 0, 0, 0);
 #pragma unroll
-        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][2], acc[vb], 0, 0, 0);
+            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][2], acc[vb], 0, 0, 0);
+        }
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][0], acc[vb], 0, 0, 0);
 #pragma unroll
@@ -200,34 +219,56 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     // 64 store instructions per workgroup at the end of a tile holds the waves (and with them the
     // matrix pipe) until the memory pipeline has taken them.
     const uint32_t st_off = (lr * a.k + wf + 4 * lh) * 4;  // in a block of 32 x k outputs; below 2^32 (host)
-    Vec4 res[2][4];
+    Vec4 res[2][SIGNS ? 1 : 4];
+    uint32_t sign_word[2] = {0, 0};
     auto settle = [&](const floatx16 (&acc)[2]) {
 #pragma unroll
-        for (int vb = 0; vb < 2; ++vb)
+        for (int vb = 0; vb < 2; ++vb) {
+            if constexpr (SIGNS) {
+                // bit 8q + 4 (l / 32) + e of the wave's 32 functions from accumulator 4q + e; the
+                // two lanes that share a vector then join their halves
+                uint32_t bits = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if constexpr (PROJ) {
-                    res[vb][q] = make_float4(acc[vb][4 * q], acc[vb][4 * q + 1], acc[vb][4 * q + 2], acc[vb][4 * q + 3]);
-                } else {
-                    int r[4];
+                for (int i = 0; i < 16; ++i) bits |= (acc[vb][i] >= 0.f ? 1u : 0u) << (8 * (i / 4) + (i % 4));
+                bits <<= 4 * lh;
+                sign_word[vb] = bits | (uint32_t)__shfl_xor((int)bits, 32);
+            } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float p = acc[vb][4 * q + e];
-                        const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
-                        r[e] = (int)floorf(h);
+                for (int q = 0; q < 4; ++q) {
+                    if constexpr (PROJ) {
+                        res[vb][q] = make_float4(acc[vb][4 * q], acc[vb][4 * q + 1], acc[vb][4 * q + 2], acc[vb][4 * q + 3]);
+                    } else {
+                        int r[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float p = acc[vb][4 * q + e];
+                            const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
+                            r[e] = (int)floorf(h);
+                        }
+                        res[vb][q] = make_int4(r[0], r[1], r[2], r[3]);
                     }
-                    res[vb][q] = make_int4(r[0], r[1], r[2], r[3]);
                 }
             }
+        }
     };
+    // signs: the wave's 32 functions are one half of the 64-bit word wf / 64 of each vector
+    const uint32_t sign_off = (lr * (a.k / 64) + wf / 64) * 8 + ((wf / 32) & 1) * 4;  // in a block of 32 vectors
     auto store_piece = [&](auto full_tag, uint64_t tile, int piece) {
         const int vb = piece / 4, q = piece % 4;
         const uint64_t vec0 = tile * TV + vb * 32;
+        if constexpr (SIGNS) {
+            if (q != 0 || lh != 0) return;
+        }
         if constexpr (!decltype(full_tag)::value) {
             if (vec0 + lr >= a.N) return;
         }
-        char *dst = reinterpret_cast<char *>(a.out) + vec0 * a.k * 4 + st_off;
-        *reinterpret_cast<Vec4 *>(dst + q * 32) = res[vb][q];
+        if constexpr (SIGNS) {
+            char *dst = reinterpret_cast<char *>(a.out) + vec0 * (a.k / 64) * 8 + sign_off;
+            *reinterpret_cast<uint32_t *>(dst) = sign_word[vb];
+        } else {
+            char *dst = reinterpret_cast<char *>(a.out) + vec0 * a.k * 4 + st_off;
+            *reinterpret_cast<Vec4 *>(dst + q * 32) = res[vb][q];
+        }
     };
     // One tile.  The vector-ALU and memory work shares the scheduling regions of the contraction
     // steps, so that the matrix pipe runs in its background (and in that of the other wave of the
@@ -271,7 +312,12 @@ bool dense_split_supported(const lsh_params *p) {
     return p->m == p->n && p->n == (uint32_t)SN && p->k % kFuncsPerWave == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
 }
 
-int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
+bool dense_split_signs_supported(const lsh_params *p) {
+    return p->n == (uint32_t)SN && p->k % 64 == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
+}
+
+// ep: 0 bucket ids, 1 raw projections, 2 sign words
+int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
                        void *stream) {
     SplitArgs a;
     a.data = d_data;
@@ -283,7 +329,7 @@ int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint
     a.inv_w = 1.0f / p->w;
     a.out = d_out;
     int exp2 = 0;
-    const bool pw = std::frexp(p->w, &exp2) == 0.5f;
+    const bool pw = ep != kIds || std::frexp(p->w, &exp2) == 0.5f;  // only the ids epilogue divides
     const uint32_t slices = (p->k + kFuncsPerBlock - 1) / kFuncsPerBlock;
     // one workgroup per CU (102 KB of LDS); every XCD needs a workgroup per slice of functions
     uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
@@ -291,9 +337,9 @@ int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint
     while (wgs / 8 < slices) wgs += 8;
     const uint32_t lds_bytes = 2 * BUF;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-#define LSH_SPLIT_CASE(P_, W_) \
-    if (proj == P_ && pw == W_) { \
-        auto fn = &dense_split_kernel<P_, W_>; \
+#define LSH_SPLIT_CASE(E_, W_) \
+    if (ep == E_ && pw == W_) { \
+        auto fn = &dense_split_kernel<E_, W_>; \
         static std::atomic<bool> granted{false};  /* the attribute call costs ~1 ms: once per kernel */ \
         if (!granted.load(std::memory_order_acquire)) { \
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
@@ -303,7 +349,7 @@ int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint
         } \
         hipLaunchKernelGGL(fn, dim3(wgs), dim3(kThreadsS), lds_bytes, s, a); \
     }
-    LSH_SPLIT_CASE(false, true) LSH_SPLIT_CASE(false, false) LSH_SPLIT_CASE(true, true) LSH_SPLIT_CASE(true, false)
+    LSH_SPLIT_CASE(kIds, true) LSH_SPLIT_CASE(kIds, false) LSH_SPLIT_CASE(kProj, true) LSH_SPLIT_CASE(kSigns, true)
 #undef LSH_SPLIT_CASE
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }

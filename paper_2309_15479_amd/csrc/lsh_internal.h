@@ -87,7 +87,7 @@ struct lsh_params {
     lsh::Sample *d_samples = nullptr;  // flat: [m_pad][kpad] step-major; chunked: per wave and range, [steps][64]
     void *d_chunk_info = nullptr;      // chunked plan: uint2 {first entry, steps} [kpad/64][nchunks]
     float *d_off = nullptr;            // [kpad]
-    float *d_dense = nullptr;          // [kpad_dense][n] when m == n (row j = a_j), else null
+    float *d_dense = nullptr;          // [kpad_dense][n]: row j = a_j written out over all n coordinates; m == n or n == 128, else null
     uint32_t kpad_dense = 0;
     int dense_arithmetic = LSH_DENSE_AUTO;  // see lsh_params_set_dense_arithmetic
     // one sample per table: operand tables of the shared-sample kernel (null when unsupported)
@@ -142,7 +142,10 @@ int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N
                  void *stream);
 // bf16 x 3 matrix-core version of the dense product (n = 128, k a multiple of 32)
 bool dense_split_supported(const lsh_params *p);
-int launch_dense_split(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
+// ... and of the sign hashes of any object with n = 128 and k a multiple of 64 (dense coefficient rows)
+bool dense_split_signs_supported(const lsh_params *p);
+// ep: 0 bucket ids, 1 raw projections, 2 sign words
+int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
                        void *stream);
 int launch_pack(const lsh_params *p, const int32_t *d_ids, uint64_t N, uint32_t L,
                 uint64_t *d_keys, void *stream);

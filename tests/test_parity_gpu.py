@@ -63,6 +63,14 @@ def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=Tr
         torch.cuda.synchronize()
         stats["signs_excluded"] = check_signs(w_gpu[rows_t].cpu().numpy().view(np.uint64), w_ora, pr, npd,
                                               p.k, label + " signs")
+        if p.n == 128 and p.k % 64 == 0:
+            # this shape's signs come from the matrix-core kernel by default: the gathered
+            # fp32 kernel is checked as well
+            p.set_dense_arithmetic(lsh.DENSE_FP32)
+            w_gpu = lsh.hash_signs(p, data_gpu)
+            torch.cuda.synchronize()
+            p.set_dense_arithmetic(lsh.DENSE_AUTO)
+            check_signs(w_gpu[rows_t].cpu().numpy().view(np.uint64), w_ora, pr, npd, p.k, label + " signs (gathered)")
     if L:
         keys = lsh.pack_keys(p, ids_gpu, L)
         torch.cuda.synchronize()
@@ -198,6 +206,28 @@ def test_dense_n128_shapes(lsh, N, k, w, fp32_only):
             p.set_dense_arithmetic(lsh.DENSE_FP32)
         say(_compare_all(lsh, p, data, np.arange(N) if N <= 4096 else workloads.sample_rows(N, 2048).numpy(),
                          label=f"dense128-{N}x{k}", dense=True, signs=False))
+
+
+@pytest.mark.parametrize("N,k,m,repl,seed", [(1, 64, 32, False, 61), (64, 128, 30, True, 62), (1000, 512, 32, False, 63),
+                                             (333, 320, 128, False, 64), (4097, 1024, 8, True, 65)])
+def test_signs_n128_matrix_core_kernel(lsh, N, k, m, repl, seed):
+    """Sign hashes at n = 128 and k a multiple of 64 run on the matrix cores from the coefficients
+    written out densely (sampling with replacement sums repeated coordinates): partial tiles,
+    idle waves, several slices of functions, m = n.  Data with a heavy tail, so that the terms
+    the two-way split leaves out matter if they are mishandled."""
+    say(f"signs n=128 case N={N} k={k} m={m} repl={repl}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    data = torch.randn((N, 128), generator=g, device="cuda") * torch.exp(
+        2.0 * torch.randn((N, 128), generator=g, device="cuda"))
+    with lsh.LshParams(128, k, m, 4.0, seed, with_replacement=repl) as p:
+        idx, coef, _ = _tables(p)
+        w_ora, pr, npd = oracle.signs(data.cpu().numpy(), idx, coef, nthreads=THREADS, want_proj=True, want_norm_prod=True)
+        w_gpu = lsh.hash_signs(p, data)
+        torch.cuda.synchronize()
+        excluded = check_signs(w_gpu.cpu().numpy().view(np.uint64), w_ora, pr, npd, k, "signs128")
+        say(f"excluded {excluded:.2e}")
+        assert excluded < 1e-3
 
 
 def test_dense_split_products_error(lsh):
