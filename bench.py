@@ -36,9 +36,9 @@ VALU_FP32_UNPACKED_TFLOPS = 78.6
 MEASURED_TRAFFIC_BYTES = {
     "fastlsh": 250604 * 2048 + 2000000 * 1024,    # 0.513 GB read + 2.048 GB written
     "pack_keys": 1000042 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
-    "e2lsh": 251131 * 2048 + 2135488 * 1024,      # 0.514 GB + 2.187 GB (bf16 x 3 kernel)
+    "e2lsh": 251131 * 2048 + 2140948 * 1024,      # 0.514 GB + 2.192 GB (bf16 x 3 kernel)
     "e2lsh_fp32": 251082 * 2048 + 2017484 * 1024,  # 0.514 GB + 2.066 GB (fp32 MFMA kernel)
-    "signs": None,                                # matrix-core kernel: counters not taken yet
+    "signs": 251098 * 2048 + 62500 * 1024,        # 0.514 GB + 0.064 GB (matrix-core kernel)
     "signs_gathered": 250574 * 2048 + 62500 * 1024,  # 0.513 GB + 0.064 GB (gathered fp32 kernel)
     "fastlsh_shared_sample": 250411 * 2048 + 2000000 * 1024,  # 0.513 GB + 2.048 GB
 }
