@@ -19,6 +19,12 @@
 //
 //   V [N][128] row-major (vectors), A [kpad][128] row-major (row j = a_j, fp32).
 //
+// Terms that are zero are skipped by tile.  Data whose values fit a bf16 (8 significant bits:
+// byte-valued descriptors, small integers) have v2 = v3 = 0, and values of at most 16
+// significant bits have v3 = 0; the waves that split a tile note the highest non-zero term
+// they saw ("level" 1, 2 or 3), and the tile then takes 3, 5 or all 6 products (signs: 2 or 3).
+// A product with an all-zero operand adds exactly nothing, so the results are the same bits.
+//
 // Workgroup = 512 threads (8 waves), persistent, one per CU.  A wave owns 32 functions and keeps
 // their coefficients, already split, in 96 registers for the whole launch (the row operand of
 // v_mfma_f32_32x32x16_bf16: lane l holds row l % 32, contraction indices 16 s + 8 (l / 32) ...
@@ -79,7 +85,10 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns;
     constexpr int NSPLIT = SIGNS ? 2 : 3;
     using Vec4 = typename std::conditional<PROJ, float4, int4>::type;
-    extern __shared__ __align__(16) char lds_s[];  // 2 x [3 planes][64 vectors][272 bytes]
+    extern __shared__ __align__(16) char lds_s[];  // 2 x [3 planes][64 vectors][272 bytes], then 2 level words
+    // level word of a buffer: 4 * (number of the tile in this workgroup's sequence + 1) + level,
+    // raised by atomic maximum, so that it never has to be cleared between tiles
+    uint32_t *const level_word = reinterpret_cast<uint32_t *>(lds_s + 2 * BUF);
 
     const uint32_t slices = (a.k + kFuncsPerBlock - 1) / kFuncsPerBlock;
     const uint64_t ntiles = (a.N + TV - 1) / TV;
@@ -147,6 +156,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             raw[q] = *reinterpret_cast<const float4 *>(a.data + vec * SN + ld_piece * 4);
         }
     };
+    uint32_t seen2 = 0, seen3 = 0;  // bits of the second and third terms this lane has produced for the tile
     auto stash_quad = [&](char *buf, int q) {
         {
             const float u[4] = {raw[q].x, raw[q].y, raw[q].z, raw[q].w};
@@ -162,16 +172,33 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             char *dst = buf + (ld_vec + 16 * q) * ROWB + ld_piece * 8;
 #pragma unroll
             for (int p = 0; p < NSPLIT; ++p) *reinterpret_cast<bf16x4 *>(dst + p * PLANE) = h[p];
+            const uint2 t2 = *reinterpret_cast<const uint2 *>(&h[1]);
+            seen2 |= (t2.x | t2.y) & 0x7fff7fffu;
+            if constexpr (NSPLIT == 3) {
+                const uint2 t3 = *reinterpret_cast<const uint2 *>(&h[2]);
+                seen3 |= (t3.x | t3.y) & 0x7fff7fffu;
+            }
         }
+    };
+    // after the last piece of a tile: one lane per wave raises the buffer's level word
+    auto publish_level = [&](uint32_t buf_index, uint32_t seq) {
+        const bool any3 = __any(seen3 != 0), any2 = __any(seen2 != 0);  // a non-zero third term implies a non-zero second
+        if ((any2 || any3) && lane == 0) atomicMax(&level_word[buf_index], 4 * (seq + 1) + (any3 ? 3u : 2u));
+        seen2 = 0;
+        seen3 = 0;
     };
     auto stash = [&](char *buf) {
 #pragma unroll
         for (int q = 0; q < kQuads; ++q) stash_quad(buf, q);
     };
 
+    if (threadIdx.x < 2) level_word[threadIdx.x] = 0;
+    __syncthreads();
     uint64_t t = stream;
+    uint32_t seq = 0;  // number of the tile in this workgroup's sequence
     fetch(t);
     stash(lds_s);
+    publish_level(0, 0);
     __syncthreads();
     fetch(t + streams);
     uint32_t cur = 0;
@@ -180,36 +207,46 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         // waves beyond the last function only help to load: same barriers as the others
         for (; t < ntiles; t += streams) {
             stash(lds_s + (cur ^ 1) * BUF);
+            publish_level(cur ^ 1, seq + 1);
             fetch(t + 2 * streams);
             __syncthreads();
             cur ^= 1;
+            ++seq;
         }
         return;
     }
 
     const uint32_t rd_off = lr * ROWB + lh * 16;  // + column block * 32 rows + plane + 32 bytes per step
     // one contraction step (16 indices) for both column blocks of 32 vectors: 12 MFMAs
-    auto step = [&](const char *base, int s, floatx16 (&acc)[2]) {
-        bf16x8 d[2][NSPLIT];
+    auto step = [&](auto level_tag, const char *base, int s, floatx16 (&acc)[2]) {
+        constexpr int LEVEL = decltype(level_tag)::value;  // highest non-zero term of the tile's vectors
+        constexpr int NREAD = LEVEL < NSPLIT ? LEVEL : NSPLIT;
+        bf16x8 d[2][NREAD];
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
-            for (int p = 0; p < NSPLIT; ++p)
+            for (int p = 0; p < NREAD; ++p)
                 d[vb][p] = *reinterpret_cast<const bf16x8 *>(base + vb * 32 * ROWB + s * 32 + p * PLANE);
         // smallest terms first; the two column blocks alternate, so that an MFMA never waits for
         // the one just issued
         if constexpr (NSPLIT == 3) {
 #pragma unroll
             for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][2], d[vb][0], acc[vb], 0, 0, 0);
+            if constexpr (LEVEL >= 2) {
 #pragma unroll
-            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][1], acc[vb], 0, 0, 0);
+                for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][1], acc[vb], 0, 0, 0);
+            }
+            if constexpr (LEVEL >= 3) {
 #pragma unroll
-            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][2], acc[vb], 0, 0, 0);
+                for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][2], acc[vb], 0, 0, 0);
+            }
         }
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][0], acc[vb], 0, 0, 0);
+        if constexpr (LEVEL >= 2) {
 #pragma unroll
-        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][1], acc[vb], 0, 0, 0);
+            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][1], acc[vb], 0, 0, 0);
+        }
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][0], acc[vb], 0, 0, 0);
     };
@@ -277,7 +314,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     // tile earlier and have the first steps to arrive; the loads of the tile after the next are
     // issued last.
     uint64_t t_prev = 0;
-    auto run_tile = [&](auto have_prev) {
+    auto contract_tile = [&](auto have_prev, auto level_tag) {
         const char *base = lds_s + cur * BUF + rd_off;
         char *next = lds_s + (cur ^ 1) * BUF;
         floatx16 acc[2];
@@ -287,16 +324,28 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             for (int i = 0; i < 16; ++i) acc[vb][i] = 0.f;
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
-            step(base, s, acc);
+            step(level_tag, base, s, acc);
             if constexpr (decltype(have_prev)::value) store_piece(std::true_type{}, t_prev, s);  // a tile with a successor is whole
             if (s >= KSTEPS - kQuads) stash_quad(next, s - (KSTEPS - kQuads));
             __builtin_amdgcn_sched_barrier(0);
         }
         settle(acc);
+    };
+    auto run_tile = [&](auto have_prev) {
+        // the level of the tile in the current buffer: stale words belong to earlier tiles
+        const uint32_t word = __builtin_amdgcn_readfirstlane(level_word[cur]);
+        const uint32_t level = (word >> 2) == seq + 1 ? (word & 3u) : 1u;
+        if (level == 1) contract_tile(have_prev, std::integral_constant<int, 1>{});
+        else if (level == 2) contract_tile(have_prev, std::integral_constant<int, 2>{});
+        else contract_tile(have_prev, std::integral_constant<int, 3>{});
+        // the loads go out after the variants have joined: none is in flight where registers
+        // might have to be copied
+        publish_level(cur ^ 1, seq + 1);
         t_prev = t;
         fetch(t + 2 * streams);
         __syncthreads();  // next buffer complete; everyone is done with the current one
         cur ^= 1;
+        ++seq;
     };
     static_assert(KSTEPS == 8, "one stored piece per contraction step");
     if (t >= ntiles) return;
@@ -335,7 +384,7 @@ int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_
     uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
     if (wgs < 8) wgs = 8;
     while (wgs / 8 < slices) wgs += 8;
-    const uint32_t lds_bytes = 2 * BUF;
+    const uint32_t lds_bytes = 2 * BUF + 16;  // two tiles and their level words
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 #define LSH_SPLIT_CASE(E_, W_) \
     if (ep == E_ && pw == W_) { \

@@ -230,6 +230,34 @@ def test_signs_n128_matrix_core_kernel(lsh, N, k, m, repl, seed):
         assert excluded < 1e-3
 
 
+def test_dense_split_levels_by_tile(lsh):
+    """The bf16 split kernels skip the products of terms that are zero for a whole tile of 64
+    vectors: byte-valued tiles (one term), tiles of 16-bit values (two terms), general tiles, and
+    tiles that are byte-valued but for one element, in one batch and in an order that makes every
+    workgroup meet several kinds; ids, projections and signs against the oracle."""
+    k, tiles = 512, 40
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    N = 64 * tiles + 17
+    data = torch.randn((N, 128), generator=g, device="cuda") * 40.0
+    kind = torch.randint(0, 4, (tiles + 1,), generator=g, device="cuda")
+    for t in range(tiles + 1):
+        rows = slice(64 * t, min(N, 64 * (t + 1)))
+        kd = int(kind[t])
+        if kd == 0:
+            data[rows] = torch.round(data[rows]).clamp(-255, 255)                  # 8 significant bits
+        elif kd == 1:
+            data[rows] = torch.round(data[rows] * 256.0).clamp(-65535, 65535) / 256.0  # 16 significant bits
+        elif kd == 2:
+            data[rows] = torch.round(data[rows]).clamp(-255, 255)
+            data[rows.start + 5, 77] = 0.1234567                                  # one general element
+    rows_all = np.arange(N)
+    with lsh.LshParams(128, k, 128, 16.0, 5) as p:
+        say("levels dense", _compare_all(lsh, p, data, rows_all, label="levels-dense", dense=True, signs=True))
+    with lsh.LshParams(128, k, 32, 16.0, 6) as p:
+        say("levels signs", _compare_all(lsh, p, data, rows_all, label="levels-fast", signs=True))
+
+
 def test_dense_split_products_error(lsh):
     """The bf16 x 3 product against the fp64 oracle on data with a wide range of magnitudes in
     one vector: the error stays at the level of fp32 rounding (a few 2^-24 of sum |a_i v_i|),
