@@ -34,7 +34,8 @@ VALU_FP32_UNPACKED_TFLOPS = 78.6
 # 1 KiB per count), taken on the kernels as they stand; the summary and its commands are in
 # profiles/sift_step_hbm_traffic.md.  Set an entry to None when its kernel changes.
 MEASURED_TRAFFIC_BYTES = {
-    "fastlsh": 250604 * 2048 + 2000000 * 1024,    # 0.513 GB read + 2.048 GB written
+    "fastlsh": None,                              # matrix-core kernel on FastLSH coefficients: not taken yet
+    "fastlsh_gathered": 250604 * 2048 + 2000000 * 1024,  # 0.513 GB read + 2.048 GB written (gathered fp32 kernel)
     "pack_keys": 1000042 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
     "e2lsh": 251131 * 2048 + 2140948 * 1024,      # 0.514 GB + 2.192 GB (bf16 x 3 kernel)
     "e2lsh_fp32": 251082 * 2048 + 2017484 * 1024,  # 0.514 GB + 2.066 GB (fp32 MFMA kernel)
@@ -176,12 +177,12 @@ def main():
                           "frac": 2.0 * tf / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES["signs"],
                           "arithmetic": "bf16 x 2 splits of the densely written coefficients; 2 of 3 MFMA products (zero terms skipped)",
                           "hbm_gbs": gbs, "hbm_frac": gbs / HBM_PEAK_GBS}
-    # the sampled kernel's arithmetic against the plain fp32 vector ceiling, for context
-    for s in ("fastlsh",):
-        alu = 2.0 * N * k * m / (ms[s] * 1e-3) / 1e12
-        rooflines[s]["alu_tflops"] = alu
-        rooflines[s]["alu_frac_of_fp32_vector_peak"] = alu / VALU_FP32_PEAK_TFLOPS
-        rooflines[s]["alu_frac_of_unpacked_fp32_issue_rate"] = alu / VALU_FP32_UNPACKED_TFLOPS
+    # FastLSH ids at n = 128 run on the same matrix-core kernel as the dense product, over the
+    # coefficients written out densely (zeros at the coordinates a function does not sample)
+    tf = 2.0 * N * n * k / (ms["fastlsh"] * 1e-3) / 1e12
+    rooflines["fastlsh"]["arithmetic"] = rooflines["e2lsh"]["arithmetic"]
+    rooflines["fastlsh"]["mfma_tflops"] = 3.0 * tf
+    rooflines["fastlsh"]["mfma_frac_of_bf16_peak"] = 3.0 * tf / MFMA_BF16_PEAK_TFLOPS
     dominant = max(stages, key=lambda s: ms[s])
 
     # Outside the timed step: the same FastLSH shape with one sample per table (L = 32 tables
@@ -217,18 +218,29 @@ def main():
     tf32 = 2.0 * N * n * k / (ms_fp32 * 1e-3) / 1e12
     e2lsh_fp32 = {"ms": ms_fp32, "bound": "mfma", "achieved": tf32, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                   "frac": tf32 / MFMA_FP32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES["e2lsh_fp32"]}
-    # and the sign hashes by the gathered fp32 kernel
+    # and the FastLSH ids and sign hashes by the gathered fp32 kernels (the sampled projection
+    # as the paper writes it: m multiply-adds per function)
     p_fast.set_dense_arithmetic(lsh.DENSE_FP32)
-    for _ in range(args.warmup):
-        lsh.hash_signs(p_fast, data, out=words)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        lsh.hash_signs(p_fast, data, out=words)
-    e1.record()
-    torch.cuda.synchronize()
+    gathered_ms = {}
+    for name, fn in (("ids", lambda: lsh.hash_fastlsh(p_fast, data, out=ids_f)),
+                     ("signs", lambda: lsh.hash_signs(p_fast, data, out=words))):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        gathered_ms[name] = e0.elapsed_time(e1) / args.steps
     p_fast.set_dense_arithmetic(lsh.DENSE_AUTO)
-    ms_sg = e0.elapsed_time(e1) / args.steps
+    ms_ig = gathered_ms["ids"]
+    gbs_ig = N * (4 * n + 4 * k) / (ms_ig * 1e-3) / 1e9
+    alu_ig = 2.0 * N * k * m / (ms_ig * 1e-3) / 1e12
+    fastlsh_gathered = {"ms": ms_ig, "bound": "hbm", "achieved": gbs_ig, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": gbs_ig / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["fastlsh_gathered"],
+                        "alu_tflops": alu_ig, "alu_frac_of_unpacked_fp32_issue_rate": alu_ig / VALU_FP32_UNPACKED_TFLOPS}
+    ms_sg = gathered_ms["signs"]
     gbs_sg = N * (4 * n + 8 * ((k + 63) // 64)) / (ms_sg * 1e-3) / 1e9
     alu_sg = 2.0 * N * k * m / (ms_sg * 1e-3) / 1e12
     signs_gathered = {"ms": ms_sg, "bound": "alu", "achieved": alu_sg, "peak": VALU_FP32_UNPACKED_TFLOPS,
@@ -241,6 +253,7 @@ def main():
     data_full = data + torch.rand_like(data)
     timings_full = {}
     for name, fn in (("e2lsh_ms", lambda: lsh.hash_e2lsh(p_dense, data_full, out=ids_d)),
+                     ("fastlsh_ms", lambda: lsh.hash_fastlsh(p_fast, data_full, out=ids_f)),
                      ("signs_ms", lambda: lsh.hash_signs(p_fast, data_full, out=words))):
         for _ in range(args.warmup):
             fn()
@@ -265,7 +278,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16x3+f32acc",
         "data": "synthetic",
         "config": {"workload": "sift-shaped: N=1000000 n=128 k=512 m=32 w=16 L=32, 100-cluster mixture in [0,255]",
                    "step": "fastlsh ids + key packing + dense e2lsh ids (m=n) + sign hashes",
@@ -282,6 +295,7 @@ def main():
         "fastlsh_shared_sample_per_table": shared_sample,
         "e2lsh_fp32_mfma": e2lsh_fp32,
         "signs_gathered_fp32": signs_gathered,
+        "fastlsh_gathered_fp32": fastlsh_gathered,
         "matrix_core_kernels_on_full_significand_data": timings_full,
     }
     if not args.no_cpu_baseline:

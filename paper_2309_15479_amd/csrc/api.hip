@@ -341,6 +341,8 @@ int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     if (p->shared_plan.supported) return launch_shared(p, 0, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+        return launch_dense_split(p, 0, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
 }
 
@@ -348,6 +350,8 @@ int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, 
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     if (p->shared_plan.supported) return launch_shared(p, 1, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+        return launch_dense_split(p, 1, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);
 }
 

@@ -378,7 +378,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
 }  // namespace
 
 bool dense_split_supported(const lsh_params *p) {
-    return p->m == p->n && p->n == (uint32_t)SN && p->k % kFuncsPerWave == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
+    return p->n == (uint32_t)SN && p->k % kFuncsPerWave == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
 }
 
 bool dense_split_signs_supported(const lsh_params *p) {

@@ -140,7 +140,9 @@ bool shared_keys_ok(const lsh_params *p, uint32_t L);
 int ensure_lds_limit(const void *fn, uint32_t lds_bytes);
 int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,
                  void *stream);
-// bf16 x 3 matrix-core version of the dense product (n = 128, k a multiple of 32)
+// bf16 x 3 matrix-core version of the dense product (n = 128, k a multiple of 32) over the
+// coefficient rows written out densely: E2LSH objects, and FastLSH objects as a dense product with
+// zeros at the coordinates a function does not sample
 bool dense_split_supported(const lsh_params *p);
 // ... and of the sign hashes of any object with n = 128 and k a multiple of 64 (dense coefficient rows)
 bool dense_split_signs_supported(const lsh_params *p);

@@ -36,7 +36,7 @@ def _tables(p):
     return p.indices(), p.coeffs(), p.offsets()
 
 
-def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=True):
+def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=True, dense_fp32=False):
     """Runs every entry point on data_gpu and checks the given rows against the oracle."""
     idx, coef, off = _tables(p)
     rows_t = torch.as_tensor(np.asarray(rows), device=data_gpu.device)
@@ -49,14 +49,27 @@ def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=Tr
     torch.cuda.synchronize()
     stats["proj_worst"] = check_proj(proj_gpu[rows_t].cpu().numpy(), ora, label + " fastlsh proj")
     stats["ids_excluded"] = check_ids(ids_gpu[rows_t].cpu().numpy(), ora, label + " fastlsh ids")
+    if p.n == 128 and p.k % 32 == 0:
+        # this shape runs as a dense product on the matrix cores by default (zeros at the
+        # coordinates a function does not sample): the gathered fp32 kernels are checked as well
+        p.set_dense_arithmetic(lsh.DENSE_FP32)
+        ids_g = lsh.hash_fastlsh(p, data_gpu)
+        proj_g = lsh.project_fastlsh(p, data_gpu)
+        torch.cuda.synchronize()
+        p.set_dense_arithmetic(lsh.DENSE_AUTO)
+        stats["proj_worst_gathered"] = check_proj(proj_g[rows_t].cpu().numpy(), ora, label + " fastlsh proj (gathered)")
+        check_ids(ids_g[rows_t].cpu().numpy(), ora, label + " fastlsh ids (gathered)")
     if dense:
         assert p.m == p.n
+        if dense_fp32:
+            p.set_dense_arithmetic(lsh.DENSE_FP32)
         ora_d = oracle.e2lsh(sub, coef, off, p.w, nthreads=THREADS, want=("proj", "abs_sum", "ids", "frac"))
         ids_d = lsh.hash_e2lsh(p, data_gpu)
         proj_d = lsh.project_e2lsh(p, data_gpu)
         torch.cuda.synchronize()
         stats["dense_proj_worst"] = check_proj(proj_d[rows_t].cpu().numpy(), ora_d, label + " e2lsh proj")
         stats["dense_ids_excluded"] = check_ids(ids_d[rows_t].cpu().numpy(), ora_d, label + " e2lsh ids")
+        p.set_dense_arithmetic(lsh.DENSE_AUTO)
     if signs:
         w_ora, pr, npd = oracle.signs(sub, idx, coef, nthreads=THREADS, want_proj=True, want_norm_prod=True)
         w_gpu = lsh.hash_signs(p, data_gpu)
@@ -202,10 +215,8 @@ def test_dense_n128_shapes(lsh, N, k, w, fp32_only):
     g.manual_seed(N * 3 + k)
     data = torch.randn((N, 128), generator=g, device="cuda") * 2.0
     with lsh.LshParams(128, k, 128, w, N + k) as p:
-        if fp32_only:
-            p.set_dense_arithmetic(lsh.DENSE_FP32)
         say(_compare_all(lsh, p, data, np.arange(N) if N <= 4096 else workloads.sample_rows(N, 2048).numpy(),
-                         label=f"dense128-{N}x{k}", dense=True, signs=False))
+                         label=f"dense128-{N}x{k}", dense=True, signs=False, dense_fp32=fp32_only))
 
 
 @pytest.mark.parametrize("N,k,m,repl,seed", [(1, 64, 32, False, 61), (64, 128, 30, True, 62), (1000, 512, 32, False, 63),
