@@ -137,7 +137,9 @@ int lsh_params_get_schedule(const lsh_params_t *params, uint32_t *order, uint32_
  * FastLSH bucket ids (Eq. 5): d_out_buckets[v*k + j] = floor((a~_j^T S_j(v) + b~_j) / w)
  * as int32 (saturating), for v < N, j < k.  Sampled-projection kernel: each vector
  * tile is read from HBM once, kept in LDS, and every function gathers its m
- * coordinates from there.  fp32 accumulation.
+ * coordinates from there.  fp32 accumulation.  (n == 128 with k a multiple of 32: by default
+ * the matrix-core kernel of lsh_params_set_dense_arithmetic instead, over the coefficients
+ * written out over all n coordinates.)
  * Errors: INVALID_ARG (null pointers), NO_DEVICE, UNSUPPORTED (n > 40384: one vector must
  * fit in LDS), HIP.
  */
@@ -154,20 +156,24 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
                    int32_t *d_out_buckets, void *stream);
 
 /*
- * Arithmetic of the matrix-core kernels (lsh_hash_e2lsh, lsh_project_e2lsh, and lsh_hash_signs
- * at n == 128) of this object.
+ * Arithmetic of the matrix-core kernels of this object: lsh_hash_e2lsh and lsh_project_e2lsh,
+ * and at n == 128 also lsh_hash_fastlsh, lsh_project_fastlsh (objects with one sample per
+ * function) and lsh_hash_signs, which then run as a dense product over the coefficients written
+ * out over all n coordinates: zeros where a function does not sample, sums where it samples a
+ * coordinate more than once.
  * LSH_DENSE_AUTO (the default): for n == 128 and k a multiple of 32 every fp32 operand is
  * split exactly into three bf16 terms and the product is formed from the six bf16 MFMA
  * products of weight >= 2^-16, accumulated in fp32; what is left out is below 2^-23 of each
  * term |a_i v_i|, one fp32 rounding, and the projections stay within the same
  * 1e-5 * sum_i |a_i v_i| of the exact value as the fp32 path.  (Operands whose bf16 rounding
- * overflows, |x| > 3.39e38, give NaN there.)  Other shapes use fp32 MFMA.  With n == 128 and k
- * a multiple of 64, lsh_hash_signs of ANY object (m <= n) runs on the matrix cores too, on the
- * coefficients written out over all n coordinates (zeros where a function does not sample, sums
- * where it samples a coordinate more than once), with two-way splits and three products: what
+ * overflows, |x| > 3.39e38, give NaN there.)  Products of terms that are zero for a whole tile
+ * of 64 vectors are skipped, which changes no bit of the result: byte-valued data take half of
+ * the products.  Other shapes use fp32 MFMA.  With n == 128 and k a multiple of 64,
+ * lsh_hash_signs runs on the matrix cores too, with two-way splits and three products: what
  * they leave out is below 3 * 2^-16 * sum_i |a_i v_i|, under half of the 1e-4 * |a| * |S(v)| around
  * zero inside which a sign bit is unspecified.
- * LSH_DENSE_FP32: fp32 MFMA for every shape, and the gathered fp32 kernel for the signs.
+ * LSH_DENSE_FP32: fp32 MFMA for every dense product, and the gathered fp32 kernels for FastLSH
+ * ids, projections and signs at every n.
  * Errors: INVALID_ARG (null, unknown mode).
  */
 #define LSH_DENSE_AUTO 0
