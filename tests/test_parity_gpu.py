@@ -241,15 +241,15 @@ def test_signs_n128_matrix_core_kernel(lsh, N, k, m, repl, seed):
         assert excluded < 1e-3
 
 
-def test_dense_split_levels_by_tile(lsh):
+@pytest.mark.parametrize("k,tiles,tail", [(512, 40, 17), (96, 2, 2), (320, 1, 0), (64, 0, 9), (1024, 300, 63)])
+def test_dense_split_levels_by_tile(lsh, k, tiles, tail):
     """The bf16 split kernels skip the products of terms that are zero for a whole tile of 64
     vectors: byte-valued tiles (one term), tiles of 16-bit values (two terms), general tiles, and
     tiles that are byte-valued but for one element, in one batch and in an order that makes every
     workgroup meet several kinds; ids, projections and signs against the oracle."""
-    k, tiles = 512, 40
     g = torch.Generator(device="cuda")
-    g.manual_seed(77)
-    N = 64 * tiles + 17
+    g.manual_seed(77 + k)
+    N = 64 * tiles + tail
     data = torch.randn((N, 128), generator=g, device="cuda") * 40.0
     kind = torch.randint(0, 4, (tiles + 1,), generator=g, device="cuda")
     for t in range(tiles + 1):
@@ -262,7 +262,7 @@ def test_dense_split_levels_by_tile(lsh):
         elif kd == 2:
             data[rows] = torch.round(data[rows]).clamp(-255, 255)
             data[rows.start + 5, 77] = 0.1234567                                  # one general element
-    rows_all = np.arange(N)
+    rows_all = np.arange(N) if N <= 4096 else workloads.sample_rows(N, 3000).numpy()
     with lsh.LshParams(128, k, 128, 16.0, 5) as p:
         say("levels dense", _compare_all(lsh, p, data, rows_all, label="levels-dense", dense=True, signs=True))
     with lsh.LshParams(128, k, 32, 16.0, 6) as p:
