@@ -157,8 +157,9 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
 
 /*
  * Arithmetic of the matrix-core kernels of this object: lsh_hash_e2lsh and lsh_project_e2lsh,
- * and at n == 128 also lsh_hash_fastlsh, lsh_project_fastlsh (objects with one sample per
- * function) and lsh_hash_signs, which then run as a dense product over the coefficients written
+ * and at n == 128 also lsh_hash_fastlsh, lsh_project_fastlsh, lsh_hash_fastlsh_keys (4 to 32
+ * functions per table; objects with one sample per function) and lsh_hash_signs, which then
+ * run as a dense product over the coefficients written
  * out over all n coordinates: zeros where a function does not sample, sums where it samples a
  * coordinate more than once.
  * LSH_DENSE_AUTO (the default): for n == 128 and k a multiple of 32 every fp32 operand is
@@ -173,7 +174,7 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
  * they leave out is below 3 * 2^-16 * sum_i |a_i v_i|, under half of the 1e-4 * |a| * |S(v)| around
  * zero inside which a sign bit is unspecified.
  * LSH_DENSE_FP32: fp32 MFMA for every dense product, and the gathered fp32 kernels for FastLSH
- * ids, projections and signs at every n.
+ * ids, projections, keys and signs at every n.
  * Errors: INVALID_ARG (null, unknown mode).
  */
 #define LSH_DENSE_AUTO 0

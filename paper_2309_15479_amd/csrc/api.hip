@@ -372,6 +372,8 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
     if (!is_pow2(g) || g > 64) return LSH_ERR_UNSUPPORTED;
     if (N == 0) return LSH_OK;
     if (shared_keys_ok(p, L)) return launch_shared(p, 2, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && !p->shared_plan.supported && dense_split_keys_supported(p, L))
+        return launch_dense_split(p, 3, d_data, N, d_out, stream, L);
     return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
 }
 

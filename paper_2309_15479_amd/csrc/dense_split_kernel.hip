@@ -73,8 +73,9 @@ struct SplitArgs {
     const float *off;   // [>= k]; not read for signs
     uint64_t N;
     uint32_t k;         // multiple of 32 (signs: of 64)
+    uint32_t g;         // keys: functions per table, 4, 8, 16 or 32
     float w, inv_w;
-    void *out;          // [N][k]
+    void *out;          // [N][k]; signs [N][k / 64]; keys [N][k / g]
 };
 
 __device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &x3) {
@@ -84,12 +85,13 @@ __device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &
     x3 = (__bf16)(r1 - (float)x2);
 }
 
-enum : int { kIds = 0, kProj = 1, kSigns = 2 };
+enum : int { kIds = 0, kProj = 1, kSigns = 2, kKeys = 3 };
 
-// EP: bucket ids, raw projections (both [N][k], 4 bytes each), or sign words ([N][k / 64] of 64 bits)
+// EP: bucket ids, raw projections (both [N][k], 4 bytes each), sign words ([N][k / 64] of 64
+// bits), or the compound keys of Sec. 3.2 folded from the ids ([N][k / g] of 64 bits)
 template <int EP, bool POW2>
 __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitArgs a) {
-    constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns;
+    constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns, KEYS = EP == kKeys;
     constexpr int NSPLIT = SIGNS ? 2 : 3;
     extern __shared__ __align__(16) char lds_s[];  // 2 x [3 planes][64 vectors][272 bytes], then 2 level words
     // level word of a buffer: 4 * (number of the tile in this workgroup's sequence + 1) + level,
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            if constexpr (EP == kIds) {
+            if constexpr (EP == kIds || EP == kKeys) {
                 const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
                 bs[i] = POW2 ? b * a.inv_w : b;
             } else {
@@ -270,12 +272,70 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t stage_wr = lr * STAGE_ROWB + 16 * lh;                // + 32 q
     const uint32_t stage_rd = (lane >> 3) * STAGE_ROWB + (lane & 7) * 16;  // + 8 j rows
     const uint32_t st_off = ((lane >> 3) * a.k + wf) * 4 + (lane & 7) * 16;  // in a block of 32 x k outputs; below 2^32 (host)
-    uintx4 res[2][SIGNS ? 1 : 4];  // ids or the bits of the projections
+    uintx4 res[2][(SIGNS || KEYS) ? 1 : 4];  // ids or the bits of the projections
     uint32_t sign_word[2] = {0, 0};
+    // keys: a lane's four ids of accumulator group q are consecutive functions 8q + 4 (l / 32) ...
+    // + 3 of the wave's 32; they are folded by Horner's rule and weighted with the power of C of
+    // their place in the table, C^(g - 4 - (8q + 4 (l / 32)) % g)
+    uint64_t key_weight[4] = {1, 1, 1, 1};
+    if constexpr (KEYS) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t expo = a.g - 4 - ((8 * q + 4 * lh) % a.g);
+            for (uint32_t e = 0; e < expo; ++e) key_weight[q] *= kKeyMultiplier;
+        }
+    }
+    uint64_t t_settle = 0;  // the tile whose accumulators settle() is given (keys are stored from there)
     auto settle = [&](const floatx16 (&acc)[2]) {
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb) {
-            if constexpr (SIGNS) {
+            if constexpr (KEYS) {
+                uint64_t part[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint64_t fold = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p = acc[vb][4 * q + e];
+                        const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
+                        fold = fold * kKeyMultiplier + (uint32_t)(int)floorf(h);
+                    }
+                    part[q] = fold * key_weight[q];
+                }
+                const uint64_t vec = t_settle * TV + vb * 32 + lr;
+                uint64_t *row = reinterpret_cast<uint64_t *>(a.out) + vec * (a.k / a.g) + wf / a.g;
+                // tables of the wave: 32 / g; a table's parts lie in one or both lanes of the vector
+                if (a.g == 4) {  // uniform; table 2q + l / 32, one part each
+                    if (vec < a.N) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) row[2 * q + lh] = part[q];
+                    }
+                } else {
+                    uint64_t key[4];
+                    int tables = 0;
+                    if (a.g == 8) {
+                        tables = 4;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) key[q] = part[q];
+                    } else if (a.g == 16) {
+                        tables = 2;
+                        key[0] = part[0] + part[1];
+                        key[1] = part[2] + part[3];
+                        key[2] = key[3] = 0;
+                    } else {
+                        tables = 1;
+                        key[0] = part[0] + part[1] + part[2] + part[3];
+                        key[1] = key[2] = key[3] = 0;
+                    }
+#pragma unroll
+                    for (int tb = 0; tb < 4; ++tb) {
+                        if (tb < tables) {  // uniform
+                            const uint64_t sum = key[tb] + __shfl_xor(key[tb], 32);
+                            if (lh == 0 && vec < a.N) row[tb] = sum;
+                        }
+                    }
+                }
+            } else if constexpr (SIGNS) {
                 // bit 8q + 4 (l / 32) + e of the wave's 32 functions from accumulator 4q + e; the
                 // two lanes that share a vector then join their halves
                 uint32_t bits = 0;
@@ -311,7 +371,9 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     auto store_piece = [&](auto full_tag, uint64_t tile, int piece) {
         const int vb = piece / 4, q = piece % 4;
         const uint64_t vec0 = tile * TV + vb * 32;
-        if constexpr (SIGNS) {
+        if constexpr (KEYS) {
+            return;  // stored by settle()
+        } else if constexpr (SIGNS) {
             if (q != 0 || lh != 0) return;
             if constexpr (!decltype(full_tag)::value) {
                 if (vec0 + lr >= a.N) return;
@@ -349,6 +411,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             if (s >= KSTEPS - kQuads) stash_quad(next, s - (KSTEPS - kQuads));
             __builtin_amdgcn_sched_barrier(0);
         }
+        t_settle = t;
         settle(acc);
     };
     auto run_tile = [&](auto have_prev) {
@@ -381,24 +444,31 @@ bool dense_split_supported(const lsh_params *p) {
     return p->n == (uint32_t)SN && p->k % kFuncsPerWave == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
 }
 
+bool dense_split_keys_supported(const lsh_params *p, uint32_t L) {
+    if (!dense_split_supported(p) || !L || p->k % L) return false;
+    const uint32_t g = p->k / L;
+    return g == 4 || g == 8 || g == 16 || g == 32;
+}
+
 bool dense_split_signs_supported(const lsh_params *p) {
     return p->n == (uint32_t)SN && p->k % 64 == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
 }
 
-// ep: 0 bucket ids, 1 raw projections, 2 sign words
+// ep: 0 bucket ids, 1 raw projections, 2 sign words, 3 keys of L tables
 int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
-                       void *stream) {
+                       void *stream, uint32_t L) {
     SplitArgs a;
     a.data = d_data;
     a.a = p->d_dense;
     a.off = p->d_off;
     a.N = N;
     a.k = p->k;
+    a.g = L ? p->k / L : 0;
     a.w = p->w;
     a.inv_w = 1.0f / p->w;
     a.out = d_out;
     int exp2 = 0;
-    const bool pw = ep != kIds || std::frexp(p->w, &exp2) == 0.5f;  // only the ids epilogue divides
+    const bool pw = (ep != kIds && ep != kKeys) || std::frexp(p->w, &exp2) == 0.5f;  // only ids and keys divide
     const uint32_t slices = (p->k + kFuncsPerBlock - 1) / kFuncsPerBlock;
     // one workgroup per CU (102 KB of LDS); every XCD needs a workgroup per slice of functions
     uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
@@ -419,6 +489,7 @@ int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_
         hipLaunchKernelGGL(fn, dim3(wgs), dim3(kThreadsS), lds_bytes, s, a); \
     }
     LSH_SPLIT_CASE(kIds, true) LSH_SPLIT_CASE(kIds, false) LSH_SPLIT_CASE(kProj, true) LSH_SPLIT_CASE(kSigns, true)
+    LSH_SPLIT_CASE(kKeys, true) LSH_SPLIT_CASE(kKeys, false)
 #undef LSH_SPLIT_CASE
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }

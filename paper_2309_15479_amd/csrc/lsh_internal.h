@@ -146,9 +146,11 @@ int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N
 bool dense_split_supported(const lsh_params *p);
 // ... and of the sign hashes of any object with n = 128 and k a multiple of 64 (dense coefficient rows)
 bool dense_split_signs_supported(const lsh_params *p);
-// ep: 0 bucket ids, 1 raw projections, 2 sign words
+// ... and of the keys of L tables of 4, 8, 16 or 32 functions
+bool dense_split_keys_supported(const lsh_params *p, uint32_t L);
+// ep: 0 bucket ids, 1 raw projections, 2 sign words, 3 keys (L tables)
 int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
-                       void *stream);
+                       void *stream, uint32_t L = 0);
 int launch_pack(const lsh_params *p, const int32_t *d_ids, uint64_t N, uint32_t L,
                 uint64_t *d_keys, void *stream);
 
