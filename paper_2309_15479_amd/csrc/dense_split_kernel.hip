@@ -1,4 +1,9 @@
-// Dense E2LSH (Sec. 2.2, Eq. 1) for n = 128 on the bf16 matrix cores, with fp32 accuracy.
+// Projections a_j . v for n = 128 as a dense product on the bf16 matrix cores, with fp32 accuracy,
+// and the epilogues on them: bucket ids (Eq. 1, Eq. 5), raw projections, compound keys (Sec. 3.2)
+// and sign hashes (Sec. 5).  The coefficient matrix is an E2LSH object's (Sec. 2.2) or a FastLSH
+// object's written out over all coordinates (Sec. 3.1: zeros at the coordinates a function does
+// not sample): at n = 128 the matrix cores do the whole row in less time than the vector ALU
+// gathers and multiplies a quarter of it.
 //
 // The fp32 MFMA of this part runs at a sixteenth of the bf16 rate, so the product is computed
 // from three-way bf16 splits instead: an fp32 value x is EXACTLY x1 + x2 + x3 with
@@ -12,10 +17,7 @@
 // Sign hashes (Sec. 5, angular similarity) need the sign of the projection only, and are
 // compared away from zero: with two-way splits and the three products a1 v1 + a1 v2 + a2 v1 the
 // terms left out are below 3 * 2^-16 |a v| per coordinate, under half of the 1e-4 |a| |S(v)|
-// inside which a sign may differ from the exact one.  For these the coefficient matrix may be a
-// FastLSH object's, written out densely (zeros at the coordinates a function does not sample):
-// at n = 128 three bf16 MFMA products over all coordinates cost less than the gathered fp32
-// multiply-adds of a quarter of them.
+// inside which a sign may differ from the exact one.
 //
 //   V [N][128] row-major (vectors), A [kpad][128] row-major (row j = a_j, fp32).
 //
@@ -34,7 +36,9 @@
 // operand uses the same contraction indices per lane, so any lane layout of them that is the
 // same for both operands gives the same sums.  As in the fp32 kernels a lane ends up with runs
 // of four consecutive functions of one vector (accumulator register i = function
-// 8 (i / 4) + 4 (l / 32) + i % 4, vector l % 32) and the results leave as 16-byte stores.
+// 8 (i / 4) + 4 (l / 32) + i % 4, vector l % 32); ids and projections then change lanes through
+// LDS so that 8 lanes store a whole 128-byte line, keys are folded from the runs where they
+// are, sign bits are gathered into half a word per vector and wave.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
