@@ -390,7 +390,9 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                 if (vec0 + 8 * q + (lane >> 3) >= a.N) return;
             }
             char *dst = reinterpret_cast<char *>(a.out) + (vec0 + 8 * q) * a.k * 4 + st_off;
-            *reinterpret_cast<uintx4 *>(dst) = res[vb][q];
+            // whole lines that nothing reads back soon: non-temporal (2-3 % on the SIFT shape; on
+            // partial lines such stores lose, as they no longer combine in L2)
+            __builtin_nontemporal_store(res[vb][q], reinterpret_cast<uintx4 *>(dst));
         }
     };
     // One tile.  The vector-ALU and memory work shares the scheduling regions of the contraction
