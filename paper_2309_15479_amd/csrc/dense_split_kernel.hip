@@ -97,12 +97,17 @@ template <int EP, bool POW2>
 __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitArgs a) {
     constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns, KEYS = EP == kKeys;
     constexpr int NSPLIT = SIGNS ? 2 : 3;
+    // blocks of 32 functions per wave.  Signs: two (their two-way splits leave the registers), so
+    // that a workgroup covers 512 functions and a tile is split once where two workgroups of 256
+    // would each split it; a wave then owns whole 64-bit sign words.
+    constexpr int FB = SIGNS ? 2 : 1;
+    constexpr uint32_t kWaveFuncs = kFuncsPerWave * FB, kBlockFuncs = kFuncsPerBlock * FB;
     extern __shared__ __align__(16) char lds_s[];  // 2 x [3 planes][64 vectors][272 bytes], then 2 level words
     // level word of a buffer: 4 * (number of the tile in this workgroup's sequence + 1) + level,
     // raised by atomic maximum, so that it never has to be cleared between tiles
     uint32_t *const level_word = reinterpret_cast<uint32_t *>(lds_s + kLevelOffset);
 
-    const uint32_t slices = (a.k + kFuncsPerBlock - 1) / kFuncsPerBlock;
+    const uint32_t slices = (a.k + kBlockFuncs - 1) / kBlockFuncs;
     const uint64_t ntiles = (a.N + TV - 1) / TV;
     // workgroups i, i + 8, ... share an XCD (and its L2): the slices of one row tile run there
     // side by side
@@ -113,26 +118,29 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
 
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t lr = lane & 31, lh = lane >> 5;
-    const uint32_t wf = slice * kFuncsPerBlock + wave * kFuncsPerWave;  // first function of the wave
+    const uint32_t wf = slice * kBlockFuncs + wave * kWaveFuncs;  // first function of the wave
     const bool active = wf < a.k;                                     // whole wave
 
     // coefficients of the wave's 32 functions, split, resident: c[s][p]
-    bf16x8 c[KSTEPS][NSPLIT];
+    bf16x8 c[FB][KSTEPS][NSPLIT];
     float bs[16];
     if (active) {
-        const float *row = a.a + (size_t)(wf + lr) * SN + 8 * lh;
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            const float4 u0 = *reinterpret_cast<const float4 *>(row + 16 * s);
-            const float4 u1 = *reinterpret_cast<const float4 *>(row + 16 * s + 4);
-            const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+        for (int fb = 0; fb < FB; ++fb) {
+            const float *row = a.a + (size_t)(wf + 32 * fb + lr) * SN + 8 * lh;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                __bf16 x1, x2, x3;
-                split3(u[e], x1, x2, x3);
-                c[s][0][e] = x1;
-                c[s][1][e] = x2;
-                if constexpr (NSPLIT == 3) c[s][2][e] = x3;
+            for (int s = 0; s < KSTEPS; ++s) {
+                const float4 u0 = *reinterpret_cast<const float4 *>(row + 16 * s);
+                const float4 u1 = *reinterpret_cast<const float4 *>(row + 16 * s + 4);
+                const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    __bf16 x1, x2, x3;
+                    split3(u[e], x1, x2, x3);
+                    c[fb][s][0][e] = x1;
+                    c[fb][s][1][e] = x2;
+                    if constexpr (NSPLIT == 3) c[fb][s][2][e] = x3;
+                }
             }
         }
 #pragma unroll
@@ -146,11 +154,13 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         }
     } else {
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
+        for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-            for (int p = 0; p < NSPLIT; ++p)
+            for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) c[s][p][e] = (__bf16)0.f;
+                for (int p = 0; p < NSPLIT; ++p)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) c[fb][s][p][e] = (__bf16)0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) bs[i] = 0.f;
     }
@@ -230,7 +240,8 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
 
     const uint32_t rd_off = lr * ROWB + lh * 16;  // + column block * 32 rows + plane + 32 bytes per step
     // one contraction step (16 indices) for both column blocks of 32 vectors: 12 MFMAs
-    auto step = [&](auto level_tag, const char *base, int s, floatx16 (&acc)[2]) {
+    // (for the column blocks vb0 <= vb < vb1 of 32 vectors)
+    auto step = [&](auto level_tag, const char *base, int s, floatx16 (&acc)[FB][2], int vb0, int vb1) {
         constexpr int LEVEL = decltype(level_tag)::value;  // highest non-zero term of the tile's vectors
         constexpr int NREAD = LEVEL < NSPLIT ? LEVEL : NSPLIT;
         bf16x8 d[2][NREAD];
@@ -238,29 +249,30 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
             for (int p = 0; p < NREAD; ++p)
-                d[vb][p] = *reinterpret_cast<const bf16x8 *>(base + vb * 32 * ROWB + s * 32 + p * PLANE);
-        // smallest terms first; the two column blocks alternate, so that an MFMA never waits for
-        // the one just issued
+                if (vb >= vb0 && vb < vb1)
+                    d[vb][p] = *reinterpret_cast<const bf16x8 *>(base + vb * 32 * ROWB + s * 32 + p * PLANE);
+        // one product of terms for all accumulator tiles at a time, smallest terms first: the
+        // tiles alternate, so that an MFMA never waits for the one just issued
+        auto product = [&](auto pc_tag, auto pd_tag) {
+            constexpr int PC = decltype(pc_tag)::value, PD = decltype(pd_tag)::value;
+#pragma unroll
+            for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+                for (int vb = 0; vb < 2; ++vb)
+                    if (vb >= vb0 && vb < vb1)
+                        acc[fb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[fb][s][PC], d[vb][PD], acc[fb][vb], 0, 0, 0);
+        };
+        using T0 = std::integral_constant<int, 0>;
+        using T1 = std::integral_constant<int, 1>;
+        using T2 = std::integral_constant<int, 2>;
         if constexpr (NSPLIT == 3) {
-#pragma unroll
-            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][2], d[vb][0], acc[vb], 0, 0, 0);
-            if constexpr (LEVEL >= 2) {
-#pragma unroll
-                for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][1], acc[vb], 0, 0, 0);
-            }
-            if constexpr (LEVEL >= 3) {
-#pragma unroll
-                for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][2], acc[vb], 0, 0, 0);
-            }
+            product(T2{}, T0{});
+            if constexpr (LEVEL >= 2) product(T1{}, T1{});
+            if constexpr (LEVEL >= 3) product(T0{}, T2{});
         }
-#pragma unroll
-        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][1], d[vb][0], acc[vb], 0, 0, 0);
-        if constexpr (LEVEL >= 2) {
-#pragma unroll
-            for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][1], acc[vb], 0, 0, 0);
-        }
-#pragma unroll
-        for (int vb = 0; vb < 2; ++vb) acc[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[s][0], d[vb][0], acc[vb], 0, 0, 0);
+        product(T1{}, T0{});
+        if constexpr (LEVEL >= 2) product(T0{}, T1{});
+        product(T0{}, T0{});
     };
     // Epilogue in two parts.  `settle` turns the accumulators of a tile into the 2 x 16 results
     // a lane keeps (bucket ids or raw projections); `store_piece` writes one 16-byte piece of
@@ -277,7 +289,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t stage_rd = (lane >> 3) * STAGE_ROWB + (lane & 7) * 16;  // + 8 j rows
     const uint32_t st_off = ((lane >> 3) * a.k + wf) * 4 + (lane & 7) * 16;  // in a block of 32 x k outputs; below 2^32 (host)
     uintx4 res[2][(SIGNS || KEYS) ? 1 : 4];  // ids or the bits of the projections
-    uint32_t sign_word[2] = {0, 0};
+    uint32_t sign_word[2][2] = {{0, 0}, {0, 0}};  // [column block][low, high half of the wave's sign word]
     // keys: a lane's four ids of accumulator group q are consecutive functions 8q + 4 (l / 32) ...
     // + 3 of the wave's 32; they are folded by Horner's rule and weighted with the power of C of
     // their place in the table, C^(g - 4 - (8q + 4 (l / 32)) % g)
@@ -290,9 +302,10 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         }
     }
     uint64_t t_settle = 0;  // the tile whose accumulators settle() is given (keys are stored from there)
-    auto settle = [&](const floatx16 (&acc)[2]) {
+    auto settle = [&](const floatx16 (&acc)[FB][2], int vb0, int vb1) {
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb) {
+            if (vb < vb0 || vb >= vb1) continue;
             if constexpr (KEYS) {
                 uint64_t part[4];
 #pragma unroll
@@ -300,7 +313,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                     uint64_t fold = 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float p = acc[vb][4 * q + e];
+                        const float p = acc[0][vb][4 * q + e];
                         const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
                         fold = fold * kKeyMultiplier + (uint32_t)(int)floorf(h);
                     }
@@ -340,20 +353,23 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                     }
                 }
             } else if constexpr (SIGNS) {
-                // bit 8q + 4 (l / 32) + e of the wave's 32 functions from accumulator 4q + e; the
+                // bit 8q + 4 (l / 32) + e of a block of 32 functions from accumulator 4q + e; the
                 // two lanes that share a vector then join their halves
-                uint32_t bits = 0;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) bits |= (acc[vb][i] >= 0.f ? 1u : 0u) << (8 * (i / 4) + (i % 4));
-                bits <<= 4 * lh;
-                sign_word[vb] = bits | (uint32_t)__shfl_xor((int)bits, 32);
+                for (int fb = 0; fb < FB; ++fb) {
+                    uint32_t bits = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) bits |= (acc[fb][vb][i] >= 0.f ? 1u : 0u) << (8 * (i / 4) + (i % 4));
+                    bits <<= 4 * lh;
+                    sign_word[vb][fb] = bits | (uint32_t)__shfl_xor((int)bits, 32);
+                }
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     uintx4 v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float p = acc[vb][4 * q + e];
+                        const float p = acc[0][vb][4 * q + e];
                         if constexpr (PROJ) {
                             v[e] = __float_as_uint(p);
                         } else {
@@ -370,8 +386,8 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             }
         }
     };
-    // signs: the wave's 32 functions are one half of the 64-bit word wf / 64 of each vector
-    const uint32_t sign_off = (lr * (a.k / 64) + wf / 64) * 8 + ((wf / 32) & 1) * 4;  // in a block of 32 vectors
+    // signs: the wave's 64 functions are the 64-bit word wf / 64 of each vector
+    const uint32_t sign_off = (lr * (a.k / 64) + wf / 64) * 8;  // in a block of 32 vectors
     auto store_piece = [&](auto full_tag, uint64_t tile, int piece) {
         const int vb = piece / 4, q = piece % 4;
         const uint64_t vec0 = tile * TV + vb * 32;
@@ -383,7 +399,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                 if (vec0 + lr >= a.N) return;
             }
             char *dst = reinterpret_cast<char *>(a.out) + vec0 * (a.k / 64) * 8 + sign_off;
-            *reinterpret_cast<uint32_t *>(dst) = sign_word[vb];
+            *reinterpret_cast<uint2 *>(dst) = make_uint2(sign_word[vb][0], sign_word[vb][1]);
         } else {
             // piece q of a column block: vectors 8q .. 8q + 7, 8 lanes each
             if constexpr (!decltype(full_tag)::value) {
@@ -405,20 +421,41 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     auto contract_tile = [&](auto have_prev, auto level_tag) {
         const char *base = lds_s + cur * BUF + rd_off;
         char *next = lds_s + (cur ^ 1) * BUF;
-        floatx16 acc[2];
+        floatx16 acc[FB][2];
 #pragma unroll
-        for (int vb = 0; vb < 2; ++vb)
+        for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[vb][i] = 0.f;
+            for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            step(level_tag, base, s, acc);
-            if constexpr (decltype(have_prev)::value) store_piece(std::true_type{}, t_prev, s);  // a tile with a successor is whole
-            if (s >= KSTEPS - kQuads) stash_quad(next, s - (KSTEPS - kQuads));
-            __builtin_amdgcn_sched_barrier(0);
+                for (int i = 0; i < 16; ++i) acc[fb][vb][i] = 0.f;
+        if constexpr (SIGNS) {
+            // two function blocks per wave: the column blocks take turns, so that only half of the
+            // accumulators are live at a time; the second pass carries the split of the next tile
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb) {
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    step(level_tag, base, s, acc, vb, vb + 1);
+                    if constexpr (decltype(have_prev)::value) {
+                        if (s == 0) store_piece(std::true_type{}, t_prev, 4 * vb);
+                    }
+                    if (vb == 1 && s >= KSTEPS - kQuads) stash_quad(next, s - (KSTEPS - kQuads));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                t_settle = t;
+                settle(acc, vb, vb + 1);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                step(level_tag, base, s, acc, 0, 2);
+                if constexpr (decltype(have_prev)::value) store_piece(std::true_type{}, t_prev, s);  // a tile with a successor is whole
+                if (s >= KSTEPS - kQuads) stash_quad(next, s - (KSTEPS - kQuads));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            t_settle = t;
+            settle(acc, 0, 2);
         }
-        t_settle = t;
-        settle(acc);
     };
     auto run_tile = [&](auto have_prev) {
         // the level of the tile in the current buffer: stale words belong to earlier tiles
@@ -475,7 +512,8 @@ int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_
     a.out = d_out;
     int exp2 = 0;
     const bool pw = (ep != kIds && ep != kKeys) || std::frexp(p->w, &exp2) == 0.5f;  // only ids and keys divide
-    const uint32_t slices = (p->k + kFuncsPerBlock - 1) / kFuncsPerBlock;
+    const uint32_t block_funcs = kFuncsPerBlock * (ep == kSigns ? 2 : 1);
+    const uint32_t slices = (p->k + block_funcs - 1) / block_funcs;
     // one workgroup per CU (102 KB of LDS); every XCD needs a workgroup per slice of functions
     uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
     if (wgs < 8) wgs = 8;
