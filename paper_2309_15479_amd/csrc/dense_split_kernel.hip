@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t wf = slice * kBlockFuncs + wave * kWaveFuncs;  // first function of the wave
     const bool active = wf < a.k;                                     // whole wave
 
-    // coefficients of the wave's 32 functions, split, resident: c[s][p]
+    // coefficients of the wave's blocks of 32 functions, split, resident: c[block][step][term]
     bf16x8 c[FB][KSTEPS][NSPLIT];
     float bs[16];
     if (active) {
