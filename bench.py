@@ -295,6 +295,14 @@ def main():
         "fastlsh_shared_sample_per_table": shared_sample,
         "e2lsh_fp32_mfma": e2lsh_fp32,
         "signs_gathered_fp32": signs_gathered,
+        # the same four stages with LSH_DENSE_FP32 (gathered fp32 kernels, fp32 MFMA), from the
+        # legs timed above one kernel at a time: the step if no bf16 product were used
+        "fp32_arithmetic_step": {
+            "ms": ms_ig + ms["pack_keys"] + ms_fp32 + ms_sg,
+            "hashes_per_s": hashes_per_step / ((ms_ig + ms["pack_keys"] + ms_fp32 + ms_sg) * 1e-3)},
+        "precision": "every output meets the same bar as the fp32 kernels against the fp64 oracle "
+                     "(projections within 1e-5 * sum|a_i v_i|, ids identical outside 1e-4 of a boundary, sign "
+                     "bits identical outside 1e-4 |a||S(v)| of zero); the bf16 terms are exact splits of the fp32 operands",
         "fastlsh_gathered_fp32": fastlsh_gathered,
         "matrix_core_kernels_on_full_significand_data": timings_full,
     }
