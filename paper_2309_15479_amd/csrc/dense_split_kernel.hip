@@ -54,6 +54,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int SN = 128;            // contraction length
 constexpr int KSTEPS = SN / 16;    // MFMA steps
@@ -175,7 +176,9 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         for (int q = 0; q < kQuads; ++q) {
             uint64_t vec = tile * TV + ld_vec + 16 * q;
             vec = vec < a.N ? vec : a.N - 1;
-            raw[q] = *reinterpret_cast<const float4 *>(a.data + vec * SN + ld_piece * 4);
+            // streamed once (the workgroup that shares the tile finds it in L2 all the same)
+            const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(a.data + vec * SN + ld_piece * 4));
+            raw[q] = make_float4(v[0], v[1], v[2], v[3]);
         }
     };
     uint32_t seen2 = 0, seen3 = 0;  // bits of the second and third terms this lane has produced for the tile
