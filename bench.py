@@ -34,12 +34,12 @@ VALU_FP32_UNPACKED_TFLOPS = 78.6
 # 1 KiB per count), taken on the kernels as they stand; the summary and its commands are in
 # profiles/sift_step_hbm_traffic.md.  Set an entry to None when its kernel changes.
 MEASURED_TRAFFIC_BYTES = {
-    "fastlsh": 251159 * 2048 + 2000004 * 1024,    # 0.514 GB read + 2.048 GB written (matrix-core kernel)
+    "fastlsh": 252146 * 2048 + 2000010 * 1024,    # 0.516 GB read + 2.048 GB written (matrix-core kernel)
     "fastlsh_gathered": 250604 * 2048 + 2000000 * 1024,  # 0.513 GB read + 2.048 GB written (gathered fp32 kernel)
     "pack_keys": 1000042 * 2048 + 250000 * 1024,  # 2.048 GB + 0.256 GB
-    "e2lsh": 251159 * 2048 + 2000004 * 1024,      # 0.514 GB + 2.048 GB (the same kernel on the E2LSH matrix)
-    "e2lsh_fp32": 251082 * 2048 + 2021875 * 1024,  # 0.514 GB + 2.070 GB (fp32 MFMA kernel)
-    "signs": 251152 * 2048 + 62500 * 1024,        # 0.514 GB + 0.064 GB (matrix-core kernel)
+    "e2lsh": 252330 * 2048 + 2000016 * 1024,      # 0.517 GB + 2.048 GB (the same kernel on the E2LSH matrix)
+    "e2lsh_fp32": 251082 * 2048 + 2020697 * 1024,  # 0.514 GB + 2.069 GB (fp32 MFMA kernel)
+    "signs": 251162 * 2048 + 62500 * 1024,        # 0.514 GB + 0.064 GB (matrix-core kernel)
     "signs_gathered": 250574 * 2048 + 62500 * 1024,  # 0.513 GB + 0.064 GB (gathered fp32 kernel)
     "fastlsh_shared_sample": 250411 * 2048 + 2000000 * 1024,  # 0.513 GB + 2.048 GB
 }
