@@ -50,6 +50,16 @@ def test_null_and_flag_arguments():
     assert lib.lsh_hash_fastlsh(None, None, 1, None, None) == -1
     assert lib.lsh_hash_fastlsh(None, None, 0, None, None) == -1   # no params object
     lib.lsh_params_destroy(None)          # no-op
+    assert lib.lsh_params_set_dense_arithmetic(None, 0) == -1
+
+
+def test_dense_arithmetic_modes():
+    with binding.LshParams(128, 64, 32, 4.0, 1) as p:
+        p.set_dense_arithmetic(binding.DENSE_FP32)
+        p.set_dense_arithmetic(binding.DENSE_AUTO)
+        with pytest.raises(binding.LshError) as e:
+            p.set_dense_arithmetic(2)
+        assert e.value.status == -1
 
 
 CASES = [
