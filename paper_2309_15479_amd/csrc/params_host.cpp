@@ -76,15 +76,16 @@ int generate_tables(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed, 
     }
     const bool replace = (flags & LSH_SAMPLE_WITH_REPLACEMENT) != 0;
     std::vector<uint32_t> deck;  // Fisher-Yates deck, restored after every function
+    std::vector<uint32_t> swapped_with;
     if (m < n && !replace) {
         try {
             deck.resize(n);
+            swapped_with.resize(m);
         } catch (const std::bad_alloc &) {
             return LSH_ERR_ALLOC;
         }
         for (uint32_t c = 0; c < n; ++c) deck[c] = c;
     }
-    std::vector<uint32_t> swapped_with(m);
     const double two_pi = 6.283185307179586476925286766559;
     for (uint32_t j = 0; j < k; ++j) {
         uint32_t *S = &idx[static_cast<size_t>(j) * m];
