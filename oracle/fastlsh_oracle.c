@@ -233,7 +233,7 @@ int oracle_fastlsh(const float *data, uint64_t N, uint32_t n, uint32_t k, uint32
     int status = ORACLE_OK;
 #ifdef _OPENMP
     if (nthreads < 1) nthreads = 1;
-#pragma omp parallel for num_threads(nthreads) schedule(static)
+#pragma omp parallel for num_threads(nthreads) schedule(static) reduction(min : status)
 #endif
     for (int64_t r = 0; r < (int64_t)N; ++r) {
         const float *v = data + (size_t)r * n;
@@ -270,7 +270,7 @@ int oracle_e2lsh(const float *data, uint64_t N, uint32_t n, uint32_t k, const fl
     int status = ORACLE_OK;
 #ifdef _OPENMP
     if (nthreads < 1) nthreads = 1;
-#pragma omp parallel for num_threads(nthreads) schedule(static)
+#pragma omp parallel for num_threads(nthreads) schedule(static) reduction(min : status)
 #endif
     for (int64_t r = 0; r < (int64_t)N; ++r) {
         const float *v = data + (size_t)r * n;
@@ -312,7 +312,7 @@ int oracle_signs(const float *data, uint64_t N, uint32_t n, uint32_t k, uint32_t
     int status = ORACLE_OK;
 #ifdef _OPENMP
     if (nthreads < 1) nthreads = 1;
-#pragma omp parallel for num_threads(nthreads) schedule(static)
+#pragma omp parallel for num_threads(nthreads) schedule(static) reduction(min : status)
 #endif
     for (int64_t r = 0; r < (int64_t)N; ++r) {
         const float *v = data + (size_t)r * n;
