@@ -234,14 +234,15 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
  * memory, owned by the index object.
  *
  * lsh_index_build: d_keys [N][L] (device, as written by lsh_pack_keys or
- *   lsh_hash_fastlsh_keys), N < 2^32.  Sorts the L columns on `stream` and WAITS for them
+ *   lsh_hash_fastlsh_keys), N < 2^31.  Sorts the L columns on `stream` and WAITS for them
  *   (temporary buffers are released before returning).
  * lsh_index_tables: N, L and the device arrays sorted keys [L][N], ids in key order [L][N]
  *   (owned by the index; any out pointer may be NULL).
  * lsh_index_probe: d_qkeys [Q][L] -> d_start [Q][L], d_count [Q][L]: the bucket of query q in
  *   table l is ids[l][start .. start + count).  count 0 = empty bucket.  Asynchronous.
  * lsh_index_candidate_offsets: exclusive prefix sum of `items` counts into d_offsets
- *   [items + 1] (the last entry is the total); waits for the stream.
+ *   [items + 1] (the last entry is the total; items = 0 writes the single 0 and d_count may
+ *   then be NULL); waits for the stream.
  * lsh_index_candidates: the buckets of every (query, table) item copied to
  *   d_out[offsets[item] ..): a query's combined candidate list is its L runs one after the
  *   other (an id met in several tables appears once per table).  Asynchronous.
@@ -256,7 +257,7 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
  *   candidate with the largest inner product v . u with the query (fp32; ties to the smaller
  *   id) -> d_best_id, d_best_ip [Q] (-inf when there is no candidate).  The index is then built
  *   from the keys of lsh_hash_mips_data and probed with those of lsh_hash_mips_query.
- * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^32, called on another device than the one
+ * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^31, called on another device than the one
  * the index was built on), ALLOC, HIP, NO_DEVICE, UNSUPPORTED (lsh_index_nearest and
  * lsh_index_best_inner_product: n > 16368).
  */
@@ -268,6 +269,18 @@ int lsh_index_tables(const lsh_index_t *index, uint64_t *N, uint32_t *L, const u
 int lsh_index_probe(const lsh_index_t *index, const uint64_t *d_qkeys, uint64_t Q, uint32_t *d_start,
                     uint32_t *d_count, void *stream);
 int lsh_index_candidate_offsets(const uint32_t *d_count, uint64_t items, uint64_t *d_offsets, void *stream);
+/*
+ * lsh_index_candidate_offsets for callers that cannot allocate device memory or wait (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same three
+ * launches, with the scan's block sums in a 16 KB device array that the library holds on every
+ * GPU it has run on until the process ends, instead of a temporary allocation.  Calls no
+ * allocator, does not wait for the stream, and records no memset.  items <= 4,194,304 (2^22);
+ * more returns UNSUPPORTED.  All calls on one GPU share that array: two calls whose kernels may
+ * overlap in time (different streams, or a graph replayed while another call runs) race; calls
+ * on one stream are ordered and safe.  Same outputs as lsh_index_candidate_offsets, bit for bit.
+ * Errors: INVALID_ARG (null pointers), UNSUPPORTED (items above the limit), HIP.
+ */
+int lsh_index_candidate_offsets_static(const uint32_t *d_count, uint64_t items, uint64_t *d_offsets, void *stream);
 int lsh_index_candidates(const lsh_index_t *index, const uint32_t *d_start, const uint32_t *d_count,
                          const uint64_t *d_offsets, uint64_t Q, uint32_t *d_out, void *stream);
 int lsh_index_nearest(const lsh_index_t *index, const float *d_data, const float *d_queries, uint32_t n,

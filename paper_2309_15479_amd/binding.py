@@ -32,7 +32,7 @@ EXPORTS = [
     "lsh_mips_kappa", "lsh_hash_mips_data", "lsh_hash_mips_query", "lsh_project_mips_data",
     "lsh_project_mips_query",
     "lsh_index_build", "lsh_index_destroy", "lsh_index_tables", "lsh_index_probe",
-    "lsh_index_candidate_offsets", "lsh_index_candidates", "lsh_index_nearest", "lsh_index_best_inner_product",
+    "lsh_index_candidate_offsets", "lsh_index_candidate_offsets_static", "lsh_index_candidates", "lsh_index_nearest", "lsh_index_best_inner_product",
 ]
 
 
@@ -98,6 +98,7 @@ def load_library():
     lib.lsh_index_tables.argtypes = [p, p, p, p, p]
     lib.lsh_index_probe.argtypes = [p, p, u64, p, p, p]
     lib.lsh_index_candidate_offsets.argtypes = [p, u64, p, p]
+    lib.lsh_index_candidate_offsets_static.argtypes = [p, u64, p, p]
     lib.lsh_index_candidates.argtypes = [p, p, p, p, u64, p, p]
     lib.lsh_index_nearest.argtypes = [p, p, p, u32, p, p, u64, u32, p, p, p]
     lib.lsh_index_best_inner_product.argtypes = [p, p, p, u32, p, p, u64, u32, p, p, p]
@@ -386,9 +387,7 @@ class LshIndex:
         ids[offsets[item] : offsets[item + 1]]."""
         import torch
         items = start.numel()
-        offsets = torch.empty(items + 1, dtype=torch.int64, device=start.device)
-        _check(load_library().lsh_index_candidate_offsets(count.data_ptr(), items, offsets.data_ptr(),
-                                                          _stream(stream)), "lsh_index_candidate_offsets")
+        offsets = candidate_offsets(count, stream=stream)
         total = int(offsets[-1].item())
         ids = torch.empty(total, dtype=torch.int32, device=start.device)
         if total:
@@ -420,6 +419,20 @@ class LshIndex:
                                              start.data_ptr(), count.data_ptr(), Q, max_candidates,
                                              best.data_ptr(), dist.data_ptr(), _stream(stream)), name)
         return best, dist
+
+
+def candidate_offsets(count, out=None, static_scratch=False, stream=None):
+    """Exclusive prefix sum of the bucket sizes: int64 [items + 1], the last entry the total.
+    static_scratch=True takes the entry point that allocates nothing and does not wait."""
+    import torch
+    assert count.is_cuda and count.dtype == torch.int32 and count.is_contiguous()
+    items = count.numel()
+    if out is None:
+        out = torch.empty(items + 1, dtype=torch.int64, device=count.device)
+    assert out.is_cuda and out.dtype == torch.int64 and out.is_contiguous() and out.numel() == items + 1
+    name = "lsh_index_candidate_offsets_static" if static_scratch else "lsh_index_candidate_offsets"
+    _check(getattr(load_library(), name)(count.data_ptr(), items, out.data_ptr(), _stream(stream)), name)
+    return out
 
 
 def e2lsh_collision_probability(s, w):

@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
+#include <mutex>
 #include <new>
 
 #include "lsh.h"
@@ -65,22 +66,138 @@ __global__ void probe_kernel(const uint64_t *__restrict__ sorted_keys, uint64_t 
     count[item] = (uint32_t)(lo - first);
 }
 
-__global__ void widen_counts(const uint32_t *__restrict__ count, uint64_t items, uint64_t *__restrict__ wide) {
-    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    if (i < items) wide[i] = count[i];
-    if (i == items) wide[i] = 0;  // the extra element turns the exclusive scan's last entry into the total
+// Exclusive prefix sum of 32-bit counts into 64-bit offsets, three small launches: (1) every
+// block of kScanBlock counts adds up its own, (2) one block turns the block sums into block
+// offsets in place, (3) every block scans its counts again on top of its offset.  `partial`
+// holds one 64-bit word per block; every word is written by (1) before it is read, so the
+// buffer needs no clearing between calls.
+constexpr uint32_t kScanThreads = 256, kScanPerThread = 8, kScanBlock = kScanThreads * kScanPerThread;
+
+// sum over the workgroup; every thread gets the total, `before` = sum over the threads below it
+__device__ __forceinline__ uint64_t block_scan(uint64_t mine, uint64_t *wave_sums, uint64_t &before) {
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t incl = mine;
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t up = __shfl_up(incl, d);
+        if (lane >= (uint32_t)d) incl += up;
+    }
+    __syncthreads();  // wave_sums may still be read from an earlier call in the same kernel
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    uint64_t below = 0, total = 0;
+    for (uint32_t w = 0; w < kScanThreads / 64; ++w) {
+        if (w < wave) below += wave_sums[w];
+        total += wave_sums[w];
+    }
+    before = below + incl - mine;
+    return total;
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_block_sums(const uint32_t *__restrict__ count, uint64_t items,
+                                                                 uint64_t *__restrict__ partial) {
+    __shared__ uint64_t wave_sums[kScanThreads / 64];
+    const uint64_t first = (uint64_t)blockIdx.x * kScanBlock + (uint64_t)threadIdx.x * kScanPerThread;
+    uint64_t mine = 0;
+    for (uint32_t e = 0; e < kScanPerThread; ++e)
+        if (first + e < items) mine += count[first + e];
+    uint64_t before;
+    const uint64_t total = block_scan(mine, wave_sums, before);
+    if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+// one workgroup: partial[b] <- sum of partial[0 .. b), for b < blocks, chunk after chunk
+__global__ __launch_bounds__(kScanThreads) void scan_partials(uint64_t *__restrict__ partial, uint64_t blocks) {
+    __shared__ uint64_t wave_sums[kScanThreads / 64];
+    uint64_t carry = 0;
+    for (uint64_t base = 0; base < blocks; base += kScanBlock) {
+        const uint64_t first = base + (uint64_t)threadIdx.x * kScanPerThread;
+        uint64_t v[kScanPerThread], mine = 0;
+        for (uint32_t e = 0; e < kScanPerThread; ++e) {
+            v[e] = first + e < blocks ? partial[first + e] : 0;
+            mine += v[e];
+        }
+        uint64_t before;
+        const uint64_t total = block_scan(mine, wave_sums, before);
+        uint64_t run = carry + before;
+        for (uint32_t e = 0; e < kScanPerThread; ++e) {
+            if (first + e < blocks) partial[first + e] = run;
+            run += v[e];
+        }
+        carry += total;
+    }
+}
+
+// offsets[i] = sum of count[0 .. i) for i <= items (the last entry is the total)
+__global__ __launch_bounds__(kScanThreads) void scan_offsets(const uint32_t *__restrict__ count, uint64_t items,
+                                                              const uint64_t *__restrict__ partial,
+                                                              uint64_t *__restrict__ offsets) {
+    __shared__ uint64_t wave_sums[kScanThreads / 64];
+    const uint64_t first = (uint64_t)blockIdx.x * kScanBlock + (uint64_t)threadIdx.x * kScanPerThread;
+    uint32_t v[kScanPerThread];
+    uint64_t mine = 0;
+    for (uint32_t e = 0; e < kScanPerThread; ++e) {
+        v[e] = first + e < items ? count[first + e] : 0;
+        mine += v[e];
+    }
+    uint64_t before;
+    block_scan(mine, wave_sums, before);
+    uint64_t run = partial[blockIdx.x] + before;
+    for (uint32_t e = 0; e < kScanPerThread; ++e) {
+        if (first + e <= items) offsets[first + e] = run;  // element `items` receives the total
+        run += v[e];
+    }
+}
+
+// the three launches; partial must hold (items / kScanBlock + 1) words
+int launch_offsets_scan(const uint32_t *d_count, uint64_t items, uint64_t *d_partial, uint64_t *d_offsets,
+                        hipStream_t s) {
+    const uint64_t blocks = items / kScanBlock + 1;  // covers element `items` too
+    hipLaunchKernelGGL(scan_block_sums, dim3((uint32_t)blocks), dim3(kScanThreads), 0, s, d_count, items, d_partial);
+    hipLaunchKernelGGL(scan_partials, dim3(1), dim3(kScanThreads), 0, s, d_partial, blocks);
+    hipLaunchKernelGGL(scan_offsets, dim3((uint32_t)blocks), dim3(kScanThreads), 0, s, d_count, items, d_partial,
+                       d_offsets);
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+// Scratch of lsh_index_candidate_offsets_static: the block sums of the scan, for callers that
+// must not allocate.  One copy per GPU, held until the process ends; its device address is
+// looked up once per device (the name below is only a host-side handle of the symbol).
+constexpr uint64_t kStaticScanItems = 1ull << 22;
+constexpr uint64_t kStaticScanWords = kStaticScanItems / kScanBlock + 1;
+static __device__ __align__(256) uint64_t scratch[kStaticScanWords];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+uint64_t *scratch_of_device[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (null on failure)
+uint64_t *static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_of_device[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        scratch_of_device[dev] = static_cast<uint64_t *>(ptr);
+    }
+    return scratch_of_device[dev];
 }
 
 // one wave per (query, table): copies the bucket's ids to the output run of that item
 __global__ void candidates_kernel(const uint32_t *__restrict__ sorted_ids, uint64_t N, uint32_t L,
                                   const uint32_t *__restrict__ start, const uint32_t *__restrict__ count,
                                   const uint64_t *__restrict__ offsets, uint64_t items, uint32_t *__restrict__ out) {
-    const uint64_t item = (blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6;
-    if (item >= items) return;
-    const uint32_t lane = threadIdx.x & 63, l = (uint32_t)(item % L);
-    const uint32_t *src = sorted_ids + (uint64_t)l * N + start[item];
-    uint32_t *dst = out + offsets[item];
-    for (uint32_t i = lane; i < count[item]; i += 64) dst[i] = src[i];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    for (uint64_t item = (blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6; item < items; item += waves) {
+        const uint32_t l = (uint32_t)(item % L);
+        const uint32_t *src = sorted_ids + (uint64_t)l * N + start[item];
+        uint32_t *dst = out + offsets[item];
+        for (uint32_t i = lane; i < count[item]; i += 64) dst[i] = src[i];
+    }
 }
 
 // one workgroup per query: squared l2 distance of every candidate of its L buckets (a candidate
@@ -157,7 +274,7 @@ extern "C" {
 int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream, lsh_index_t **out) {
     if (!out) return LSH_ERR_INVALID_ARG;
     *out = nullptr;
-    if (!d_keys || !N || !L || N >= (1ull << 32)) return LSH_ERR_INVALID_ARG;
+    if (!d_keys || !N || !L || N >= (1ull << 31)) return LSH_ERR_INVALID_ARG;  // the sort counts in int
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
         (void)hipGetLastError();
@@ -207,8 +324,12 @@ int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream
 
 void lsh_index_destroy(lsh_index_t *ix) {
     if (!ix) return;
+    int prev = -1;  // the tables live on the device the index was built on
+    const bool switched = ix->device >= 0 && hipGetDevice(&prev) == hipSuccess && prev != ix->device &&
+                          hipSetDevice(ix->device) == hipSuccess;
     if (ix->d_keys) (void)hipFree(ix->d_keys);
     if (ix->d_ids) (void)hipFree(ix->d_ids);
+    if (switched) (void)hipSetDevice(prev);
     delete ix;
 }
 
@@ -236,27 +357,24 @@ int lsh_index_probe(const lsh_index_t *ix, const uint64_t *d_qkeys, uint64_t Q, 
 }
 
 int lsh_index_candidate_offsets(const uint32_t *d_count, uint64_t items, uint64_t *d_offsets, void *stream) {
-    if (!d_count || !d_offsets || items >= (1ull << 31)) return LSH_ERR_INVALID_ARG;
+    if (!d_offsets || (items && !d_count) || items >= (1ull << 31)) return LSH_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    uint64_t *wide = nullptr;
-    void *temp = nullptr;
-    size_t temp_bytes = 0;
+    uint64_t *partial = nullptr;
     int rc = LSH_OK;
-    if (hipMalloc(&wide, (items + 1) * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
-    if (rc == LSH_OK) {
-        hipLaunchKernelGGL(widen_counts, dim3((uint32_t)((items + 256) / 256)), dim3(256), 0, s, d_count, items, wide);
-        if (hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, wide, d_offsets, (int)(items + 1), s) != hipSuccess)
-            rc = LSH_ERR_HIP;
-    }
-    if (rc == LSH_OK && hipMalloc(&temp, temp_bytes ? temp_bytes : 1) != hipSuccess) rc = LSH_ERR_ALLOC;
-    if (rc == LSH_OK &&
-        hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, wide, d_offsets, (int)(items + 1), s) != hipSuccess)
-        rc = LSH_ERR_HIP;
+    if (hipMalloc(&partial, (items / kScanBlock + 1) * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK) rc = launch_offsets_scan(d_count, items, partial, d_offsets, s);
     if (rc == LSH_OK && hipStreamSynchronize(s) != hipSuccess) rc = LSH_ERR_HIP;
-    if (wide) (void)hipFree(wide);
-    if (temp) (void)hipFree(temp);
-    if (rc == LSH_OK && hipGetLastError() != hipSuccess) rc = LSH_ERR_HIP;
+    if (partial) (void)hipFree(partial);
+    if (rc != LSH_OK) (void)hipGetLastError();
     return rc;
+}
+
+int lsh_index_candidate_offsets_static(const uint32_t *d_count, uint64_t items, uint64_t *d_offsets, void *stream) {
+    if (!d_offsets || (items && !d_count)) return LSH_ERR_INVALID_ARG;
+    if (items > kStaticScanItems) return LSH_ERR_UNSUPPORTED;
+    uint64_t *partial = static_scratch();
+    if (!partial) return LSH_ERR_HIP;
+    return launch_offsets_scan(d_count, items, partial, d_offsets, reinterpret_cast<hipStream_t>(stream));
 }
 
 int lsh_index_candidates(const lsh_index_t *ix, const uint32_t *d_start, const uint32_t *d_count,
@@ -267,7 +385,8 @@ int lsh_index_candidates(const lsh_index_t *ix, const uint32_t *d_start, const u
     int rc = on_index_device(ix);
     if (rc != LSH_OK) return rc;
     const uint64_t items = Q * ix->L;
-    hipLaunchKernelGGL(candidates_kernel, dim3((uint32_t)((items * 64 + 255) / 256)), dim3(256), 0,
+    const uint64_t wanted = (items * 64 + 255) / 256;  // one wave per item, up to 2^20 workgroups
+    hipLaunchKernelGGL(candidates_kernel, dim3((uint32_t)(wanted < (1u << 20) ? wanted : (1u << 20))), dim3(256), 0,
                        reinterpret_cast<hipStream_t>(stream), ix->d_ids, ix->N, ix->L, d_start, d_count, d_offsets, items,
                        d_out);
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
