@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstring>
 #include <new>
 
 #include "lsh_internal.h"
@@ -17,7 +18,10 @@ void free_tables(lsh_params *p) {
     if (p->d_samples) (void)hipFree(p->d_samples);
     if (p->d_off) (void)hipFree(p->d_off);
     if (p->d_dense) (void)hipFree(p->d_dense);
-    if (p->d_chunk_info) (void)hipFree(p->d_chunk_info);
+    if (p->d_triples) (void)hipFree(p->d_triples);
+    if (p->d_list_len) (void)hipFree(p->d_list_len);
+    if (p->d_stream) (void)hipFree(p->d_stream);
+    p->d_triples = p->d_list_len = p->d_stream = nullptr;
     if (p->d_shared_coef) (void)hipFree(p->d_shared_coef);
     if (p->d_shared_sample_off) (void)hipFree(p->d_shared_sample_off);
     if (p->d_shared_offset) (void)hipFree(p->d_shared_offset);
@@ -29,7 +33,6 @@ void free_tables(lsh_params *p) {
     p->d_samples = nullptr;
     p->d_off = nullptr;
     p->d_dense = nullptr;
-    p->d_chunk_info = nullptr;
     if (prev >= 0 && prev != p->device) (void)hipSetDevice(prev);
     p->device = -1;
 }
@@ -65,48 +68,65 @@ int upload_tables(lsh_params *p) {
             hipMemcpy(p->d_off, off.data(), off.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
             rc = LSH_ERR_HIP;
 
-        if (rc == LSH_OK && p->plan.supported && p->plan.chunked) {
-            // per wave and coordinate range: [steps][64] entries in scheduled order, offsets
-            // relative to the range's first coordinate
+        if (rc == LSH_OK && p->plan.supported && p->plan.ranged) {
+            // one stream of list blocks per gathering wave, in the order the wave consumes them:
+            // range after range, within a range the wave's functions-per-lane sets one after the
+            // other.  A block is kRangeBlockTriples triples x 64 lanes x 16 bytes: three
+            // coefficients and three 10-bit slot numbers (coordinate minus the range's first).
             const SampledPlan &pl = p->plan;
-            const uint32_t slot_bytes = pl.sp * pl.rt * 4u;
-            const uint32_t waves = kpad / 64, real_waves = (p->k + 63) / 64;
-            std::vector<uint2> info((size_t)waves * pl.nchunks, make_uint2(0, 0));
-            std::vector<Sample> tab(p->order.size() ? p->order.size() : 1, Sample{pl.chunk * slot_bytes, 0.f});
-            size_t base = 0;
-            for (uint32_t w = 0; w < real_waves; ++w)
-                for (uint32_t q = 0; q < pl.nchunks; ++q) {
-                    const uint32_t steps = p->chunk_steps[(size_t)w * pl.nchunks + q];
-                    info[(size_t)w * pl.nchunks + q] = make_uint2((uint32_t)base, steps);
-                    for (uint32_t st = 0; st < steps; ++st)
-                        for (uint32_t l = 0; l < 64; ++l) {
-                            Sample &s = tab[base + (size_t)st * 64 + l];
-                            const uint32_t e = p->order[base + (size_t)st * 64 + l];
-                            const uint32_t j = w * 64 + l;
-                            if ((e & kPadSample) || j >= p->k) {
-                                const uint32_t want = e & ~kPadSample;
-                                for (uint32_t z = pl.chunk; z < pl.chunk + pl.classes; ++z)
-                                    if (z % pl.classes == want) s.lds_byte_offset = z * slot_bytes;
-                                s.coef = 0.f;
-                            } else {
-                                const uint32_t c = p->idx[(size_t)j * p->m + e];
-                                s.lds_byte_offset = (c - q * pl.chunk) * slot_bytes;
-                                s.coef = p->coef[(size_t)j * p->m + e];
-                            }
-                        }
-                    base += (size_t)steps * 64;
+            const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockTriples, fpt = pl.fpt;
+            const uint32_t real_sets = (p->k + 63) / 64, streams = pl.kblocks * CW;
+            std::vector<size_t> first_entry((size_t)real_sets * R);  // of each (set, range) in p->order
+            size_t at = 0;
+            for (uint32_t s = 0; s < real_sets; ++s)
+                for (uint32_t q = 0; q < R; ++q) {
+                    first_entry[(size_t)s * R + q] = at;
+                    at += (size_t)p->chunk_steps[(size_t)s * R + q] * 64;
                 }
-            if (hipMalloc(&p->d_samples, tab.size() * sizeof(Sample)) != hipSuccess) rc = LSH_ERR_ALLOC;
-            if (rc == LSH_OK && hipMemcpy(p->d_samples, tab.data(), tab.size() * sizeof(Sample),
-                                          hipMemcpyHostToDevice) != hipSuccess)
-                rc = LSH_ERR_HIP;
-            if (rc == LSH_OK && hipMalloc(&p->d_chunk_info, info.size() * sizeof(uint2)) != hipSuccess)
-                rc = LSH_ERR_ALLOC;
-            if (rc == LSH_OK && hipMemcpy(p->d_chunk_info, info.data(), info.size() * sizeof(uint2),
-                                          hipMemcpyHostToDevice) != hipSuccess)
-                rc = LSH_ERR_HIP;
+            std::vector<uint32_t> list_len((size_t)streams * R * fpt, 0);
+            std::vector<uint2> stream_info(streams, make_uint2(0, 0));
+            std::vector<uint32_t> words;
+            uint32_t blocks = 0;
+            for (uint32_t y = 0; y < pl.kblocks; ++y)
+                for (uint32_t cw = 0; cw < CW; ++cw) {
+                    const uint32_t start = blocks;
+                    for (uint32_t q = 0; q < R; ++q)
+                        for (uint32_t f = 0; f < fpt; ++f) {
+                            const uint32_t s = (y * fpt + f) * CW + cw;
+                            const uint32_t T = s < real_sets ? p->chunk_steps[(size_t)s * R + q] : 0;  // multiple of 3
+                            list_len[((size_t)(y * CW + cw) * R + q) * fpt + f] = T;
+                            const uint32_t nb = (T / 3 + U - 1) / U;
+                            words.resize((size_t)(blocks + nb) * U * 64 * 4, 0u);
+                            for (uint32_t e = 0; e < T; ++e)
+                                for (uint32_t l = 0; l < 64; ++l) {
+                                    const uint32_t ent = p->order[first_entry[(size_t)s * R + q] + (size_t)e * 64 + l];
+                                    const uint32_t j = s * 64 + l;
+                                    uint32_t slot;
+                                    float c = 0.f;
+                                    if ((ent & kPadSample) || j >= p->k) {
+                                        slot = (ent & ~kPadSample) % pl.classes;  // a slot of the wanted bank class
+                                    } else {
+                                        slot = p->idx[(size_t)j * p->m + ent] - q * pl.chunk;
+                                        c = p->coef[(size_t)j * p->m + ent];
+                                    }
+                                    uint32_t *t = &words[(((size_t)blocks * U + e / 3) * 64 + l) * 4];
+                                    std::memcpy(&t[e % 3], &c, 4);
+                                    t[3] |= slot << (10 * (e % 3));
+                                }
+                            blocks += nb;
+                        }
+                    stream_info[y * CW + cw] = make_uint2(start, blocks - start);
+                }
+            if (words.empty()) words.assign(4, 0u);
+            auto upload = [&](void **dst, const void *src, size_t bytes) {
+                if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
+                if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
+            };
+            upload(&p->d_triples, words.data(), words.size() * sizeof(uint32_t));
+            upload(&p->d_list_len, list_len.data(), list_len.size() * sizeof(uint32_t));
+            upload(&p->d_stream, stream_info.data(), stream_info.size() * sizeof(uint2));
         }
-        if (rc == LSH_OK && p->plan.supported && !p->plan.chunked) {
+        if (rc == LSH_OK && p->plan.supported && !p->plan.ranged) {
             // step-major [m_pad][kpad] in scheduled order; padding samples (and the lanes
             // beyond k) read a zero slot with coefficient 0
             const SampledPlan &pl = p->plan;
@@ -222,9 +242,9 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
             try {
                 const SampledPlan &pl = p->plan;
                 p->schedule_cost =
-                    pl.chunked ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 8, pl.group, pl.classes,
-                                                  p->chunk_steps, p->order)
-                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, pl.copies,
+                    pl.ranged ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 3, pl.group, pl.classes,
+                                                 p->chunk_steps, p->order)
+                              : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, pl.copies,
                                                   p->order);
             } catch (const std::bad_alloc &) {
                 rc = LSH_ERR_ALLOC;
@@ -304,7 +324,8 @@ int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *st
     const SampledPlan &pl = p->plan;
     if (!pl.supported) return LSH_ERR_UNSUPPORTED;
     uint32_t nsteps = pl.m_pad;
-    if (pl.chunked) {  // longest concatenation of a wave's per-range lists
+    const bool by_range = pl.ranged;
+    if (by_range) {  // longest concatenation of a wave's per-range lists
         nsteps = 0;
         for (uint32_t w = 0; w < (p->k + 63) / 64; ++w) {
             uint32_t total = 0;
@@ -317,7 +338,7 @@ int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *st
     if (classes) *classes = pl.classes;
     if (modelled_passes) *modelled_passes = p->schedule_cost;
     if (!order) return LSH_OK;
-    if (!pl.chunked) {
+    if (!by_range) {
         std::copy(p->order.begin(), p->order.end(), order);
         return LSH_OK;
     }

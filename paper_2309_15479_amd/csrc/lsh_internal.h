@@ -31,9 +31,9 @@ struct SampledPlan {
     uint32_t lds_bytes = 0;  // LDS bytes of one tile buffer (both copies when copies == 2)
     uint32_t copies = 1;     // 2: the tile is kept twice, the second copy with rotated bank classes
     bool reg_table = false;  // register-list kernel: (offset, coef) lists live in VGPRs
-    bool chunked = false;    // chunked kernel: lists bucketed by coordinate range
-    uint32_t chunk = 0, nchunks = 0;  // chunked kernel: coordinates per range, number of ranges
-    uint32_t fpt = 1;        // chunked kernel: functions per lane
+    bool ranged = false;     // ranged kernel (ranged_kernel.hip): lists bucketed by 1024-coordinate range, packed triples
+    uint32_t chunk = 0, nchunks = 0;  // ranged kernel: coordinates per range, number of ranges
+    uint32_t fpt = 1;        // ranged kernel: functions per lane
     uint32_t prefetch = 0;   // register-list kernel: 64-coordinate chunks fetched per wave and tile
     bool supported = false;
 };
@@ -83,9 +83,10 @@ struct lsh_params {
     lsh::SampledPlan plan;
     std::vector<uint32_t> order;       // [k][m_pad] visiting order of each function's samples
     uint64_t schedule_cost = 0;        // modelled LDS passes (see schedule.cpp)
-    std::vector<uint32_t> chunk_steps; // chunked plan: [waves][nchunks] list length
-    lsh::Sample *d_samples = nullptr;  // flat: [m_pad][kpad] step-major; chunked: per wave and range, [steps][64]
-    void *d_chunk_info = nullptr;      // chunked plan: uint2 {first entry, steps} [kpad/64][nchunks]
+    std::vector<uint32_t> chunk_steps; // ranged plan: [sets of 64 functions][nchunks] list length
+    lsh::Sample *d_samples = nullptr;  // flat plans: [m_pad][kpad] step-major
+    // ranged plan: packed list blocks, list lengths [stream][range][fpt], streams {first block, blocks}
+    void *d_triples = nullptr, *d_list_len = nullptr, *d_stream = nullptr;
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n]: row j = a_j written out over all n coordinates; m == n or n == 128, else null
     uint32_t kpad_dense = 0;
@@ -124,6 +125,12 @@ void free_tables(lsh_params *p);
 enum class Epilogue : int { Ids = 0, Proj = 1, Signs = 2, Keys = 3 };
 int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                    uint32_t L, void *stream);
+// ranged kernel (ranged_kernel.hip): geometry constants the host tables are built for
+constexpr uint32_t kRangeCoords = 1024;      // coordinates per range (one LDS buffer holds 16 vectors of them)
+constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather (the others load tiles)
+constexpr uint32_t kRangeBlockTriples = 4;   // packed triples per lane in one list block
+int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
+                  uint32_t L, void *stream);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
                          std::vector<float> &offset, std::vector<float> &extra);

@@ -20,312 +20,23 @@
 // they can to the matrix pipe, the scalar ALU and single instructions (see finish()).  The
 // lists are stored step-major ([step][function]) so that a wave reads them coalesced.
 //
-// Three kernels: sampled_reg_kernel keeps lists of up to 64 samples in registers for the whole
-// launch (small n); sampled_kernel streams longer lists through registers for every
-// full-dimension tile; sampled_chunked_kernel cuts large vectors into coordinate ranges that
-// fill LDS and walks per-range lists.
+// Two kernels here: sampled_reg_kernel keeps lists of up to 64 samples in registers for the
+// whole launch (small n); sampled_kernel streams longer lists through registers for every
+// full-dimension tile.  Large vectors are cut into coordinate ranges by the kernel of
+// ranged_kernel.hip.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
 #include <type_traits>
 #include <unordered_map>
 
-#include "device_utils.h"
-#include "lsh_internal.h"
+#include "sampled_common.h"
 
 namespace lsh {
 namespace {
 
 constexpr int kChunk = 32;                     // samples held in registers at a time
 constexpr uint32_t kLdsBudget = 158u * 1024u;  // of the CU's 160 KB
-// chunked kernel: 64-coordinate pieces of the next chunk a wave prefetches into registers
-// (6 x 16 waves cover the 1376 coordinates x 4 sub-tiles that fill LDS)
-constexpr int kChunkPre = 6;
-
-template <int RT>
-__device__ __forceinline__ void lds_read_slot(const char *slot, float (&x)[RT]) {
-    if constexpr (RT == 4) {
-        const float4 q = *reinterpret_cast<const float4 *>(slot);
-        x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
-    } else if constexpr (RT == 2) {
-        const float2 q = *reinterpret_cast<const float2 *>(slot);
-        x[0] = q.x; x[1] = q.y;
-    } else {
-        x[0] = *reinterpret_cast<const float *>(slot);
-    }
-}
-
-template <int RT>
-__device__ __forceinline__ void lds_write_slot(float *slot, const float (&x)[RT]) {
-    if constexpr (RT == 4) {
-        *reinterpret_cast<float4 *>(slot) = make_float4(x[0], x[1], x[2], x[3]);
-    } else if constexpr (RT == 2) {
-        *reinterpret_cast<float2 *>(slot) = make_float2(x[0], x[1]);
-    } else {
-        *slot = x[0];
-    }
-}
-
-// Empty volatile asm through which four accumulators flow: it emits nothing, but the FMAs
-// that produce its inputs cannot be sunk below it (nor the next ones hoisted above), which
-// keeps them inside the scheduling region they were written in.
-__device__ __forceinline__ void pin(float (&v)[4]) {
-    asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
-}
-
-// Returns v through an empty asm: the compiler can no longer treat values derived from it as
-// loop invariants, so it recomputes cheap per-lane addresses where they are used instead of
-// keeping dozens of them (and spilling) across the gather loops.
-__device__ __forceinline__ uint32_t fresh(uint32_t v) {
-    asm volatile("" : "+v"(v));
-    return v;
-}
-
-struct SampledArgs {
-    const float *data;   // [N][n]
-    uint64_t N;
-    uint32_t n, k, m_pad, kpad, classes;
-    const Sample *tab;   // [m_pad][kpad]
-    const float *off;    // [kpad]
-    float w, inv_w;
-    int w_is_pow2;
-    int epilogue;        // Epilogue
-    void *out;
-    uint32_t L, g;       // key groups (Epilogue::Keys)
-    // register-list kernel only: floats per tile buffer; float offset of the second,
-    // class-rotated tile copy inside a buffer (0: single copy)
-    uint32_t buf_floats, copy_b_floats;
-    // chunked kernel only
-    uint32_t chunk, nchunks;     // coordinates per LDS chunk, number of chunks
-    const uint2 *chunk_info;     // [waves][nchunks] {first table entry, steps}
-};
-
-// The LDS slot (one coordinate of four vectors) that lane `lane` of a wave contributes to a
-// 64-coordinate piece: coordinate c_first + lane of vectors row_first .. row_first + 3.
-// With n a multiple of 4 each lane loads 16 contiguous bytes instead of four separate
-// words (coordinates c_first + 4*(lane/4) .. + 3 of vector row_first + lane % 4: a quad of
-// lanes covers 4 vectors x 4 coordinates, a wave reads 256 contiguous bytes of each vector):
-// a quarter of the vector-memory instructions.  The registers then hold the transpose of
-// the slot; slot_from_raw() turns them into the slot just before it is written to LDS.
-// `limit` bounds the coordinates of the piece (exclusive); it is a multiple of 4 when vec4.
-template <bool vec4>
-__device__ __forceinline__ void load_raw(const float *__restrict__ tile_rows, uint32_t rows_valid, uint32_t n,
-                                         uint32_t row_first, uint32_t c_first, uint32_t limit, uint32_t lane,
-                                         float (&x)[4]) {
-    // tile_rows = first vector of the tile (wave-uniform pointer); rows and coordinates are
-    // 32-bit offsets from it.  Rows past the end of the data and coordinates past `limit`
-    // read element 0 of the tile instead (always valid memory): their values are never used.
-    if (vec4) {
-        const uint32_t row = row_first + (lane & 3);
-        const uint32_t c = c_first + (lane & ~3u);
-        const uint32_t off = (c < limit && row < rows_valid) ? row * n + c : 0u;
-        // a tile is read once: non-temporal, which leaves L2 to the sample lists (2 % at n = 4096,
-        // m = 64; nothing elsewhere)
-        typedef float floatx4 __attribute__((ext_vector_type(4)));
-        const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(tile_rows + off));
-        x[0] = q[0]; x[1] = q[1]; x[2] = q[2]; x[3] = q[3];
-    } else {
-        const uint32_t c = c_first + lane;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t off = (c < limit && row_first + r < rows_valid) ? (row_first + r) * n + c : 0u;
-            x[r] = __builtin_nontemporal_load(tile_rows + off);
-        }
-    }
-}
-
-template <bool vec4>
-__device__ __forceinline__ void slot_from_raw(float (&x)[4]) {
-    if (vec4) {
-        uint32_t v[4] = {__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
-        quad_transpose(v);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) x[r] = __uint_as_float(v[r]);
-    }
-}
-
-// Sum of a 64-bit value over each aligned group of g consecutive lanes (g a power of two
-// <= 64); every lane of the group gets the sum.  Steps inside a row of 16 lanes are DPP moves
-// (quad permutes, half-row and row mirrors: no LDS traffic, the resource the gather is short
-// of); only the steps across rows use the LDS crossbar.
-template <int CTRL>
-__device__ __forceinline__ uint64_t dpp_u64(uint64_t v) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)v, CTRL, 0xf, 0xf, true);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(v >> 32), CTRL, 0xf, 0xf, true);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-__device__ __forceinline__ uint64_t group_sum(uint64_t v, uint32_t g) {
-    if (g >= 2) v += dpp_u64<0xB1>(v);    // quad_perm [1,0,3,2]
-    if (g >= 4) v += dpp_u64<0x4E>(v);    // quad_perm [2,3,0,1]
-    if (g >= 8) v += dpp_u64<0x141>(v);   // row_half_mirror: the other quad of the half row
-    if (g >= 16) v += dpp_u64<0x140>(v);  // row_mirror: the other half of the row
-    if (g >= 32) v += __shfl_xor(v, 16);
-    if (g >= 64) v += __shfl_xor(v, 32);
-    return v;
-}
-
-// The same transpose for fp32 values, on the matrix pipe instead of the vector ALU (which is
-// what bounds the sampled kernels): the 4x4x1 MFMA computes, in every quad of lanes,
-// D[i][u] += A[i] * B[u] with A[i], B[u] taken from lanes i, u of the quad and D[i][u] landing in
-// register i of lane u.  Four of them, with A = x[t] and B = [u == t], leave x[u] of lane i in
-// register i of lane u.  Multiplying by 1 and adding zeros is exact for finite values;
-// callers clamp first, so that a non-finite value cannot leak into its quad neighbours.
-typedef float float4v __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void quad_transpose_mfma(float (&x)[4], const float (&unit)[4]) {
-    float4v d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int t = 0; t < 4; ++t) d = __builtin_amdgcn_mfma_f32_4x4x1f32(x[t], unit[t], d, 0, 0, 0);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) x[t] = d[t];
-}
-
-// v_writelane_b32 as a compiler intrinsic (this compiler has no builtin of that name); written
-// as inline assembly instead it would miss the wait states the hardware needs between a
-// vector compare that writes the scalar value and the lane write that reads it.
-extern "C" __device__ int write_lane(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
-
-// One tile's results of one lane: acc[s][r] belongs to vector row0 + s*RT + r.  A vector
-// memory instruction costs the memory pipeline about the same whether a lane moves 4 or 16
-// bytes, and this kernel issues one store per (wave, vector): so with 4-vector slots the ids
-// of a quad of lanes are transposed in registers first and leave as 16-byte stores (four
-// consecutive functions of one vector per lane), and sign words leave one store per tile.
-// For a power-of-two w, (p + b) / w is computed as fma(p, 1/w, b/w): scaling by a power of two
-// commutes with the rounding of the sum, so the result is the same float.
-// FULL: every vector of the tile exists; the stores then go to a wave-uniform base (scalar
-// arithmetic) plus the per-lane byte offset full_off the caller keeps in a register:
-// ((lane % 4) * k + (j & ~3)) * 4 for ids, (lane % 64 * ceil(k / 64) + j / 64) * 8 for sign words.
-template <int RT, int SUB, int EP, bool FULL = false>
-__device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint32_t j,
-                                       const float (&acc)[SUB][RT], float b, uint64_t key_pow,
-                                       uint32_t full_off = 0) {
-    const bool live = j < a.k;
-    switch (EP) {
-        case (int)Epilogue::Ids:
-        case (int)Epilogue::Proj: {
-            constexpr bool ids = EP == (int)Epilogue::Ids;
-            uint32_t *out = reinterpret_cast<uint32_t *>(a.out);
-            const bool wide = RT == 4 && (a.k & 3) == 0;
-            const float b_scaled = b * a.inv_w;
-            float unit[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) unit[t] = (threadIdx.x & 3) == (uint32_t)t ? 1.f : 0.f;
-#pragma unroll
-            for (int s = 0; s < SUB; ++s) {
-                float q[RT];
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const float p = acc[s][r];
-                    q[r] = !ids ? p : a.w_is_pow2 ? fmaf(p, a.inv_w, b_scaled) : (p + b) / a.w;
-                }
-                if constexpr (RT == 4) {
-                    if (wide) {  // uniform
-                        // beyond +-2^31 the conversion saturates anyway
-                        const float bound = ids ? 2147483648.f : 3.4028234664e38f;
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) q[r] = __builtin_amdgcn_fmed3f(q[r], -bound, bound);
-                        quad_transpose_mfma(q, unit);
-                        const uint64_t row = row0 + s * RT + (threadIdx.x & 3);
-                        const uint32_t j4 = j & ~3u;
-                        uint32_t v[4];
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) v[r] = ids ? (uint32_t)(int)floorf(q[r]) : __float_as_uint(q[r]);
-                        if constexpr (FULL) {
-                            char *base = reinterpret_cast<char *>(out + (row0 + s * RT) * a.k);  // uniform
-                            if (j4 < a.k) *reinterpret_cast<uint4 *>(base + full_off) = make_uint4(v[0], v[1], v[2], v[3]);
-                        } else if (j4 < a.k && row < a.N) {
-                            *reinterpret_cast<uint4 *>(out + row * a.k + j4) = make_uint4(v[0], v[1], v[2], v[3]);
-                        }
-                        continue;
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const uint64_t row = row0 + s * RT + r;
-                    if (live && row < a.N) out[row * a.k + j] = ids ? (uint32_t)(int)floorf(q[r]) : __float_as_uint(q[r]);
-                }
-            }
-            break;
-        }
-        case (int)Epilogue::Signs: {
-            uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
-            const uint32_t words = (a.k + 63) / 64;
-            const uint32_t lane = threadIdx.x & 63;
-            uint32_t lo = 0, hi = 0;  // lane v of the wave keeps the word of the tile's vector v
-#pragma unroll
-            for (int s = 0; s < SUB; ++s)
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const uint64_t word = __ballot(live && acc[s][r] >= 0.f);  // whole waves get here
-                    // the wave-uniform word goes into lane s * RT + r only
-                    lo = (uint32_t)write_lane((int)(uint32_t)word, s * RT + r, (int)lo);
-                    hi = (uint32_t)write_lane((int)(uint32_t)(word >> 32), s * RT + r, (int)hi);
-                }
-            const uint64_t mine = ((uint64_t)hi << 32) | lo;
-            const uint64_t row = row0 + lane;
-            if constexpr (FULL) {
-                char *base = reinterpret_cast<char *>(out + row0 * words);  // uniform
-                if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k) *reinterpret_cast<uint64_t *>(base + full_off) = mine;
-            } else if (lane < (uint32_t)(SUB * RT) && (j & ~63u) < a.k && row < a.N) {
-                out[row * words + (j >> 6)] = mine;
-            }
-            break;
-        }
-        default: {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64
-            uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
-            if constexpr (RT == 4) {
-                if (a.g >= 4) {  // uniform
-                    // As for ids, the quads are transposed first: a lane then holds the ids of the
-                    // quad's four consecutive functions for ONE vector, folds them by Horner's rule
-                    // (three multiplications by C and one by its power of C, instead of one 64-bit
-                    // multiplication per id and vector), and only the g / 4 partials of a vector are
-                    // left to add across lanes: those of the lanes i, i + 4, i + 8, ... of the key
-                    // group, by DPP shifts inside a row of 16 lanes and exchanges across rows.
-                    // (for g >= 4 the kernels pass key_pow = C^(g-1-(t|3)), the power of the quad's last function)
-                    // everything per lane is derived from j, which the register-list kernels pass
-                    // through an empty asm every tile: derived from threadIdx.x it would be hoisted
-                    // out of the tile loop and held in registers across the gather
-                    const uint32_t g_log2 = 31 - __builtin_clz(a.g), t = j & (a.g - 1), u_mine = j & 3;  // workgroup sizes are multiples of 4
-                    float unit[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) unit[u] = u_mine == (uint32_t)u ? 1.f : 0.f;
-                    const float b_scaled = b * a.inv_w;
-#pragma unroll
-                    for (int s = 0; s < SUB; ++s) {
-                        float q[RT];
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) {
-                            const float v = a.w_is_pow2 ? fmaf(acc[s][r], a.inv_w, b_scaled) : (acc[s][r] + b) / a.w;
-                            q[r] = __builtin_amdgcn_fmed3f(v, -2147483648.f, 2147483648.f);
-                        }
-                        quad_transpose_mfma(q, unit);
-                        uint64_t part = (uint32_t)(int)floorf(q[0]);
-                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[1]);
-                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[2]);
-                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[3]);
-                        part *= key_pow;
-                        if (a.g >= 8) part += dpp_u64<0x104>(part);   // row_shl:4: lane i takes lane i + 4 (0 past the row)
-                        if (a.g >= 16) part += dpp_u64<0x108>(part);  // row_shl:8
-                        if (a.g >= 32) part += __shfl_down(part, 16);
-                        if (a.g >= 64) part += __shfl_down(part, 32);
-                        const uint64_t row = row0 + s * RT + u_mine;
-                        if (live && row < a.N && t < 4) out[row * a.L + (j >> g_log2)] = part;
-                    }
-                    break;
-                }
-            }
-#pragma unroll
-            for (int s = 0; s < SUB; ++s)
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const uint64_t row = row0 + s * RT + r;
-                    const float q = a.w_is_pow2 ? (acc[s][r] + b) * a.inv_w : (acc[s][r] + b) / a.w;
-                    const uint64_t key = group_sum((uint64_t)(uint32_t)(int)floorf(q) * key_pow, a.g);
-                    if (live && row < a.N && (j % a.g) == 0) out[row * a.L + j / a.g] = key;
-                }
-        }
-    }
-}
 
 // Streamed-list kernel: every tile, each lane streams its (offset, coefficient) list through
 // registers one chunk at a time and applies the chunk to all SUB sub-tiles.
@@ -588,142 +299,6 @@ __global__ __launch_bounds__(512, MCH == 1 ? 4 : 2) void sampled_reg_kernel(cons
     }
 }
 
-// Chunked kernel for large n (or long lists at large n): the tile holds 4*SUB vectors times a
-// range of `chunk` coordinates (one workgroup per CU with nearly all of its LDS), so that enough vectors share one pass over the lists to keep
-// list traffic (L2 -> registers) well below the LDS gather traffic.  Every function's samples
-// are bucketed by coordinate range on the host; the 64 lists of a wave for one range are
-// padded to a common length (wave-uniform trip count) and bank-scheduled like the flat lists.
-// Accumulators persist across the ranges of a tile.
-template <int SUB, int FPT, int EP>
-__global__ __launch_bounds__(1024) void sampled_chunked_kernel(const SampledArgs a) {
-    constexpr int RT = 4;
-    constexpr int kStep = 8;   // list entries fetched at a time; list lengths are multiples of it
-    constexpr int kPre = kChunkPre;  // 64-coordinate pieces of the next chunk a wave holds in registers
-    extern __shared__ __align__(16) float tile[];  // [chunk + classes][SP][RT]
-    constexpr uint32_t SP = SUB == 1 ? 1 : SUB + 1;
-    constexpr uint32_t kTileRows = RT * SUB;
-    const uint32_t n = a.n;
-    // a lane owns FPT functions, blockDim.x apart: j0 + f * blockDim.x
-    const uint32_t j0 = blockIdx.y * blockDim.x * FPT + threadIdx.x;
-    const uint64_t ntiles = (a.N + kTileRows - 1) / kTileRows;
-    float b[FPT];
-    uint64_t key_pow[FPT];
-#pragma unroll
-    for (int f = 0; f < FPT; ++f) {
-        const uint32_t j = j0 + f * blockDim.x;  // < kpad
-        b[f] = a.off[j];
-        key_pow[f] = 1;
-        if (EP == (int)Epilogue::Keys) {
-            uint32_t t = j % a.g;
-            if (RT == 4 && a.g >= 4) t |= 3;  // the transposed fold multiplies by the power of the quad's last function
-            for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow[f] *= kKeyMultiplier;
-        }
-    }
-
-    for (uint32_t e = threadIdx.x; e < a.classes * SP * RT; e += blockDim.x)
-        tile[(size_t)a.chunk * SP * RT + e] = 0.f;
-
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t nwaves = blockDim.x >> 6;
-    const uint32_t wave_global = __builtin_amdgcn_readfirstlane(j0 >> 6);
-    const uint32_t pieces = SUB * ((a.chunk + 63) / 64);  // 64-coordinate pieces of one chunk (<= kPre * nwaves)
-    const bool vec4 = (n & 3) == 0;
-    const char *base = reinterpret_cast<const char *>(tile);
-
-    // The next chunk (of this tile, or the first of the next tile) travels HBM -> registers
-    // while the current one is gathered from LDS, and is written to LDS between two barriers.
-    float pre[kPre][RT];
-    auto fetch_as = [&](uint64_t row0, uint32_t q, auto vec) {
-        constexpr bool V = decltype(vec)::value;
-        const uint32_t c0 = q * a.chunk;
-        const float *rows = a.data + row0 * n;
-        const uint32_t rows_valid = (uint32_t)min((uint64_t)kTileRows, a.N - row0);
-        const uint32_t end = c0 + a.chunk < n ? c0 + a.chunk : n;  // chunk % 16 == 0
-        const uint32_t ln = fresh(lane);
-#pragma unroll
-        for (int f = 0; f < kPre; ++f) {
-            const uint32_t pc = wave + f * nwaves;
-            load_raw<V>(rows, rows_valid, n, (pc % SUB) * RT, c0 + (pc / SUB) * 64, pc < pieces ? end : 0, ln,
-                        pre[f]);
-        }
-    };
-    auto stash_as = [&](auto vec) {
-        constexpr bool V = decltype(vec)::value;
-        const uint32_t ln = fresh(lane);
-#pragma unroll
-        for (int f = 0; f < kPre; ++f) {
-            const uint32_t pc = wave + f * nwaves;
-            const uint32_t st = pc % SUB, cc = (pc / SUB) * 64 + ln;
-            slot_from_raw<V>(pre[f]);
-            if (pc < pieces && cc < a.chunk) lds_write_slot<RT>(tile + ((size_t)cc * SP + st) * RT, pre[f]);
-        }
-    };
-    auto fetch = [&](uint64_t row0, uint32_t q) {
-        if (vec4) fetch_as(row0, q, std::true_type{});
-        else fetch_as(row0, q, std::false_type{});
-    };
-    auto stash = [&]() {
-        if (vec4) stash_as(std::true_type{});
-        else stash_as(std::false_type{});
-    };
-
-    uint64_t t = blockIdx.x;
-    if (t >= ntiles) return;
-    fetch(t * kTileRows, 0);
-    stash();
-    __syncthreads();
-    for (; t < ntiles; t += gridDim.x) {
-        const uint64_t row0 = t * kTileRows;
-        float acc[FPT][SUB][RT];
-#pragma unroll
-        for (int f = 0; f < FPT; ++f)
-#pragma unroll
-            for (int st = 0; st < SUB; ++st)
-#pragma unroll
-                for (int r = 0; r < RT; ++r) acc[f][st][r] = 0.f;
-
-        for (uint32_t q = 0; q < a.nchunks; ++q) {
-            const bool last = q + 1 == a.nchunks;
-            const uint64_t t_next = t + gridDim.x;
-            const bool more = !last || t_next < ntiles;
-            if (more) fetch((last ? t_next : t) * kTileRows, last ? 0 : q + 1);
-
-#pragma unroll
-            for (int f = 0; f < FPT; ++f) {
-                const uint2 info = a.chunk_info[(size_t)(wave_global + f * nwaves) * a.nchunks + q];
-                const Sample *list = a.tab + info.x + lane;
-                for (uint32_t s0 = 0; s0 < info.y; s0 += kStep) {
-                    Sample e[kStep];
-#pragma unroll
-                    for (int i = 0; i < kStep; ++i) e[i] = list[(size_t)(s0 + i) * 64];
-#pragma unroll
-                    for (int i = 0; i < kStep; ++i) {
-                        __builtin_amdgcn_sched_barrier(0);
-                        float4 x[SUB];
-#pragma unroll
-                        for (int st = 0; st < SUB; ++st)
-                            x[st] = *reinterpret_cast<const float4 *>(base + e[i].lds_byte_offset + st * 16);
-#pragma unroll
-                        for (int st = 0; st < SUB; ++st) {
-                            acc[f][st][0] = fmaf(e[i].coef, x[st].x, acc[f][st][0]);
-                            acc[f][st][1] = fmaf(e[i].coef, x[st].y, acc[f][st][1]);
-                            acc[f][st][2] = fmaf(e[i].coef, x[st].z, acc[f][st][2]);
-                            acc[f][st][3] = fmaf(e[i].coef, x[st].w, acc[f][st][3]);
-                            pin(acc[f][st]);
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                if (last) finish<RT, SUB, EP>(a, row0, fresh(j0) + f * blockDim.x, acc[f], b[f], key_pow[f]);
-            }
-            __syncthreads();  // every lane is done reading this chunk
-            if (more) stash();
-            __syncthreads();
-        }
-    }
-}
-
 template <typename Kernel>
 int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 grid, dim3 block,
                   hipStream_t stream) {
@@ -764,18 +339,17 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
     };
     // 16-byte reads: 16 lanes per pass over 16 classes; 8-byte: 32 lanes over 32; 4-byte:
     // 32 lanes over 64 banks
-    if (!(fits(4, 8, 16) || fits(4, 4, 16) || fits(4, 2, 16) || fits(4, 1, 16) || fits(2, 1, 32) ||
-          fits(1, 1, 64)))
-        return pl;  // unsupported: one vector does not fit in LDS
-    pl.m_pad = (m + kChunk - 1) / kChunk * kChunk;
     const uint32_t k64 = (k + 63) / 64 * 64;
+    const bool whole_vector_fits = fits(4, 8, 16) || fits(4, 4, 16) || fits(4, 2, 16) || fits(4, 1, 16) ||
+                                   fits(2, 1, 32) || fits(1, 1, 64);
+    pl.m_pad = (m + kChunk - 1) / kChunk * kChunk;
     // Register-list kernel: lists of at most two chunks, 16-byte slots, two tile buffers in LDS.
     // The kernel is bound by vector-ALU issue (a 64-lane FMA takes a SIMD four cycles), so the
     // tile is the largest whose accumulators and in-flight reads still fit the 128 registers of
     // a lane (16 vectors): the per-sample address arithmetic and the per-tile load and barrier
     // code are then shared by the most FMAs.  Only while a tile stays small (at most 2 prefetch
     // pieces per wave): with large n one tile's gather is shorter than the latency of the next
-    // tile's loads, and the chunked kernel, which shares a bigger tile among more functions, wins.
+    // tile's loads, and the ranged kernel, which shares a bigger tile among more functions, wins.
     pl.reg_table = false;
     if (pl.m_pad <= 2u * kChunk && pl.rt == 4) {
         const uint32_t block = k64 >= 512 ? 512 : k64;
@@ -800,32 +374,32 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
             break;
         }
     }
-    // Chunked kernel: when a full-dimension tile would hold fewer than 16 vectors and the lists
-    // do not stay in registers.  16 vectors x `chunk` coordinates, two workgroups per CU.
-    pl.chunked = false;
-    if (!pl.reg_table && (pl.rt != 4 || pl.sub < 4) && k64 >= 512) {  // enough waves to prefetch a chunk
-        const uint32_t slot = 5 * 16;  // SUB = 4: 5 slots of 16 bytes per coordinate
-        const uint32_t block = k64 >= 1024 ? 1024 : k64;
-        // the chunk must fit in LDS and its pieces in the waves' prefetch registers (kChunkPre pieces
-        // of 64 coordinates x 4 sub-tiles per wave)
-        uint32_t cmax = (kLdsBudget / slot - 16) / 16 * 16;
-        const uint32_t by_regs = (uint32_t)kChunkPre * (block / 64) / 4 * 64;
-        if (cmax > by_regs) cmax = by_regs;
-        pl.nchunks = (n + cmax - 1) / cmax;
-        pl.chunk = ((n + pl.nchunks - 1) / pl.nchunks + 15) / 16 * 16;
-        pl.nchunks = (n + pl.chunk - 1) / pl.chunk;
-        pl.rt = 4; pl.sub = 4; pl.sp = 5; pl.classes = 16; pl.group = 16;
-        pl.lds_bytes = (pl.chunk + 16) * slot;
-        pl.chunked = true;
-        // with more than 1024 functions a lane takes two (1024 apart), so that a chunk is
-        // loaded once for 2048 functions
-        pl.fpt = k64 > 1024 ? 2 : 1;
+    // Ranged kernel (ranged_kernel.hip): when a full-dimension tile would hold fewer than 16
+    // vectors (or none) and the lists do not stay in registers, given enough functions for its 8
+    // gathering waves.  A lane owns up to 4 functions (sets of 64 functions, 8 sets apart).
+    pl.ranged = false;
+    if (!pl.reg_table && (!whole_vector_fits || pl.rt != 4 || pl.sub < 4) && k64 >= 64 * kRangeComputeWaves) {
+        const uint32_t nsets = k64 / 64;
+        const uint32_t per_wg_max = kRangeComputeWaves * 4;
+        pl.kblocks = (nsets + per_wg_max - 1) / per_wg_max;
+        const uint32_t per_wg = (nsets + pl.kblocks - 1) / pl.kblocks;
+        pl.fpt = (per_wg + kRangeComputeWaves - 1) / kRangeComputeWaves;
+        pl.kpad = pl.kblocks * kRangeComputeWaves * pl.fpt * 64;
+        pl.block = 64 * kRangeComputeWaves;
+        pl.chunk = kRangeCoords;
+        pl.nchunks = (n + kRangeCoords - 1) / kRangeCoords;
+        pl.rt = 4; pl.sub = 4; pl.sp = 4; pl.classes = 16; pl.group = 16;
+        pl.lds_bytes = 2 * 4 * kRangeCoords * 16;
+        pl.copies = 1;
+        pl.ranged = true;
+        pl.supported = true;
+        return pl;
     }
+    if (!whole_vector_fits) return pl;  // unsupported: too few functions for the ranged kernel
     const uint32_t max_block = pl.reg_table ? 512 : 1024;
     pl.block = k64 >= max_block ? max_block : k64;
-    const uint32_t per_wg = pl.block * (pl.chunked ? pl.fpt : 1);
-    pl.kblocks = (k64 + per_wg - 1) / per_wg;
-    pl.kpad = per_wg * pl.kblocks;
+    pl.kblocks = (k64 + pl.block - 1) / pl.block;
+    pl.kpad = pl.block * pl.kblocks;
     pl.supported = true;
     return pl;
 }
@@ -834,7 +408,8 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
                    uint32_t L, void *stream) {
     const SampledPlan &pl = p->plan;
     if (!pl.supported) return LSH_ERR_UNSUPPORTED;
-    SampledArgs a;
+    if (pl.ranged) return launch_ranged(p, ep, d_data, N, d_out, L, stream);
+    SampledArgs a = {};
     a.data = d_data;
     a.N = N;
     a.n = p->n;
@@ -854,9 +429,6 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     a.g = L ? p->k / L : 1;
     a.buf_floats = pl.lds_bytes / 4;
     a.copy_b_floats = pl.copies == 2 ? (p->n + pl.classes) * pl.sp * pl.rt : 0;
-    a.chunk = pl.chunk;
-    a.nchunks = pl.nchunks;
-    a.chunk_info = static_cast<const uint2 *>(p->d_chunk_info);
     const uint64_t tile_rows = (uint64_t)pl.rt * pl.sub;
     const uint64_t ntiles = (N + tile_rows - 1) / tile_rows;
     // persistent workgroups: as many per CU as LDS and waves allow (at most 2048 lanes), count
@@ -925,8 +497,6 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
         return LSH_ERR_UNSUPPORTED;
     }
 #define LSH_GEN_ALL(EP_) \
-    if (pl.chunked && pl.fpt == 2) return launch_kernel(&sampled_chunked_kernel<4, 2, EP_>, lds_bytes, a, grid, block, s); \
-    if (pl.chunked) return launch_kernel(&sampled_chunked_kernel<4, 1, EP_>, lds_bytes, a, grid, block, s); \
     if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8, EP_>, lds_bytes, a, grid, block, s); \
     if (pl.rt == 4 && pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4, EP_>, lds_bytes, a, grid, block, s); \
     if (pl.rt == 4 && pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2, EP_>, lds_bytes, a, grid, block, s); \
