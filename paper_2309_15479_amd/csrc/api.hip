@@ -18,6 +18,8 @@ void free_tables(lsh_params *p) {
     if (p->d_samples) (void)hipFree(p->d_samples);
     if (p->d_off) (void)hipFree(p->d_off);
     if (p->d_dense) (void)hipFree(p->d_dense);
+    if (p->d_dense_planes) (void)hipFree(p->d_dense_planes);
+    p->d_dense_planes = nullptr;
     if (p->d_triples) (void)hipFree(p->d_triples);
     if (p->d_list_len) (void)hipFree(p->d_list_len);
     if (p->d_stream) (void)hipFree(p->d_stream);
@@ -57,7 +59,11 @@ int upload_tables(lsh_params *p) {
     p->kpad_dense = 0;
     // n == 128: the matrix-core sign kernel takes any object's coefficients written out densely
     if (p->m == p->n || p->n == 128) p->kpad_dense = (p->k + dense_col_tile() - 1) / dense_col_tile() * dense_col_tile();
-    const uint32_t off_len = kpad > p->kpad_dense ? kpad : p->kpad_dense;
+    // the wide matrix-core kernel reads offsets up to its function tiles
+    const bool wide = p->m == p->n && p->n != 128 && p->n % 4 == 0;
+    const uint32_t kpad_wide = wide ? (p->k + dense_wide_row_tile() - 1) / dense_wide_row_tile() * dense_wide_row_tile() : 0;
+    uint32_t off_len = kpad > p->kpad_dense ? kpad : p->kpad_dense;
+    if (off_len < kpad_wide) off_len = kpad_wide;
 
     int rc = LSH_OK;
     try {
@@ -188,6 +194,16 @@ int upload_tables(lsh_params *p) {
             if (rc == LSH_OK && hipMemcpy(p->d_dense, dense.data(), dense.size() * sizeof(float),
                                           hipMemcpyHostToDevice) != hipSuccess)
                 rc = LSH_ERR_HIP;
+            if (rc == LSH_OK && wide) {
+                // the same matrix as exact three-way bf16 splits, for the wide matrix-core kernel
+                const uint32_t npad = (p->n + dense_wide_col_step() - 1) / dense_wide_col_step() * dense_wide_col_step();
+                std::vector<uint16_t> planes;
+                build_dense_planes(p->coef.data(), p->k, p->n, kpad_wide, npad, planes);
+                if (hipMalloc(&p->d_dense_planes, planes.size() * sizeof(uint16_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
+                if (rc == LSH_OK && hipMemcpy(p->d_dense_planes, planes.data(), planes.size() * sizeof(uint16_t),
+                                              hipMemcpyHostToDevice) != hipSuccess)
+                    rc = LSH_ERR_HIP;
+            }
         }
     } catch (const std::bad_alloc &) {
         rc = LSH_ERR_ALLOC;
@@ -453,6 +469,8 @@ int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32
     if (N == 0) return LSH_OK;
     if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
         return launch_dense_split(p, 0, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_wide_supported(p))
+        return launch_dense_wide(p, false, d_data, N, d_out, stream);
     return launch_dense(p, false, d_data, N, d_out, stream);
 }
 
@@ -463,6 +481,8 @@ int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, fl
     if (N == 0) return LSH_OK;
     if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
         return launch_dense_split(p, 1, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_wide_supported(p))
+        return launch_dense_wide(p, true, d_data, N, d_out, stream);
     return launch_dense(p, true, d_data, N, d_out, stream);
 }
 

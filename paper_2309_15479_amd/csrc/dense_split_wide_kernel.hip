@@ -1,0 +1,353 @@
+// Dense E2LSH projections (Sec. 2.2, Eq. 1) for any dimension n on the bf16 matrix cores of
+// gfx950, with fp32 accuracy: P = V A^T from exact three-way bf16 splits of both operands and
+// the six products of weight >= 2^-16 (see dense_split_kernel.hip for the arithmetic and its
+// error: what is left out is below 2^-23 of each term |a_i v_i|).  The fp32 MFMA runs at a
+// sixteenth of the bf16 rate, so six bf16 products are 16/6 of its speed at best.
+//
+//   V [N][n] fp32 row-major; A already split on the host into three bf16 planes
+//   [3][kpad][npad] (row j = a_j, zero rows up to a multiple of 256, zero columns up to a
+//   multiple of 16).
+//
+// Workgroup = 8 waves, tile = 256 functions x 128 vectors, contraction in stages of 16
+// coordinates.  A wave owns 64 functions x 64 vectors (2 x 2 blocks of
+// v_mfma_f32_32x32x16_bf16; functions are the row operand, so an accumulator lane holds runs of
+// four consecutive functions of one vector).  Per stage every thread brings 16 bytes of the
+// vector tile (4 fp32, split here on their way to LDS) and 16 bytes of each coefficient plane
+// (8 bf16); LDS holds three stages, [plane][row][32 bytes], the two 16-byte halves of a row
+// swapped in rows whose number has bit 3 set, which makes the 16-byte operand reads of 32
+// consecutive rows (and the writes) conflict-free without padding.  While stage s is
+// contracted, the operand registers it has finished with are refilled from stage s + 1,
+// stage s + 2 is written to LDS, and the global loads of stage s + 5 go out (a ring of three
+// register sets: one stage of matrix work per wave is far shorter than a trip to memory).
+// One barrier per stage, placed where the matrix pipe has products queued.
+//
+// Placement: workgroup g runs on XCD g % 8.  With at least 8 function tiles XCD x takes the
+// tiles x, x + 8, ..., with fewer the XCDs share them; the CUs of an XCD walk the vector tiles
+// of one function tile in step, so the coefficient stages (the larger operand) are fetched into
+// that XCD's L2 once per stage, and the vector tiles, read by the XCDs at about the same time,
+// come from memory once.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "lsh_internal.h"
+
+namespace lsh {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int TF = 256;    // functions per tile
+constexpr int TVW = 128;   // vectors per tile
+constexpr int KB = 16;     // coordinates per stage = one MFMA step
+constexpr int ROWB = 32;   // bytes per row and plane in a stage: two 16-byte halves, swapped in rows with bit 3 set
+constexpr int A_PLANE = TF * ROWB, V_PLANE = TVW * ROWB;
+constexpr int STAGE = 3 * (A_PLANE + V_PLANE);  // 36864 bytes
+constexpr int kThreadsW = 512;
+constexpr int kLdsBytesW = 3 * STAGE;
+
+struct WideArgs {
+    const float *data;       // [N][n]
+    const uint16_t *planes;  // [3][kpad][npad] bf16 bit patterns
+    const float *off;        // [>= kpad]
+    uint64_t N;
+    uint32_t n, npad, k, kpad;
+    float w, inv_w;
+    void *out;               // [N][k]
+};
+
+// x = x1 + x2 + x3 exactly, each a bf16 (round to nearest even)
+__device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &x3) {
+    x1 = (__bf16)x;
+    const float r1 = x - (float)x1;
+    x2 = (__bf16)r1;
+    x3 = (__bf16)(r1 - (float)x2);
+}
+
+// PROJ: raw projections instead of bucket ids.  POW2: w is a power of two (fma(p, 1/w, b/w) is
+// then the same float as (p + b) / w).  VEC: k is a multiple of 4 (16-byte stores).
+template <bool PROJ, bool POW2, bool VEC>
+__global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideArgs a) {
+    extern __shared__ __align__(16) char lds_w[];  // 3 stages x ([3][256][32] coefficients, [3][128][32] vectors)
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lr = lane & 31, lh = lane >> 5;
+    const uint32_t fw = wave & 3, vw = wave >> 2;  // the wave's quarter of the functions, half of the vectors
+
+    // which (function tile, vector tile) pairs this workgroup takes
+    const uint32_t F = a.kpad / TF;
+    const uint64_t Vt = (a.N + TVW - 1) / TVW;
+    const uint32_t x = blockIdx.x & 7, i = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
+    uint32_t ft_first, ft_step, reps, rep;
+    if (F >= 8) {
+        ft_first = x; ft_step = 8; reps = 1; rep = 0;
+    } else {
+        ft_first = x % F; ft_step = F;  // one function tile per XCD
+        reps = (8 - ft_first + F - 1) / F;  // XCDs that share it
+        rep = x / F;
+    }
+
+    // loading roles: 16 bytes of the vector tile and of each coefficient plane per stage
+    const uint32_t vr = threadIdx.x >> 2, vq = threadIdx.x & 3;  // vector row, 4-coordinate piece
+    const uint32_t ar = threadIdx.x >> 1, ah = threadIdx.x & 1;  // coefficient row, 8-coordinate half
+    const uint32_t stages = a.npad / KB;
+
+    // operand read and write offsets inside a stage (half h of row r sits at 16 * (h ^ bit 3 of r))
+    const uint32_t rd_a = (fw * 64 + lr) * ROWB + ((lh ^ ((lr >> 3) & 1)) << 4);                // + rb * 32 rows + plane
+    const uint32_t rd_v = 3 * A_PLANE + (vw * 64 + lr) * ROWB + ((lh ^ ((lr >> 3) & 1)) << 4);  // + cb * 32 rows + plane
+    const uint32_t wr_a = ar * ROWB + ((ah ^ ((ar >> 3) & 1)) << 4);
+    const uint32_t wr_v = 3 * A_PLANE + vr * ROWB + (((vq >> 1) ^ ((vr >> 3) & 1)) << 4) + ((vq & 1) << 3);
+
+    for (uint32_t ft = ft_first; ft < F; ft += ft_step) {
+        const uint16_t *arow = a.planes + ((size_t)ft * TF + ar) * a.npad + ah * 8;
+        const size_t plane_stride = (size_t)a.kpad * a.npad;
+        for (uint64_t vt = (uint64_t)i * reps + rep; vt < Vt; vt += (uint64_t)per_xcd * reps) {
+            uint64_t row = vt * TVW + vr;
+            row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
+            const float *vrow = a.data + row * a.n + vq * 4;
+
+            // ring of three register sets for the global loads: set s % 3 holds stage s
+            floatx4 gv[3];
+            uintx4 ga[3][3];
+            // Every load is issued unconditionally (the compiler can then count the loads in flight
+            // exactly and wait for the oldest set only): stages beyond the last read the last
+            // stage's coefficients against zeros.
+            auto gload = [&](uint32_t s, floatx4 &v, uintx4 (&c)[3]) __attribute__((always_inline)) {
+                const uint32_t k0 = s * KB;
+                // coordinates beyond n read the row's first ones instead; lstore() replaces them by zeros
+                v = *reinterpret_cast<const floatx4 *>(vrow + (k0 + vq * 4 < a.n ? k0 : 0u));
+                const uint32_t ka = s < stages ? k0 : (stages - 1) * KB;
+#pragma unroll
+                for (int p = 0; p < 3; ++p) c[p] = *reinterpret_cast<const uintx4 *>(arow + p * plane_stride + ka);
+            };
+            auto lstore = [&](char *stage, uint32_t s, const floatx4 &v, const uintx4 (&c)[3]) __attribute__((always_inline)) {
+                const bool inside = s * KB + vq * 4 < a.n;
+                bf16x4 h[3];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    __bf16 x1, x2, x3;
+                    split3(inside ? v[e] : 0.f, x1, x2, x3);
+                    h[0][e] = x1;
+                    h[1][e] = x2;
+                    h[2][e] = x3;
+                }
+#pragma unroll
+                for (int p = 0; p < 3; ++p) {
+                    *reinterpret_cast<bf16x4 *>(stage + wr_v + p * V_PLANE) = h[p];
+                    *reinterpret_cast<uintx4 *>(stage + wr_a + p * A_PLANE) = c[p];
+                }
+            };
+
+            floatx16 acc[2][2];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[rb][cb][e] = 0.f;
+
+            // Operand registers of the stage being contracted: fa[block][plane], fv[block][plane].
+            // A plane's registers are read again, for the next stage, as soon as the last product
+            // that uses them has been issued.
+            bf16x8 fa[2][3], fv[2][3];
+            auto read_a = [&](const char *stage, int p) __attribute__((always_inline)) {
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    fa[b][p] = *reinterpret_cast<const bf16x8 *>(stage + rd_a + b * 32 * ROWB + p * A_PLANE);
+            };
+            auto read_v = [&](const char *stage, int p) __attribute__((always_inline)) {
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    fv[b][p] = *reinterpret_cast<const bf16x8 *>(stage + rd_v + b * 32 * ROWB + p * V_PLANE);
+            };
+#define LSH_PRODUCT(PA, PV) \
+    _Pragma("unroll") for (int rb = 0; rb < 2; ++rb) \
+        _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) \
+            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[rb][PA], fv[cb][PV], acc[rb][cb], 0, 0, 0);
+
+            // One stage.  LDS holds three stages: s (in the operand registers by now), s + 1 (written
+            // during the previous iteration, read into the freed operand registers during this one)
+            // and s + 2 (written during this one from register set (s + 2) % 3, which then takes
+            // the loads of stage s + 5).  The barrier sits after the first two products: what it
+            // waits for was issued long before, and the matrix pipe has work queued.
+            auto iteration = [&](uint32_t s, floatx4 &v_set, uintx4 (&c_set)[3]) __attribute__((always_inline)) {
+                const char *nxt = lds_w + ((s + 1) % 3) * STAGE;
+                char *far = lds_w + ((s + 2) % 3) * STAGE;
+                // product order and refills: every plane is read again at least eight MFMAs before
+                // the next stage's first product that needs it
+                __builtin_amdgcn_sched_barrier(0);
+                LSH_PRODUCT(1, 1)
+                LSH_PRODUCT(1, 0)
+                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();  // stage s + 1 is complete in LDS; nobody reads stage s - 1 any more
+                read_a(nxt, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                LSH_PRODUCT(2, 0)
+                __builtin_amdgcn_sched_barrier(0);
+                read_a(nxt, 2);
+                lstore(far, s + 2, v_set, c_set);
+                __builtin_amdgcn_sched_barrier(0);
+                LSH_PRODUCT(0, 1)
+                __builtin_amdgcn_sched_barrier(0);
+                read_v(nxt, 1);
+                gload(s + 5, v_set, c_set);
+                __builtin_amdgcn_sched_barrier(0);
+                LSH_PRODUCT(0, 0)
+                __builtin_amdgcn_sched_barrier(0);
+                read_v(nxt, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                LSH_PRODUCT(0, 2)
+                __builtin_amdgcn_sched_barrier(0);
+                read_a(nxt, 0);
+                read_v(nxt, 2);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+
+            // prologue: stages 0 and 1 to LDS, stages 2, 3, 4 on their way (stage j lives in set j % 3)
+            gload(0, gv[0], ga[0]);
+            gload(1, gv[1], ga[1]);
+            gload(2, gv[2], ga[2]);
+            lstore(lds_w, 0, gv[0], ga[0]);
+            gload(3, gv[0], ga[0]);
+            lstore(lds_w + STAGE, 1, gv[1], ga[1]);
+            gload(4, gv[1], ga[1]);
+            __syncthreads();
+            read_a(lds_w, 1);  // in the order of the refills
+            read_a(lds_w, 2);
+            read_v(lds_w, 1);
+            read_v(lds_w, 0);
+            read_a(lds_w, 0);
+            read_v(lds_w, 2);
+            // the stage count is rounded up to the ring's three: a stage beyond the last multiplies
+            // coefficients with zeros
+            for (uint32_t s = 0; s < stages; s += 3) {
+                iteration(s, gv[2], ga[2]);
+                iteration(s + 1, gv[0], ga[0]);
+                iteration(s + 2, gv[1], ga[1]);
+            }
+#undef LSH_PRODUCT
+            __syncthreads();  // the next tile's prologue writes stages that the last iterations read
+
+            // epilogue: register 4q + e of block (rb, cb) is function 8q + 4 (l / 32) + e of the
+            // block's 32, vector l % 32
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t j = ft * TF + fw * 64 + rb * 32 + 8 * q + 4 * lh;  // < kpad
+                    float b4[4] = {0.f, 0.f, 0.f, 0.f};
+                    if constexpr (!PROJ) {
+                        const floatx4 t = *reinterpret_cast<const floatx4 *>(a.off + j);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) b4[e] = POW2 ? t[e] * a.inv_w : t[e];
+                    }
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb) {
+                        const uint64_t vec = vt * TVW + vw * 64 + cb * 32 + lr;
+                        uintx4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float p = acc[rb][cb][4 * q + e];
+                            if constexpr (PROJ) {
+                                v[e] = __float_as_uint(p);
+                            } else {
+                                const float h = POW2 ? fmaf(p, a.inv_w, b4[e]) : (p + b4[e]) / a.w;
+                                v[e] = (uint32_t)(int)floorf(h);
+                            }
+                        }
+                        if (vec < a.N) {
+                            uint32_t *dst = reinterpret_cast<uint32_t *>(a.out) + vec * a.k + j;
+                            if constexpr (VEC) {
+                                if (j < a.k) *reinterpret_cast<uintx4 *>(dst) = v;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (j + e < a.k) dst[e] = v[e];
+                            }
+                        }
+                    }
+                }
+        }
+    }
+}
+
+uint16_t to_bf16(float x) {  // round to nearest even; NaN stays NaN
+    uint32_t u;
+    std::memcpy(&u, &x, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)((u >> 16) | ((u & 0xFFFFu) ? 0x40u : 0u));
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+float from_bf16(uint16_t h) {
+    const uint32_t u = (uint32_t)h << 16;
+    float x;
+    std::memcpy(&x, &u, 4);
+    return x;
+}
+
+}  // namespace
+
+uint32_t dense_wide_row_tile() { return TF; }
+uint32_t dense_wide_col_step() { return KB; }
+
+// the three bf16 planes [3][kpad][npad] of a coefficient matrix [k][n]
+void build_dense_planes(const float *a, uint32_t k, uint32_t n, uint32_t kpad, uint32_t npad,
+                        std::vector<uint16_t> &planes) {
+    planes.assign((size_t)3 * kpad * npad, 0);
+    const size_t plane = (size_t)kpad * npad;
+    for (uint32_t j = 0; j < k; ++j)
+        for (uint32_t c = 0; c < n; ++c) {
+            const float x = a[(size_t)j * n + c];
+            const uint16_t h1 = to_bf16(x);
+            const float r1 = x - from_bf16(h1);
+            const uint16_t h2 = to_bf16(r1);
+            const uint16_t h3 = to_bf16(r1 - from_bf16(h2));
+            const size_t at = (size_t)j * npad + c;
+            planes[at] = h1;
+            planes[plane + at] = h2;
+            planes[2 * plane + at] = h3;
+        }
+}
+
+bool dense_wide_supported(const lsh_params *p) {
+    return p->m == p->n && p->d_dense_planes != nullptr && p->n % 4 == 0 && (uint64_t)p->k * 4 < (1ull << 32);
+}
+
+int launch_dense_wide(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out, void *stream) {
+    WideArgs a;
+    a.data = d_data;
+    a.planes = static_cast<const uint16_t *>(p->d_dense_planes);
+    a.off = p->d_off;
+    a.N = N;
+    a.n = p->n;
+    a.npad = (p->n + KB - 1) / KB * KB;
+    a.k = p->k;
+    a.kpad = (p->k + TF - 1) / TF * TF;
+    a.w = p->w;
+    a.inv_w = 1.0f / p->w;
+    a.out = d_out;
+    int exp2 = 0;
+    const bool pw = proj || std::frexp(p->w, &exp2) == 0.5f;
+    const bool vec = p->k % 4 == 0;
+    // one workgroup per CU (108 KB of LDS), a multiple of 8 so that every XCD gets the same number
+    uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
+    if (wgs < 8) wgs = 8;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+#define LSH_WIDE_CASE(P_, W_, V_) \
+    if (proj == P_ && pw == W_ && vec == V_) { \
+        auto fn = &dense_split_wide_kernel<P_, W_, V_>; \
+        if (ensure_lds_limit(reinterpret_cast<const void *>(fn), kLdsBytesW) != LSH_OK) return LSH_ERR_HIP; \
+        hipLaunchKernelGGL(fn, dim3(wgs), dim3(kThreadsW), kLdsBytesW, s, a); \
+    }
+    LSH_WIDE_CASE(false, true, true) LSH_WIDE_CASE(false, false, true) LSH_WIDE_CASE(true, true, true)
+    LSH_WIDE_CASE(false, true, false) LSH_WIDE_CASE(false, false, false) LSH_WIDE_CASE(true, true, false)
+#undef LSH_WIDE_CASE
+    return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
+}
+
+}  // namespace lsh

@@ -90,6 +90,7 @@ struct lsh_params {
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n]: row j = a_j written out over all n coordinates; m == n or n == 128, else null
     uint32_t kpad_dense = 0;
+    void *d_dense_planes = nullptr;    // m == n, n != 128: the same matrix as three bf16 planes [3][kpad 256][npad 16]
     int dense_arithmetic = LSH_DENSE_AUTO;  // see lsh_params_set_dense_arithmetic
     // one sample per table: operand tables of the shared-sample kernel (null when unsupported)
     lsh::SharedPlan shared_plan;
@@ -158,6 +159,14 @@ bool dense_split_keys_supported(const lsh_params *p, uint32_t L);
 // ep: 0 bucket ids, 1 raw projections, 2 sign words, 3 keys (L tables)
 int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
                        void *stream, uint32_t L = 0);
+// bf16 x 3 matrix-core version of the dense product for any n that is a multiple of 4
+// (dense_split_wide_kernel.hip), over the coefficient planes split on the host
+bool dense_wide_supported(const lsh_params *p);
+uint32_t dense_wide_row_tile();
+uint32_t dense_wide_col_step();
+void build_dense_planes(const float *a, uint32_t k, uint32_t n, uint32_t kpad, uint32_t npad,
+                        std::vector<uint16_t> &planes);
+int launch_dense_wide(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out, void *stream);
 int launch_pack(const lsh_params *p, const int32_t *d_ids, uint64_t N, uint32_t L,
                 uint64_t *d_keys, void *stream);
 

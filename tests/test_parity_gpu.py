@@ -191,15 +191,25 @@ def test_shared_sample_shapes(lsh, N, n, k, m, w, seed, repl, L):
         say(_compare_all(lsh, p, data, np.arange(N), L=L, label=f"shared{seed}"))
 
 
+@pytest.mark.parametrize("fp32_only", [False, True])
 @pytest.mark.parametrize("N,n,k", [(130, 128, 128), (129, 100, 200), (1, 37, 5), (515, 36, 257), (64, 4096, 64),
-                                   (300, 128, 192), (257, 128, 70), (400, 124, 256)])
-def test_dense_shapes(lsh, N, n, k):
-    say(f"dense case N={N} n={n} k={k}")
+                                   (300, 128, 192), (257, 128, 70), (400, 124, 256),
+                                   # the bf16 x 3 kernel for n != 128: 128-vector x 256-function tiles in stages of
+                                   # 16 coordinates; partial tiles both ways, n not a multiple of 16, k not of 4,
+                                   # more function tiles than XCDs, a single vector
+                                   (300, 960, 320), (131, 4096, 520), (257, 132, 260), (1000, 64, 2304), (1, 16, 4),
+                                   (128, 20, 256), (640, 512, 1027)])
+def test_dense_shapes(lsh, N, n, k, fp32_only):
+    say(f"dense case N={N} n={n} k={k} fp32_only={fp32_only}")
     g = torch.Generator(device="cuda")
     g.manual_seed(N * 7 + n)
-    data = torch.randn((N, n), generator=g, device="cuda") * 2.0
-    with lsh.LshParams(n, k, n, 1.5, N + n + k) as p:
-        say(_compare_all(lsh, p, data, np.arange(N), label=f"dense{N}x{n}x{k}", dense=True, signs=False))
+    # long rows: unit-variance data and w = 8 as in the high-dimensional workload (fp32 accumulation over
+    # thousands of terms resolves a bucket boundary to about 1e-4 w only while sum |a_i v_i| / w stays in the hundreds)
+    scale, w = (2.0, 1.5) if n < 512 else (1.0, 8.0)
+    data = torch.randn((N, n), generator=g, device="cuda") * scale
+    with lsh.LshParams(n, k, n, w, N + n + k) as p:
+        say(_compare_all(lsh, p, data, np.arange(N), label=f"dense{N}x{n}x{k}", dense=True, signs=False,
+                         dense_fp32=fp32_only))
 
 
 @pytest.mark.parametrize("fp32_only", [False, True])
@@ -269,16 +279,18 @@ def test_dense_split_levels_by_tile(lsh, k, tiles, tail):
         say("levels signs", _compare_all(lsh, p, data, rows_all, label="levels-fast", signs=True))
 
 
-def test_dense_split_products_error(lsh):
-    """The bf16 x 3 product against the fp64 oracle on data with a wide range of magnitudes in
-    one vector: the error stays at the level of fp32 rounding (a few 2^-24 of sum |a_i v_i|),
-    far inside the 1e-5 bound, and no worse than twice the fp32 MFMA path's."""
+@pytest.mark.parametrize("n", [128, 960])
+def test_dense_split_products_error(lsh, n):
+    """The bf16 x 3 product (both kernels: n = 128 and the general one) against the fp64 oracle on
+    data with a wide range of magnitudes in one vector: the error stays at the level of fp32
+    rounding (a few 2^-24 of sum |a_i v_i|), far inside the 1e-5 bound, and no worse than twice
+    the fp32 MFMA path's."""
     N, k = 512, 256
     g = torch.Generator(device="cuda")
     g.manual_seed(99)
-    data = torch.randn((N, 128), generator=g, device="cuda") * torch.exp(
-        6.0 * torch.randn((N, 128), generator=g, device="cuda"))
-    with lsh.LshParams(128, k, 128, 4.0, 99) as p:
+    data = torch.randn((N, n), generator=g, device="cuda") * torch.exp(
+        6.0 * torch.randn((N, n), generator=g, device="cuda"))
+    with lsh.LshParams(n, k, n, 4.0, 99) as p:
         _, coef, off = _tables(p)
         ora = oracle.e2lsh(data.cpu().numpy(), coef, off, p.w, nthreads=THREADS, want=("proj", "abs_sum"))
         split = lsh.project_e2lsh(p, data).cpu().numpy()
