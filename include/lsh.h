@@ -234,8 +234,11 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
  * memory, owned by the index object.
  *
  * lsh_index_build: d_keys [N][L] (device, as written by lsh_pack_keys or
- *   lsh_hash_fastlsh_keys), N < 2^31.  Sorts the L columns on `stream` and WAITS for them
- *   (temporary buffers are released before returning).
+ *   lsh_hash_fastlsh_keys), N < 2^31, L <= 65535.  Sorts all L columns together on `stream`
+ *   (a stable radix sort of this library, eight passes of 8 bits, the keys read in place) and
+ *   does not wait: d_keys must stay alive until the stream has passed the build, and the index
+ *   may be used by later work on the same stream (or after synchronising).  A second buffer of
+ *   12 bytes per pair is allocated and released in stream order.
  * lsh_index_tables: N, L and the device arrays sorted keys [L][N], ids in key order [L][N]
  *   (owned by the index; any out pointer may be NULL).
  * lsh_index_probe: d_qkeys [Q][L] -> d_start [Q][L], d_count [Q][L]: the bucket of query q in
@@ -257,7 +260,7 @@ int lsh_time_launches(const lsh_params_t *params, int which, const void *d_in, u
  *   candidate with the largest inner product v . u with the query (fp32; ties to the smaller
  *   id) -> d_best_id, d_best_ip [Q] (-inf when there is no candidate).  The index is then built
  *   from the keys of lsh_hash_mips_data and probed with those of lsh_hash_mips_query.
- * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^31, called on another device than the one
+ * Errors: INVALID_ARG (null pointers, N = 0, N >= 2^31, L > 65535, called on another device than the one
  * the index was built on), ALLOC, HIP, NO_DEVICE, UNSUPPORTED (lsh_index_nearest and
  * lsh_index_best_inner_product: n > 16368).
  */

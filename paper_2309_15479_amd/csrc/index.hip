@@ -4,7 +4,7 @@
 // The paper fixes what a table holds (every vector's id under its key H_l(v)) and how a query
 // uses it (fetch the L buckets H_1(u) .. H_L(u), evaluate the candidates), not a layout.  Here a
 // table is the vector ids sorted by key (a stable radix sort of N <key, id> pairs, ids
-// ascending inside a bucket): a bucket is a contiguous run of the sorted ids, found by binary
+// ascending inside a bucket; all tables are sorted together by the kernels below): a bucket is a contiguous run of the sorted ids, found by binary
 // search of the sorted keys.  No chains, no resizing, 12 bytes per vector and table.
 //
 //   build      keys [N][L] -> per table: sorted keys [N], ids in key order [N]
@@ -15,7 +15,6 @@
 //              exact version) or only the first max_candidates of the combined list (the
 //              approximate version evaluates no more than 3L points)
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
 
 #include <mutex>
 #include <new>
@@ -31,14 +30,6 @@ struct lsh_index {
 };
 
 namespace {
-
-__global__ void take_column(const uint64_t *__restrict__ keys, uint64_t N, uint32_t L, uint32_t l,
-                            uint64_t *__restrict__ column, uint32_t *__restrict__ ids) {
-    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < N; i += (uint64_t)gridDim.x * blockDim.x) {
-        column[i] = keys[i * L + l];
-        ids[i] = (uint32_t)i;
-    }
-}
 
 // one thread per (query, table): lower and upper bound of the query's key in the table
 __global__ void probe_kernel(const uint64_t *__restrict__ sorted_keys, uint64_t N, uint32_t L,
@@ -159,6 +150,122 @@ int launch_offsets_scan(const uint32_t *d_count, uint64_t items, uint64_t *d_par
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
 
+// Stable least-significant-digit radix sort of all L key columns at once (one grid row per
+// table): eight passes of 8 bits.  A pass is three launches: per-tile digit histograms, an
+// exclusive scan of the (digit, tile) counts of every table, and the scatter.  A tile is 4096
+// consecutive pairs; wave w of the workgroup owns pairs 1024 w ... 1024 w + 1023 of it, slot i
+// of lane l being pair 64 i + l, so (wave, slot, lane) order is memory order and the ranks
+// below keep equal keys in their original order (ids ascending inside a bucket).  The first
+// pass reads the keys in place from the caller's [N][L] array and numbers the pairs itself.
+constexpr uint32_t kSortThreads = 256, kSortSlots = 16, kSortTile = kSortThreads * kSortSlots;
+constexpr uint32_t kSortWaves = kSortThreads / 64;
+
+template <bool FIRST>
+__device__ __forceinline__ uint64_t sort_key(const uint64_t *__restrict__ keys, uint64_t N, uint32_t L, uint32_t l,
+                                             uint64_t i) {
+    return FIRST ? keys[i * L + l] : keys[(uint64_t)l * N + i];
+}
+
+// hist[(l * 256 + digit) * tiles + tile] = pairs of the tile with that digit
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void sort_histogram(const uint64_t *__restrict__ keys, uint64_t N, uint32_t L,
+                                                                uint32_t shift, uint32_t tiles,
+                                                                uint32_t *__restrict__ hist) {
+    __shared__ uint32_t bins[256];
+    const uint32_t l = blockIdx.y, tile = blockIdx.x;
+    bins[threadIdx.x] = 0;
+    __syncthreads();
+    const uint64_t first = (uint64_t)tile * kSortTile;
+    for (uint32_t e = threadIdx.x; e < kSortTile; e += kSortThreads) {
+        const uint64_t i = first + e;
+        if (i < N) atomicAdd(&bins[(uint32_t)(sort_key<FIRST>(keys, N, L, l, i) >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[((size_t)l * 256 + threadIdx.x) * tiles + tile] = bins[threadIdx.x];
+}
+
+// one workgroup per table: hist <- exclusive prefix sum over its 256 * tiles counts, in place
+__global__ __launch_bounds__(kScanThreads) void sort_scan(uint32_t *__restrict__ hist, uint32_t tiles) {
+    __shared__ uint64_t wave_sums[kScanThreads / 64];
+    uint32_t *mine = hist + (size_t)blockIdx.x * 256 * tiles;
+    const uint64_t count = (uint64_t)256 * tiles;
+    uint64_t carry = 0;
+    for (uint64_t base = 0; base < count; base += kScanBlock) {
+        const uint64_t first = base + (uint64_t)threadIdx.x * kScanPerThread;
+        uint32_t v[kScanPerThread];
+        uint64_t sum = 0;
+        for (uint32_t e = 0; e < kScanPerThread; ++e) {
+            v[e] = first + e < count ? mine[first + e] : 0;
+            sum += v[e];
+        }
+        uint64_t before;
+        const uint64_t total = block_scan(sum, wave_sums, before);
+        uint64_t run = carry + before;
+        for (uint32_t e = 0; e < kScanPerThread; ++e) {
+            if (first + e < count) mine[first + e] = (uint32_t)run;  // below N < 2^31
+            run += v[e];
+        }
+        carry += total;
+    }
+}
+
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void sort_scatter(const uint64_t *__restrict__ keys,
+                                                              const uint32_t *__restrict__ ids, uint64_t N, uint32_t L,
+                                                              uint32_t shift, uint32_t tiles,
+                                                              const uint32_t *__restrict__ offsets,
+                                                              uint64_t *__restrict__ out_keys,
+                                                              uint32_t *__restrict__ out_ids) {
+    __shared__ uint32_t counter[kSortWaves][256];  // per wave: pairs seen so far per digit, then its base position
+    const uint32_t l = blockIdx.y, tile = blockIdx.x;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint32_t w = 0; w < kSortWaves; ++w) counter[w][threadIdx.x] = 0;
+    __syncthreads();
+    const uint64_t first = (uint64_t)tile * kSortTile + (uint64_t)wave * (kSortSlots * 64) + lane;
+    const uint64_t below = (1ull << lane) - 1;
+    uint64_t key[kSortSlots];
+    uint32_t rank[kSortSlots];
+    volatile uint32_t *mine = counter[wave];
+#pragma unroll
+    for (uint32_t i = 0; i < kSortSlots; ++i) {
+        const uint64_t at = first + (uint64_t)i * 64;
+        const bool valid = at < N;
+        key[i] = valid ? sort_key<FIRST>(keys, N, L, l, at) : 0;
+        const uint32_t digit = (uint32_t)(key[i] >> shift) & 255u;
+        // lanes of the wave that hold the same digit in this slot
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (uint32_t bit = 0; bit < 8; ++bit) {
+            const uint64_t set = __ballot((digit >> bit) & 1u);
+            peers &= ((digit >> bit) & 1u) ? set : ~set;
+        }
+        const uint32_t seen = mine[digit];
+        rank[i] = seen + (uint32_t)__popcll(peers & below);
+        __builtin_amdgcn_wave_barrier();
+        if (valid && (peers & below) == 0) mine[digit] = seen + (uint32_t)__popcll(peers);  // the first of the peers
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    {   // thread d: positions of digit d for each wave = scanned offset of (digit, tile) + the waves before
+        uint32_t run = offsets[((size_t)l * 256 + threadIdx.x) * tiles + tile];
+        for (uint32_t w = 0; w < kSortWaves; ++w) {
+            const uint32_t c = counter[w][threadIdx.x];
+            counter[w][threadIdx.x] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t i = 0; i < kSortSlots; ++i) {
+        const uint64_t at = first + (uint64_t)i * 64;
+        if (at >= N) continue;
+        const uint32_t digit = (uint32_t)(key[i] >> shift) & 255u;
+        const uint64_t pos = (uint64_t)l * N + counter[wave][digit] + rank[i];
+        out_keys[pos] = key[i];
+        out_ids[pos] = FIRST ? (uint32_t)at : ids[(uint64_t)l * N + at];
+    }
+}
+
 // Scratch of lsh_index_candidate_offsets_static: the block sums of the scan, for callers that
 // must not allocate.  One copy per GPU, held until the process ends; its device address is
 // looked up once per device (the name below is only a host-side handle of the symbol).
@@ -274,7 +381,7 @@ extern "C" {
 int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream, lsh_index_t **out) {
     if (!out) return LSH_ERR_INVALID_ARG;
     *out = nullptr;
-    if (!d_keys || !N || !L || N >= (1ull << 31)) return LSH_ERR_INVALID_ARG;  // the sort counts in int
+    if (!d_keys || !N || !L || N >= (1ull << 31) || L > 65535) return LSH_ERR_INVALID_ARG;  // positions are 32-bit, tables a grid row
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
         (void)hipGetLastError();
@@ -285,35 +392,49 @@ int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream
     ix->N = N;
     ix->L = L;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    uint64_t *column = nullptr;
-    uint32_t *iota = nullptr;
-    void *temp = nullptr;
-    size_t temp_bytes = 0;
+    const uint32_t tiles = (uint32_t)((N + kSortTile - 1) / kSortTile);
+    // the other half of the ping-pong, and the (digit, tile) counts of every table
+    uint64_t *tmp_keys = nullptr;
+    uint32_t *tmp_ids = nullptr, *hist = nullptr;
     int rc = LSH_OK;
     if (hipGetDevice(&ix->device) != hipSuccess) rc = LSH_ERR_HIP;
     if (rc == LSH_OK && hipMalloc(&ix->d_keys, (size_t)L * N * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
     if (rc == LSH_OK && hipMalloc(&ix->d_ids, (size_t)L * N * sizeof(uint32_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
-    if (rc == LSH_OK && hipMalloc(&column, N * sizeof(uint64_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
-    if (rc == LSH_OK && hipMalloc(&iota, N * sizeof(uint32_t)) != hipSuccess) rc = LSH_ERR_ALLOC;
-    if (rc == LSH_OK &&
-        hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, column, ix->d_keys, iota, ix->d_ids, (int)N, 0, 64, s) !=
-            hipSuccess)
-        rc = LSH_ERR_HIP;
-    if (rc == LSH_OK && hipMalloc(&temp, temp_bytes ? temp_bytes : 1) != hipSuccess) rc = LSH_ERR_ALLOC;
-    const uint32_t blocks = (uint32_t)((N + 255) / 256 < 4096 ? (N + 255) / 256 : 4096);
-    for (uint32_t l = 0; rc == LSH_OK && l < L; ++l) {
-        hipLaunchKernelGGL(take_column, dim3(blocks), dim3(256), 0, s, d_keys, N, L, l, column, iota);
-        // stable least-significant-digit radix sort: equal keys keep ascending ids
-        if (hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, column, ix->d_keys + (size_t)l * N, iota,
-                                               ix->d_ids + (size_t)l * N, (int)N, 0, 64, s) != hipSuccess)
-            rc = LSH_ERR_HIP;
+    // temporaries are allocated and released in stream order: the host does not wait for the sort
+    if (rc == LSH_OK && hipMallocAsync(reinterpret_cast<void **>(&tmp_keys), (size_t)L * N * sizeof(uint64_t), s) != hipSuccess)
+        rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK && hipMallocAsync(reinterpret_cast<void **>(&tmp_ids), (size_t)L * N * sizeof(uint32_t), s) != hipSuccess)
+        rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK && hipMallocAsync(reinterpret_cast<void **>(&hist), (size_t)L * 256 * tiles * sizeof(uint32_t), s) != hipSuccess)
+        rc = LSH_ERR_ALLOC;
+    if (rc == LSH_OK) {
+        const dim3 grid(tiles, L), block(kSortThreads);
+        // eight passes; odd passes write the index's own arrays, so the last one ends there
+        for (uint32_t pass = 0; pass < 8; ++pass) {
+            const uint32_t shift = 8 * pass;
+            const uint64_t *src_keys = pass == 0 ? d_keys : (pass & 1) ? tmp_keys : ix->d_keys;
+            const uint32_t *src_ids = (pass & 1) ? tmp_ids : ix->d_ids;
+            uint64_t *dst_keys = (pass & 1) ? ix->d_keys : tmp_keys;
+            uint32_t *dst_ids = (pass & 1) ? ix->d_ids : tmp_ids;
+            if (pass == 0) {
+                hipLaunchKernelGGL(sort_histogram<true>, grid, block, 0, s, src_keys, N, L, shift, tiles, hist);
+                hipLaunchKernelGGL(sort_scan, dim3(L), dim3(kScanThreads), 0, s, hist, tiles);
+                hipLaunchKernelGGL(sort_scatter<true>, grid, block, 0, s, src_keys, src_ids, N, L, shift, tiles, hist,
+                                   dst_keys, dst_ids);
+            } else {
+                hipLaunchKernelGGL(sort_histogram<false>, grid, block, 0, s, src_keys, N, L, shift, tiles, hist);
+                hipLaunchKernelGGL(sort_scan, dim3(L), dim3(kScanThreads), 0, s, hist, tiles);
+                hipLaunchKernelGGL(sort_scatter<false>, grid, block, 0, s, src_keys, src_ids, N, L, shift, tiles, hist,
+                                   dst_keys, dst_ids);
+            }
+        }
+        if (hipGetLastError() != hipSuccess) rc = LSH_ERR_HIP;
     }
-    if (rc == LSH_OK && hipStreamSynchronize(s) != hipSuccess) rc = LSH_ERR_HIP;
-    if (rc == LSH_OK && hipGetLastError() != hipSuccess) rc = LSH_ERR_HIP;
-    if (column) (void)hipFree(column);
-    if (iota) (void)hipFree(iota);
-    if (temp) (void)hipFree(temp);
+    if (tmp_keys) (void)hipFreeAsync(tmp_keys, s);
+    if (tmp_ids) (void)hipFreeAsync(tmp_ids, s);
+    if (hist) (void)hipFreeAsync(hist, s);
     if (rc != LSH_OK) {
+        (void)hipStreamSynchronize(s);
         (void)hipGetLastError();
         lsh_index_destroy(ix);
         return rc;
