@@ -77,11 +77,13 @@ int upload_tables(lsh_params *p) {
         if (rc == LSH_OK && p->plan.supported && p->plan.ranged) {
             // one stream of list blocks per gathering wave, in the order the wave consumes them:
             // range after range, within a range the wave's functions-per-lane sets one after the
-            // other.  A block is kRangeBlockTriples triples x 64 lanes x 16 bytes: three
-            // coefficients and three 10-bit slot numbers (coordinate minus the range's first).
+            // other.  A block is kRangeBlockQuads quads of entries x 64 lanes: 16 bytes of
+            // coefficients per quad and lane, then 8 bytes of 16-bit LDS byte offsets
+            // (16 x (coordinate minus the range's first)).
             const SampledPlan &pl = p->plan;
-            const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockTriples, fpt = pl.fpt;
+            const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockQuads, fpt = pl.fpt;
             const uint32_t real_sets = (p->k + 63) / 64, streams = pl.kblocks * CW;
+            const size_t block_words = (size_t)U * 64 * 6, off_base = (size_t)U * 64 * 4;
             std::vector<size_t> first_entry((size_t)real_sets * R);  // of each (set, range) in p->order
             size_t at = 0;
             for (uint32_t s = 0; s < real_sets; ++s)
@@ -99,10 +101,10 @@ int upload_tables(lsh_params *p) {
                     for (uint32_t q = 0; q < R; ++q)
                         for (uint32_t f = 0; f < fpt; ++f) {
                             const uint32_t s = (y * fpt + f) * CW + cw;
-                            const uint32_t T = s < real_sets ? p->chunk_steps[(size_t)s * R + q] : 0;  // multiple of 3
+                            const uint32_t T = s < real_sets ? p->chunk_steps[(size_t)s * R + q] : 0;  // multiple of 4
                             list_len[((size_t)(y * CW + cw) * R + q) * fpt + f] = T;
-                            const uint32_t nb = (T / 3 + U - 1) / U;
-                            words.resize((size_t)(blocks + nb) * U * 64 * 4, 0u);
+                            const uint32_t nb = (T / 4 + U - 1) / U;
+                            words.resize((size_t)(blocks + nb) * block_words, 0u);
                             for (uint32_t e = 0; e < T; ++e)
                                 for (uint32_t l = 0; l < 64; ++l) {
                                     const uint32_t ent = p->order[first_entry[(size_t)s * R + q] + (size_t)e * 64 + l];
@@ -115,9 +117,10 @@ int upload_tables(lsh_params *p) {
                                         slot = p->idx[(size_t)j * p->m + ent] - q * pl.chunk;
                                         c = p->coef[(size_t)j * p->m + ent];
                                     }
-                                    uint32_t *t = &words[(((size_t)blocks * U + e / 3) * 64 + l) * 4];
-                                    std::memcpy(&t[e % 3], &c, 4);
-                                    t[3] |= slot << (10 * (e % 3));
+                                    const size_t blk = (size_t)(blocks + e / (4 * U)) * block_words;
+                                    const uint32_t quad = e / 4 % U, pos = e % 4;
+                                    std::memcpy(&words[blk + ((size_t)quad * 64 + l) * 4 + pos], &c, 4);
+                                    words[blk + off_base + ((size_t)quad * 64 + l) * 2 + pos / 2] |= (slot * 16u) << (16 * (pos % 2));
                                 }
                             blocks += nb;
                         }
@@ -258,7 +261,7 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
             try {
                 const SampledPlan &pl = p->plan;
                 p->schedule_cost =
-                    pl.ranged ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 3, pl.group, pl.classes,
+                    pl.ranged ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 4, pl.group, pl.classes,
                                                  p->chunk_steps, p->order)
                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, pl.copies,
                                                   p->order);

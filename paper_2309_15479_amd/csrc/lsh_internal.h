@@ -85,7 +85,7 @@ struct lsh_params {
     uint64_t schedule_cost = 0;        // modelled LDS passes (see schedule.cpp)
     std::vector<uint32_t> chunk_steps; // ranged plan: [sets of 64 functions][nchunks] list length
     lsh::Sample *d_samples = nullptr;  // flat plans: [m_pad][kpad] step-major
-    // ranged plan: packed list blocks, list lengths [stream][range][fpt], streams {first block, blocks}
+    // ranged plan: packed list blocks (quads of entries), list lengths [stream][range][fpt], streams {first block, blocks}
     void *d_triples = nullptr, *d_list_len = nullptr, *d_stream = nullptr;
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n]: row j = a_j written out over all n coordinates; m == n or n == 128, else null
@@ -129,7 +129,7 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
 // ranged kernel (ranged_kernel.hip): geometry constants the host tables are built for
 constexpr uint32_t kRangeCoords = 1024;      // coordinates per range (one LDS buffer holds 16 vectors of them)
 constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather (the others load tiles)
-constexpr uint32_t kRangeBlockTriples = 4;   // packed triples per lane in one list block
+constexpr uint32_t kRangeBlockQuads = 3;     // quads of list entries per lane in one list block
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                   uint32_t L, void *stream);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);

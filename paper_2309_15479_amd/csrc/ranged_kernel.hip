@@ -19,20 +19,21 @@
 //    own counters of outstanding memory operations, so a gatherer's wait for list entries never
 //    waits for tile data.
 //
-//  * Packed lists.  A vector memory instruction costs the memory pipeline the same whether a
-//    lane moves 4 or 16 bytes, and with lists this long the instructions that stream them from
-//    L2 are what binds.  A lane's list is therefore stored as 16-byte triples: three
-//    coefficients and one word holding three 10-bit slot numbers.  Lists are cut into blocks of
-//    four triples; the blocks of one gathering wave form one contiguous stream in the order the
-//    wave consumes them (range after range, and within a range function after function), so
-//    the next block is always prefetched, across list boundaries and around the end of the
-//    stream to the next tile.
+//  * Packed lists.  The kernel is bound by vector-ALU issue (sixteen multiply-adds per list
+//    entry), so everything else an entry costs is kept small: a lane's list is stored in quads
+//    of entries, 16 bytes of coefficients and 8 bytes holding four 16-bit LDS byte offsets, which
+//    one add with a sub-word operand turns into the entry's address (one instruction per entry;
+//    a vector memory instruction per 2.7 entries).  Lists are cut into blocks of three quads; the
+//    blocks of one gathering wave form one contiguous stream in the order the wave consumes
+//    them (range after range, and within a range function after function), so the next block
+//    is always prefetched, across list boundaries and around the end of the stream to the next
+//    tile.
 //
 //  * A lane owns up to four functions (sets of 64 functions, 8 sets apart), so that a
 //    workgroup covers up to 2048 functions per tile load.
 //
 // Padding entries (a wave's 64 lists of one range are padded to a common length, a multiple of
-// three) carry coefficient 0 and read one of the first 16 slots of the range, whichever bank
+// four) carry coefficient 0 and read one of the first 16 slots of the range, whichever bank
 // class the schedule wants; the loaders write zeros to the slots beyond the last coordinate,
 // so such an entry always multiplies a finite value of the same vector by zero.
 #include <hip/hip_runtime.h>
@@ -51,16 +52,16 @@ constexpr int kThreads = (kCW + kLW) * 64;
 constexpr int kC = (int)kRangeCoords;
 constexpr int kSubBytes = kC * 16;            // one sub-tile of one buffer
 constexpr int kBufBytes = 4 * kSubBytes;      // 64 KB
-constexpr int kU = (int)kRangeBlockTriples;   // triples per lane in a list block
+constexpr int kU = (int)kRangeBlockQuads;     // quads of entries per lane in a list block
 constexpr int kPieces = kC / 64;              // 64-coordinate pieces of a sub-tile
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// LDS address of entry e (0..2) of a packed triple: three 10-bit slot numbers in the last word
-__device__ __forceinline__ const char *entry_slot(const char *buf, uint32_t word, int e) {
-    const uint32_t slot = e == 2 ? word >> 20 : (word >> (10 * e)) & 0x3FFu;
-    return buf + (slot << 4);
-}
+// one block of a lane's list: kU quads of entries
+struct ListBlock {
+    uint4 coef[kU];  // four coefficients (float bits)
+    uint2 off[kU];   // four 16-bit LDS byte offsets of the entries' slots in sub-tile 0
+};
 
 // the four 16-byte slots of one entry: the same coordinate in the four sub-tiles
 __device__ __forceinline__ void read_entry(const char *p, float4 (&x)[4]) {
@@ -79,31 +80,34 @@ __device__ __forceinline__ void fma_entry(float c, const float4 (&x)[4], float (
     }
 }
 
-// Three entries of a lane's list against the 16 vectors of the tile; the LDS reads of an entry
-// go out before the multiply-adds of the entry before it.  (The kernel is bound by vector-ALU
-// issue: deeper read-ahead, tried with a ring of three register sets and with all twelve reads
-// of a triple up front, changes nothing but the register count.)
-__device__ __forceinline__ void gather_triple(const char *buf, const uint4 t, float (&acc)[4][4]) {
+// Four entries of a lane's list against the 16 vectors of the tile; the LDS reads of an entry go
+// out before the multiply-adds of the entry before it.  (Deeper read-ahead, tried with a ring of
+// three register sets and with all reads of a group up front, changes nothing but the register
+// count: the vector ALU is busy in 96 % of the cycles.)
+__device__ __forceinline__ void gather_quad(const char *buf, const uint4 c, const uint2 o, float (&acc)[4][4]) {
     float4 x[2][4];
     __builtin_amdgcn_sched_barrier(0);
-    read_entry(entry_slot(buf, t.w, 0), x[0]);
+    read_entry(buf + (o.x & 0xFFFFu), x[0]);
     __builtin_amdgcn_sched_barrier(0);
-    read_entry(entry_slot(buf, t.w, 1), x[1]);
-    fma_entry(__uint_as_float(t.x), x[0], acc);
+    read_entry(buf + (o.x >> 16), x[1]);
+    fma_entry(__uint_as_float(c.x), x[0], acc);
     __builtin_amdgcn_sched_barrier(0);
-    read_entry(entry_slot(buf, t.w, 2), x[0]);
-    fma_entry(__uint_as_float(t.y), x[1], acc);
+    read_entry(buf + (o.y & 0xFFFFu), x[0]);
+    fma_entry(__uint_as_float(c.y), x[1], acc);
     __builtin_amdgcn_sched_barrier(0);
-    fma_entry(__uint_as_float(t.z), x[0], acc);
+    read_entry(buf + (o.y >> 16), x[1]);
+    fma_entry(__uint_as_float(c.z), x[0], acc);
+    __builtin_amdgcn_sched_barrier(0);
+    fma_entry(__uint_as_float(c.w), x[1], acc);
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// the first `triples` (1..kU) triples of a block
-__device__ __forceinline__ void gather_block(const char *buf, const uint4 (&blk)[kU], uint32_t triples,
+// the first `quads` (1..kU) quads of a block
+__device__ __forceinline__ void gather_block(const char *buf, const ListBlock &blk, uint32_t quads,
                                              float (&acc)[4][4]) {
 #pragma unroll
     for (int t = 0; t < kU; ++t)
-        if ((uint32_t)t < triples) gather_triple(buf, blk[t], acc);  // uniform
+        if ((uint32_t)t < quads) gather_quad(buf, blk.coef[t], blk.off[t], acc);  // uniform
 }
 
 template <int FPT, int EP>
@@ -175,16 +179,21 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
     // ---- gathering waves
     const uint32_t stream_id = blockIdx.y * kCW + wave;
     const uint2 si = streams[stream_id];  // {first block, blocks}
-    const uint4 *sbase = a.triples + (size_t)si.x * (kU * 64) + lane;
+    // a block in memory: kU x 64 lanes x 16 bytes of coefficients, then kU x 64 x 8 bytes of offsets
+    constexpr uint32_t kBlockWords = kU * 64 * 6;
+    const uint32_t *sbase = reinterpret_cast<const uint32_t *>(a.triples) + (size_t)si.x * kBlockWords;
     const uint32_t sblocks = si.y;
     const uint32_t *len_base = list_len + (size_t)stream_id * R * FPT;
     // list registers: the block in use and the one after it (always on its way)
-    uint4 P[kU], Q[kU];
+    ListBlock P, Q;
     uint32_t next_block = 0;
-    auto load_block = [&](uint4 (&blk)[kU]) __attribute__((always_inline)) {
-        const uint4 *src = sbase + (size_t)next_block * (kU * 64);
+    auto load_block = [&](ListBlock &blk) __attribute__((always_inline)) {
+        const uint32_t *src = sbase + (size_t)next_block * kBlockWords;
 #pragma unroll
-        for (int i = 0; i < kU; ++i) blk[i] = src[i * 64];
+        for (int i = 0; i < kU; ++i) {
+            blk.coef[i] = *reinterpret_cast<const uint4 *>(src + (i * 64 + lane) * 4);
+            blk.off[i] = *reinterpret_cast<const uint2 *>(src + kU * 64 * 4 + (i * 64 + lane) * 2);
+        }
         next_block = next_block + 1 == sblocks ? 0 : next_block + 1;
     };
     if (sblocks) load_block(P);
@@ -220,18 +229,17 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
             const char *buf = lds + b * kBufBytes;
 #pragma unroll
             for (int f = 0; f < FPT; ++f) {
-                const uint32_t triples = len_base[r * FPT + f] / 3;  // list lengths are multiples of three
+                const uint32_t quads = len_base[r * FPT + f] / 4;  // list lengths are multiples of four
                 // blocks two at a time, the registers of one being refilled while the other is used
-                for (uint32_t done = 0; done < triples; done += 2 * kU) {
+                for (uint32_t done = 0; done < quads; done += 2 * kU) {
                     load_block(Q);
-                    const uint32_t left = triples - done;
+                    const uint32_t left = quads - done;
                     gather_block(buf, P, left < (uint32_t)kU ? left : kU, acc[f]);
                     if (left > (uint32_t)kU) {
                         load_block(P);
                         gather_block(buf, Q, left - kU < (uint32_t)kU ? left - kU : kU, acc[f]);
                     } else {
-#pragma unroll
-                        for (int i = 0; i < kU; ++i) P[i] = Q[i];
+                        P = Q;
                     }
                 }
             }

@@ -65,7 +65,7 @@ struct SampledArgs {
     uint32_t buf_floats, copy_b_floats;
     // ranged kernel only (ranged_kernel.hip)
     uint32_t chunk, nchunks;     // coordinates per range, number of ranges
-    const uint4 *triples;        // list blocks of 4 x 64 packed triples, stream after stream
+    const uint4 *triples;        // list blocks (quads of entries: coefficients, then 16-bit LDS offsets), stream after stream
     const uint32_t *list_len;    // [stream][range][functions per lane] entries of each list
     const uint2 *stream;         // [stream] {first block, blocks}
     uint32_t fpt;                // functions per lane

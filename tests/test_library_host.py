@@ -180,7 +180,7 @@ def test_chunked_gather_schedule_is_a_padded_permutation(n, k, m, repl):
         used_len = (~unused).sum(axis=1)
         for w0 in range(0, k, 64):
             assert len(set(used_len[w0:w0 + 64].tolist())) == 1
-            assert (used_len[w0:w0 + 64] % 3 == 0).all()           # lists are stored as triples
+            assert (used_len[w0:w0 + 64] % 4 == 0).all()           # lists are stored as quads of entries
         for j in range(k):
             row = order[j][real[j]]
             assert sorted(row.tolist()) == list(range(m))
