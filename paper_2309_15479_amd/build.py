@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblsh.so")
-SOURCES = ["api.hip", "sampled_kernel.hip", "ranged_kernel.hip", "shared_kernel.hip", "dense_kernel.hip",
+SOURCES = ["api.hip", "sampled_kernel.hip", "ranged_kernel.hip", "shared_kernel.hip", "shared_ranged_kernel.hip", "dense_kernel.hip",
            "dense_split_kernel.hip", "dense_split_wide_kernel.hip", "pack_kernel.hip", "index.hip", "params_host.cpp", "schedule.cpp",
            "collision_law.cpp"]
 

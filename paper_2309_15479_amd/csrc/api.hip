@@ -28,6 +28,10 @@ void free_tables(lsh_params *p) {
     if (p->d_shared_sample_off) (void)hipFree(p->d_shared_sample_off);
     if (p->d_shared_offset) (void)hipFree(p->d_shared_offset);
     if (p->d_shared_extra) (void)hipFree(p->d_shared_extra);
+    if (p->d_sr_lists) (void)hipFree(p->d_sr_lists);
+    if (p->d_sr_list_len) (void)hipFree(p->d_sr_list_len);
+    if (p->d_sr_stream) (void)hipFree(p->d_sr_stream);
+    p->d_sr_lists = p->d_sr_list_len = p->d_sr_stream = nullptr;
     p->d_shared_extra = nullptr;
     p->d_shared_coef = nullptr;
     p->d_shared_sample_off = nullptr;
@@ -181,6 +185,17 @@ int upload_tables(lsh_params *p) {
             upload(reinterpret_cast<void **>(&p->d_shared_offset), offset.data(), offset.size() * sizeof(float));
             upload(reinterpret_cast<void **>(&p->d_shared_extra), extra.data(), extra.size() * sizeof(float));
         }
+        if (rc == LSH_OK && p->shared_ranged_plan.supported) {
+            std::vector<uint32_t> lists, list_len, stream_info;
+            build_shared_ranged_tables(p, lists, list_len, stream_info);
+            auto upload = [&](void **dst, const void *src, size_t bytes) {
+                if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
+                if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
+            };
+            upload(&p->d_sr_lists, lists.data(), lists.size() * sizeof(uint32_t));
+            upload(&p->d_sr_list_len, list_len.data(), list_len.size() * sizeof(uint32_t));
+            upload(&p->d_sr_stream, stream_info.data(), stream_info.size() * sizeof(uint32_t));
+        }
         if (rc == LSH_OK && p->kpad_dense) {
             // m == n: S_j is the identity, so the canonical coefficient table IS the dense
             // matrix A [k][n]; rows up to the tile grid are zero.  m < n: zeros at the coordinates
@@ -257,6 +272,7 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
     if (rc == LSH_OK) {
         p->plan = plan_sampled(n, k, m);
         p->shared_plan = plan_shared(n, k, m, L);
+        if (!p->shared_plan.supported) p->shared_ranged_plan = plan_shared_ranged(n, k, m, L);
         if (p->plan.supported) {
             try {
                 const SampledPlan &pl = p->plan;
@@ -381,6 +397,7 @@ int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     if (p->shared_plan.supported) return launch_shared(p, 0, d_data, N, d_out, stream);
+    if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 0, d_data, N, d_out, stream);
     if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
         return launch_dense_split(p, 0, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
@@ -390,6 +407,7 @@ int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, 
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
     if (p->shared_plan.supported) return launch_shared(p, 1, d_data, N, d_out, stream);
+    if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 1, d_data, N, d_out, stream);
     if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
         return launch_dense_split(p, 1, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);

@@ -173,8 +173,13 @@ SHARED = [
     (90, 960, 128, 128, 1.0, 49, False, 8),      # 64 < m <= 128: 32 MFMA steps, 16-vector tiles (the GIST shape's geometry)
     (300, 256, 512, 100, 4.0, 53, True, 32),     # 32 steps with padded samples, 64-vector tiles
     (33, 1260, 64, 65, 2.0, 54, False, 4),       # the widest n the 32-step kernel takes
-    (40, 1264, 64, 65, 2.0, 55, False, 4),       # one more: gather kernels
-    (40, 960, 128, 160, 1.0, 56, False, 8),      # m > 128: gather kernels
+    (40, 1264, 64, 65, 2.0, 55, False, 4),       # one more: the kernel for large dimensions, two ranges
+    (40, 960, 128, 160, 1.0, 56, False, 8),      # m > 128: the same kernel, one range
+    (100, 4096, 256, 64, 8.0, 57, False, 16),    # four ranges, tables of 16 = one block each, two blocks per wave
+    (37, 4100, 96, 40, 2.0, 58, True, 8),        # a fifth range of 4 coordinates, tables of 12, duplicates in S
+    (50, 2048, 1024, 30, 4.0, 59, False, 64),    # eight blocks per wave
+    (20, 4096, 4096, 64, 8.0, 60, False, 128),   # tables of 32 (two blocks each), four workgroups along the functions
+    (33, 16384, 128, 512, 1.0, 61, False, 4),    # sixteen ranges, long lists
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
 ]
 
@@ -430,6 +435,15 @@ def test_gist_full_size_shared_sample(lsh):
     rows = _sampled(wl.N, 8192)
     with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
         say("gist shared-sample fastlsh", _compare_all(lsh, p, data, rows, L=wl.L, label="gist-shared", signs=False))
+
+
+def test_highdim_full_size_shared_sample(lsh):
+    """The high-dimensional workload with one sample per table (L = 128 tables of 16 functions) at
+    m = 64: the matrix-core kernel for large dimensions, in the launch configuration the benchmark times."""
+    wl, data = workloads.make_data("highdim", "cuda")
+    rows = _sampled(wl.N, 4096)
+    with lsh.LshParams(wl.n, wl.k, wl.m[0], wl.w, wl.seed, shared_tables=wl.L) as p:
+        say("highdim shared sample", _compare_all(lsh, p, data, rows, label="highdim-shared", signs=False))
 
 
 def test_gist_full_size(lsh):
