@@ -29,9 +29,10 @@ void free_tables(lsh_params *p) {
     if (p->d_shared_offset) (void)hipFree(p->d_shared_offset);
     if (p->d_shared_extra) (void)hipFree(p->d_shared_extra);
     if (p->d_sr_lists) (void)hipFree(p->d_sr_lists);
+    if (p->d_sr_offs) (void)hipFree(p->d_sr_offs);
     if (p->d_sr_list_len) (void)hipFree(p->d_sr_list_len);
     if (p->d_sr_stream) (void)hipFree(p->d_sr_stream);
-    p->d_sr_lists = p->d_sr_list_len = p->d_sr_stream = nullptr;
+    p->d_sr_lists = p->d_sr_offs = p->d_sr_list_len = p->d_sr_stream = nullptr;
     p->d_shared_extra = nullptr;
     p->d_shared_coef = nullptr;
     p->d_shared_sample_off = nullptr;
@@ -186,14 +187,16 @@ int upload_tables(lsh_params *p) {
             upload(reinterpret_cast<void **>(&p->d_shared_extra), extra.data(), extra.size() * sizeof(float));
         }
         if (rc == LSH_OK && p->shared_ranged_plan.supported) {
-            std::vector<uint32_t> lists, list_len, stream_info;
-            build_shared_ranged_tables(p, lists, list_len, stream_info);
+            std::vector<float> lists;
+            std::vector<uint32_t> offs, range_groups, stream_info;
+            build_shared_ranged_tables(p, lists, offs, range_groups, stream_info);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
             };
-            upload(&p->d_sr_lists, lists.data(), lists.size() * sizeof(uint32_t));
-            upload(&p->d_sr_list_len, list_len.data(), list_len.size() * sizeof(uint32_t));
+            upload(&p->d_sr_lists, lists.data(), lists.size() * sizeof(float));
+            upload(&p->d_sr_offs, offs.data(), offs.size() * sizeof(uint32_t));
+            upload(&p->d_sr_list_len, range_groups.data(), range_groups.size() * sizeof(uint32_t));
             upload(&p->d_sr_stream, stream_info.data(), stream_info.size() * sizeof(uint32_t));
         }
         if (rc == LSH_OK && p->kpad_dense) {

@@ -61,8 +61,10 @@ struct SharedRangedPlan {
     uint32_t blocks_per_table = 0;  // blocks of 16 functions per table
     uint32_t nblocks = 0;           // L * blocks_per_table
     uint32_t kblocks = 0;           // workgroups along the function axis
-    uint32_t bpw = 0;               // blocks per contracting wave (1, 2, 4, 8 or 16)
+    uint32_t bpw = 0;               // blocks per contracting wave (4, 8 or 16)
     uint32_t R = 0;                 // coordinate ranges
+    uint32_t block_steps = 0;       // MFMA steps per list block (set when the lists are built)
+    bool short_lists = false;       // every list is one block (else whole turns of the four-block ring)
     bool supported = false;
 };
 
@@ -111,7 +113,7 @@ struct lsh_params {
     float *d_shared_extra = nullptr;
     // one sample per table, large n: lists of the shared-sample ranged kernel (null when unused)
     lsh::SharedRangedPlan shared_ranged_plan;
-    void *d_sr_lists = nullptr, *d_sr_list_len = nullptr, *d_sr_stream = nullptr;
+    void *d_sr_lists = nullptr, *d_sr_offs = nullptr, *d_sr_list_len = nullptr, *d_sr_stream = nullptr;
 };
 
 namespace lsh {
@@ -146,11 +148,10 @@ constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather
 constexpr uint32_t kRangeBlockQuads = 3;     // quads of list entries per lane in one list block
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                   uint32_t L, void *stream);
-constexpr uint32_t kSharedRangeBlockSteps = 6;      // MFMA steps per lane in one list block of the shared-sample ranged kernel
 constexpr uint32_t kSharedRangeBlocksPerWave = 16;  // blocks of 16 functions a contracting wave owns at most
 SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
-void build_shared_ranged_tables(const lsh_params *p, std::vector<uint32_t> &lists, std::vector<uint32_t> &list_len,
-                                std::vector<uint32_t> &stream_info);
+void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::vector<uint32_t> &offs,
+                                std::vector<uint32_t> &range_groups, std::vector<uint32_t> &stream_info);
 int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uint64_t N, void *d_out, void *stream);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,

@@ -18,13 +18,28 @@
 // one coefficient (row l % 16, sample l / 16 of the step) and one LDS offset from its list,
 // reads the sampled coordinate of vector l % 16 from the tile (the four coordinates of a step
 // differ modulo 4 where the table allows it, so that the 64 lanes hit 64 banks), and issues
-// one MFMA.  A wave's lists form one stream of list blocks (six steps each) in consumption order
-// (range after range, block of functions after block), prefetched three list blocks ahead
-// through a ring of four register sets; accumulators persist across ranges.  A table's list
-// for one range is padded to whole list blocks with coefficient 0 (the matrix pipe has time to
-// spare: the launch is bound by memory).
+// one MFMA.
+//
+// With the samples gathered once per table, what is left to stream per tile is the lists: they
+// come from L2, many times the bytes of the tile itself, and set the pace of the launch.  So
+// they are kept small: a list block of U steps holds U x 64 coefficients (one per lane and
+// step) and, apart from them, one record of U 16-bit offsets per sample slot l / 16, which the
+// sixteen lanes of a slot all read from the same address (a few bytes per block out of L2
+// instead of a word per lane and step).
+//
+// The lists are also what a wave waits for if they arrive late, so they are asked for well ahead: a
+// wave's list blocks (U steps each) form one stream in consumption order (range after range,
+// block of functions after block) that runs through a ring of four register sets, a block
+// being requested while the block three places before it is used.  The position in the ring
+// must be the same on every path through the code (the compiler counts outstanding loads per
+// path and otherwise waits for the newest), so list lengths are uniform: all lists of a range
+// are padded with zero coefficients to the longest one, which is either one block for every
+// range (short lists: the 16 blocks of a wave go round the ring) or a multiple of four blocks
+// (a list goes round the ring whole turns).  The matrix pipe has time to spare for the padding
+// steps: with the lists on time the launch is bound by reading the data.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -40,10 +55,10 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 constexpr int kCWs = (int)kRangeComputeWaves;  // contracting waves
 constexpr int kLWs = 4;                        // loading waves: wave kCWs + s loads vectors 4s .. 4s + 3
 constexpr int kThreadsSR = (kCWs + kLWs) * 64;
+constexpr int kLongRing = 4;                   // ring sets for long lists (short lists: four)
 constexpr int kCs = (int)kRangeCoords;
 constexpr int kRowFloats = kCs + 4;            // row stride: 4 floats of padding spread the vectors over the banks
 constexpr int kBufBytesSR = 16 * kRowFloats * 4;
-constexpr int kUs = (int)kSharedRangeBlockSteps;  // MFMA steps per lane in a list block
 
 // Returns v through an empty asm: values derived from it are recomputed where they are used
 // instead of being kept in registers across the contraction loops.
@@ -60,13 +75,17 @@ struct SharedRangedArgs {
     float w, inv_w;
     int w_is_pow2, proj;
     void *out;
-    const uint2 *lists;  // list blocks: kUs x 64 lanes x {coefficient bits, LDS byte offset}
+    const float *coefs;     // list blocks: U steps x 64 lanes
+    const uint32_t *offs;   // per list block: 4 sample slots x (U + 1) / 2 words of two 16-bit LDS byte offsets
 };
 
-template <int BPW>
+// BPW: blocks of 16 functions per contracting wave; U: steps per list block; SHORT: every list is one block
+template <int BPW, int U, bool SHORT>
 __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedRangedArgs a,
-                                                                   const uint32_t *__restrict__ list_len,
+                                                                   const uint32_t *__restrict__ range_groups,
                                                                    const uint2 *__restrict__ streams) {
+    static_assert(!SHORT || BPW % 4 == 0, "short lists go round the ring of four by blocks");
+    constexpr int NR = SHORT ? 4 : kLongRing;  // ring sets
     extern __shared__ __align__(16) char lds_sr[];  // 2 buffers x [16 vectors][1028 floats]
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
@@ -76,7 +95,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
 
     if (wave >= (uint32_t)kCWs) {
         // ---- loading waves: four vectors each, a vector's range as four pieces of 256 coordinates
-        // (a wave instruction moves 1 KB of one vector), two vectors at a time
+        // (a wave instruction moves 1 KB of one vector), all sixteen pieces in flight at once
         const uint32_t v0 = (wave - kCWs) * 4;
         uint64_t t_next = first_tile;
         uint32_t r_next = 0, b = 1;
@@ -85,31 +104,28 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
             if (more) {
                 const uint32_t c0 = r_next * kCs;
                 char *dst = lds_sr + (b ^ 1) * kBufBytesSR + lane * 16;
+                floatx4 pre[4][4];
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    floatx4 pre[2][4];
+                for (int v = 0; v < 4; ++v) {
+                    uint64_t row = t_next * 16 + v0 + v;
+                    row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
+                    const float *src = a.data + row * n;
 #pragma unroll
-                    for (int v = 0; v < 2; ++v) {
-                        uint64_t row = t_next * 16 + v0 + 2 * half + v;
-                        row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
-                        const float *src = a.data + row * n;
-#pragma unroll
-                        for (int piece = 0; piece < 4; ++piece) {
-                            const uint32_t c = c0 + piece * 256 + lane * 4;
-                            // coordinates beyond n read the row's first ones; zeros are stored for them
-                            pre[v][piece] = *reinterpret_cast<const floatx4 *>(src + (c < n ? c : 0u));
-                        }
+                    for (int piece = 0; piece < 4; ++piece) {
+                        const uint32_t c = c0 + piece * 256 + lane * 4;
+                        // coordinates beyond n read the row's first ones; zeros are stored for them
+                        pre[v][piece] = *reinterpret_cast<const floatx4 *>(src + (c < n ? c : 0u));
                     }
-#pragma unroll
-                    for (int v = 0; v < 2; ++v)
-#pragma unroll
-                        for (int piece = 0; piece < 4; ++piece) {
-                            const bool inside = c0 + piece * 256 + lane * 4 < n;
-                            const floatx4 x = pre[v][piece];
-                            const floatx4 z = {inside ? x[0] : 0.f, inside ? x[1] : 0.f, inside ? x[2] : 0.f, inside ? x[3] : 0.f};
-                            *reinterpret_cast<floatx4 *>(dst + (v0 + 2 * half + v) * kRowFloats * 4 + piece * 1024) = z;
-                        }
                 }
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int piece = 0; piece < 4; ++piece) {
+                        const bool inside = c0 + piece * 256 + lane * 4 < n;
+                        const floatx4 x = pre[v][piece];
+                        const floatx4 z = {inside ? x[0] : 0.f, inside ? x[1] : 0.f, inside ? x[2] : 0.f, inside ? x[3] : 0.f};
+                        *reinterpret_cast<floatx4 *>(dst + (v0 + v) * kRowFloats * 4 + piece * 1024) = z;
+                    }
             }
             __syncthreads();
             if (!more) break;
@@ -125,28 +141,29 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
     // ---- contracting waves
     const uint32_t stream_id = blockIdx.y * kCWs + wave;
     const uint2 si = streams[stream_id];  // {first list block, list blocks}
-    const uint2 *sbase = a.lists + (size_t)si.x * (kUs * 64) + lane;
-    const uint32_t sblocks = si.y;
-    const uint32_t *len_base = list_len + (size_t)stream_id * R * BPW;
-    // List registers: a ring of four blocks.  Block i of the stream lives in ring[i % 4]; when
-    // block i is about to be used, block i + 3 is asked for (into the set used just before), so
-    // a block has the time of three others to arrive: a table's list for one range is rarely
-    // longer than one block, far shorter than a trip to L2.  The ring position is static in the
-    // code: the loop over a list's blocks is entered at the position where the last list ended.
-    uint2 ring[4][kUs];
+    constexpr int OW = (U + 1) / 2;  // words of offsets per sample slot and block
+    // uniform block pointers plus a per-lane index: the loads take a scalar base and a 32-bit lane offset
+    const float *cbase = a.coefs + (size_t)si.x * (U * 64);
+    const uint32_t *obase = a.offs + (size_t)si.x * (4 * OW);
+    const uint32_t oslot = (lane >> 4) * OW;
+    const uint32_t sblocks = si.y;  // at least the ring
+    // Block i of the stream lives in ring set i % NR; when block i is about to be used, block
+    // i + NR - 1 is requested into the set used just before.
+    float ring_c[NR][U];
+    uint32_t ring_o[NR][OW];
     uint32_t next_block = 0;
-    auto load_block = [&](uint2 (&blk)[kUs]) __attribute__((always_inline)) {
-        const uint2 *src = sbase + (size_t)next_block * (kUs * 64);
+    auto load_block = [&](int set) __attribute__((always_inline)) {
+        const float *cs = cbase + (size_t)next_block * (U * 64);
+        const uint32_t *os = obase + (size_t)next_block * (4 * OW);
 #pragma unroll
-        for (int i = 0; i < kUs; ++i) blk[i] = src[i * 64];
+        for (int i = 0; i < U; ++i) ring_c[set][i] = cs[i * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < OW; ++i) ring_o[set][i] = os[oslot + i];
         next_block = next_block + 1 == sblocks ? 0 : next_block + 1;
+        __builtin_amdgcn_sched_barrier(0);  // the request stays here, three blocks ahead of its use
     };
-    if (sblocks) {
-        load_block(ring[0]);
-        load_block(ring[1]);
-        load_block(ring[2]);
-    }
-    uint32_t phase = 0;  // ring set of the next block to use
+#pragma unroll
+    for (int i = 0; i < NR - 1; ++i) load_block(i);
     const uint32_t row_off = (lane & 15) * kRowFloats * 4;  // this lane's vector in the tile
 
     __syncthreads();  // first buffer written
@@ -157,41 +174,39 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
         for (int f = 0; f < BPW; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
         for (uint32_t r = 0; r < R; ++r) {
             const char *buf = lds_sr + b * kBufBytesSR + row_off;
+            // one block: all reads, then the MFMAs
+            auto run = [&](int set, floatx4 &c) __attribute__((always_inline)) {
+                float x[U];
+                // the offsets are taken apart here, not where they were requested (which would wait for them there)
 #pragma unroll
-            for (int f = 0; f < BPW; ++f) {
-                uint32_t left = len_base[r * BPW + f];  // list blocks of kUs steps (the last one padded with zero steps)
-                // one block: all reads, then the MFMAs (padding steps multiply zeros: the matrix pipe has time to spare)
-                auto run = [&](const uint2 (&blk)[kUs]) __attribute__((always_inline)) {
-                    float x[kUs];
+                for (int i = 0; i < OW; ++i) asm volatile("" : "+v"(ring_o[set][i]));
 #pragma unroll
-                    for (int s = 0; s < kUs; ++s) x[s] = *reinterpret_cast<const float *>(buf + blk[s].y);
+                for (int s = 0; s < U; ++s) {
+                    const uint32_t off = (ring_o[set][s >> 1] >> (16 * (s & 1))) & 0xFFFFu;
+                    x[s] = *reinterpret_cast<const float *>(buf + off);
+                }
 #pragma unroll
-                    for (int s = 0; s < kUs; ++s)
-                        acc[f] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(blk[s].x), x[s], acc[f], 0, 0, 0);
-                };
-                while (left) {
-                    switch (phase) {
-                        case 0:
-                            load_block(ring[3]);
-                            run(ring[0]);
-                            if (--left == 0) { phase = 1; break; }
-                            [[fallthrough]];
-                        case 1:
-                            load_block(ring[0]);
-                            run(ring[1]);
-                            if (--left == 0) { phase = 2; break; }
-                            [[fallthrough]];
-                        case 2:
-                            load_block(ring[1]);
-                            run(ring[2]);
-                            if (--left == 0) { phase = 3; break; }
-                            [[fallthrough]];
-                        default:
-                            load_block(ring[2]);
-                            run(ring[3]);
-                            --left;
-                            phase = 0;
-                    }
+                for (int s = 0; s < U; ++s) c = __builtin_amdgcn_mfma_f32_16x16x4f32(ring_c[set][s], x[s], c, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            if constexpr (SHORT) {
+#pragma unroll
+                for (int f = 0; f < BPW; ++f) {
+                    load_block((f + 3) & 3);
+                    run(f & 3, acc[f]);
+                }
+            } else {
+                const uint32_t groups = range_groups[r];  // turns of the ring per list in this range, at least one
+#pragma unroll
+                for (int f = 0; f < BPW; ++f) {
+                    uint32_t left = groups;
+                    do {
+#pragma unroll
+                        for (int q = 0; q < NR; ++q) {
+                            load_block((q + NR - 1) % NR);
+                            run(q, acc[f]);
+                        }
+                    } while (--left);
                 }
             }
             if (r + 1 == R) {
@@ -242,8 +257,8 @@ SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t
     pl.kblocks = (pl.nblocks + per_wg_max - 1) / per_wg_max;
     const uint32_t per_wg = (pl.nblocks + pl.kblocks - 1) / pl.kblocks;
     pl.bpw = (per_wg + kRangeComputeWaves - 1) / kRangeComputeWaves;
-    // instantiated: 1, 2, 4, 8, 16 blocks per wave
-    uint32_t inst = 1;
+    // instantiated: 4, 8, 16 blocks per wave (blocks beyond the last one hold zero lists)
+    uint32_t inst = 4;
     while (inst < pl.bpw) inst *= 2;
     pl.bpw = inst;
     pl.R = (n + kRangeCoords - 1) / kRangeCoords;
@@ -254,16 +269,18 @@ SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t
 // Host tables: per contracting wave one stream of list blocks in consumption order (range after
 // range, within a range the wave's blocks one after the other); per step and lane the
 // coefficient of (row l % 16, sample l / 16) and the LDS byte offset of that sample's coordinate
-// inside the range.
-void build_shared_ranged_tables(const lsh_params *p, std::vector<uint32_t> &lists, std::vector<uint32_t> &list_len,
-                                std::vector<uint32_t> &stream_info) {
-    const SharedRangedPlan &pl = p->shared_ranged_plan;
-    const uint32_t R = pl.R, CW = kRangeComputeWaves, U = kSharedRangeBlockSteps, bpw = pl.bpw, m = p->m;
+// inside the range.  Chooses the list layout (steps per block, short or long lists) and notes
+// it in the plan; range_groups holds, per range, the turns of the ring a list takes (long lists).
+void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::vector<uint32_t> &offs,
+                                std::vector<uint32_t> &range_groups, std::vector<uint32_t> &stream_info) {
+    SharedRangedPlan &pl = p->shared_ranged_plan;
+    const uint32_t R = pl.R, CW = kRangeComputeWaves, bpw = pl.bpw, m = p->m;
     const uint32_t tables = pl.nblocks / pl.blocks_per_table, streams = pl.kblocks * CW;
     // per table and range: the samples dealt to steps of four, coordinates of a step distinct
     // modulo 4 where the classes allow it; 0xFFFFFFFF marks a padding slot
     constexpr uint32_t kPad = 0xFFFFFFFFu;
     std::vector<std::vector<uint32_t>> slots((size_t)tables * R);
+    std::vector<uint32_t> longest(R, 0);  // steps of the longest list of a range
     for (uint32_t table = 0; table < tables; ++table) {
         const uint32_t *S = &p->idx[(size_t)table * pl.g * m];
         std::vector<std::vector<uint32_t>> cls((size_t)R * 4);
@@ -290,51 +307,72 @@ void build_shared_ranged_tables(const lsh_params *p, std::vector<uint32_t> &list
                     }
                 }
             }
+            longest[r] = std::max(longest[r], (uint32_t)out.size() / 4);
         }
     }
-    list_len.assign((size_t)streams * R * bpw, 0);
+    // layout: short lists (one block of up to 8 steps per list) if every list fits, else whole
+    // turns of the long-list ring (4 blocks of 3 to 8 steps), whichever pads least
+    const uint32_t top = *std::max_element(longest.begin(), longest.end());
+    range_groups.assign(R, 1);
+    if (top <= 8) {
+        pl.short_lists = true;
+        pl.block_steps = std::max(top, 3u);
+    } else {
+        pl.short_lists = false;
+        uint64_t best = ~0ull;
+        for (uint32_t u = 3; u <= 8; ++u) {
+            uint64_t cost = 0;
+            for (uint32_t r = 0; r < R; ++r) cost += std::max(1u, (longest[r] + kLongRing * u - 1) / (kLongRing * u)) * kLongRing * u;
+            if (cost <= best) {  // ties: the larger block (requests reach further ahead)
+                best = cost;
+                pl.block_steps = u;
+            }
+        }
+        for (uint32_t r = 0; r < R; ++r)
+            range_groups[r] = std::max(1u, (longest[r] + kLongRing * pl.block_steps - 1) / (kLongRing * pl.block_steps));
+    }
+    const uint32_t U = pl.block_steps, OW = (U + 1) / 2;
+    std::vector<uint32_t> list_blocks(R);
+    uint32_t per_stream = 0;
+    for (uint32_t r = 0; r < R; ++r) {
+        list_blocks[r] = pl.short_lists ? 1 : kLongRing * range_groups[r];
+        per_stream += list_blocks[r] * bpw;
+    }
     stream_info.assign((size_t)streams * 2, 0);
-    lists.clear();
-    uint32_t blocks = 0;
+    coefs.assign((size_t)streams * per_stream * U * 64, 0.f);
+    offs.assign((size_t)streams * per_stream * 4 * OW, 0u);
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
-            const uint32_t start = blocks;
+            const uint32_t stream = y * CW + cw;
+            uint32_t blocks = stream * per_stream;
+            stream_info[(size_t)stream * 2] = blocks;
+            stream_info[(size_t)stream * 2 + 1] = per_stream;
             for (uint32_t r = 0; r < R; ++r)
-                for (uint32_t f = 0; f < bpw; ++f) {
+                for (uint32_t f = 0; f < bpw; ++f, blocks += list_blocks[r]) {
                     const uint32_t blk = (y * bpw + f) * CW + cw;
-                    if (blk >= pl.nblocks) continue;
+                    if (blk >= pl.nblocks) continue;  // a list of zeros
                     const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
                     const std::vector<uint32_t> &sl = slots[(size_t)table * R + r];
                     const uint32_t steps = (uint32_t)sl.size() / 4;
-                    const uint32_t nb = (steps + U - 1) / U;  // the steps that pad the last block multiply by zero
-                    list_len[((size_t)(y * CW + cw) * R + r) * bpw + f] = nb;
-                    lists.resize((size_t)(blocks + nb) * U * 64 * 2, 0u);
                     for (uint32_t s = 0; s < steps; ++s)
                         for (uint32_t kq = 0; kq < 4; ++kq) {
                             const uint32_t smp = sl[(size_t)s * 4 + kq];
-                            const uint32_t coord = smp == kPad ? 0 : p->idx[(size_t)table * pl.g * m + smp] - r * kRangeCoords;
-                            for (uint32_t i = 0; i < 16; ++i) {
-                                float c = 0.f;
-                                if (smp != kPad && first + i < pl.g) c = p->coef[(size_t)(table * pl.g + first + i) * m + smp];
-                                uint32_t bits;
-                                std::memcpy(&bits, &c, 4);
-                                const size_t at = (((size_t)blocks + s / U) * U + s % U) * 64 + kq * 16 + i;
-                                lists[at * 2] = bits;
-                                lists[at * 2 + 1] = coord * 4;
-                            }
+                            if (smp == kPad) continue;
+                            const size_t block = (size_t)blocks + s / U;
+                            const uint32_t in_block = s % U;
+                            const uint32_t coord = p->idx[(size_t)table * pl.g * m + smp] - r * kRangeCoords;
+                            offs[(block * 4 + kq) * OW + in_block / 2] |= (coord * 4) << (16 * (in_block & 1));
+                            for (uint32_t i = 0; i < 16 && first + i < pl.g; ++i)  // rows beyond the table keep zero
+                                coefs[(block * U + in_block) * 64 + kq * 16 + i] = p->coef[(size_t)(table * pl.g + first + i) * m + smp];
                         }
-                    blocks += nb;
                 }
-            stream_info[(size_t)(y * CW + cw) * 2] = start;
-            stream_info[(size_t)(y * CW + cw) * 2 + 1] = blocks - start;
         }
-    if (lists.empty()) lists.assign(2, 0u);
 }
 
 // proj != 0: raw projections instead of bucket ids
 int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uint64_t N, void *d_out, void *stream) {
     const SharedRangedPlan &pl = p->shared_ranged_plan;
-    if (!pl.supported || !p->d_sr_lists) return LSH_ERR_UNSUPPORTED;
+    if (!pl.supported || !p->d_sr_lists || !p->d_sr_offs) return LSH_ERR_UNSUPPORTED;
     SharedRangedArgs a;
     a.data = d_data;
     a.N = N;
@@ -351,8 +389,9 @@ int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uin
     a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
     a.proj = proj;
     a.out = d_out;
-    a.lists = static_cast<const uint2 *>(p->d_sr_lists);
-    const uint32_t *len = static_cast<const uint32_t *>(p->d_sr_list_len);
+    a.coefs = static_cast<const float *>(p->d_sr_lists);
+    a.offs = static_cast<const uint32_t *>(p->d_sr_offs);
+    const uint32_t *groups = static_cast<const uint32_t *>(p->d_sr_list_len);
     const uint2 *streams = static_cast<const uint2 *>(p->d_sr_stream);
     const uint64_t ntiles = (N + 15) / 16;
     // one workgroup per CU (two 64 KB buffers); the kblocks workgroups of a tile run on one XCD
@@ -361,18 +400,30 @@ int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uin
     if (gx > ntiles) gx = ntiles;
     const dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-#define LSH_SR_CASE(B_) \
-    case B_: { \
-        auto fn = &shared_ranged_kernel<B_>; \
+#define LSH_SR_LAUNCH(B_, U_, S_) \
+    { \
+        auto fn = &shared_ranged_kernel<B_, U_, S_>; \
         if (ensure_lds_limit(reinterpret_cast<const void *>(fn), 2 * kBufBytesSR) != LSH_OK) return LSH_ERR_HIP; \
-        hipLaunchKernelGGL(fn, grid, dim3(kThreadsSR), 2 * kBufBytesSR, s, a, len, streams); \
-        break; \
+        hipLaunchKernelGGL(fn, grid, dim3(kThreadsSR), 2 * kBufBytesSR, s, a, groups, streams); \
     }
+#define LSH_SR_STEPS(B_, U_) \
+    case U_: \
+        if (pl.short_lists) LSH_SR_LAUNCH(B_, U_, true) else LSH_SR_LAUNCH(B_, U_, false) \
+        break;
+#define LSH_SR_CASE(B_) \
+    case B_: \
+        switch (pl.block_steps) { \
+            LSH_SR_STEPS(B_, 3) LSH_SR_STEPS(B_, 4) LSH_SR_STEPS(B_, 5) LSH_SR_STEPS(B_, 6) LSH_SR_STEPS(B_, 7) LSH_SR_STEPS(B_, 8) \
+            default: return LSH_ERR_UNSUPPORTED; \
+        } \
+        break;
     switch (pl.bpw) {
-        LSH_SR_CASE(1) LSH_SR_CASE(2) LSH_SR_CASE(4) LSH_SR_CASE(8) LSH_SR_CASE(16)
+        LSH_SR_CASE(4) LSH_SR_CASE(8) LSH_SR_CASE(16)
         default: return LSH_ERR_UNSUPPORTED;
     }
 #undef LSH_SR_CASE
+#undef LSH_SR_STEPS
+#undef LSH_SR_LAUNCH
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
 
