@@ -137,6 +137,20 @@ def dense_roofline(N, n, k, ms, arithmetic, traffic=None):
             "fp32_equivalent_tflops": tf}
 
 
+def shared_roofline(N, n, k, m, ms):
+    """One sample per table: the gathered coordinates of a table meet its functions on the fp32
+    matrix cores (2 k m flops per vector); the roofline that binds is the one with the longer
+    ideal time."""
+    hbm = hbm_roofline(N * (4 * n + 4 * k), ms)
+    tf = 2.0 * N * k * m / (ms * 1e-3) / 1e12
+    mfma = {"bound": "mfma", "achieved": tf, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": tf / MFMA_FP32_PEAK_TFLOPS, "traffic": None}
+    first, second = (hbm, mfma) if hbm["frac"] >= mfma["frac"] else (mfma, hbm)
+    first = dict(first)
+    first["other"] = second
+    return first
+
+
 def parity_ids(torch, oracle, threads, host_rows, got_ids, got_proj, tables, w, dense):
     """Sampled rows against the oracle: ids outside the boundary band must agree; reports the
     excluded fraction and how many projections meet a plain relative 1e-5."""
@@ -411,6 +425,18 @@ class Bench:
                 e["speedup_over_e2lsh"] = ms["e2lsh"] / ms[leg]
                 e["operation_count_ratio_n_over_m"] = n / p.m
             entries.append(e)
+        # the variant with one sample S per table (Sec. 3.1 read literally), timed outside the step
+        L = wl.L or 128
+        for m in wl.m:
+            with lsh.LshParams(n, k, m, wl.w, wl.seed, shared_tables=L) as p:
+                sms = self.timer.measure(lambda: lsh.hash_fastlsh(p, data, out=out))
+                entries.append({"workload": "highdim", "call": "lsh_hash_fastlsh", "variant": "one sample per table",
+                                "L": L, "N": N, "n": n, "k": k, "m": m, "w": wl.w, "ms": sms,
+                                "hashes_per_s": N * k / (sms * 1e-3), "vectors_per_s": N / (sms * 1e-3),
+                                "dtype": "f32", "timed": "outside the step",
+                                "parity": self.check_ids(p, wl, data, out, dense=False),
+                                "roofline": shared_roofline(N, n, k, m, sms),
+                                "speedup_over_per_function_samples": ms[f"fastlsh_m{m}"] / sms})
         dominant = max(legs, key=lambda leg: ms[leg])
         dom = entries[legs.index(dominant)]
         result = {"elapsed": elapsed, "ms": ms, "entries": entries, "dominant": dominant, "roofline": dom["roofline"],

@@ -80,8 +80,10 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
  * Every hash call accepts such an object; lsh_hash_fastlsh, lsh_project_fastlsh and (called
  * with the same L, g <= 32) lsh_hash_fastlsh_keys then gather each table's sub-vector once and
  * contract it with the g coefficient vectors on the matrix cores when the shape allows
- * (n % 4 == 0, g % 4 == 0, and m <= 64 with n <= 612 or 64 < m <= 128 with n <= 1260), and
- * fall back to the per-function gather kernels otherwise.  L == 0 is lsh_params_create_ex.
+ * (n % 4 == 0 and g % 4 == 0; lsh_hash_fastlsh_keys only with m <= 64 and n <= 612 or
+ * 64 < m <= 128 and n <= 1260, where whole vectors stay in LDS; ids and projections at any
+ * larger n or m < n too, by coordinate ranges), and fall back to the per-function gather
+ * kernels otherwise.  L == 0 is lsh_params_create_ex.
  * Errors: as lsh_params_create, and INVALID_ARG when k % L != 0.
  */
 int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,
@@ -169,12 +171,17 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
  * 1e-5 * sum_i |a_i v_i| of the exact value as the fp32 path.  (Operands whose bf16 rounding
  * overflows, |x| > 3.39e38, give NaN there.)  Products of terms that are zero for a whole tile
  * of 64 vectors are skipped, which changes no bit of the result: byte-valued data take half of
- * the products.  Other shapes use fp32 MFMA.  With n == 128 and k a multiple of 64,
+ * the products.  With n == 128 and k a multiple of 64,
  * lsh_hash_signs runs on the matrix cores too, with two-way splits and three products: what
  * they leave out is below 3 * 2^-16 * sum_i |a_i v_i|, under half of the 1e-4 * |a| * |S(v)| around
- * zero inside which a sign bit is unspecified.
+ * zero inside which a sign bit is unspecified.  Objects with m == n and another n that is a
+ * multiple of 4 take the same six products in lsh_hash_e2lsh and lsh_project_e2lsh (no
+ * products skipped); any other shape uses fp32 MFMA.
  * LSH_DENSE_FP32: fp32 MFMA for every dense product, and the gathered fp32 kernels for FastLSH
  * ids, projections, keys and signs at every n.
+ * The mode is a plain field of the object, read by every hash call when it launches: set it
+ * while no other thread is calling into the same object (calls already enqueued keep the mode
+ * they were launched with).
  * Errors: INVALID_ARG (null, unknown mode).
  */
 #define LSH_DENSE_AUTO 0
