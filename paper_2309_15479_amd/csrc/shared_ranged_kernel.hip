@@ -340,7 +340,11 @@ void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::v
     }
     stream_info.assign((size_t)streams * 2, 0);
     coefs.assign((size_t)streams * per_stream * U * 64, 0.f);
+    // steps and slots that only pad (coefficient zero) read coordinate kq of the range: four different
+    // banks per vector, like a step of real samples
     offs.assign((size_t)streams * per_stream * 4 * OW, 0u);
+    for (size_t rec = 0; rec < offs.size() / OW; ++rec)
+        for (uint32_t s = 0; s < U; ++s) offs[rec * OW + s / 2] |= ((uint32_t)(rec & 3) * 4u) << (16 * (s & 1));
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
             const uint32_t stream = y * CW + cw;
@@ -361,7 +365,8 @@ void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::v
                             const size_t block = (size_t)blocks + s / U;
                             const uint32_t in_block = s % U;
                             const uint32_t coord = p->idx[(size_t)table * pl.g * m + smp] - r * kRangeCoords;
-                            offs[(block * 4 + kq) * OW + in_block / 2] |= (coord * 4) << (16 * (in_block & 1));
+                            uint32_t &word = offs[(block * 4 + kq) * OW + in_block / 2];
+                            word = (word & ~(0xFFFFu << (16 * (in_block & 1)))) | (coord * 4) << (16 * (in_block & 1));
                             for (uint32_t i = 0; i < 16 && first + i < pl.g; ++i)  // rows beyond the table keep zero
                                 coefs[(block * U + in_block) * 64 + kq * 16 + i] = p->coef[(size_t)(table * pl.g + first + i) * m + smp];
                         }
