@@ -39,11 +39,24 @@ PROJ_RTOL = 1e-5   # projections: |dp| <= PROJ_RTOL * sum_i |a_i v_i|  (pass/fai
 CSRC = os.path.join(ROOT, "paper_2309_15479_amd", "csrc")
 
 # HBM bytes per launch from rocprofv3's FETCH_SIZE and WRITE_SIZE counters (two runs, each scaled
-# by what the same counter reads for a 1 GiB device copy), per kernel and workload:
-# name -> (fetch bytes, write bytes, summary under profiles/, {source file: sha256 prefix of the
-# kernel source the counters were taken on}).  An entry is reported only while its source files
-# still hash to the recorded values; otherwise `traffic` is null.
+# by what the same counter reads for a 1 GiB device copy: factors 1.0000 and 1.0000), per kernel
+# and workload: name -> (fetch bytes, write bytes, summary under profiles/, {source file: sha256
+# prefix of the kernel source the counters were taken on}).  An entry is reported only while its
+# source files still hash to the recorded values; otherwise `traffic` is null.  (FETCH_SIZE counts
+# 64 bytes per read request and these kernels fetch 128-byte lines: a lower bound, see the summary.)
+_KIB = 1024
+_RANGED = {"ranged_kernel.hip": "3bd441f908fde17f", "sampled_common.h": "99849688e06e600e"}
+_SUMMARY = "profiles/hbm_traffic_all_workloads.md"
 MEASURED_TRAFFIC = {
+    "highdim/fastlsh/m64": (1871689 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
+    "highdim/fastlsh/m256": (2398575 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
+    "highdim/fastlsh/m1024": (4341454 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
+    "highdim/e2lsh": (15523701 * _KIB, 3022842 * _KIB, _SUMMARY, {"dense_split_wide_kernel.hip": "9b3b9b757a0619f0"}),
+    "sift/fastlsh/m32": (250605 * _KIB, 2000000 * _KIB, _SUMMARY,
+                         {"sampled_kernel.hip": "92f92fc2d9bc2268", "sampled_common.h": "99849688e06e600e"}),
+    "gist/fastlsh/m128": (2373356 * _KIB, 4000000 * _KIB, _SUMMARY,
+                          {"sampled_kernel.hip": "92f92fc2d9bc2268", "sampled_common.h": "99849688e06e600e"}),
+    "angular/signs/m512": (73894811 * _KIB, 250635 * _KIB, _SUMMARY, _RANGED),
 }
 
 
@@ -53,13 +66,31 @@ def source_hash(name):
 
 
 def traffic_of(key):
+    """HBM bytes per launch from the counters (a number), or None when there is no figure for the
+    kernel as it stands."""
     entry = MEASURED_TRAFFIC.get(key)
     if not entry:
         return None
     fetch, write, summary, sources = entry
     if any(source_hash(f) != h for f, h in sources.items()):
         return None
-    return {"bytes": fetch + write, "fetch_bytes": fetch, "write_bytes": write, "from": summary}
+    return fetch + write
+
+
+def with_traffic(roofline, key):
+    """Attaches the measured HBM traffic of `key` (bytes per launch, and where it comes from)."""
+    roofline["traffic"] = traffic_of(key)
+    detail = traffic_detail(key)
+    if detail:
+        roofline["traffic_detail"] = detail
+    return roofline
+
+
+def traffic_detail(key):
+    entry = MEASURED_TRAFFIC.get(key)
+    if not entry or traffic_of(key) is None:
+        return None
+    return {"fetch_bytes": entry[0], "write_bytes": entry[1], "from": entry[2]}
 
 
 class Timer:
@@ -243,7 +274,7 @@ class Bench:
             entry["schedule"] = padding_ratio(p)
         entry.update({"ms": ms, "hashes_per_s": N * k / (ms * 1e-3), "vectors_per_s": N / (ms * 1e-3),
                       "dtype": "f32",
-                      "roofline": gather_roofline(N, n, k, m, 4 * k, ms, traffic_of(f"{wl.name}/fastlsh/m{m}"))})
+                      "roofline": with_traffic(gather_roofline(N, n, k, m, 4 * k, ms), f"{wl.name}/fastlsh/m{m}")})
         return entry
 
     def e2lsh_entry(self, wl, data, out):
@@ -274,7 +305,7 @@ class Bench:
                 arithmetic = "fp32"
         entry.update({"ms": ms, "hashes_per_s": N * k / (ms * 1e-3), "vectors_per_s": N / (ms * 1e-3),
                       "dtype": "f32" if arithmetic == "fp32" else "bf16x3+f32acc",
-                      "roofline": dense_roofline(N, n, k, ms, arithmetic, traffic_of(f"{wl.name}/e2lsh"))})
+                      "roofline": with_traffic(dense_roofline(N, n, k, ms, arithmetic), f"{wl.name}/e2lsh")})
         entry["roofline"]["hbm_frac"] = N * (4 * n + 4 * k) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         return entry
 
@@ -293,8 +324,8 @@ class Bench:
                 entry = {"workload": name, "call": "lsh_hash_signs", "N": N, "n": n, "k": k, "m": m,
                          "ms": ms, "hashes_per_s": N * k / (ms * 1e-3), "vectors_per_s": N / (ms * 1e-3),
                          "dtype": "f32", "schedule": padding_ratio(p),
-                         "roofline": gather_roofline(N, n, k, m, 8 * ((k + 63) // 64), ms,
-                                                     traffic_of(f"{name}/signs/m{m}"))}
+                         "roofline": with_traffic(gather_roofline(N, n, k, m, 8 * ((k + 63) // 64), ms),
+                                                  f"{name}/signs/m{m}")}
                 if not self.args.no_parity:
                     import numpy as np
                     rows = self.rows(wl, 48)
@@ -318,7 +349,7 @@ class Bench:
                 ms = self.timer.measure(lambda: lsh.pack_keys(p, out, wl.L, out=keys))
                 entries.append({"workload": name, "call": "lsh_pack_keys", "N": N, "k": k, "L": wl.L, "ms": ms,
                                 "dtype": "u64",
-                                "roofline": hbm_roofline(N * (4 * k + 8 * wl.L), ms, traffic_of(f"{name}/pack_keys"))})
+                                "roofline": with_traffic(hbm_roofline(N * (4 * k + 8 * wl.L), ms), f"{name}/pack_keys")})
                 if not self.args.no_parity:
                     import numpy as np
                     rows = self.rows(wl, 96)
@@ -411,7 +442,7 @@ class Bench:
                  "parity": self.check_ids(p, wl, data, out, dense, count=48 if dense else 96)}
             if dense:
                 e["dtype"] = "bf16x3+f32acc"
-                e["roofline"] = dense_roofline(N, n, k, ms[leg], {"products": 6}, traffic_of("highdim/e2lsh"))
+                e["roofline"] = with_traffic(dense_roofline(N, n, k, ms[leg], {"products": 6}), "highdim/e2lsh")
                 e["roofline"]["hbm_frac"] = N * (4 * n + 4 * k) / (ms[leg] * 1e-3) / 1e9 / HBM_PEAK_GBS
                 # the same launch on the fp32 matrix cores, timed outside the step
                 p.set_dense_arithmetic(lsh.DENSE_FP32)
@@ -421,7 +452,7 @@ class Bench:
                 e["speedup_over_fp32_mfma"] = fp32_ms / ms[leg]
             else:
                 e["schedule"] = padding_ratio(p)
-                e["roofline"] = gather_roofline(N, n, k, p.m, 4 * k, ms[leg], traffic_of(f"highdim/fastlsh/m{p.m}"))
+                e["roofline"] = with_traffic(gather_roofline(N, n, k, p.m, 4 * k, ms[leg]), f"highdim/fastlsh/m{p.m}")
                 e["speedup_over_e2lsh"] = ms["e2lsh"] / ms[leg]
                 e["operation_count_ratio_n_over_m"] = n / p.m
             entries.append(e)
