@@ -362,6 +362,25 @@ class Bench:
                                 # at n = 128 this call runs on the matrix cores (dense product with zeros)
                                 "roofline": hbm_roofline(N * (4 * n + 8 * wl.L), ms) if n == 128 else
                                 gather_roofline(N, n, k, wl.m[0], 8 * wl.L, ms)})
+                # ids and keys in one call (one launch on these shapes), against the two launches
+                ids2 = torch.empty_like(out)
+                ms = self.timer.measure(lambda: lsh.hash_fastlsh_ids_keys(p, data, wl.L, out_ids=ids2, out_keys=keys))
+                two = entries[0]["matrix_core_route_ms"] if "matrix_core_route_ms" in entries[0] else entries[0]["ms"]
+                entry = {"workload": name, "call": "lsh_hash_fastlsh_ids_keys", "N": N, "n": n, "k": k, "m": wl.m[0],
+                         "L": wl.L, "ms": ms, "dtype": "f32", "two_launches_ms": two + entries[-2]["ms"],
+                         "roofline": hbm_roofline(N * (4 * n + 4 * k + 8 * wl.L), ms) if n == 128 else
+                         gather_roofline(N, n, k, wl.m[0], 4 * k + 8 * wl.L, ms)}
+                if not self.args.no_parity:
+                    import numpy as np
+                    lsh.hash_fastlsh(p, data, out=out)
+                    rows = self.rows(wl, 96)
+                    entry["parity"] = {
+                        "ids_differing_from_lsh_hash_fastlsh": int((ids2 != out).sum().item()),
+                        "keys_checked": int(rows.numel() * wl.L),
+                        "key_mismatches": int((keys[rows].cpu().numpy().view(np.uint64) !=
+                                               self.oracle.pack_keys(ids2[rows].cpu().numpy(), wl.L)).sum())}
+                entries.append(entry)
+                del ids2
             del keys
         del out, data
         torch.cuda.empty_cache()

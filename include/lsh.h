@@ -216,6 +216,20 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *params, const float *d_data, uint6
                           uint64_t *d_out_keys, void *stream);
 
 /*
+ * Bucket ids AND compound keys (Sec. 3.2) in one pass over the data, for callers that want
+ * both (ids for exact verification or re-ranking, keys for the tables): d_out_buckets as
+ * lsh_hash_fastlsh writes them, d_out_keys as lsh_pack_keys would fold them from exactly those
+ * ids.  One kernel launch, the ids being in registers when the keys are folded, for objects
+ * with one sample per function when g = k/L is 4, 8, 16 or 32 at n == 128 (k a multiple of 32,
+ * default arithmetic), or a power of two from 4 to 64 with k a multiple of 4 on the shapes of
+ * the streamed-list gather kernels (lists too long for registers: the 960-, 4096- and
+ * 16384-dimensional workloads); any other object or L runs the two launches inside the call.
+ * Errors: INVALID_ARG (null pointers, L == 0, k % L != 0), and those of lsh_hash_fastlsh.
+ */
+int lsh_hash_fastlsh_ids_keys(const lsh_params_t *params, const float *d_data, uint64_t N, uint32_t L,
+                              int32_t *d_out_buckets, uint64_t *d_out_keys, void *stream);
+
+/*
  * Raw fp32 projections a~_j^T S_j(v) (before + b, / w, floor), d_out_proj[v*k + j]; for
  * accuracy checks.  lsh_project_e2lsh requires m == n and uses the MFMA path.
  */

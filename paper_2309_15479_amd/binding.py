@@ -25,7 +25,7 @@ EXPORTS = [
     "lsh_params_get_tables", "lsh_params_get_mips_coeffs", "lsh_params_get_schedule",
     "lsh_params_set_dense_arithmetic",
     "lsh_hash_fastlsh",
-    "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys",
+    "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys", "lsh_hash_fastlsh_ids_keys",
     "lsh_project_fastlsh", "lsh_project_e2lsh", "lsh_time_launches", "lsh_status_string",
     "lsh_e2lsh_collision_probability", "lsh_pair_statistics", "lsh_fastlsh_collision_probability",
     "lsh_fastlsh_moment_factors", "lsh_equivalent_width", "lsh_mips_collision_probability",
@@ -83,6 +83,7 @@ def load_library():
     lib.lsh_mips_kappa.argtypes = [p, p, u64, i, p, p]
     lib.lsh_pack_keys.argtypes = [p, p, u64, u32, p, p]
     lib.lsh_hash_fastlsh_keys.argtypes = [p, p, u64, u32, p, p]
+    lib.lsh_hash_fastlsh_ids_keys.argtypes = [p, p, u64, u32, p, p, p]
     lib.lsh_time_launches.argtypes = [p, i, p, u64, u32, p, p, i, ctypes.POINTER(f32)]
     f64 = ctypes.c_double
     lib.lsh_e2lsh_collision_probability.argtypes = [f64, f64, p]
@@ -331,6 +332,18 @@ def hash_fastlsh_keys(params, data, L, out=None, stream=None):
     _check(load_library().lsh_hash_fastlsh_keys(params.handle, data.data_ptr(), N, L, out.data_ptr(),
                                                 _stream(stream)), "lsh_hash_fastlsh_keys")
     return out
+
+
+def hash_fastlsh_ids_keys(params, data, L, out_ids=None, out_keys=None, stream=None):
+    """Bucket ids [N, k] (int32) and compound keys [N, L] (uint64 bit patterns in int64) in one call."""
+    import torch
+    _dev_in(data, torch.float32, params.n)
+    N = data.shape[0]
+    out_ids = _out(data, N, params.k, torch.int32, out_ids)
+    out_keys = _out(data, N, L, torch.int64, out_keys)
+    _check(load_library().lsh_hash_fastlsh_ids_keys(params.handle, data.data_ptr(), N, L, out_ids.data_ptr(),
+                                                    out_keys.data_ptr(), _stream(stream)), "lsh_hash_fastlsh_ids_keys")
+    return out_ids, out_keys
 
 
 _WHICH = {"fastlsh": 0, "e2lsh": 1, "signs": 2, "pack_keys": 3, "fastlsh_keys": 4}

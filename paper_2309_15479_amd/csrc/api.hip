@@ -438,6 +438,25 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
     return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
 }
 
+int lsh_hash_fastlsh_ids_keys(const lsh_params_t *p, const float *d_data, uint64_t N, uint32_t L,
+                              int32_t *d_ids, uint64_t *d_keys, void *stream) {
+    int rc = check_hash_args(p, d_data, d_ids, N);
+    if (rc != LSH_OK) return rc;
+    if (!L || p->k % L || (N && !d_keys)) return LSH_ERR_INVALID_ARG;
+    if (N == 0) return LSH_OK;
+    // one launch where a kernel has the epilogue for it; the results are those of the two calls
+    // either way (the keys are folded from the very ids that are stored)
+    const bool per_function = !p->shared_plan.supported && !p->shared_ranged_plan.supported;
+    if (per_function && p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_keys_supported(p, L))
+        return launch_dense_split(p, 4, d_data, N, d_ids, stream, L, d_keys);
+    if (per_function && !(p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p)) &&
+        sampled_ids_keys_supported(p, L))
+        return launch_sampled(p, Epilogue::IdsKeys, d_data, N, d_ids, L, stream, d_keys);
+    rc = lsh_hash_fastlsh(p, d_data, N, d_ids, stream);
+    if (rc != LSH_OK) return rc;
+    return launch_pack(p, d_ids, N, L, d_keys, stream);
+}
+
 int lsh_mips_kappa(const lsh_params_t *p, const float *d_data, uint64_t N, int accumulate, float *d_kappa2,
                    void *stream) {
     if (!d_kappa2) return LSH_ERR_INVALID_ARG;

@@ -19,7 +19,6 @@
 // every lane then reads 4 consecutive floats (one 16-byte LDS read) per group.
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <type_traits>
 
 #include "lsh_internal.h"
@@ -634,13 +633,7 @@ int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N
 #define LSH_LEAN_CASE(P_, W_) \
     if (proj == P_ && pw == W_) { \
         auto fn = &dense_lean_kernel<P_, W_>; \
-        static std::atomic<bool> granted{false}; \
-        if (!granted.load(std::memory_order_acquire)) { \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
-                return LSH_ERR_HIP; \
-            granted.store(true, std::memory_order_release); \
-        } \
+        if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP; \
         hipLaunchKernelGGL(fn, g2, b2, lds_bytes, s, a); \
     }
             LSH_LEAN_CASE(false, true) LSH_LEAN_CASE(false, false) LSH_LEAN_CASE(true, true) LSH_LEAN_CASE(true, false)
@@ -650,13 +643,7 @@ int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N
 #define LSH_SHORT_CASE(V_, P_, W_) \
     if (vec4 == V_ && proj == P_ && pw == W_) { \
         auto fn = &dense_short_kernel<V_, P_, W_>; \
-        static std::atomic<bool> granted{false};  /* the attribute call costs ~1 ms: once per kernel */ \
-        if (!granted.load(std::memory_order_acquire)) { \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
-                return LSH_ERR_HIP; \
-            granted.store(true, std::memory_order_release); \
-        } \
+        if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP; \
         hipLaunchKernelGGL(fn, g2, b2, lds_bytes, s, a); \
     }
         LSH_SHORT_CASE(true, false, true) LSH_SHORT_CASE(true, false, false)

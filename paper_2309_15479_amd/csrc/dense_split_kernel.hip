@@ -41,7 +41,6 @@
 // are, sign bits are gathered into half a word per vector and wave.
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <cmath>
 #include <type_traits>
 
@@ -81,6 +80,7 @@ struct SplitArgs {
     uint32_t g;         // keys: functions per table, 4, 8, 16 or 32
     float w, inv_w;
     void *out;          // [N][k]; signs [N][k / 64]; keys [N][k / g]
+    void *out2;         // ids and keys in one launch: the keys [N][k / g] (the ids go to out)
 };
 
 __device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &x3) {
@@ -90,13 +90,15 @@ __device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &
     x3 = (__bf16)(r1 - (float)x2);
 }
 
-enum : int { kIds = 0, kProj = 1, kSigns = 2, kKeys = 3 };
+enum : int { kIds = 0, kProj = 1, kSigns = 2, kKeys = 3, kIdsKeys = 4 };
 
 // EP: bucket ids, raw projections (both [N][k], 4 bytes each), sign words ([N][k / 64] of 64
-// bits), or the compound keys of Sec. 3.2 folded from the ids ([N][k / g] of 64 bits)
+// bits), the compound keys of Sec. 3.2 folded from the ids ([N][k / g] of 64 bits), or ids and
+// keys together (the ids are in registers when the keys are folded: one pass over the data
+// instead of a hashing launch and a packing launch that reads the ids back)
 template <int EP, bool POW2>
 __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitArgs a) {
-    constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns, KEYS = EP == kKeys;
+    constexpr bool PROJ = EP == kProj, SIGNS = EP == kSigns, KEYS = EP == kKeys, BOTH = EP == kIdsKeys;
     constexpr int NSPLIT = SIGNS ? 2 : 3;
     // blocks of 32 functions per wave.  Signs: two (their two-way splits leave the registers), so
     // that a workgroup covers 512 functions and a tile is split once where two workgroups of 256
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            if constexpr (EP == kIds || EP == kKeys) {
+            if constexpr (EP == kIds || EP == kKeys || EP == kIdsKeys) {
                 const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
                 bs[i] = POW2 ? b * a.inv_w : b;
             } else {
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t stage_wr = lr * STAGE_ROWB + 16 * lh;                // + 32 q
     const uint32_t stage_rd = (lane >> 3) * STAGE_ROWB + (lane & 7) * 16;  // + 8 j rows
     const uint32_t st_off = ((lane >> 3) * a.k + wf) * 4 + (lane & 7) * 16;  // in a block of 32 x k outputs; below 2^32 (host)
-    uintx4 res[2][(SIGNS || KEYS) ? 1 : 4];  // ids or the bits of the projections
+    uintx4 res[2][(SIGNS || KEYS || BOTH) ? 1 : 4];  // ids or the bits of the projections
     uint32_t sign_word[2][2] = {{0, 0}, {0, 0}};  // [column block][low, high half of the wave's sign word]
     // keys: a lane's four ids of accumulator group q are consecutive functions 8q + 4 (l / 32) ...
     // + 3 of the wave's 32; they are folded by Horner's rule and weighted with the power of C of
@@ -304,7 +306,55 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
             for (uint32_t e = 0; e < expo; ++e) key_weight[q] *= kKeyMultiplier;
         }
     }
+    // the four weighted partial keys of a lane (one per accumulator group) of column block vb:
+    // summed per table inside the lane and across the two lanes that share a vector, and stored
+    // ids and keys: the keys are folded from the staged pieces: lane l then holds the ids of
+    // functions 4 (l % 8) .. + 3 of the wave's 32 for one vector, folds them by Horner's rule,
+    // weights them with the power of C of their place in the table, and the g / 4 neighbouring
+    // lanes of a table add up.  This epilogue stores ids and keys at the end of the tile instead of
+    // spreading the ids over the next tile's steps: the 32 registers that would hold them are
+    // what the fold needs.
+    uint64_t piece_weight = 1;
+    if constexpr (BOTH) {
+        const uint32_t expo = a.g - 4 - ((4 * (lane & 7)) % a.g);
+        for (uint32_t e = 0; e < expo; ++e) piece_weight *= kKeyMultiplier;
+    }
     uint64_t t_settle = 0;  // the tile whose accumulators settle() is given (keys are stored from there)
+    auto store_keys = [&](const uint64_t (&part)[4], int vb) {
+        const uint64_t vec = t_settle * TV + vb * 32 + lr;
+        uint64_t *row = reinterpret_cast<uint64_t *>(a.out) + vec * (a.k / a.g) + wf / a.g;
+        // tables of the wave: 32 / g; a table's parts lie in one or both lanes of the vector
+        if (a.g == 4) {  // uniform; table 2q + l / 32, one part each
+            if (vec < a.N) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) row[2 * q + lh] = part[q];
+            }
+        } else {
+            uint64_t key[4];
+            int tables = 0;
+            if (a.g == 8) {
+                tables = 4;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) key[q] = part[q];
+            } else if (a.g == 16) {
+                tables = 2;
+                key[0] = part[0] + part[1];
+                key[1] = part[2] + part[3];
+                key[2] = key[3] = 0;
+            } else {
+                tables = 1;
+                key[0] = part[0] + part[1] + part[2] + part[3];
+                key[1] = key[2] = key[3] = 0;
+            }
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) {
+                if (tb < tables) {  // uniform
+                    const uint64_t sum = key[tb] + __shfl_xor(key[tb], 32);
+                    if (lh == 0 && vec < a.N) row[tb] = sum;
+                }
+            }
+        }
+    };
     auto settle = [&](const floatx16 (&acc)[FB][2], int vb0, int vb1) {
 #pragma unroll
         for (int vb = 0; vb < 2; ++vb) {
@@ -322,39 +372,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                     }
                     part[q] = fold * key_weight[q];
                 }
-                const uint64_t vec = t_settle * TV + vb * 32 + lr;
-                uint64_t *row = reinterpret_cast<uint64_t *>(a.out) + vec * (a.k / a.g) + wf / a.g;
-                // tables of the wave: 32 / g; a table's parts lie in one or both lanes of the vector
-                if (a.g == 4) {  // uniform; table 2q + l / 32, one part each
-                    if (vec < a.N) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) row[2 * q + lh] = part[q];
-                    }
-                } else {
-                    uint64_t key[4];
-                    int tables = 0;
-                    if (a.g == 8) {
-                        tables = 4;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) key[q] = part[q];
-                    } else if (a.g == 16) {
-                        tables = 2;
-                        key[0] = part[0] + part[1];
-                        key[1] = part[2] + part[3];
-                        key[2] = key[3] = 0;
-                    } else {
-                        tables = 1;
-                        key[0] = part[0] + part[1] + part[2] + part[3];
-                        key[1] = key[2] = key[3] = 0;
-                    }
-#pragma unroll
-                    for (int tb = 0; tb < 4; ++tb) {
-                        if (tb < tables) {  // uniform
-                            const uint64_t sum = key[tb] + __shfl_xor(key[tb], 32);
-                            if (lh == 0 && vec < a.N) row[tb] = sum;
-                        }
-                    }
-                }
+                store_keys(part, vb);
             } else if constexpr (SIGNS) {
                 // bit 8q + 4 (l / 32) + e of a block of 32 functions from accumulator 4q + e; the
                 // two lanes that share a vector then join their halves
@@ -382,6 +400,30 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                     }
                     *reinterpret_cast<uintx4 *>(stage + stage_wr + 32 * q) = v;
                 }
+                if constexpr (BOTH) {
+                    const uint64_t vec0 = t_settle * TV + vb * 32;
+                    const uint32_t first = 4 * (lane & 7);  // of the wave's 32 functions
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {  // piece j: vectors 8j .. 8j + 7, 8 lanes each
+                        const uintx4 v = *reinterpret_cast<const uintx4 *>(stage + stage_rd + 8 * j * STAGE_ROWB);
+                        const uint64_t vec = vec0 + 8 * j + (lane >> 3);
+                        uint64_t fold = v[0];
+#pragma unroll
+                        for (int e = 1; e < 4; ++e) fold = fold * kKeyMultiplier + v[e];
+                        fold *= piece_weight;
+                        if (a.g >= 8) fold += __shfl_xor(fold, 1);  // uniform
+                        if (a.g >= 16) fold += __shfl_xor(fold, 2);
+                        if (a.g >= 32) fold += __shfl_xor(fold, 4);
+                        if (vec < a.N) {
+                            char *dst = reinterpret_cast<char *>(a.out) + (vec0 + 8 * j) * a.k * 4 + st_off;
+                            __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(dst));
+                            if (first % a.g == 0)
+                                reinterpret_cast<uint64_t *>(a.out2)[vec * (a.k / a.g) + (wf + first) / a.g] = fold;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);  // one piece at a time: no registers for four
+                    }
+                    continue;
+                }
                 // the wave's own LDS accesses execute in order: no wait between writes and reads
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -394,7 +436,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     auto store_piece = [&](auto full_tag, uint64_t tile, int piece) {
         const int vb = piece / 4, q = piece % 4;
         const uint64_t vec0 = tile * TV + vb * 32;
-        if constexpr (KEYS) {
+        if constexpr (KEYS || BOTH) {
             return;  // stored by settle()
         } else if constexpr (SIGNS) {
             if (q != 0 || lh != 0) return;
@@ -500,9 +542,9 @@ bool dense_split_signs_supported(const lsh_params *p) {
     return p->n == (uint32_t)SN && p->k % 64 == 0 && p->k <= (1u << 24) && p->d_dense != nullptr;
 }
 
-// ep: 0 bucket ids, 1 raw projections, 2 sign words, 3 keys of L tables
+// ep: 0 bucket ids, 1 raw projections, 2 sign words, 3 keys of L tables, 4 ids (d_out) and keys (d_out2)
 int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
-                       void *stream, uint32_t L) {
+                       void *stream, uint32_t L, void *d_out2) {
     SplitArgs a;
     a.data = d_data;
     a.a = p->d_dense;
@@ -513,8 +555,9 @@ int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_
     a.w = p->w;
     a.inv_w = 1.0f / p->w;
     a.out = d_out;
+    a.out2 = d_out2;
     int exp2 = 0;
-    const bool pw = (ep != kIds && ep != kKeys) || std::frexp(p->w, &exp2) == 0.5f;  // only ids and keys divide
+    const bool pw = (ep != kIds && ep != kKeys && ep != kIdsKeys) || std::frexp(p->w, &exp2) == 0.5f;  // only ids and keys divide
     const uint32_t block_funcs = kFuncsPerBlock * (ep == kSigns ? 2 : 1);
     const uint32_t slices = (p->k + block_funcs - 1) / block_funcs;
     // one workgroup per CU (102 KB of LDS); every XCD needs a workgroup per slice of functions
@@ -526,17 +569,11 @@ int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_
 #define LSH_SPLIT_CASE(E_, W_) \
     if (ep == E_ && pw == W_) { \
         auto fn = &dense_split_kernel<E_, W_>; \
-        static std::atomic<bool> granted{false};  /* the attribute call costs ~1 ms: once per kernel */ \
-        if (!granted.load(std::memory_order_acquire)) { \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fn), \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
-                return LSH_ERR_HIP; \
-            granted.store(true, std::memory_order_release); \
-        } \
+        if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP; \
         hipLaunchKernelGGL(fn, dim3(wgs), dim3(kThreadsS), lds_bytes, s, a); \
     }
     LSH_SPLIT_CASE(kIds, true) LSH_SPLIT_CASE(kIds, false) LSH_SPLIT_CASE(kProj, true) LSH_SPLIT_CASE(kSigns, true)
-    LSH_SPLIT_CASE(kKeys, true) LSH_SPLIT_CASE(kKeys, false)
+    LSH_SPLIT_CASE(kKeys, true) LSH_SPLIT_CASE(kKeys, false) LSH_SPLIT_CASE(kIdsKeys, true) LSH_SPLIT_CASE(kIdsKeys, false)
 #undef LSH_SPLIT_CASE
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }

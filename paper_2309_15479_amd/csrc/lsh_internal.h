@@ -139,15 +139,16 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m);
 int upload_tables(lsh_params *p);
 void free_tables(lsh_params *p);
 
-enum class Epilogue : int { Ids = 0, Proj = 1, Signs = 2, Keys = 3 };
+enum class Epilogue : int { Ids = 0, Proj = 1, Signs = 2, Keys = 3, IdsKeys = 4 };  // IdsKeys: ids to d_out, keys to d_out2
 int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
-                   uint32_t L, void *stream);
+                   uint32_t L, void *stream, void *d_out2 = nullptr);
+bool sampled_ids_keys_supported(const lsh_params *p, uint32_t L);
 // ranged kernel (ranged_kernel.hip): geometry constants the host tables are built for
 constexpr uint32_t kRangeCoords = 1024;      // coordinates per range (one LDS buffer holds 16 vectors of them)
 constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather (the others load tiles)
 constexpr uint32_t kRangeBlockQuads = 3;     // quads of list entries per lane in one list block
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
-                  uint32_t L, void *stream);
+                  uint32_t L, void *stream, void *d_out2 = nullptr);
 constexpr uint32_t kSharedRangeBlocksPerWave = 16;  // blocks of 16 functions a contracting wave owns at most
 SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::vector<uint32_t> &offs,
@@ -179,7 +180,7 @@ bool dense_split_signs_supported(const lsh_params *p);
 bool dense_split_keys_supported(const lsh_params *p, uint32_t L);
 // ep: 0 bucket ids, 1 raw projections, 2 sign words, 3 keys (L tables)
 int launch_dense_split(const lsh_params *p, int ep, const float *d_data, uint64_t N, void *d_out,
-                       void *stream, uint32_t L = 0);
+                       void *stream, uint32_t L = 0, void *d_out2 = nullptr);
 // bf16 x 3 matrix-core version of the dense product for any n that is a multiple of 4
 // (dense_split_wide_kernel.hip), over the coefficient planes split on the host
 bool dense_wide_supported(const lsh_params *p);

@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
         const uint32_t j = j0 + f * kCW * 64;  // < kpad
         bias[f] = a.off[j];
         key_pow[f] = 1;
-        if (EP == (int)Epilogue::Keys) {
+        if (EP == (int)Epilogue::Keys || EP == (int)Epilogue::IdsKeys) {
             uint32_t t = j % a.g;
             if (a.g >= 4) t |= 3;  // the transposed fold multiplies by the power of the quad's last function
             for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow[f] *= kKeyMultiplier;
@@ -264,7 +264,7 @@ int launch(Kernel fn, const SampledArgs &args, dim3 grid, hipStream_t stream) {
 }  // namespace
 
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out, uint32_t L,
-                  void *stream) {
+                  void *stream, void *d_out2) {
     const SampledPlan &pl = p->plan;
     if (!pl.ranged || !p->d_triples) return LSH_ERR_UNSUPPORTED;
     SampledArgs a = {};
@@ -281,6 +281,7 @@ int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_
     a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
     a.epilogue = (int)ep;
     a.out = d_out;
+    a.out2 = d_out2;
     a.L = L;
     a.g = L ? p->k / L : 1;
     a.chunk = pl.chunk;
@@ -309,6 +310,7 @@ int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_
         case Epilogue::Ids: LSH_RANGED_FPT((int)Epilogue::Ids)
         case Epilogue::Proj: LSH_RANGED_FPT((int)Epilogue::Proj)
         case Epilogue::Signs: LSH_RANGED_FPT((int)Epilogue::Signs)
+        case Epilogue::IdsKeys: LSH_RANGED_FPT((int)Epilogue::IdsKeys)
         default: LSH_RANGED_FPT((int)Epilogue::Keys)
     }
 #undef LSH_RANGED_FPT

@@ -59,7 +59,8 @@ struct SampledArgs {
     int w_is_pow2;
     int epilogue;        // Epilogue
     void *out;
-    uint32_t L, g;       // key groups (Epilogue::Keys)
+    void *out2;          // Epilogue::IdsKeys: the keys (the ids go to out)
+    uint32_t L, g;       // key groups (Epilogue::Keys, Epilogue::IdsKeys)
     // register-list kernel only: floats per tile buffer; float offset of the second,
     // class-rotated tile copy inside a buffer (0: single copy)
     uint32_t buf_floats, copy_b_floats;
@@ -243,9 +244,12 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
             break;
         }
         default: {  // Keys: g consecutive lanes fold their ids; g is a power of two <= 64
-            uint64_t *out = reinterpret_cast<uint64_t *>(a.out);
+            // IdsKeys (launched only with 4-vector sub-tiles, g >= 4 and k a multiple of 4): the
+            // transposed path below, which also stores the four ids a lane holds after the transpose
+            constexpr bool both = EP == (int)Epilogue::IdsKeys;
+            uint64_t *out = reinterpret_cast<uint64_t *>(both ? a.out2 : a.out);
             if constexpr (RT == 4) {
-                if (a.g >= 4) {  // uniform
+                if (both || a.g >= 4) {  // uniform
                     // As for ids, the quads are transposed first: a lane then holds the ids of the
                     // quad's four consecutive functions for ONE vector, folds them by Horner's rule
                     // (three multiplications by C and one by its power of C, instead of one 64-bit
@@ -270,10 +274,20 @@ __device__ __forceinline__ void finish(const SampledArgs &a, uint64_t row0, uint
                             q[r] = __builtin_amdgcn_fmed3f(v, -2147483648.f, 2147483648.f);
                         }
                         quad_transpose_mfma(q, unit);
-                        uint64_t part = (uint32_t)(int)floorf(q[0]);
-                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[1]);
-                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[2]);
-                        part = part * kKeyMultiplier + (uint32_t)(int)floorf(q[3]);
+                        uint32_t id[4];
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) id[r] = (uint32_t)(int)floorf(q[r]);
+                        if constexpr (both) {
+                            // functions j & ~3 .. + 3 of vector row0 + s * RT + u_mine, as in the ids epilogue
+                            const uint64_t id_row = row0 + s * RT + u_mine;
+                            if ((j & ~3u) < a.k && id_row < a.N)
+                                *reinterpret_cast<uint4 *>(reinterpret_cast<uint32_t *>(a.out) + id_row * a.k + (j & ~3u)) =
+                                    make_uint4(id[0], id[1], id[2], id[3]);
+                        }
+                        uint64_t part = id[0];
+                        part = part * kKeyMultiplier + id[1];
+                        part = part * kKeyMultiplier + id[2];
+                        part = part * kKeyMultiplier + id[3];
                         part *= key_pow;
                         if (a.g >= 8) part += dpp_u64<0x104>(part);   // row_shl:4: lane i takes lane i + 4 (0 past the row)
                         if (a.g >= 16) part += dpp_u64<0x108>(part);  // row_shl:8

@@ -26,9 +26,9 @@
 // ranged_kernel.hip.
 #include <hip/hip_runtime.h>
 
+#include <map>
 #include <mutex>
 #include <type_traits>
-#include <unordered_map>
 
 #include "sampled_common.h"
 
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(1024) void sampled_kernel(const SampledArgs a) {
         tile[(size_t)n * SP * RT + e] = 0.f;
 
     uint64_t key_pow = 1;  // C^(g-1-t) for this lane's position t in its key group
-    if (EP == (int)Epilogue::Keys) {
+    if (EP == (int)Epilogue::Keys || EP == (int)Epilogue::IdsKeys) {
         uint32_t t = j % a.g;
         if (RT == 4 && a.g >= 4) t |= 3;  // the transposed fold multiplies by the power of the quad's last function
         for (uint32_t e = 0; e + 1 + t < a.g; ++e) key_pow *= kKeyMultiplier;
@@ -310,16 +310,19 @@ int launch_kernel(Kernel fn, uint32_t lds_bytes, const SampledArgs &args, dim3 g
 }  // namespace
 
 // hipFuncSetAttribute costs about a millisecond of host time: raise a kernel's dynamic LDS
-// limit once (per kernel and size), not per launch.
+// limit once per kernel, size and device (the attribute belongs to the kernel as loaded on the
+// current device), not per launch.
 int ensure_lds_limit(const void *fn, uint32_t lds_bytes) {
     static std::mutex mu;
-    static std::unordered_map<const void *, uint32_t> granted;
+    static std::map<std::pair<int, const void *>, uint32_t> granted;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return LSH_ERR_HIP;
     std::lock_guard<std::mutex> lock(mu);
-    auto it = granted.find(fn);
+    auto it = granted.find({dev, fn});
     if (it != granted.end() && it->second >= lds_bytes) return LSH_OK;
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
         return LSH_ERR_HIP;
-    granted[fn] = lds_bytes;
+    granted[{dev, fn}] = lds_bytes;
     return LSH_OK;
 }
 
@@ -404,11 +407,23 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
     return pl;
 }
 
+// Shapes whose gather kernel has the epilogue that writes ids and keys: tiles of 4-vector
+// sub-tiles (the ids of a quad of lanes are transposed), tables of a power of two >= 4 functions,
+// k a multiple of 4; not the register-list kernels.
+bool sampled_ids_keys_supported(const lsh_params *p, uint32_t L) {
+    const SampledPlan &pl = p->plan;
+    if (!pl.supported || !L || p->k % L || (p->k & 3)) return false;
+    const uint32_t g = p->k / L;
+    if (g < 4 || g > 64 || (g & (g - 1))) return false;
+    return pl.ranged || (!pl.reg_table && pl.rt == 4);
+}
+
 int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
-                   uint32_t L, void *stream) {
+                   uint32_t L, void *stream, void *d_out2) {
     const SampledPlan &pl = p->plan;
     if (!pl.supported) return LSH_ERR_UNSUPPORTED;
-    if (pl.ranged) return launch_ranged(p, ep, d_data, N, d_out, L, stream);
+    if (ep == Epilogue::IdsKeys && !sampled_ids_keys_supported(p, L)) return LSH_ERR_UNSUPPORTED;
+    if (pl.ranged) return launch_ranged(p, ep, d_data, N, d_out, L, stream, d_out2);
     SampledArgs a = {};
     a.data = d_data;
     a.N = N;
@@ -425,6 +440,7 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
     a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
     a.epilogue = (int)ep;
     a.out = d_out;
+    a.out2 = d_out2;
     a.L = L;
     a.g = L ? p->k / L : 1;
     a.buf_floats = pl.lds_bytes / 4;
@@ -495,6 +511,13 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
 #undef LSH_REG_CASE
 #undef LSH_REG_LAUNCH
         return LSH_ERR_UNSUPPORTED;
+    }
+    if (ep == Epilogue::IdsKeys) {  // 4-vector sub-tiles only (checked above)
+        constexpr int EK = (int)Epilogue::IdsKeys;
+        if (pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8, EK>, lds_bytes, a, grid, block, s);
+        if (pl.sub == 4) return launch_kernel(&sampled_kernel<4, 4, EK>, lds_bytes, a, grid, block, s);
+        if (pl.sub == 2) return launch_kernel(&sampled_kernel<4, 2, EK>, lds_bytes, a, grid, block, s);
+        return launch_kernel(&sampled_kernel<4, 1, EK>, lds_bytes, a, grid, block, s);
     }
 #define LSH_GEN_ALL(EP_) \
     if (pl.rt == 4 && pl.sub == 8) return launch_kernel(&sampled_kernel<4, 8, EP_>, lds_bytes, a, grid, block, s); \

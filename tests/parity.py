@@ -34,6 +34,10 @@ def check_proj(gpu_proj, ora, label=""):
     tol = PROJ_RTOL * ora["abs_sum"] + 1e-30
     worst = float((err / tol).max()) if err.size else 0.0
     assert worst <= 1.0, f"{label}: projection error {worst:.3f} x tolerance"
+    # reported, not required: under cancellation no fp32 sum can be within 1e-5 of a projection near 0
+    plain = float((err <= PROJ_RTOL * np.abs(ora["proj"])).mean()) if err.size else 1.0
+    print(f"{label}: worst projection error {worst:.3f} x tolerance; within a plain relative "
+          f"{PROJ_RTOL:g} of the value: {plain:.4f} of {err.size}")
     return worst
 
 

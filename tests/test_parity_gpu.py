@@ -358,6 +358,43 @@ def test_pack_keys_group_sizes(lsh, k, L):
         assert np.array_equal(keys.cpu().numpy().view(np.uint64), want)
 
 
+@pytest.mark.parametrize("N,n,k,m,L,w,fp32,shared", [
+    (1000, 128, 512, 32, 32, 16.0, False, 0),    # matrix-core kernel, tables of 16
+    (333, 128, 256, 32, 64, 4.0, False, 0),      # tables of 4
+    (333, 128, 256, 32, 32, 3.0, False, 0),      # tables of 8, w not a power of two
+    (65, 128, 64, 16, 2, 4.0, False, 0),         # tables of 32
+    (1, 128, 512, 32, 32, 16.0, False, 0),       # one vector
+    (500, 128, 512, 32, 32, 16.0, True, 0),      # fp32 arithmetic: register-list kernel, two launches inside the call
+    (300, 128, 96, 32, 48, 4.0, False, 0),       # tables of 2: two launches
+    (257, 960, 1024, 128, 64, 1.0, False, 0),    # streamed lists, 16-vector tiles, tables of 16
+    (90, 960, 256, 100, 64, 0.75, False, 0),     # tables of 4, w not a power of two
+    (100, 4096, 2048, 64, 128, 8.0, False, 0),   # ranged kernel, tables of 16
+    (37, 4100, 512, 40, 8, 2.0, False, 0),       # ranged kernel, tables of 64, ragged last range
+    (50, 2048, 520, 30, 130, 4.0, False, 0),     # ranged kernel, k not a multiple of 64
+    (200, 128, 512, 32, 32, 16.0, False, 32),    # one sample per table: two launches
+])
+def test_ids_and_keys_in_one_call(lsh, N, n, k, m, L, w, fp32, shared):
+    """lsh_hash_fastlsh_ids_keys: the ids are those of lsh_hash_fastlsh bit for bit, and the keys
+    are the fold (Sec. 3.2) of exactly those ids, checked with the oracle's packing."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(N * 7 + n)
+    scale = 40.0 if n == 128 else 1.0
+    data = torch.randn((N, n), generator=g, device="cuda") * scale
+    p = lsh.LshParams(n, k, m, w, 77, shared_tables=shared) if shared else lsh.LshParams(n, k, m, w, 77)
+    with p:
+        if fp32:
+            p.set_dense_arithmetic(lsh.DENSE_FP32)
+        want_ids = lsh.hash_fastlsh(p, data)
+        # outputs pre-filled: every element must be written
+        ids = torch.full((N, k), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+        keys = torch.full((N, L), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+        lsh.hash_fastlsh_ids_keys(p, data, L, out_ids=ids, out_keys=keys)
+        torch.cuda.synchronize()
+        assert torch.equal(ids, want_ids)
+        want_keys = oracle.pack_keys(ids.cpu().numpy(), L)
+        assert np.array_equal(keys.cpu().numpy().view(np.uint64), want_keys)
+
+
 def test_empty_input_and_errors(lsh):
     with lsh.LshParams(128, 64, 32, 4.0, 1) as p:
         data = torch.empty((0, 128), device="cuda")
@@ -374,6 +411,11 @@ def test_empty_input_and_errors(lsh):
         with pytest.raises(lsh.LshError) as e:          # k % L != 0 on the fused path too
             lsh.hash_fastlsh_keys(p, x, 5)
         assert e.value.status == -1
+        with pytest.raises(lsh.LshError) as e:
+            lsh.hash_fastlsh_ids_keys(p, x, 5)
+        assert e.value.status == -1
+        i0, k0 = lsh.hash_fastlsh_ids_keys(p, data, 8)
+        assert i0.shape == (0, 64) and k0.shape == (0, 8)
     with lsh.LshParams(50000, 8, 4, 1.0, 1) as p:       # one vector does not fit in LDS
         with pytest.raises(lsh.LshError) as e:
             lsh.hash_fastlsh(p, torch.zeros((2, 50000), device="cuda"))
