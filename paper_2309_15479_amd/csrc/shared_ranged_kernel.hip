@@ -22,10 +22,12 @@
 //
 // With the samples gathered once per table, what is left to stream per tile is the lists: they
 // come from L2, many times the bytes of the tile itself, and set the pace of the launch.  So
-// they are kept small: a list block of U steps holds U x 64 coefficients (one per lane and
-// step) and, apart from them, one record of U 16-bit offsets per sample slot l / 16, which the
-// sixteen lanes of a slot all read from the same address (a few bytes per block out of L2
-// instead of a word per lane and step).
+// they are kept small and cheap to fetch: a list block of U steps holds U x 64 coefficients (one
+// per lane and step, a lane's four consecutive steps side by side so that one 16-byte load
+// brings them) and, apart from them, one record of U 16-bit offsets per sample slot l / 16,
+// which the sixteen lanes of a slot all read from the same address (a few bytes per block out
+// of L2 instead of a word per lane and step).  A vector memory instruction costs the CU's
+// memory pipeline 9 to 14 clocks whatever it hits, so their number per MFMA is what counts.
 //
 // The lists are also what a wave waits for if they arrive late, so they are asked for well ahead: a
 // wave's list blocks (U steps each) form one stream in consumption order (range after range,
@@ -50,6 +52,7 @@ namespace lsh {
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCWs = (int)kRangeComputeWaves;  // contracting waves
@@ -85,6 +88,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                                                                    const uint32_t *__restrict__ range_groups,
                                                                    const uint2 *__restrict__ streams) {
     static_assert(!SHORT || BPW % 4 == 0, "short lists go round the ring of four by blocks");
+    static_assert(U % 2 == 0, "a lane loads the coefficients of four or two steps at a time");
     constexpr int NR = SHORT ? 4 : kLongRing;  // ring sets
     extern __shared__ __align__(16) char lds_sr[];  // 2 buffers x [16 vectors][1028 floats]
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -155,8 +159,18 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
     auto load_block = [&](int set) __attribute__((always_inline)) {
         const float *cs = cbase + (size_t)next_block * (U * 64);
         const uint32_t *os = obase + (size_t)next_block * (4 * OW);
+        // coefficients of four steps per load, [steps / 4][lane][4], then of the last two, [lane][2]
 #pragma unroll
-        for (int i = 0; i < U; ++i) ring_c[set][i] = cs[i * 64 + lane];
+        for (int i = 0; i < U / 4; ++i) {
+            const floatx4 c4 = *reinterpret_cast<const floatx4 *>(cs + i * 256 + lane * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ring_c[set][4 * i + e] = c4[e];
+        }
+        if constexpr (U % 4 == 2) {
+            const floatx2 c2 = *reinterpret_cast<const floatx2 *>(cs + (U / 4) * 256 + lane * 2);
+            ring_c[set][U - 2] = c2[0];
+            ring_c[set][U - 1] = c2[1];
+        }
 #pragma unroll
         for (int i = 0; i < OW; ++i) ring_o[set][i] = os[oslot + i];
         next_block = next_block + 1 == sblocks ? 0 : next_block + 1;
@@ -185,6 +199,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                     const uint32_t off = (ring_o[set][s >> 1] >> (16 * (s & 1))) & 0xFFFFu;
                     x[s] = *reinterpret_cast<const float *>(buf + off);
                 }
+                __builtin_amdgcn_sched_barrier(0);  // all reads of the block go out before its first MFMA
 #pragma unroll
                 for (int s = 0; s < U; ++s) c = __builtin_amdgcn_mfma_f32_16x16x4f32(ring_c[set][s], x[s], c, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
@@ -310,17 +325,17 @@ void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::v
             longest[r] = std::max(longest[r], (uint32_t)out.size() / 4);
         }
     }
-    // layout: short lists (one block of up to 8 steps per list) if every list fits, else whole
-    // turns of the long-list ring (4 blocks of 3 to 8 steps), whichever pads least
+    // layout: short lists (one block of 4, 6 or 8 steps per list) if every list fits, else whole
+    // turns of the long-list ring (4 blocks of 4, 6 or 8 steps), whichever pads least
     const uint32_t top = *std::max_element(longest.begin(), longest.end());
     range_groups.assign(R, 1);
     if (top <= 8) {
         pl.short_lists = true;
-        pl.block_steps = std::max(top, 3u);
+        pl.block_steps = top <= 4 ? 4 : top <= 6 ? 6 : 8;
     } else {
         pl.short_lists = false;
         uint64_t best = ~0ull;
-        for (uint32_t u = 3; u <= 8; ++u) {
+        for (uint32_t u = 4; u <= 8; u += 2) {
             uint64_t cost = 0;
             for (uint32_t r = 0; r < R; ++r) cost += std::max(1u, (longest[r] + kLongRing * u - 1) / (kLongRing * u)) * kLongRing * u;
             if (cost <= best) {  // ties: the larger block (requests reach further ahead)
@@ -367,8 +382,11 @@ void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::v
                             const uint32_t coord = p->idx[(size_t)table * pl.g * m + smp] - r * kRangeCoords;
                             uint32_t &word = offs[(block * 4 + kq) * OW + in_block / 2];
                             word = (word & ~(0xFFFFu << (16 * (in_block & 1)))) | (coord * 4) << (16 * (in_block & 1));
+                            // steps in fours [lane][4]; the last two of a block of six [lane][2]
+                            const uint32_t four = in_block / 4 * 4, width = U - four >= 4 ? 4 : 2;
                             for (uint32_t i = 0; i < 16 && first + i < pl.g; ++i)  // rows beyond the table keep zero
-                                coefs[(block * U + in_block) * 64 + kq * 16 + i] = p->coef[(size_t)(table * pl.g + first + i) * m + smp];
+                                coefs[(block * U + four) * 64 + (kq * 16 + i) * width + in_block % 4] =
+                                    p->coef[(size_t)(table * pl.g + first + i) * m + smp];
                         }
                 }
         }
@@ -418,7 +436,7 @@ int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uin
 #define LSH_SR_CASE(B_) \
     case B_: \
         switch (pl.block_steps) { \
-            LSH_SR_STEPS(B_, 3) LSH_SR_STEPS(B_, 4) LSH_SR_STEPS(B_, 5) LSH_SR_STEPS(B_, 6) LSH_SR_STEPS(B_, 7) LSH_SR_STEPS(B_, 8) \
+            LSH_SR_STEPS(B_, 4) LSH_SR_STEPS(B_, 6) LSH_SR_STEPS(B_, 8) \
             default: return LSH_ERR_UNSUPPORTED; \
         } \
         break;
