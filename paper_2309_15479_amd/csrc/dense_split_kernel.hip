@@ -69,7 +69,8 @@ constexpr int kQuads = TV * (SN / 4) / kThreadsS;  // 16-byte pieces of a tile p
 constexpr int STAGE_ROWB = 32 * 4 + 16;
 constexpr int STAGE = 32 * STAGE_ROWB;
 constexpr int kLevelOffset = 2 * BUF, kStageOffset = 2 * BUF + 16;
-constexpr int kLdsBytes = kStageOffset + 8 * STAGE;  // 141 328
+constexpr int kOffsetsOffset = kStageOffset + 8 * STAGE;  // ids-and-keys epilogue: the waves' 32 offsets b~ each
+constexpr int kLdsBytes = kOffsetsOffset + 8 * 128;       // 142 352
 
 struct SplitArgs {
     const float *data;  // [N][128]
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            if constexpr (EP == kIds || EP == kKeys || EP == kIdsKeys) {
+            if constexpr (EP == kIds || EP == kKeys) {
                 const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
                 bs[i] = POW2 ? b * a.inv_w : b;
             } else {
@@ -293,6 +294,15 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t stage_wr = lr * STAGE_ROWB + 16 * lh;                // + 32 q
     const uint32_t stage_rd = (lane >> 3) * STAGE_ROWB + (lane & 7) * 16;  // + 8 j rows
     const uint32_t st_off = ((lane >> 3) * a.k + wf) * 4 + (lane & 7) * 16;  // in a block of 32 x k outputs; below 2^32 (host)
+    // ids and keys: the wave's 32 offsets wait in LDS and are read at the tile's end (that
+    // epilogue has no 16 registers to hold them through the contraction)
+    float *const wave_offsets = reinterpret_cast<float *>(lds_s + kOffsetsOffset + wave * 128);
+    if constexpr (BOTH) {
+        if (lane < 32) {
+            const float b = a.off[wf + lane];
+            wave_offsets[lane] = POW2 ? b * a.inv_w : b;
+        }
+    }
     uintx4 res[2][(SIGNS || KEYS || BOTH) ? 1 : 4];  // ids or the bits of the projections
     uint32_t sign_word[2][2] = {{0, 0}, {0, 0}};  // [column block][low, high half of the wave's sign word]
     // keys: a lane's four ids of accumulator group q are consecutive functions 8q + 4 (l / 32) ...
@@ -388,13 +398,16 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     uintx4 v;
+                    [[maybe_unused]] floatx4 b4;
+                    if constexpr (BOTH) b4 = *reinterpret_cast<const floatx4 *>(wave_offsets + 8 * q + 4 * lh);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float p = acc[0][vb][4 * q + e];
                         if constexpr (PROJ) {
                             v[e] = __float_as_uint(p);
                         } else {
-                            const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
+                            const float bq = BOTH ? b4[e] : bs[4 * q + e];
+                            const float h = POW2 ? fmaf(p, a.inv_w, bq) : (p + bq) / a.w;
                             v[e] = (uint32_t)(int)floorf(h);
                         }
                     }
