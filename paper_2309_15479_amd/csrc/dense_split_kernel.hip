@@ -69,7 +69,7 @@ constexpr int kQuads = TV * (SN / 4) / kThreadsS;  // 16-byte pieces of a tile p
 constexpr int STAGE_ROWB = 32 * 4 + 16;
 constexpr int STAGE = 32 * STAGE_ROWB;
 constexpr int kLevelOffset = 2 * BUF, kStageOffset = 2 * BUF + 16;
-constexpr int kOffsetsOffset = kStageOffset + 8 * STAGE;  // ids-and-keys epilogue: the waves' 32 offsets b~ each
+constexpr int kOffsetsOffset = kStageOffset + 8 * STAGE;  // the waves' 32 offsets b~ each
 constexpr int kLdsBytes = kOffsetsOffset + 8 * 128;       // 142 352
 
 struct SplitArgs {
@@ -127,7 +127,6 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
 
     // coefficients of the wave's blocks of 32 functions, split, resident: c[block][step][term]
     bf16x8 c[FB][KSTEPS][NSPLIT];
-    float bs[16];
     if (active) {
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb) {
@@ -147,15 +146,6 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                 }
             }
         }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            if constexpr (EP == kIds || EP == kKeys) {
-                const float b = a.off[wf + 8 * (i / 4) + 4 * lh + (i % 4)];
-                bs[i] = POW2 ? b * a.inv_w : b;
-            } else {
-                bs[i] = 0.f;
-            }
-        }
     } else {
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)
@@ -165,8 +155,6 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                 for (int p = 0; p < NSPLIT; ++p)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) c[fb][s][p][e] = (__bf16)0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) bs[i] = 0.f;
     }
 
     // loader: thread t takes the 16-byte pieces t, t + 512, ... of the tile (32 pieces per vector);
@@ -294,10 +282,12 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
     const uint32_t stage_wr = lr * STAGE_ROWB + 16 * lh;                // + 32 q
     const uint32_t stage_rd = (lane >> 3) * STAGE_ROWB + (lane & 7) * 16;  // + 8 j rows
     const uint32_t st_off = ((lane >> 3) * a.k + wf) * 4 + (lane & 7) * 16;  // in a block of 32 x k outputs; below 2^32 (host)
-    // ids and keys: the wave's 32 offsets wait in LDS and are read at the tile's end (that
-    // epilogue has no 16 registers to hold them through the contraction)
+    // The wave's 32 offsets b~ wait in LDS and are read back four at a time at the tile's end:
+    // held in registers through the contraction they cost 16 per lane (the ids epilogue then
+    // needs 252 registers instead of 238 and runs 5 % slower; ids and keys together spill).
+    constexpr bool OFFSETS = EP == kIds || EP == kKeys || EP == kIdsKeys;
     float *const wave_offsets = reinterpret_cast<float *>(lds_s + kOffsetsOffset + wave * 128);
-    if constexpr (BOTH) {
+    if constexpr (OFFSETS) {
         if (lane < 32) {
             const float b = a.off[wf + lane];
             wave_offsets[lane] = POW2 ? b * a.inv_w : b;
@@ -374,10 +364,11 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     uint64_t fold = 0;
+                    const floatx4 b4 = *reinterpret_cast<const floatx4 *>(wave_offsets + 8 * q + 4 * lh);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float p = acc[0][vb][4 * q + e];
-                        const float h = POW2 ? fmaf(p, a.inv_w, bs[4 * q + e]) : (p + bs[4 * q + e]) / a.w;
+                        const float h = POW2 ? fmaf(p, a.inv_w, b4[e]) : (p + b4[e]) / a.w;
                         fold = fold * kKeyMultiplier + (uint32_t)(int)floorf(h);
                     }
                     part[q] = fold * key_weight[q];
@@ -399,15 +390,14 @@ __global__ __launch_bounds__(kThreadsS, 2) void dense_split_kernel(const SplitAr
                 for (int q = 0; q < 4; ++q) {
                     uintx4 v;
                     [[maybe_unused]] floatx4 b4;
-                    if constexpr (BOTH) b4 = *reinterpret_cast<const floatx4 *>(wave_offsets + 8 * q + 4 * lh);
+                    if constexpr (OFFSETS) b4 = *reinterpret_cast<const floatx4 *>(wave_offsets + 8 * q + 4 * lh);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float p = acc[0][vb][4 * q + e];
                         if constexpr (PROJ) {
                             v[e] = __float_as_uint(p);
                         } else {
-                            const float bq = BOTH ? b4[e] : bs[4 * q + e];
-                            const float h = POW2 ? fmaf(p, a.inv_w, bq) : (p + bq) / a.w;
+                            const float h = POW2 ? fmaf(p, a.inv_w, b4[e]) : (p + b4[e]) / a.w;
                             v[e] = (uint32_t)(int)floorf(h);
                         }
                     }
