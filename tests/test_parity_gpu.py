@@ -180,6 +180,9 @@ SHARED = [
     (50, 2048, 1024, 30, 4.0, 59, False, 64),    # eight blocks per wave
     (20, 4096, 4096, 64, 8.0, 60, False, 128),   # tables of 32 (two blocks each), four workgroups along the functions
     (33, 16384, 128, 512, 1.0, 61, False, 4),    # sixteen ranges, long lists
+    (1, 4096, 64, 32, 4.0, 62, False, 4),        # one vector, one block per wave and idle blocks
+    (17, 8192, 2048, 4, 8.0, 63, False, 128),    # four samples per table: most lists of a range are empty
+    (45, 1264, 256, 200, 2.0, 64, True, 16),     # just above the whole-vector kernel's n: a second range of 240 coordinates, blocks of six steps
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
 ]
 
