@@ -382,9 +382,44 @@ class Bench:
                 entries.append(entry)
                 del ids2
             del keys
+        if name == "tiny":
+            entries.append(self.graph_entry(wl, data))
         del out, data
         torch.cuda.empty_cache()
         return entries
+
+    def graph_entry(self, wl, data):
+        """The launch-bound shape as it should be run: the step's four launches captured once in a
+        HIP graph and replayed (the hash calls allocate nothing and never synchronise)."""
+        torch, lsh = self.torch, self.lsh
+        N, n, k, L = wl.N, wl.n, wl.k, wl.L
+        ids = torch.empty((N, k), dtype=torch.int32, device=self.dev)
+        dense = torch.empty_like(ids)
+        keys = torch.empty((N, L), dtype=torch.int64, device=self.dev)
+        words = torch.empty((N, (k + 63) // 64), dtype=torch.int64, device=self.dev)
+        with lsh.LshParams(n, k, wl.m[0], wl.w, wl.seed) as pf, lsh.LshParams(n, k, n, wl.w, wl.seed) as pd:
+            def step():
+                lsh.hash_fastlsh(pf, data, out=ids)
+                lsh.pack_keys(pf, ids, L, out=keys)
+                lsh.hash_e2lsh(pd, data, out=dense)
+                lsh.hash_signs(pf, data, out=words)
+            step()  # eager once: raises the kernels' LDS limits
+            torch.cuda.synchronize()
+            eager_ms = self.timer.measure(step)
+            want = ids.clone()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            ids.zero_()
+            graph_ms = self.timer.measure(graph.replay)
+            torch.cuda.synchronize()
+            same = bool(torch.equal(ids, want))
+        bytes_per_step = N * (3 * 4 * n + 4 * k + 4 * k + 8 * L + 4 * k + 8 * ((k + 63) // 64))
+        return {"workload": wl.name, "call": "fastlsh ids + pack_keys + e2lsh ids + signs as one HIP graph", "N": N,
+                "n": n, "k": k, "ms": graph_ms, "eager_ms": eager_ms, "dtype": "f32",
+                "replay_equals_eager": same, "roofline": hbm_roofline(bytes_per_step, graph_ms)}
 
     def cpu_baseline(self, wl, data, params, budget_s=14.0):
         """The oracle as it stands on a bounded sample of the headline batch: all four legs of the
