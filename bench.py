@@ -381,12 +381,85 @@ class Bench:
                                                self.oracle.pack_keys(ids2[rows].cpu().numpy(), wl.L)).sum())}
                 entries.append(entry)
                 del ids2
+                entries.extend(self.index_entries(wl, data, p, keys))
             del keys
         if name == "tiny":
             entries.append(self.graph_entry(wl, data))
         del out, data
         torch.cuda.empty_cache()
         return entries
+
+    def index_entries(self, wl, data, p, keys):
+        """Sec. 3.2 beyond the hash: the L tables built from the keys of the whole batch, the bucket
+        lookup of 4096 queries (perturbed copies of indexed vectors) and the exact evaluation of
+        their candidates; a few queries are checked against the definition written out in numpy."""
+        import numpy as np
+        torch, lsh = self.torch, self.lsh
+        N, n, L, Q = wl.N, wl.n, wl.L, 4096
+        lsh.hash_fastlsh_keys(p, data, L, out=keys)
+        torch.cuda.synchronize()
+        lsh.LshIndex(keys).close()  # first build: one-time set-up
+        builds = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ix = lsh.LshIndex(keys)
+            e1.record()
+            torch.cuda.synchronize()
+            builds.append(e0.elapsed_time(e1))
+            ix.close()
+        g = torch.Generator(device=self.dev)
+        g.manual_seed(wl.seed + 100)
+        rows = torch.randint(0, N, (Q,), generator=g, device=self.dev)
+        scale = float(data[:1024].std().item())
+        queries = (data[rows] + 0.01 * scale * torch.randn((Q, n), generator=g, device=self.dev)).contiguous()
+        qkeys = lsh.hash_fastlsh_keys(p, queries, L)
+        out = []
+        with lsh.LshIndex(keys) as ix:
+            probe_ms = self.timer.measure(lambda: ix.probe(qkeys))
+            start, count = ix.probe(qkeys)
+            nearest_ms = self.timer.measure(lambda: ix.nearest(data, queries, start, count))
+            best, dist2 = ix.nearest(data, queries, start, count)
+            torch.cuda.synchronize()
+            candidates = int(count.to(torch.int64).sum().item())
+            found_source = float((best.to(torch.int64) == rows).float().mean().item())
+            parity = None
+            if not self.args.no_parity:
+                # the definition, for 6 queries: table l's bucket = ids (ascending) whose key equals the query's
+                off, cand = ix.candidates(start[:6].contiguous(), count[:6].contiguous())
+                off, cand = off.cpu().numpy(), cand.cpu().numpy()
+                hk, hq = keys.cpu().numpy(), qkeys[:6].cpu().numpy()
+                hd, hqv = data, queries[:6].cpu().numpy().astype(np.float64)
+                bad_buckets = bad_nearest = 0
+                for q in range(6):
+                    mine = []
+                    for l in range(L):
+                        want = np.nonzero(hk[:, l] == hq[q, l])[0]
+                        got = cand[off[q * L + l]:off[q * L + l + 1]]
+                        bad_buckets += int(not np.array_equal(want, got))
+                        mine.extend(want.tolist())
+                    uniq = sorted(set(mine))
+                    if uniq:
+                        d = ((hd[torch.as_tensor(uniq, device=self.dev)].cpu().numpy().astype(np.float64) - hqv[q]) ** 2).sum(1)
+                        j = int(np.argmin(d))
+                        got_id = int(best[q].item())
+                        ok = got_id == uniq[j] or (got_id in uniq and d[uniq.index(got_id)] <= d[j] * (1 + 1e-5))
+                        bad_nearest += int(not ok)
+                    else:
+                        bad_nearest += int(int(best[q].item()) != -1)
+                parity = {"queries_checked": 6, "buckets_checked": 6 * L, "bucket_mismatches": bad_buckets,
+                          "nearest_mismatches": bad_nearest}
+        build_ms = sum(builds) / len(builds)
+        base = {"workload": wl.name, "N": N, "L": L, "dtype": "u64"}
+        out.append(dict(base, call="lsh_index_build", ms=build_ms, pairs_per_s=N * L / (build_ms * 1e-3),
+                        # 8 passes of 8 bits over <key, id> pairs: per pass the keys are read for the histogram (8 B)
+                        # and the pairs are read and written (12 + 12 B)
+                        roofline=hbm_roofline(N * L * 8 * 32, build_ms)))
+        out.append(dict(base, call="lsh_index_probe", queries=Q, ms=probe_ms, parity=parity))
+        out.append(dict(base, call="lsh_index_nearest", queries=Q, ms=nearest_ms, candidates=candidates,
+                        dtype="f32", queries_whose_source_vector_is_returned=found_source,
+                        roofline=hbm_roofline(candidates * 4 * n, nearest_ms)))
+        return out
 
     def graph_entry(self, wl, data):
         """The launch-bound shape as it should be run: the step's four launches captured once in a
