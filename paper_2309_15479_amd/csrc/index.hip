@@ -172,7 +172,9 @@ __global__ __launch_bounds__(kSortThreads) void sort_histogram(const uint64_t *_
                                                                 uint32_t shift, uint32_t tiles,
                                                                 uint32_t *__restrict__ hist) {
     __shared__ uint32_t bins[256];
-    const uint32_t l = blockIdx.y, tile = blockIdx.x;
+    // first pass: the L workgroups that read one tile of the caller's [N][L] rows are neighbours
+    // in launch order and find it in L2 (else every table would fetch the whole array again)
+    const uint32_t l = FIRST ? blockIdx.x % L : blockIdx.y, tile = FIRST ? blockIdx.x / L : blockIdx.x;
     bins[threadIdx.x] = 0;
     __syncthreads();
     const uint64_t first = (uint64_t)tile * kSortTile;
@@ -209,6 +211,13 @@ __global__ __launch_bounds__(kScanThreads) void sort_scan(uint32_t *__restrict__
     }
 }
 
+// The scatter of a pass.  A pair's place in the output is (pairs of smaller digits in its
+// table) + (pairs of its digit in earlier tiles) + (pairs of its digit before it in its tile);
+// the first two come scanned from the histograms, the third from wave ballots in memory order.
+// The tile is first put in that order in LDS and then written out by consecutive threads:
+// pairs of one digit are then neighbours in LDS and in memory, so the stores of a wave are a
+// few runs instead of 64 separate 8-byte writes (about three times faster than scattering from the
+// registers on this part).
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void sort_scatter(const uint64_t *__restrict__ keys,
                                                               const uint32_t *__restrict__ ids, uint64_t N, uint32_t L,
@@ -216,14 +225,20 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(const uint64_t *__r
                                                               const uint32_t *__restrict__ offsets,
                                                               uint64_t *__restrict__ out_keys,
                                                               uint32_t *__restrict__ out_ids) {
-    __shared__ uint32_t counter[kSortWaves][256];  // per wave: pairs seen so far per digit, then its base position
-    const uint32_t l = blockIdx.y, tile = blockIdx.x;
+    __shared__ uint32_t counter[kSortWaves][256];  // per wave: pairs seen so far per digit, then its first place in the tile's order
+    __shared__ uint32_t delta[256];                // per digit: first output position minus first place in the tile's order
+    __shared__ uint32_t wave_total[kSortWaves];
+    __shared__ uint64_t tile_keys[kSortTile];
+    __shared__ uint32_t tile_ids[kSortTile];
+    const uint32_t l = FIRST ? blockIdx.x % L : blockIdx.y, tile = FIRST ? blockIdx.x / L : blockIdx.x;  // as in sort_histogram
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (uint32_t w = 0; w < kSortWaves; ++w) counter[w][threadIdx.x] = 0;
     __syncthreads();
-    const uint64_t first = (uint64_t)tile * kSortTile + (uint64_t)wave * (kSortSlots * 64) + lane;
+    const uint64_t tile_first = (uint64_t)tile * kSortTile;
+    const uint64_t first = tile_first + (uint64_t)wave * (kSortSlots * 64) + lane;
     const uint64_t below = (1ull << lane) - 1;
     uint64_t key[kSortSlots];
+    uint32_t id[kSortSlots];
     uint32_t rank[kSortSlots];
     volatile uint32_t *mine = counter[wave];
 #pragma unroll
@@ -231,6 +246,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(const uint64_t *__r
         const uint64_t at = first + (uint64_t)i * 64;
         const bool valid = at < N;
         key[i] = valid ? sort_key<FIRST>(keys, N, L, l, at) : 0;
+        id[i] = FIRST ? (uint32_t)at : valid ? ids[(uint64_t)l * N + at] : 0u;
         const uint32_t digit = (uint32_t)(key[i] >> shift) & 255u;
         // lanes of the wave that hold the same digit in this slot
         uint64_t peers = __ballot(valid);
@@ -246,12 +262,27 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(const uint64_t *__r
         __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
-    {   // thread d: positions of digit d for each wave = scanned offset of (digit, tile) + the waves before
-        uint32_t run = offsets[((size_t)l * 256 + threadIdx.x) * tiles + tile];
+    {   // thread d: the tile's pairs of digit d, their first place in the tile's order (an exclusive
+        // scan over the digits) and, per wave, the first place of that wave's pairs of the digit
+        uint32_t per_wave[kSortWaves], total = 0;
         for (uint32_t w = 0; w < kSortWaves; ++w) {
-            const uint32_t c = counter[w][threadIdx.x];
-            counter[w][threadIdx.x] = run;
-            run += c;
+            per_wave[w] = counter[w][threadIdx.x];
+            total += per_wave[w];
+        }
+        uint32_t incl = total;  // inclusive scan over the 64 digits of this wave, then over the waves
+#pragma unroll
+        for (uint32_t step = 1; step < 64; step <<= 1) {
+            const uint32_t up = __shfl_up(incl, step);
+            if (lane >= step) incl += up;
+        }
+        if (lane == 63) wave_total[wave] = incl;
+        __syncthreads();
+        uint32_t start = incl - total;
+        for (uint32_t w = 0; w < wave; ++w) start += wave_total[w];
+        delta[threadIdx.x] = offsets[((size_t)l * 256 + threadIdx.x) * tiles + tile] - start;
+        for (uint32_t w = 0; w < kSortWaves; ++w) {
+            counter[w][threadIdx.x] = start;
+            start += per_wave[w];
         }
     }
     __syncthreads();
@@ -260,9 +291,17 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(const uint64_t *__r
         const uint64_t at = first + (uint64_t)i * 64;
         if (at >= N) continue;
         const uint32_t digit = (uint32_t)(key[i] >> shift) & 255u;
-        const uint64_t pos = (uint64_t)l * N + counter[wave][digit] + rank[i];
-        out_keys[pos] = key[i];
-        out_ids[pos] = FIRST ? (uint32_t)at : ids[(uint64_t)l * N + at];
+        const uint32_t place = counter[wave][digit] + rank[i];
+        tile_keys[place] = key[i];
+        tile_ids[place] = id[i];
+    }
+    __syncthreads();
+    const uint32_t pairs = (uint32_t)(N - tile_first < kSortTile ? N - tile_first : kSortTile);
+    for (uint32_t place = threadIdx.x; place < pairs; place += kSortThreads) {
+        const uint64_t k64 = tile_keys[place];
+        const uint64_t pos = (uint64_t)l * N + (uint32_t)(delta[(uint32_t)(k64 >> shift) & 255u] + place);
+        out_keys[pos] = k64;
+        out_ids[pos] = tile_ids[place];
     }
 }
 
@@ -387,6 +426,8 @@ int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream
         (void)hipGetLastError();
         return LSH_ERR_NO_DEVICE;
     }
+    // the first pass launches one workgroup per (tile, table) in a row
+    if (((N + kSortTile - 1) / kSortTile) * L >= (1ull << 31)) return LSH_ERR_UNSUPPORTED;
     lsh_index *ix = new (std::nothrow) lsh_index;
     if (!ix) return LSH_ERR_ALLOC;
     ix->N = N;
@@ -417,9 +458,10 @@ int lsh_index_build(const uint64_t *d_keys, uint64_t N, uint32_t L, void *stream
             uint64_t *dst_keys = (pass & 1) ? ix->d_keys : tmp_keys;
             uint32_t *dst_ids = (pass & 1) ? ix->d_ids : tmp_ids;
             if (pass == 0) {
-                hipLaunchKernelGGL(sort_histogram<true>, grid, block, 0, s, src_keys, N, L, shift, tiles, hist);
+                const dim3 linear(tiles * L);  // below 2^31 (checked above)
+                hipLaunchKernelGGL(sort_histogram<true>, linear, block, 0, s, src_keys, N, L, shift, tiles, hist);
                 hipLaunchKernelGGL(sort_scan, dim3(L), dim3(kScanThreads), 0, s, hist, tiles);
-                hipLaunchKernelGGL(sort_scatter<true>, grid, block, 0, s, src_keys, src_ids, N, L, shift, tiles, hist,
+                hipLaunchKernelGGL(sort_scatter<true>, linear, block, 0, s, src_keys, src_ids, N, L, shift, tiles, hist,
                                    dst_keys, dst_ids);
             } else {
                 hipLaunchKernelGGL(sort_histogram<false>, grid, block, 0, s, src_keys, N, L, shift, tiles, hist);
