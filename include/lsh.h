@@ -136,6 +136,18 @@ int lsh_params_get_schedule(const lsh_params_t *params, uint32_t *order, uint32_
                             uint32_t *group, uint32_t *classes, uint64_t *modelled_passes);
 
 /*
+ * Host-side check of the list tables of the kernels that work by coordinate ranges (the
+ * sampled projection, Eq. 5, at large n; with one sample per table the matrix-core kernel for
+ * large n): the tables are built as for the device and walked as the kernels walk them on a
+ * pseudo-random vector derived from seed, in double precision; *worst receives the largest
+ * |walked - direct| / sum_i |a~_j[i] v[S_j[i]]| over the functions, direct being the sum of
+ * Eq. 5 taken from the canonical tables (about 1e-16 when the tables are right, infinity when a
+ * stream is inconsistent).  Needs no GPU.
+ * Errors: INVALID_ARG (null), UNSUPPORTED (the object's kernels use no such lists), ALLOC.
+ */
+int lsh_params_check_lists(const lsh_params_t *params, uint64_t seed, double *worst);
+
+/*
  * FastLSH bucket ids (Eq. 5): d_out_buckets[v*k + j] = floor((a~_j^T S_j(v) + b~_j) / w)
  * as int32 (saturating), for v < N, j < k.  Sampled-projection kernel: each vector
  * tile is read from HBM once, kept in LDS, and every function gathers its m

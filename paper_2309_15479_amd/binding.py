@@ -22,7 +22,7 @@ DENSE_FP32 = 1
 EXPORTS = [
     "lsh_params_create", "lsh_params_create_ex", "lsh_params_create_shared", "lsh_params_destroy",
     "lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape",
-    "lsh_params_get_tables", "lsh_params_get_mips_coeffs", "lsh_params_get_schedule",
+    "lsh_params_get_tables", "lsh_params_get_mips_coeffs", "lsh_params_get_schedule", "lsh_params_check_lists",
     "lsh_params_set_dense_arithmetic",
     "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys", "lsh_hash_fastlsh_ids_keys",
@@ -189,6 +189,15 @@ class LshParams:
         order = np.empty((self.k, steps.value), np.uint32)
         _check(lib.lsh_params_get_schedule(self.handle, order.ctypes.data, None, None, None, None), "get_schedule")
         return order, group.value, classes.value, passes.value
+
+    def check_lists(self, seed=1):
+        """Largest relative deviation of the kernel-side list tables, walked on the host as the
+        ranged kernels walk them, from the projections of the canonical tables."""
+        worst = ctypes.c_double()
+        lib = load_library()
+        lib.lsh_params_check_lists.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+        _check(lib.lsh_params_check_lists(self.handle, seed, ctypes.addressof(worst)), "lsh_params_check_lists")
+        return worst.value
 
     def shared_tables(self):
         L = ctypes.c_uint32()

@@ -11,7 +11,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblsh.so")
 SOURCES = ["api.hip", "sampled_kernel.hip", "ranged_kernel.hip", "shared_kernel.hip", "shared_ranged_kernel.hip", "dense_kernel.hip",
            "dense_split_kernel.hip", "dense_split_wide_kernel.hip", "pack_kernel.hip", "index.hip", "params_host.cpp", "schedule.cpp",
-           "collision_law.cpp"]
+           "collision_law.cpp", "selfcheck.cpp"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-ffp-contract=off", "-fno-gpu-rdc",

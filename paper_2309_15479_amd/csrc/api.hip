@@ -80,65 +80,15 @@ int upload_tables(lsh_params *p) {
             rc = LSH_ERR_HIP;
 
         if (rc == LSH_OK && p->plan.supported && p->plan.ranged) {
-            // one stream of list blocks per gathering wave, in the order the wave consumes them:
-            // range after range, within a range the wave's functions-per-lane sets one after the
-            // other.  A block is kRangeBlockQuads quads of entries x 64 lanes: 16 bytes of
-            // coefficients per quad and lane, then 8 bytes of 16-bit LDS byte offsets
-            // (16 x (coordinate minus the range's first)).
-            const SampledPlan &pl = p->plan;
-            const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockQuads, fpt = pl.fpt;
-            const uint32_t real_sets = (p->k + 63) / 64, streams = pl.kblocks * CW;
-            const size_t block_words = (size_t)U * 64 * 6, off_base = (size_t)U * 64 * 4;
-            std::vector<size_t> first_entry((size_t)real_sets * R);  // of each (set, range) in p->order
-            size_t at = 0;
-            for (uint32_t s = 0; s < real_sets; ++s)
-                for (uint32_t q = 0; q < R; ++q) {
-                    first_entry[(size_t)s * R + q] = at;
-                    at += (size_t)p->chunk_steps[(size_t)s * R + q] * 64;
-                }
-            std::vector<uint32_t> list_len((size_t)streams * R * fpt, 0);
-            std::vector<uint2> stream_info(streams, make_uint2(0, 0));
-            std::vector<uint32_t> words;
-            uint32_t blocks = 0;
-            for (uint32_t y = 0; y < pl.kblocks; ++y)
-                for (uint32_t cw = 0; cw < CW; ++cw) {
-                    const uint32_t start = blocks;
-                    for (uint32_t q = 0; q < R; ++q)
-                        for (uint32_t f = 0; f < fpt; ++f) {
-                            const uint32_t s = (y * fpt + f) * CW + cw;
-                            const uint32_t T = s < real_sets ? p->chunk_steps[(size_t)s * R + q] : 0;  // multiple of 4
-                            list_len[((size_t)(y * CW + cw) * R + q) * fpt + f] = T;
-                            const uint32_t nb = (T / 4 + U - 1) / U;
-                            words.resize((size_t)(blocks + nb) * block_words, 0u);
-                            for (uint32_t e = 0; e < T; ++e)
-                                for (uint32_t l = 0; l < 64; ++l) {
-                                    const uint32_t ent = p->order[first_entry[(size_t)s * R + q] + (size_t)e * 64 + l];
-                                    const uint32_t j = s * 64 + l;
-                                    uint32_t slot;
-                                    float c = 0.f;
-                                    if ((ent & kPadSample) || j >= p->k) {
-                                        slot = (ent & ~kPadSample) % pl.classes;  // a slot of the wanted bank class
-                                    } else {
-                                        slot = p->idx[(size_t)j * p->m + ent] - q * pl.chunk;
-                                        c = p->coef[(size_t)j * p->m + ent];
-                                    }
-                                    const size_t blk = (size_t)(blocks + e / (4 * U)) * block_words;
-                                    const uint32_t quad = e / 4 % U, pos = e % 4;
-                                    std::memcpy(&words[blk + ((size_t)quad * 64 + l) * 4 + pos], &c, 4);
-                                    words[blk + off_base + ((size_t)quad * 64 + l) * 2 + pos / 2] |= (slot * 16u) << (16 * (pos % 2));
-                                }
-                            blocks += nb;
-                        }
-                    stream_info[y * CW + cw] = make_uint2(start, blocks - start);
-                }
-            if (words.empty()) words.assign(4, 0u);
+            std::vector<uint32_t> words, list_len, stream_info;
+            build_ranged_tables(p, words, list_len, stream_info);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
             };
             upload(&p->d_triples, words.data(), words.size() * sizeof(uint32_t));
             upload(&p->d_list_len, list_len.data(), list_len.size() * sizeof(uint32_t));
-            upload(&p->d_stream, stream_info.data(), stream_info.size() * sizeof(uint2));
+            upload(&p->d_stream, stream_info.data(), stream_info.size() * sizeof(uint32_t));
         }
         if (rc == LSH_OK && p->plan.supported && !p->plan.ranged) {
             // step-major [m_pad][kpad] in scheduled order; padding samples (and the lanes
@@ -189,7 +139,7 @@ int upload_tables(lsh_params *p) {
         if (rc == LSH_OK && p->shared_ranged_plan.supported) {
             std::vector<float> lists;
             std::vector<uint32_t> offs, range_groups, stream_info;
-            build_shared_ranged_tables(p, lists, offs, range_groups, stream_info);
+            build_shared_ranged_tables(p, p->shared_ranged_plan, lists, offs, range_groups, stream_info);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;

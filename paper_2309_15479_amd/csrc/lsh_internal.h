@@ -149,10 +149,13 @@ constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather
 constexpr uint32_t kRangeBlockQuads = 3;     // quads of list entries per lane in one list block
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                   uint32_t L, void *stream, void *d_out2 = nullptr);
+void build_ranged_tables(const lsh_params *p, std::vector<uint32_t> &words, std::vector<uint32_t> &list_len,
+                         std::vector<uint32_t> &stream_info);
 constexpr uint32_t kSharedRangeBlocksPerWave = 16;  // blocks of 16 functions a contracting wave owns at most
 SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
-void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::vector<uint32_t> &offs,
-                                std::vector<uint32_t> &range_groups, std::vector<uint32_t> &stream_info);
+void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::vector<float> &coefs,
+                                std::vector<uint32_t> &offs, std::vector<uint32_t> &range_groups,
+                                std::vector<uint32_t> &stream_info);
 int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uint64_t N, void *d_out, void *stream);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,

@@ -39,6 +39,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstring>
+#include <vector>
 #include <type_traits>
 
 #include "sampled_common.h"
@@ -262,6 +264,64 @@ int launch(Kernel fn, const SampledArgs &args, dim3 grid, hipStream_t stream) {
 }
 
 }  // namespace
+
+// Host tables of the ranged kernel (stream_info: {first block, blocks} per gathering wave).
+void build_ranged_tables(const lsh_params *p, std::vector<uint32_t> &words, std::vector<uint32_t> &list_len,
+                         std::vector<uint32_t> &stream_info) {
+    // one stream of list blocks per gathering wave, in the order the wave consumes them:
+    // range after range, within a range the wave's functions-per-lane sets one after the
+    // other.  A block is kRangeBlockQuads quads of entries x 64 lanes: 16 bytes of
+    // coefficients per quad and lane, then 8 bytes of 16-bit LDS byte offsets
+    // (16 x (coordinate minus the range's first)).
+    const SampledPlan &pl = p->plan;
+    const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockQuads, fpt = pl.fpt;
+    const uint32_t real_sets = (p->k + 63) / 64, streams = pl.kblocks * CW;
+    const size_t block_words = (size_t)U * 64 * 6, off_base = (size_t)U * 64 * 4;
+    std::vector<size_t> first_entry((size_t)real_sets * R);  // of each (set, range) in p->order
+    size_t at = 0;
+    for (uint32_t s = 0; s < real_sets; ++s)
+        for (uint32_t q = 0; q < R; ++q) {
+            first_entry[(size_t)s * R + q] = at;
+            at += (size_t)p->chunk_steps[(size_t)s * R + q] * 64;
+        }
+    list_len.assign((size_t)streams * R * fpt, 0);
+    stream_info.assign((size_t)streams * 2, 0);
+    words.clear();
+    uint32_t blocks = 0;
+    for (uint32_t y = 0; y < pl.kblocks; ++y)
+        for (uint32_t cw = 0; cw < CW; ++cw) {
+            const uint32_t start = blocks;
+            for (uint32_t q = 0; q < R; ++q)
+                for (uint32_t f = 0; f < fpt; ++f) {
+                    const uint32_t s = (y * fpt + f) * CW + cw;
+                    const uint32_t T = s < real_sets ? p->chunk_steps[(size_t)s * R + q] : 0;  // multiple of 4
+                    list_len[((size_t)(y * CW + cw) * R + q) * fpt + f] = T;
+                    const uint32_t nb = (T / 4 + U - 1) / U;
+                    words.resize((size_t)(blocks + nb) * block_words, 0u);
+                    for (uint32_t e = 0; e < T; ++e)
+                        for (uint32_t l = 0; l < 64; ++l) {
+                            const uint32_t ent = p->order[first_entry[(size_t)s * R + q] + (size_t)e * 64 + l];
+                            const uint32_t j = s * 64 + l;
+                            uint32_t slot;
+                            float c = 0.f;
+                            if ((ent & kPadSample) || j >= p->k) {
+                                slot = (ent & ~kPadSample) % pl.classes;  // a slot of the wanted bank class
+                            } else {
+                                slot = p->idx[(size_t)j * p->m + ent] - q * pl.chunk;
+                                c = p->coef[(size_t)j * p->m + ent];
+                            }
+                            const size_t blk = (size_t)(blocks + e / (4 * U)) * block_words;
+                            const uint32_t quad = e / 4 % U, pos = e % 4;
+                            std::memcpy(&words[blk + ((size_t)quad * 64 + l) * 4 + pos], &c, 4);
+                            words[blk + off_base + ((size_t)quad * 64 + l) * 2 + pos / 2] |= (slot * 16u) << (16 * (pos % 2));
+                        }
+                    blocks += nb;
+                }
+            stream_info[(size_t)(y * CW + cw) * 2] = start;
+            stream_info[(size_t)(y * CW + cw) * 2 + 1] = blocks - start;
+        }
+    if (words.empty()) words.assign(4, 0u);
+}
 
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out, uint32_t L,
                   void *stream, void *d_out2) {

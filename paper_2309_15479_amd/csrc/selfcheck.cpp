@@ -1,0 +1,134 @@
+// Host-side check of the list tables that the ranged kernels consume (ranged_kernel.hip,
+// shared_ranged_kernel.hip): the tables are built exactly as for the device and walked the way
+// the kernels walk them (stream after stream, range after range, block after block, the same
+// index arithmetic) on a pseudo-random vector, in double precision; the result must be the
+// projection of Eq. 5, p_j = sum_i a~_j[i] v[S_j[i]], computed straight from the canonical
+// tables.  Needs no GPU: the most intricate host code of the library is testable where it is
+// written.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "lsh_internal.h"
+
+namespace lsh {
+namespace {
+
+// a deterministic vector with entries in [-1, 1) (SplitMix64; nothing of the hashing path)
+std::vector<double> test_vector(uint32_t n, uint64_t seed) {
+    std::vector<double> v(n);
+    uint64_t x = seed;
+    for (uint32_t c = 0; c < n; ++c) {
+        x += 0x9E3779B97F4A7C15ull;
+        uint64_t z = x;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        v[c] = (double)(z >> 11) * (2.0 / 9007199254740992.0) - 1.0;
+    }
+    return v;
+}
+
+// worst |walked - direct| / sum_i |a v| over the functions
+double compare(const lsh_params *p, const std::vector<double> &v, const std::vector<double> &walked) {
+    double worst = 0.0;
+    for (uint32_t j = 0; j < p->k; ++j) {
+        double direct = 0.0, scale = 0.0;
+        for (uint32_t i = 0; i < p->m; ++i) {
+            const double t = (double)p->coef[(size_t)j * p->m + i] * v[p->idx[(size_t)j * p->m + i]];
+            direct += t;
+            scale += std::fabs(t);
+        }
+        const double err = std::fabs(walked[j] - direct) / (scale > 0.0 ? scale : 1.0);
+        if (!(err <= worst)) worst = err;  // NaN counts as the worst
+    }
+    return worst;
+}
+
+double walk_ranged(const lsh_params *p, const std::vector<double> &v) {
+    const SampledPlan &pl = p->plan;
+    std::vector<uint32_t> words, list_len, info;
+    build_ranged_tables(p, words, list_len, info);
+    const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockQuads, fpt = pl.fpt;
+    const size_t block_words = (size_t)U * 64 * 6, off_base = (size_t)U * 64 * 4;
+    std::vector<double> walked(p->k, 0.0);
+    for (uint32_t y = 0; y < pl.kblocks; ++y)
+        for (uint32_t cw = 0; cw < CW; ++cw) {
+            const uint32_t stream = y * CW + cw, first = info[(size_t)stream * 2], blocks = info[(size_t)stream * 2 + 1];
+            uint32_t next = 0;
+            for (uint32_t r = 0; r < R; ++r)
+                for (uint32_t f = 0; f < fpt; ++f) {
+                    const uint32_t T = list_len[((size_t)stream * R + r) * fpt + f];
+                    for (uint32_t e = 0; e < T; ++e) {
+                        const uint32_t *blk = &words[(size_t)(first + next + e / (4 * U)) * block_words];
+                        const uint32_t quad = e / 4 % U, pos = e % 4;
+                        for (uint32_t l = 0; l < 64; ++l) {
+                            float c;
+                            std::memcpy(&c, &blk[((size_t)quad * 64 + l) * 4 + pos], 4);
+                            const uint32_t pair = blk[off_base + ((size_t)quad * 64 + l) * 2 + pos / 2];
+                            const uint32_t slot = ((pair >> (16 * (pos % 2))) & 0xFFFFu) / 16;
+                            const uint32_t coord = r * pl.chunk + slot;
+                            const uint32_t j = ((y * fpt + f) * CW + cw) * 64 + l;
+                            if (j < p->k) walked[j] += (double)c * (coord < p->n ? v[coord] : 0.0);
+                            else if (c != 0.f) return INFINITY;  // a lane beyond k must not contribute
+                        }
+                    }
+                    next += (T / 4 + U - 1) / U;
+                }
+            if (next != blocks) return INFINITY;  // the stream must end where the next tile's begins
+        }
+    return compare(p, v, walked);
+}
+
+double walk_shared_ranged(const lsh_params *p, const std::vector<double> &v) {
+    SharedRangedPlan pl = p->shared_ranged_plan;
+    std::vector<float> coefs;
+    std::vector<uint32_t> offs, groups, info;
+    build_shared_ranged_tables(p, pl, coefs, offs, groups, info);
+    const uint32_t U = pl.block_steps, OW = (U + 1) / 2, CW = kRangeComputeWaves, ring = 4;
+    std::vector<double> walked(p->k, 0.0);
+    for (uint32_t y = 0; y < pl.kblocks; ++y)
+        for (uint32_t cw = 0; cw < CW; ++cw) {
+            const uint32_t stream = y * CW + cw, first = info[(size_t)stream * 2], blocks = info[(size_t)stream * 2 + 1];
+            uint32_t next = 0;
+            for (uint32_t r = 0; r < pl.R; ++r)
+                for (uint32_t f = 0; f < pl.bpw; ++f) {
+                    const uint32_t nb = pl.short_lists ? 1 : ring * groups[r];
+                    const uint32_t blk = (y * pl.bpw + f) * CW + cw;  // global block number
+                    for (uint32_t b = 0; b < nb; ++b, ++next) {
+                        const float *cb = &coefs[(size_t)(first + next) * U * 64];
+                        const uint32_t *ob = &offs[(size_t)(first + next) * 4 * OW];
+                        for (uint32_t s = 0; s < U; ++s)
+                            for (uint32_t l = 0; l < 64; ++l) {
+                                const uint32_t four = s / 4 * 4, width = U - four >= 4 ? 4 : 2;
+                                const float c = cb[(size_t)four * 64 + l * width + s % 4];
+                                const uint32_t off = (ob[(l / 16) * OW + s / 2] >> (16 * (s & 1))) & 0xFFFFu;
+                                const uint32_t coord = r * kRangeCoords + off / 4;
+                                const uint32_t in_table = (blk % pl.blocks_per_table) * 16 + l % 16;
+                                const uint32_t j = (blk / pl.blocks_per_table) * pl.g + in_table;
+                                if (blk < pl.nblocks && in_table < pl.g) walked[j] += (double)c * (coord < p->n ? v[coord] : 0.0);
+                                else if (c != 0.f) return INFINITY;
+                            }
+                    }
+                }
+            if (next != blocks || blocks < ring) return INFINITY;
+        }
+    return compare(p, v, walked);
+}
+
+}  // namespace
+}  // namespace lsh
+
+int lsh_params_check_lists(const lsh_params_t *p, uint64_t seed, double *worst) {
+    if (!p || !worst) return LSH_ERR_INVALID_ARG;
+    const bool shared = p->shared_ranged_plan.supported;
+    const bool ranged = !shared && !p->shared_plan.supported && p->plan.supported && p->plan.ranged;
+    if (!shared && !ranged) return LSH_ERR_UNSUPPORTED;
+    try {
+        const std::vector<double> v = lsh::test_vector(p->n, seed);
+        *worst = shared ? lsh::walk_shared_ranged(p, v) : lsh::walk_ranged(p, v);
+    } catch (const std::bad_alloc &) {
+        return LSH_ERR_ALLOC;
+    }
+    return LSH_OK;
+}

@@ -286,9 +286,9 @@ SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t
 // coefficient of (row l % 16, sample l / 16) and the LDS byte offset of that sample's coordinate
 // inside the range.  Chooses the list layout (steps per block, short or long lists) and notes
 // it in the plan; range_groups holds, per range, the turns of the ring a list takes (long lists).
-void build_shared_ranged_tables(lsh_params *p, std::vector<float> &coefs, std::vector<uint32_t> &offs,
-                                std::vector<uint32_t> &range_groups, std::vector<uint32_t> &stream_info) {
-    SharedRangedPlan &pl = p->shared_ranged_plan;
+void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::vector<float> &coefs,
+                                std::vector<uint32_t> &offs, std::vector<uint32_t> &range_groups,
+                                std::vector<uint32_t> &stream_info) {
     const uint32_t R = pl.R, CW = kRangeComputeWaves, bpw = pl.bpw, m = p->m;
     const uint32_t tables = pl.nblocks / pl.blocks_per_table, streams = pl.kblocks * CW;
     // per table and range: the samples dealt to steps of four, coordinates of a step distinct

@@ -187,3 +187,30 @@ def test_chunked_gather_schedule_is_a_padded_permutation(n, k, m, repl):
             assert not unused[j][:used_len[j]].any()           # the unused part is a tail
         assert ((order[pad] & 0x7fffffff) < classes).all()
         assert passes >= (~unused).sum() / group
+
+
+@pytest.mark.parametrize("n,k,m,w,seed,repl,L", [
+    (4096, 2048, 64, 8.0, 4, False, 0),      # ranged gather kernel, four functions per lane
+    (4096, 520, 256, 8.0, 5, True, 0),       # k not a multiple of 64, duplicates in S
+    (4100, 512, 40, 2.0, 6, False, 0),       # a fifth range of four coordinates
+    (16384, 1024, 96, 1.0, 7, False, 0),     # sixteen ranges
+    (4096, 2048, 64, 8.0, 4, False, 128),    # one sample per table: short lists, blocks of eight steps
+    (4096, 2048, 256, 8.0, 4, False, 128),   # long lists, blocks of six steps
+    (4096, 1024, 1024, 8.0, 4, False, 32),   # tables of 32 functions (two blocks), blocks of four steps
+    (4100, 96, 40, 2.0, 58, True, 8),        # tables of 12, idle blocks, a short last range
+    (8192, 2048, 4, 8.0, 63, False, 128),    # nearly empty lists
+])
+def test_list_tables_walked_on_the_host(n, k, m, w, seed, repl, L):
+    """The list tables of the kernels that work by coordinate ranges, built as for the device and
+    walked on the host the way the kernels walk them, give the projections of Eq. 5 taken
+    straight from the canonical tables (lsh_params_check_lists; no GPU involved)."""
+    with binding.LshParams(n, k, m, w, seed, with_replacement=repl, shared_tables=L) as p:
+        for vector_seed in (1, 2):
+            assert p.check_lists(vector_seed) < 1e-14
+
+
+def test_list_check_needs_a_ranged_kernel():
+    with binding.LshParams(128, 64, 32, 4.0, 1) as p:   # whole vectors in LDS, lists in registers
+        with pytest.raises(binding.LshError) as e:
+            p.check_lists()
+        assert e.value.status == -4
