@@ -348,11 +348,14 @@ int lsh_index_best_inner_product(const lsh_index_t *index, const float *d_data, 
  * lsh_hash_mips_query d_out [Q][k] int32 bucket ids of the queries (a query whose sub-vector is
  *                     all zero projects to 0).
  * lsh_project_mips_*  the value before "+ b~_j) / w" as float, for parity checks.
- * All arithmetic is fp32; norms are summed in sample order, four partial sums.  The ids feed
+ * All arithmetic is fp32; a norm is the sum of four partial sums, each taken in the order the
+ * kernel walks the sample (the kappa~ pass and the data hash walk it alike, so the vector that
+ * attains kappa~_l gets exactly 0 under the root).  The ids feed
  * lsh_pack_keys and the index like any others.  Pointers are device pointers, outputs are the
  * caller's; asynchronous on `stream`.
  * Errors: as lsh_hash_fastlsh; UNSUPPORTED when the object has no shared samples or its shape
- * is outside the matrix-core kernel's (see lsh_params_create_shared).
+ * is outside the matrix-core kernels' (n % 4 == 0 and g % 4 == 0 at any n, see
+ * lsh_params_create_shared; there is no per-function gather fallback for these calls).
  */
 int lsh_mips_kappa(const lsh_params_t *params, const float *d_data, uint64_t N, int accumulate,
                    float *d_kappa2, void *stream);

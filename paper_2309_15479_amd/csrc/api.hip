@@ -30,9 +30,10 @@ void free_tables(lsh_params *p) {
     if (p->d_shared_extra) (void)hipFree(p->d_shared_extra);
     if (p->d_sr_lists) (void)hipFree(p->d_sr_lists);
     if (p->d_sr_offs) (void)hipFree(p->d_sr_offs);
+    if (p->d_sr_extra) (void)hipFree(p->d_sr_extra);
     if (p->d_sr_list_len) (void)hipFree(p->d_sr_list_len);
     if (p->d_sr_stream) (void)hipFree(p->d_sr_stream);
-    p->d_sr_lists = p->d_sr_offs = p->d_sr_list_len = p->d_sr_stream = nullptr;
+    p->d_sr_lists = p->d_sr_offs = p->d_sr_list_len = p->d_sr_stream = p->d_sr_extra = nullptr;
     p->d_shared_extra = nullptr;
     p->d_shared_coef = nullptr;
     p->d_shared_sample_off = nullptr;
@@ -139,13 +140,15 @@ int upload_tables(lsh_params *p) {
         if (rc == LSH_OK && p->shared_ranged_plan.supported) {
             std::vector<float> lists;
             std::vector<uint32_t> offs, range_groups, stream_info;
-            build_shared_ranged_tables(p, p->shared_ranged_plan, lists, offs, range_groups, stream_info);
+            std::vector<float> extra;
+            build_shared_ranged_tables(p, p->shared_ranged_plan, lists, offs, range_groups, stream_info, &extra);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
             };
             upload(&p->d_sr_lists, lists.data(), lists.size() * sizeof(float));
             upload(&p->d_sr_offs, offs.data(), offs.size() * sizeof(uint32_t));
+            upload(&p->d_sr_extra, extra.data(), extra.size() * sizeof(float));
             upload(&p->d_sr_list_len, range_groups.data(), range_groups.size() * sizeof(uint32_t));
             upload(&p->d_sr_stream, stream_info.data(), stream_info.size() * sizeof(uint32_t));
         }
@@ -412,9 +415,10 @@ int lsh_mips_kappa(const lsh_params_t *p, const float *d_data, uint64_t N, int a
     if (!d_kappa2) return LSH_ERR_INVALID_ARG;
     int rc = check_hash_args(p, d_data, d_kappa2, N);
     if (rc != LSH_OK) return rc;
-    if (!p->shared_plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (!p->shared_plan.supported && !p->shared_ranged_plan.supported) return LSH_ERR_UNSUPPORTED;
     if (!accumulate) rc = clear_floats(d_kappa2, p->shared_tables, stream);
     if (rc != LSH_OK || N == 0) return rc;
+    if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 3, d_data, N, d_kappa2, stream);
     return launch_shared(p, 3, d_data, N, d_kappa2, stream);
 }
 
@@ -423,16 +427,18 @@ static int mips_data(const lsh_params_t *p, const float *d_data, uint64_t N, con
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK) return rc;
     if (N && !d_kappa2) return LSH_ERR_INVALID_ARG;
-    if (!p->shared_plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (!p->shared_plan.supported && !p->shared_ranged_plan.supported) return LSH_ERR_UNSUPPORTED;
     if (N == 0) return LSH_OK;
+    if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 4, d_data, N, d_out, stream, d_kappa2, raw);
     return launch_shared(p, 4, d_data, N, d_out, stream, d_kappa2, raw);
 }
 
 static int mips_query(const lsh_params_t *p, const float *d_queries, uint64_t Q, void *d_out, void *stream, int raw) {
     int rc = check_hash_args(p, d_queries, d_out, Q);
     if (rc != LSH_OK) return rc;
-    if (!p->shared_plan.supported) return LSH_ERR_UNSUPPORTED;
+    if (!p->shared_plan.supported && !p->shared_ranged_plan.supported) return LSH_ERR_UNSUPPORTED;
     if (Q == 0) return LSH_OK;
+    if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 5, d_queries, Q, d_out, stream, nullptr, raw);
     return launch_shared(p, 5, d_queries, Q, d_out, stream, nullptr, raw);
 }
 

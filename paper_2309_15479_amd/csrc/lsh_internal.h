@@ -113,7 +113,7 @@ struct lsh_params {
     float *d_shared_extra = nullptr;
     // one sample per table, large n: lists of the shared-sample ranged kernel (null when unused)
     lsh::SharedRangedPlan shared_ranged_plan;
-    void *d_sr_lists = nullptr, *d_sr_offs = nullptr, *d_sr_list_len = nullptr, *d_sr_stream = nullptr;
+    void *d_sr_lists = nullptr, *d_sr_offs = nullptr, *d_sr_list_len = nullptr, *d_sr_stream = nullptr, *d_sr_extra = nullptr;
 };
 
 namespace lsh {
@@ -155,8 +155,9 @@ constexpr uint32_t kSharedRangeBlocksPerWave = 16;  // blocks of 16 functions a 
 SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::vector<float> &coefs,
                                 std::vector<uint32_t> &offs, std::vector<uint32_t> &range_groups,
-                                std::vector<uint32_t> &stream_info);
-int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uint64_t N, void *d_out, void *stream);
+                                std::vector<uint32_t> &stream_info, std::vector<float> *extra = nullptr);
+int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uint64_t N, void *d_out, void *stream,
+                         const float *d_kappa2 = nullptr, int raw = 0);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
                          std::vector<float> &offset, std::vector<float> &extra);

@@ -103,7 +103,7 @@ double walk_shared_ranged(const lsh_params *p, const std::vector<double> &v) {
                                 const uint32_t four = s / 4 * 4, width = U - four >= 4 ? 4 : 2;
                                 const float c = cb[(size_t)four * 64 + l * width + s % 4];
                                 const uint32_t off = (ob[(l / 16) * OW + s / 2] >> (16 * (s & 1))) & 0xFFFFu;
-                                const uint32_t coord = r * kRangeCoords + off / 4;
+                                const uint32_t coord = off / 4 < kRangeCoords ? r * kRangeCoords + off / 4 : p->n;  // beyond the range: a zero float
                                 const uint32_t in_table = (blk % pl.blocks_per_table) * 16 + l % 16;
                                 const uint32_t j = (blk / pl.blocks_per_table) * pl.g + in_table;
                                 if (blk < pl.nblocks && in_table < pl.g) walked[j] += (double)c * (coord < p->n ? v[coord] : 0.0);

@@ -39,6 +39,14 @@
 // range (short lists: the 16 blocks of a wave go round the ring) or a multiple of four blocks
 // (a list goes round the ring whole turns).  The matrix pipe has time to spare for the padding
 // steps: with the lists on time the launch is bound by reading the data.
+//
+// Maximum inner product search (appendix; one sample per table): as in shared_kernel.hip the
+// lanes hold the sampled coordinates, so ||S_l(v)||^2 costs one multiply-add per LDS read
+// (padding steps read a zero) and one MFMA with an all-ones row operand per block and tile to
+// add the four partial sums of a vector.  Modes: 3 kappa~_l^2 = max_v ||S_l(v)||^2 (atomic
+// maximum per table), 4 data hash, the projection plus a0_j sqrt(kappa~_l^2 - ||S_l(v)||^2),
+// 5 query hash, the projection divided by ||S_l(u)||; the extra component and the offset enter
+// as one more MFMA step with the row operand (a0_j, b~_j, 0, 0).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -78,18 +86,23 @@ struct SharedRangedArgs {
     float w, inv_w;
     int w_is_pow2, proj;
     void *out;
+    const float *extra;     // [nblocks][64] row operand (a0, b~, 0, 0) of the extra step (maximum inner product)
+    const float *kappa2;    // [tables] kappa~_l^2, input of the data hash
+    int raw;                // maximum-inner-product modes: projections instead of ids
     const float *coefs;     // list blocks: U steps x 64 lanes
     const uint32_t *offs;   // per list block: 4 sample slots x (U + 1) / 2 words of two 16-bit LDS byte offsets
 };
 
-// BPW: blocks of 16 functions per contracting wave; U: steps per list block; SHORT: every list is one block
-template <int BPW, int U, bool SHORT>
+// BPW: blocks of 16 functions per contracting wave; U: steps per list block; SHORT: every list is one block;
+// MODE: 0 ids or projections, 3 kappa~^2, 4 maximum-inner-product data hash, 5 query hash
+template <int BPW, int U, bool SHORT, int MODE>
 __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedRangedArgs a,
                                                                    const uint32_t *__restrict__ range_groups,
                                                                    const uint2 *__restrict__ streams) {
     static_assert(!SHORT || BPW % 4 == 0, "short lists go round the ring of four by blocks");
     static_assert(U % 2 == 0, "a lane loads the coefficients of four or two steps at a time");
     constexpr int NR = SHORT ? 4 : kLongRing;  // ring sets
+    constexpr bool KAPPA = MODE == 3, MDATA = MODE == 4, MQUERY = MODE == 5, NORMS = MODE >= 3;
     extern __shared__ __align__(16) char lds_sr[];  // 2 buffers x [16 vectors][1028 floats]
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
@@ -179,17 +192,28 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
 #pragma unroll
     for (int i = 0; i < NR - 1; ++i) load_block(i);
     const uint32_t row_off = (lane & 15) * kRowFloats * 4;  // this lane's vector in the tile
+    // the four floats after a row's 1024 coordinates stay zero: what padding steps read
+    if (wave == 0) {
+        const uint32_t buffer = lane >> 5, row = (lane >> 1) & 15, half = lane & 1;
+        *reinterpret_cast<uint2 *>(lds_sr + buffer * kBufBytesSR + row * kRowFloats * 4 + kCs * 4 + half * 8) = make_uint2(0u, 0u);
+    }
+    [[maybe_unused]] float kmax[KAPPA ? BPW : 1];  // kappa~^2 pass: largest ||S(v)||^2 seen per block
+#pragma unroll
+    for (int f = 0; f < (KAPPA ? BPW : 1); ++f) kmax[f] = 0.f;
 
     __syncthreads();  // first buffer written
     uint32_t b = 0;
     for (uint64_t t = first_tile; t < ntiles; t += gridDim.x) {
         floatx4 acc[BPW];
+        [[maybe_unused]] float nrm[NORMS ? BPW : 1];  // this lane's share of ||S(v)||^2 per block
 #pragma unroll
         for (int f = 0; f < BPW; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int f = 0; f < (NORMS ? BPW : 1); ++f) nrm[f] = 0.f;
         for (uint32_t r = 0; r < R; ++r) {
             const char *buf = lds_sr + b * kBufBytesSR + row_off;
             // one block: all reads, then the MFMAs
-            auto run = [&](int set, floatx4 &c) __attribute__((always_inline)) {
+            auto run = [&](int set, floatx4 &c, [[maybe_unused]] float &n2) __attribute__((always_inline)) {
                 float x[U];
                 // the offsets are taken apart here, not where they were requested (which would wait for them there)
 #pragma unroll
@@ -201,14 +225,17 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                 }
                 __builtin_amdgcn_sched_barrier(0);  // all reads of the block go out before its first MFMA
 #pragma unroll
-                for (int s = 0; s < U; ++s) c = __builtin_amdgcn_mfma_f32_16x16x4f32(ring_c[set][s], x[s], c, 0, 0, 0);
+                for (int s = 0; s < U; ++s) {
+                    if constexpr (!KAPPA) c = __builtin_amdgcn_mfma_f32_16x16x4f32(ring_c[set][s], x[s], c, 0, 0, 0);
+                    if constexpr (NORMS) n2 = fmaf(x[s], x[s], n2);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             };
             if constexpr (SHORT) {
 #pragma unroll
                 for (int f = 0; f < BPW; ++f) {
                     load_block((f + 3) & 3);
-                    run(f & 3, acc[f]);
+                    run(f & 3, acc[f], nrm[NORMS ? f : 0]);
                 }
             } else {
                 const uint32_t groups = range_groups[r];  // turns of the ring per list in this range, at least one
@@ -219,7 +246,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
 #pragma unroll
                         for (int q = 0; q < NR; ++q) {
                             load_block((q + NR - 1) % NR);
-                            run(q, acc[f]);
+                            run(q, acc[f], nrm[NORMS ? f : 0]);
                         }
                     } while (--left);
                 }
@@ -233,11 +260,44 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                     const uint32_t blk = (blockIdx.y * BPW + f) * kCWs + wave;  // global block number
                     const uint32_t in_table = (blk % a.blocks_per_table) * 16 + 4 * (ln >> 4);
                     const uint32_t j = (blk / a.blocks_per_table) * a.g + in_table;
+                    [[maybe_unused]] float norm2 = 0.f;
+                    if constexpr (NORMS) {
+                        // lanes c, c + 16, c + 32, c + 48 hold the partial sums of vector c: an MFMA with an
+                        // all-ones row operand adds them and leaves the sum in every lane of the vector (the
+                        // same instruction on the same operands in the kappa~ pass and in the data hash)
+                        const floatx4 sum = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, nrm[f], floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                        norm2 = sum[0];
+                    }
+                    if constexpr (KAPPA) {
+                        kmax[f] = fmaxf(kmax[f], norm2);  // rows beyond N repeat the last vector
+                        continue;
+                    }
+                    if constexpr (MDATA || MQUERY) {
+                        if (blk < a.nblocks) {  // uniform
+                            // data: sqrt(kappa~^2 - ||S(v)||^2) (0 when the norm exceeds kappa~); query: 1 / ||S(u)||
+                            float scale;
+                            if constexpr (MDATA) {
+                                scale = __builtin_amdgcn_sqrtf(fmaxf(a.kappa2[blk / a.blocks_per_table] - norm2, 0.f));  // 1 ulp; sqrt(0) = 0
+                            } else {
+                                scale = norm2 > 0.f ? __builtin_amdgcn_rsqf(norm2) : 0.f;
+                                acc[f] *= scale;
+                            }
+                            // the extra step: + a0_j * scale (data) + b~_j (ids)
+                            const uint32_t slot = ln >> 4;
+                            const float one = a.raw ? 0.f : 1.f;
+                            const float colx = slot == 0 ? (MDATA ? scale : 0.f) : (slot == 1 ? one : 0.f);
+                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.extra[(size_t)blk * 64 + ln], colx, acc[f], 0, 0, 0);
+                        }
+                    }
                     if (blk < a.nblocks && in_table < a.g && vec < a.N) {  // g is a multiple of 4: whole quads
                         uintx4 v;
-                        if (a.proj) {
+                        if (NORMS ? a.raw : a.proj) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(acc[f][e]);
+                        } else if constexpr (NORMS) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)  // b~ is in the accumulator already
+                                v[e] = (uint32_t)(int)floorf(a.w_is_pow2 ? acc[f][e] * a.inv_w : acc[f][e] / a.w);
                         } else {
                             const floatx4 bq = *reinterpret_cast<const floatx4 *>(a.off + j);
 #pragma unroll
@@ -252,6 +312,19 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
             }
             __syncthreads();  // the other buffer is complete, everyone is done with this one
             b ^= 1;
+        }
+    }
+    if constexpr (KAPPA) {
+        // max over the wave's 16 vector columns, then one atomic per block; norms are >= 0, so
+        // their bit patterns order like the values
+#pragma unroll
+        for (int f = 0; f < BPW; ++f) {
+            float v = kmax[f];
+#pragma unroll
+            for (int s = 1; s < 16; s *= 2) v = fmaxf(v, __shfl_xor(v, s));
+            const uint32_t blk = (blockIdx.y * BPW + f) * kCWs + wave;
+            if (lane == 0 && blk < a.nblocks)
+                atomicMax(reinterpret_cast<unsigned int *>(a.out) + blk / a.blocks_per_table, __float_as_uint(v));
         }
     }
 }
@@ -288,7 +361,17 @@ SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t
 // it in the plan; range_groups holds, per range, the turns of the ring a list takes (long lists).
 void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::vector<float> &coefs,
                                 std::vector<uint32_t> &offs, std::vector<uint32_t> &range_groups,
-                                std::vector<uint32_t> &stream_info) {
+                                std::vector<uint32_t> &stream_info, std::vector<float> *extra) {
+    if (extra) {  // row operand of the extra step: sample slot 0 holds a0_j, slot 1 the offset b~_j
+        extra->assign((size_t)pl.nblocks * 64, 0.f);
+        for (uint32_t blk = 0; blk < pl.nblocks; ++blk) {
+            const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
+            for (uint32_t i = 0; i < 16 && first + i < pl.g; ++i) {
+                if (!p->extra.empty()) (*extra)[(size_t)blk * 64 + i] = p->extra[table * pl.g + first + i];
+                (*extra)[(size_t)blk * 64 + 16 + i] = p->off[table * pl.g + first + i];
+            }
+        }
+    }
     const uint32_t R = pl.R, CW = kRangeComputeWaves, bpw = pl.bpw, m = p->m;
     const uint32_t tables = pl.nblocks / pl.blocks_per_table, streams = pl.kblocks * CW;
     // per table and range: the samples dealt to steps of four, coordinates of a step distinct
@@ -355,11 +438,13 @@ void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::
     }
     stream_info.assign((size_t)streams * 2, 0);
     coefs.assign((size_t)streams * per_stream * U * 64, 0.f);
-    // steps and slots that only pad (coefficient zero) read coordinate kq of the range: four different
-    // banks per vector, like a step of real samples
+    // steps and slots that only pad (coefficient zero) read one of the four zero floats that follow a
+    // row's 1024 coordinates: four different banks per vector, like a step of real samples, and
+    // nothing for the squared norms of the maximum-inner-product modes
     offs.assign((size_t)streams * per_stream * 4 * OW, 0u);
     for (size_t rec = 0; rec < offs.size() / OW; ++rec)
-        for (uint32_t s = 0; s < U; ++s) offs[rec * OW + s / 2] |= ((uint32_t)(rec & 3) * 4u) << (16 * (s & 1));
+        for (uint32_t s = 0; s < U; ++s)
+            offs[rec * OW + s / 2] |= ((kRangeCoords + (uint32_t)(rec & 3)) * 4u) << (16 * (s & 1));
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
             const uint32_t stream = y * CW + cw;
@@ -392,8 +477,10 @@ void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::
         }
 }
 
-// proj != 0: raw projections instead of bucket ids
-int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uint64_t N, void *d_out, void *stream) {
+// mode: 0 bucket ids, 1 raw projections, 3 kappa~^2 per table (atomic maximum into d_out), 4 and 5
+// the maximum-inner-product data and query hashes (raw != 0: their projections)
+int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uint64_t N, void *d_out, void *stream,
+                         const float *d_kappa2, int raw) {
     const SharedRangedPlan &pl = p->shared_ranged_plan;
     if (!pl.supported || !p->d_sr_lists || !p->d_sr_offs) return LSH_ERR_UNSUPPORTED;
     SharedRangedArgs a;
@@ -410,7 +497,11 @@ int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uin
     a.inv_w = 1.0f / p->w;
     int exp2 = 0;
     a.w_is_pow2 = (std::frexp(p->w, &exp2) == 0.5f) ? 1 : 0;
-    a.proj = proj;
+    a.proj = mode == 1;
+    a.extra = static_cast<const float *>(p->d_sr_extra);
+    a.kappa2 = d_kappa2;
+    a.raw = raw;
+    if (mode >= 3 && !p->d_sr_extra) return LSH_ERR_UNSUPPORTED;
     a.out = d_out;
     a.coefs = static_cast<const float *>(p->d_sr_lists);
     a.offs = static_cast<const uint32_t *>(p->d_sr_offs);
@@ -423,15 +514,23 @@ int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uin
     if (gx > ntiles) gx = ntiles;
     const dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-#define LSH_SR_LAUNCH(B_, U_, S_) \
+#define LSH_SR_LAUNCH(B_, U_, S_, M_) \
     { \
-        auto fn = &shared_ranged_kernel<B_, U_, S_>; \
+        auto fn = &shared_ranged_kernel<B_, U_, S_, M_>; \
         if (ensure_lds_limit(reinterpret_cast<const void *>(fn), 2 * kBufBytesSR) != LSH_OK) return LSH_ERR_HIP; \
         hipLaunchKernelGGL(fn, grid, dim3(kThreadsSR), 2 * kBufBytesSR, s, a, groups, streams); \
     }
+#define LSH_SR_MODES(B_, U_, S_) \
+    { \
+        if (mode <= 1) LSH_SR_LAUNCH(B_, U_, S_, 0) \
+        else if (mode == 3) LSH_SR_LAUNCH(B_, U_, S_, 3) \
+        else if (mode == 4) LSH_SR_LAUNCH(B_, U_, S_, 4) \
+        else if (mode == 5) LSH_SR_LAUNCH(B_, U_, S_, 5) \
+        else return LSH_ERR_INVALID_ARG; \
+    }
 #define LSH_SR_STEPS(B_, U_) \
     case U_: \
-        if (pl.short_lists) LSH_SR_LAUNCH(B_, U_, true) else LSH_SR_LAUNCH(B_, U_, false) \
+        if (pl.short_lists) LSH_SR_MODES(B_, U_, true) else LSH_SR_MODES(B_, U_, false) \
         break;
 #define LSH_SR_CASE(B_) \
     case B_: \
@@ -446,6 +545,7 @@ int launch_shared_ranged(const lsh_params *p, int proj, const float *d_data, uin
     }
 #undef LSH_SR_CASE
 #undef LSH_SR_STEPS
+#undef LSH_SR_MODES
 #undef LSH_SR_LAUNCH
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }
