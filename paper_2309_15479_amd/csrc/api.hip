@@ -1,6 +1,7 @@
 // C ABI of liblsh (see include/lsh.h): argument checks, table upload, dispatch.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -83,6 +84,7 @@ int upload_tables(lsh_params *p) {
         if (rc == LSH_OK && p->plan.supported && p->plan.ranged) {
             std::vector<uint32_t> words, list_len, stream_info;
             build_ranged_tables(p, words, list_len, stream_info);
+            p->ranged_bar_stride = (uint32_t)(list_len.size() / p->plan.kblocks);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
@@ -233,8 +235,11 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
             try {
                 const SampledPlan &pl = p->plan;
                 p->schedule_cost =
-                    pl.ranged ? schedule_chunked(p->idx, k, m, pl.chunk, pl.nchunks, 4, pl.group, pl.classes,
-                                                 p->chunk_steps, p->order)
+                    pl.ranged ? schedule_windowed(p->idx, k, m, pl.chunk, pl.nchunks, pl.stages, kWindowLook,
+                                                  pl.fpt * kRangeComputeWaves, 4 * pl.qpf,
+                                                  m + (uint32_t)std::sqrt((double)m),  // spare steps: see schedule_windowed
+                                                  pl.group, pl.classes,
+                                                  p->chunk_steps, p->order)
                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, pl.copies,
                                                   p->order);
             } catch (const std::bad_alloc &) {
@@ -316,12 +321,14 @@ int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *st
     if (!pl.supported) return LSH_ERR_UNSUPPORTED;
     uint32_t nsteps = pl.m_pad;
     const bool by_range = pl.ranged;
-    if (by_range) {  // longest concatenation of a wave's per-range lists
+    const uint32_t sets_per_wg = pl.fpt * kRangeComputeWaves;
+    std::vector<uint32_t> wg_steps;
+    if (by_range) {  // the longest list of any workgroup (all lists of a workgroup are equally long)
         nsteps = 0;
-        for (uint32_t w = 0; w < (p->k + 63) / 64; ++w) {
-            uint32_t total = 0;
-            for (uint32_t q = 0; q < pl.nchunks; ++q) total += p->chunk_steps[(size_t)w * pl.nchunks + q];
-            nsteps = total > nsteps ? total : nsteps;
+        wg_steps.assign(pl.kblocks, 0);
+        for (uint32_t y = 0; y < pl.kblocks; ++y) {
+            for (uint32_t q = 0; q < pl.stages; ++q) wg_steps[y] += p->chunk_steps[(size_t)y * pl.stages + q];
+            nsteps = std::max(nsteps, wg_steps[y]);
         }
     }
     if (steps) *steps = nsteps;
@@ -334,17 +341,13 @@ int lsh_params_get_schedule(const lsh_params_t *p, uint32_t *order, uint32_t *st
         return LSH_OK;
     }
     std::fill(order, order + (size_t)p->k * nsteps, 0xFFFFFFFFu);
-    size_t base = 0;
+    size_t base = 0;  // p->order: set after set, each stage after stage, steps x 64
     for (uint32_t w = 0; w < (p->k + 63) / 64; ++w) {
-        uint32_t at = 0;
-        for (uint32_t q = 0; q < pl.nchunks; ++q) {
-            const uint32_t len = p->chunk_steps[(size_t)w * pl.nchunks + q];
-            for (uint32_t st = 0; st < len; ++st)
-                for (uint32_t l = 0; l < 64 && w * 64 + l < p->k; ++l)
-                    order[(size_t)(w * 64 + l) * nsteps + at + st] = p->order[base + (size_t)st * 64 + l];
-            at += len;
-            base += (size_t)len * 64;
-        }
+        const uint32_t len = wg_steps[w / sets_per_wg];
+        for (uint32_t st = 0; st < len; ++st)
+            for (uint32_t l = 0; l < 64 && w * 64 + l < p->k; ++l)
+                order[(size_t)(w * 64 + l) * nsteps + st] = p->order[base + (size_t)st * 64 + l];
+        base += (size_t)len * 64;
     }
     return LSH_OK;
 }

@@ -31,9 +31,11 @@ struct SampledPlan {
     uint32_t lds_bytes = 0;  // LDS bytes of one tile buffer (both copies when copies == 2)
     uint32_t copies = 1;     // 2: the tile is kept twice, the second copy with rotated bank classes
     bool reg_table = false;  // register-list kernel: (offset, coef) lists live in VGPRs
-    bool ranged = false;     // ranged kernel (ranged_kernel.hip): lists bucketed by 1024-coordinate range, packed triples
+    bool ranged = false;     // ranged kernel (ranged_kernel.hip): lists cut by coordinate range, packed quads of entries
     uint32_t chunk = 0, nchunks = 0;  // ranged kernel: coordinates per range, number of ranges
+    uint32_t stages = 0;     // ranged kernel: steps of the range ring per tile (>= nchunks; divides or is a multiple of the ring)
     uint32_t fpt = 1;        // ranged kernel: functions per lane
+    uint32_t qpf = 1;        // ranged kernel: quads of entries per function in one list block
     uint32_t prefetch = 0;   // register-list kernel: 64-coordinate chunks fetched per wave and tile
     bool supported = false;
 };
@@ -96,10 +98,11 @@ struct lsh_params {
     lsh::SampledPlan plan;
     std::vector<uint32_t> order;       // [k][m_pad] visiting order of each function's samples
     uint64_t schedule_cost = 0;        // modelled LDS passes (see schedule.cpp)
-    std::vector<uint32_t> chunk_steps; // ranged plan: [sets of 64 functions][nchunks] list length
+    std::vector<uint32_t> chunk_steps; // ranged plan: [workgroups along the function axis][stages] entries per function and stage
     lsh::Sample *d_samples = nullptr;  // flat plans: [m_pad][kpad] step-major
-    // ranged plan: packed list blocks (quads of entries), list lengths [stream][range][fpt], streams {first block, blocks}
+    // ranged plan: packed list blocks (quads of entries), barriers after each block [kblocks][blocks + 1], streams {first block, blocks}
     void *d_triples = nullptr, *d_list_len = nullptr, *d_stream = nullptr;
+    uint32_t ranged_bar_stride = 0;    // barrier counts per workgroup in d_list_len
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n]: row j = a_j written out over all n coordinates; m == n or n == 128, else null
     uint32_t kpad_dense = 0;
@@ -130,9 +133,10 @@ int generate_extra_coefficients(uint32_t k, uint64_t seed, std::vector<float> &e
 uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t m_pad,
                           uint32_t group, uint32_t classes, uint32_t copies, std::vector<uint32_t> &order_out);
 
-uint64_t schedule_chunked(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t chunk,
-                          uint32_t nchunks, uint32_t step_quantum, uint32_t group, uint32_t classes,
-                          std::vector<uint32_t> &steps_out, std::vector<uint32_t> &order_out);
+uint64_t schedule_windowed(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t chunk,
+                           uint32_t nchunks, uint32_t stages, uint32_t look, uint32_t sets_per_workgroup,
+                           uint32_t step_quantum, uint32_t min_steps, uint32_t group, uint32_t classes,
+                           std::vector<uint32_t> &steps_out, std::vector<uint32_t> &order_out);
 
 // device: plan + upload + launches (defined in the .hip files)
 SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m);
@@ -144,9 +148,11 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
                    uint32_t L, void *stream, void *d_out2 = nullptr);
 bool sampled_ids_keys_supported(const lsh_params *p, uint32_t L);
 // ranged kernel (ranged_kernel.hip): geometry constants the host tables are built for
-constexpr uint32_t kRangeCoords = 1024;      // coordinates per range (one LDS buffer holds 16 vectors of them)
-constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather (the others load tiles)
-constexpr uint32_t kRangeBlockQuads = 3;     // quads of list entries per lane in one list block
+constexpr uint32_t kRangeCoords = 1024;      // shared-sample ranged kernel: coordinates per range
+constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather or contract (the others load tiles)
+constexpr uint32_t kWindowCoords = 256;      // gather ranged kernel: coordinates per range (one ring slot holds 16 vectors of them)
+constexpr uint32_t kWindowSlots = 8;         // ring slots in LDS
+constexpr uint32_t kWindowLook = 6;          // a stage may read its own range and this many after it (the last slot is being filled)
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                   uint32_t L, void *stream, void *d_out2 = nullptr);
 void build_ranged_tables(const lsh_params *p, std::vector<uint32_t> &words, std::vector<uint32_t> &list_len,

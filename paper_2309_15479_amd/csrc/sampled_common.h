@@ -66,9 +66,10 @@ struct SampledArgs {
     uint32_t buf_floats, copy_b_floats;
     // ranged kernel only (ranged_kernel.hip)
     uint32_t chunk, nchunks;     // coordinates per range, number of ranges
-    const uint4 *triples;        // list blocks (quads of entries: coefficients, then 16-bit LDS offsets), stream after stream
-    const uint32_t *list_len;    // [stream][range][functions per lane] entries of each list
-    const uint2 *stream;         // [stream] {first block, blocks}
+    uint32_t stages, bar_stride; // stages per tile (a multiple of the ring's slots); words per workgroup in list_len
+    const uint4 *triples;        // list blocks (quads of entries: coefficients, then 16-bit LDS slot numbers), stream after stream
+    const uint32_t *list_len;    // [workgroup along the function axis][bar_stride] barriers before the first block of a tile and after each block
+    const uint2 *stream;         // [stream] {first block, blocks per tile}
     uint32_t fpt;                // functions per lane
 };
 

@@ -389,10 +389,16 @@ SampledPlan plan_sampled(uint32_t n, uint32_t k, uint32_t m) {
         pl.fpt = (per_wg + kRangeComputeWaves - 1) / kRangeComputeWaves;
         pl.kpad = pl.kblocks * kRangeComputeWaves * pl.fpt * 64;
         pl.block = 64 * kRangeComputeWaves;
-        pl.chunk = kRangeCoords;
-        pl.nchunks = (n + kRangeCoords - 1) / kRangeCoords;
+        pl.chunk = kWindowCoords;
+        pl.nchunks = (n + kWindowCoords - 1) / kWindowCoords;
+        // quads of a function per list block: blocks of 4 quads (3 with three functions per
+        // lane) keep the next block's loads far enough ahead, but a stage is a whole number of
+        // blocks, so no more quads than a function has samples per range
+        pl.qpf = 4 / pl.fpt;
+        while (pl.qpf > 1 && (uint64_t)pl.qpf * 4 * pl.nchunks > m) pl.qpf /= 2;
+        pl.stages = (pl.nchunks + kWindowSlots - 1) / kWindowSlots * kWindowSlots;
         pl.rt = 4; pl.sub = 4; pl.sp = 4; pl.classes = 16; pl.group = 16;
-        pl.lds_bytes = 2 * 4 * kRangeCoords * 16;
+        pl.lds_bytes = kWindowSlots * 4 * kWindowCoords * 16;
         pl.copies = 1;
         pl.ranged = true;
         pl.supported = true;

@@ -27,8 +27,8 @@
 // (balance_copies), and the decomposition above comes out conflict-free or nearly so.
 //
 // Two table shapes are built from it: the flat one (every function's m samples, padded to
-// m_pad) and the chunked one (samples bucketed by coordinate range, every wave's bucket
-// padded to the longest list among its 64 lanes).
+// m_pad) and the windowed one for large n (samples visited range by range with a window of
+// ranges to work ahead in; see schedule_windowed).
 #include <algorithm>
 #include <numeric>
 
@@ -177,6 +177,283 @@ std::vector<uint32_t> balance_copies(const std::vector<uint32_t> &a, const std::
     return cur;
 }
 
+// Orders one stage of a pass group: every lane has at most `steps` samples (cls[l][i] = bank
+// class); out[l][step] = i or kPadSample | class.  A class wanted at most `steps` times gets
+// one vertex, a class wanted more often one vertex per `steps` samples; padding entries fill
+// every lane up to `steps` edges on vertices that still have room.  Lanes and vertices then
+// have at most `steps` edges each, so the edges can be coloured with `steps` colours with no
+// colour twice at a lane or a vertex (Koenig's edge-colouring theorem; alternating-path
+// recolouring), and colour = step: two lanes collide in a step only through a class's second
+// vertex, that is once per sample beyond `steps` at most.
+struct StageColoring {
+    struct Edge { int lane, vertex; uint32_t payload; int colour; };
+    std::vector<Edge> edges;
+    std::vector<std::vector<int>> at_lane, at_vertex;  // [lane or vertex][colour] -> edge or -1
+    std::vector<int> degree, load;
+
+    int free_colour(const std::vector<int> &row) const {
+        for (size_t c = 0; c < row.size(); ++c)
+            if (row[c] < 0) return (int)c;
+        return -1;
+    }
+
+    uint64_t run(const std::vector<std::vector<uint32_t>> &cls, int classes, int steps,
+                 std::vector<std::vector<uint32_t>> &out) {
+        const int lanes = (int)cls.size();
+        edges.clear();
+        std::vector<int> wanted(classes, 0);
+        int vertices = classes;
+        for (int l = 0; l < lanes; ++l)
+            for (uint32_t i = 0; i < cls[l].size(); ++i) {
+                const int c = (int)cls[l][i], copy = wanted[c]++ / steps;
+                edges.push_back({l, c + copy * classes, i, -1});
+                vertices = std::max(vertices, c + (copy + 1) * classes);
+            }
+        degree.assign(vertices, 0);
+        for (const Edge &e : edges) ++degree[e.vertex];
+        for (int l = 0; l < lanes; ++l)
+            for (int pad = (int)cls[l].size(); pad < steps; ++pad) {
+                int best = 0;  // the emptiest class: its first vertex has room, since all edges together are lanes x steps
+                for (int c = 1; c < classes; ++c)
+                    if (degree[c] < degree[best]) best = c;
+                ++degree[best];
+                edges.push_back({l, best, kPadSample | (uint32_t)best, -1});
+            }
+        at_lane.assign(lanes, std::vector<int>(steps, -1));
+        at_vertex.assign(vertices, std::vector<int>(steps, -1));
+        std::vector<int> path;
+        for (int e = 0; e < (int)edges.size(); ++e) {
+            const int l = edges[e].lane, v = edges[e].vertex;
+            const int a = free_colour(at_lane[l]);
+            int b = free_colour(at_vertex[v]);
+            if (at_vertex[v][a] >= 0) {
+                // colour a is taken at v: swap a and b along the path of edges coloured a, b, a, ...
+                // that starts at v (it cannot come back to l, which has no edge of colour a)
+                path.clear();
+                int x = at_vertex[v][a];
+                bool on_vertex_side = true;  // x was found from its vertex end; continue from its lane end
+                while (x >= 0) {
+                    path.push_back(x);
+                    const int want = edges[x].colour == a ? b : a;
+                    x = on_vertex_side ? at_lane[edges[x].lane][want] : at_vertex[edges[x].vertex][want];
+                    on_vertex_side = !on_vertex_side;
+                }
+                for (int y : path) {
+                    at_lane[edges[y].lane][edges[y].colour] = -1;
+                    at_vertex[edges[y].vertex][edges[y].colour] = -1;
+                }
+                for (int y : path) {
+                    edges[y].colour = edges[y].colour == a ? b : a;
+                    at_lane[edges[y].lane][edges[y].colour] = y;
+                    at_vertex[edges[y].vertex][edges[y].colour] = y;
+                }
+            }
+            edges[e].colour = a;
+            at_lane[l][a] = e;
+            at_vertex[v][a] = e;
+        }
+        out.assign(lanes, std::vector<uint32_t>(steps, kPadSample));
+        uint64_t cost = 0;
+        for (int st = 0; st < steps; ++st) {
+            load.assign(classes, 0);
+            for (int l = 0; l < lanes; ++l) {
+                const Edge &e = edges[at_lane[l][st]];
+                out[l][st] = e.payload;
+                ++load[e.vertex % classes];
+            }
+            cost += (uint64_t)*std::max_element(load.begin(), load.end());
+        }
+        return cost;
+    }
+};
+
+// Schedules one pass group over the stages of a tile (see schedule_windowed): stage by stage it
+// picks the samples every lane visits in that stage so that no bank class is wanted more often
+// than the stage has steps, then leaves the order inside the stage to StageColoring.
+struct WindowScheduler {
+    int lanes = 0, classes = 0;
+    std::vector<std::vector<uint32_t>> by;            // [lane] list positions bucketed by (range, class)
+    std::vector<std::vector<uint32_t>> bucket_first;  // [lane][range * classes + class] first entry of the bucket in `by`
+    std::vector<std::vector<uint32_t>> bucket_left;   // [lane][range * classes + class] entries not yet visited
+    std::vector<std::vector<int>> left_in;            // [lane][range] samples not yet visited
+    std::vector<int> total_left;
+    std::vector<std::vector<int>> avail, flow;        // [lane][class] optional samples on offer / taken
+    std::vector<int> room, cap, from_lane, from_class, seen_lane, seen_class, want, class_order;
+    StageColoring inner;
+
+    // takes one sample of class c from the earliest of lane l's ranges first .. last that has one
+    uint32_t take(int l, int c, int first, int last) {
+        for (int r = first; r <= last; ++r) {
+            uint32_t &left = bucket_left[l][(size_t)r * classes + c];
+            if (!left) continue;
+            --left;
+            --left_in[l][r];
+            --total_left[l];
+            return by[l][bucket_first[l][(size_t)r * classes + c] + left];
+        }
+        return kPadSample;  // not reached: the caller counted the class in
+    }
+
+    // One more optional sample for lane l0 (a lane with room): an augmenting path lane -> class
+    // with spare capacity, re-routing what other lanes have taken.
+    bool augment(int l0) {
+        std::fill(seen_lane.begin(), seen_lane.end(), 0);
+        std::fill(seen_class.begin(), seen_class.end(), 0);
+        std::vector<int> queue_l(1, l0);
+        seen_lane[l0] = 1;
+        from_lane.assign(lanes, -1);  // class through which a lane was reached (giving one up)
+        for (size_t q = 0; q < queue_l.size(); ++q) {
+            const int l = queue_l[q];
+            for (int c : class_order) {  // the classes the group still wants most first
+                if (seen_class[c] || flow[l][c] >= avail[l][c]) continue;
+                seen_class[c] = 1;
+                from_class[c] = l;
+                if (cap[c] > 0) {  // spare capacity: push one unit along the path
+                    --cap[c];
+                    int cc = c;
+                    for (;;) {
+                        const int ll = from_class[cc];
+                        ++flow[ll][cc];
+                        if (ll == l0) return true;
+                        cc = from_lane[ll];
+                        --flow[ll][cc];
+                    }
+                }
+                for (int l2 = 0; l2 < lanes; ++l2)  // a lane that holds a sample of c could take another class instead
+                    if (!seen_lane[l2] && flow[l2][c] > 0) {
+                        seen_lane[l2] = 1;
+                        from_lane[l2] = c;
+                        queue_l.push_back(l2);
+                    }
+            }
+        }
+        return false;
+    }
+
+    // range_of[l][i], cls[l][i]: range and bank class of lane l's i-th sample (ranges ascending).
+    // out[l][step] = i or kPadSample | class, over the sum of len[] steps.
+    uint64_t run(const std::vector<std::vector<uint32_t>> &range_of, const std::vector<std::vector<uint32_t>> &cls,
+                 int nclasses, int nranges, int look, const uint32_t *len, int stages,
+                 std::vector<std::vector<uint32_t>> &out) {
+        lanes = (int)cls.size();
+        classes = nclasses;
+        uint32_t steps_total = 0;
+        for (int s = 0; s < stages; ++s) steps_total += len[s];
+        by.resize(lanes);
+        bucket_first.resize(lanes);
+        bucket_left.resize(lanes);
+        left_in.assign(lanes, std::vector<int>(nranges, 0));
+        total_left.assign(lanes, 0);
+        avail.assign(lanes, std::vector<int>(classes, 0));
+        flow.assign(lanes, std::vector<int>(classes, 0));
+        room.assign(lanes, 0);
+        cap.assign(classes, 0);
+        from_class.assign(classes, -1);
+        seen_lane.assign(lanes, 0);
+        seen_class.assign(classes, 0);
+        out.assign(lanes, std::vector<uint32_t>(steps_total, 0));
+        for (int l = 0; l < lanes; ++l) {
+            by[l].clear();
+            // bucket the positions by (range, class), last first so that taking from the back yields list order
+            std::vector<std::vector<uint32_t>> tmp((size_t)nranges * classes);
+            for (uint32_t i = (uint32_t)cls[l].size(); i-- > 0;) tmp[(size_t)range_of[l][i] * classes + cls[l][i]].push_back(i);
+            bucket_first[l].assign((size_t)nranges * classes + 1, 0);
+            bucket_left[l].assign((size_t)nranges * classes, 0);
+            for (size_t b = 0; b < tmp.size(); ++b) {
+                bucket_first[l][b + 1] = bucket_first[l][b] + (uint32_t)tmp[b].size();
+                bucket_left[l][b] = (uint32_t)tmp[b].size();
+                by[l].insert(by[l].end(), tmp[b].begin(), tmp[b].end());
+            }
+            for (uint32_t i = 0; i < cls[l].size(); ++i) ++left_in[l][range_of[l][i]];
+            total_left[l] = (int)cls[l].size();
+        }
+        std::vector<uint32_t> after(nranges);  // steps between the end of this stage and the end of stage r
+        std::vector<std::vector<uint32_t>> picked(lanes), picked_cls(lanes), order;
+        uint64_t cost = 0;
+        uint32_t at = 0;
+        for (int s = 0; s < stages; at += len[s], ++s) {
+            const int T = (int)len[s];
+            if (!T) continue;
+            {
+                uint32_t u = 0;
+                for (int r = s; r < nranges; ++r) {
+                    if (r > s) u += len[r];
+                    after[r] = u;
+                }
+            }
+            const int last_readable = std::min(nranges - 1, s + look);
+            std::fill(cap.begin(), cap.end(), T);
+            // what every lane has to visit now to keep its deadlines: with unvisited(r) samples of
+            // ranges <= r and after[r] steps left for them later, the earliest
+            // max_r (unvisited(r) - after[r]) samples (earliest range first)
+            for (int l = 0; l < lanes; ++l) {
+                picked[l].clear();
+                picked_cls[l].clear();
+                int unvisited = 0, due = 0;
+                for (int r = s; r < nranges && unvisited < total_left[l]; ++r) {
+                    unvisited += left_in[l][r];
+                    due = std::max(due, unvisited - (int)after[r]);
+                }
+                for (int r = s; r <= last_readable && due > 0; ++r) {
+                    while (due > 0 && left_in[l][r] > 0) {
+                        // of a range that is only partly due, the classes with the most capacity left
+                        int best = -1;
+                        for (int c = 0; c < classes; ++c)
+                            if (bucket_left[l][(size_t)r * classes + c] && (best < 0 || cap[c] > cap[best])) best = c;
+                        picked[l].push_back(take(l, best, r, r));
+                        picked_cls[l].push_back((uint32_t)best);
+                        --cap[best];
+                        --due;
+                    }
+                }
+                room[l] = T - (int)picked[l].size();
+            }
+            // optional samples: as many as fit without pushing a class beyond T, the ranges that
+            // are due soonest offered first (what is visited now will not crowd their own stage)
+            for (int l = 0; l < lanes; ++l) {
+                std::fill(flow[l].begin(), flow[l].end(), 0);
+                std::fill(avail[l].begin(), avail[l].end(), 0);
+            }
+            for (int c = 0; c < classes; ++c) cap[c] = std::max(cap[c], 0);
+            class_order.resize(classes);
+            for (int r = s; r <= last_readable; ++r) {
+                want.assign(classes, 0);
+                for (int l = 0; l < lanes; ++l) {
+                    if (!left_in[l][r]) continue;
+                    for (int c = 0; c < classes; ++c) {
+                        avail[l][c] += (int)bucket_left[l][(size_t)r * classes + c];
+                        want[c] += (int)bucket_left[l][(size_t)r * classes + c];
+                    }
+                }
+                std::iota(class_order.begin(), class_order.end(), 0);
+                std::stable_sort(class_order.begin(), class_order.end(), [&](int a, int b) { return want[a] > want[b]; });
+                for (bool more = true; more;) {  // one unit per lane and round, so that the lanes share the capacity evenly
+                    more = false;
+                    for (int l = 0; l < lanes; ++l) {
+                        int taken = 0;
+                        for (int c = 0; c < classes; ++c) taken += flow[l][c];
+                        if (taken < room[l] && augment(l)) more = true;
+                    }
+                }
+            }
+            for (int l = 0; l < lanes; ++l)
+                for (int c = 0; c < classes; ++c)
+                    for (int f = 0; f < flow[l][c]; ++f) {
+                        picked[l].push_back(take(l, c, s, last_readable));
+                        picked_cls[l].push_back((uint32_t)c);
+                    }
+            // the order inside the stage
+            cost += inner.run(picked_cls, classes, T, order);
+            for (int l = 0; l < lanes; ++l)
+                for (int st = 0; st < T; ++st) {
+                    const uint32_t v = order[l][st];
+                    out[l][at + st] = (v & kPadSample) ? v : picked[l][v];
+                }
+        }
+        return cost;
+    }
+};
+
 // lanes of a wave in pass order: `group` consecutive entries are served together
 void pass_order_of(uint32_t group, uint32_t (&order)[64]) {
     for (uint32_t l = 0; l < 64; ++l) order[l] = l;
@@ -232,55 +509,116 @@ uint64_t schedule_samples(const std::vector<uint32_t> &idx, uint32_t k, uint32_t
     return cost;
 }
 
-// Chunked schedule: coordinates are cut into nchunks ranges of `chunk` coordinates; the
-// samples of a function are bucketed by range, and for every wave (64 consecutive functions)
-// and range the 64 buckets are padded to a common length (a multiple of `step_quantum`) and
-// scheduled per pass group.  steps_out[wave * nchunks + q] = that length; order_out holds, wave
-// after wave and range after range, steps x 64 entries (step-major, lane-minor), each a
-// position in the function's canonical list or kPadSample | class.
-uint64_t schedule_chunked(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t chunk,
-                          uint32_t nchunks, uint32_t step_quantum, uint32_t group, uint32_t classes,
-                          std::vector<uint32_t> &steps_out, std::vector<uint32_t> &order_out) {
-    const uint32_t nwaves = (k + 63) / 64;
-    steps_out.assign((size_t)nwaves * nchunks, 0);
+// Windowed schedule for large n.  Coordinates are cut into `nchunks` ranges of `chunk`
+// coordinates that pass through a ring of LDS slots: at stage s of a tile (stage s < nchunks
+// brings in range s, later stages nothing) the ranges s .. s + look are readable.  All lanes
+// of a workgroup (sets_per_workgroup sets of 64 consecutive functions) walk every stage in
+// lockstep, so a stage has one length for all of them; but a sample of range r may be visited
+// in any of the stages r - look .. r, which lets a lane whose ranges are unevenly filled work
+// ahead instead of waiting: since every function has the same m samples, the lists then
+// need hardly any padding (with one fixed stage per range the 64 lists of a wave had to be
+// padded to the longest of them, range by range: 1.6 entries per sample at m = 64, n = 4096).
+//
+// Stage lengths: stage after stage, the shortest length (a multiple of step_quantum) in which
+// every lane can still visit all samples whose last stage this is, given that each lane has
+// visited, earliest range first, as many readable samples as the stages so far had room for.
+// Earliest-deadline-first is optimal for unit tasks whose windows are ordered like their
+// deadlines, so these are the pointwise smallest cumulative lengths of any valid schedule.
+// Given the stage lengths, each pass group is scheduled step by step like a flat list, except
+// that a lane's choice at a step is limited to what keeps its own deadlines: with slack(r) =
+// steps left until the end of stage r minus the lane's unvisited samples of ranges <= r, it
+// may take a sample of range q (readable: q <= stage + look) only if slack(r) >= 1 for all
+// r < q, and a padding entry only if slack(r) >= 1 for all r.  Inside these limits the step
+// is a maximum matching of lanes to bank classes as above.
+//
+// steps_out[workgroup * stages + s] = entries per function in stage s; order_out holds,
+// workgroup after workgroup, set after set and stage after stage, steps x 64 entries
+// (step-major, lane-minor), each a position in the function's canonical list or
+// kPadSample | class.
+uint64_t schedule_windowed(const std::vector<uint32_t> &idx, uint32_t k, uint32_t m, uint32_t chunk,
+                           uint32_t nchunks, uint32_t stages, uint32_t look, uint32_t sets_per_workgroup,
+                           uint32_t step_quantum, uint32_t min_steps, uint32_t group, uint32_t classes,
+                           std::vector<uint32_t> &steps_out, std::vector<uint32_t> &order_out) {
+    const uint32_t nsets = (k + 63) / 64;
+    const uint32_t nwg = (nsets + sets_per_workgroup - 1) / sets_per_workgroup;
+    steps_out.assign((size_t)nwg * stages, 0);
     order_out.clear();
     uint32_t pass_order[64];
     pass_order_of(group, pass_order);
     uint64_t cost = 0;
-    GroupScheduler g;
-    std::vector<std::vector<std::vector<uint32_t>>> bucket(64);  // [lane][range] -> canonical positions
-    std::vector<std::vector<uint32_t>> cls, out;
-    std::vector<uint32_t> lanes_of_group;
-    for (uint32_t w = 0; w < nwaves; ++w) {
-        for (uint32_t l = 0; l < 64; ++l) {
-            bucket[l].assign(nchunks, {});
-            const uint32_t j = w * 64 + l;
-            if (j >= k) continue;
-            for (uint32_t i = 0; i < m; ++i) bucket[l][idx[(size_t)j * m + i] / chunk].push_back(i);
+    WindowScheduler ws;
+    std::vector<std::vector<uint32_t>> cls, rng, out;
+    std::vector<uint32_t> sorted, first_of_range, done;
+    for (uint32_t y = 0; y < nwg; ++y) {
+        const uint32_t set0 = y * sets_per_workgroup, set1 = std::min(nsets, set0 + sets_per_workgroup);
+        const uint32_t lanes = (set1 - set0) * 64;
+        // every lane's canonical positions sorted by range (stable), and where each range starts
+        sorted.assign((size_t)lanes * m, 0);
+        first_of_range.assign((size_t)lanes * (nchunks + 1), 0);
+        for (uint32_t t = 0; t < lanes; ++t) {
+            const uint32_t j = set0 * 64 + t;
+            uint32_t *first = &first_of_range[(size_t)t * (nchunks + 1)];
+            if (j >= k) continue;  // no samples: all zeros
+            for (uint32_t i = 0; i < m; ++i) ++first[idx[(size_t)j * m + i] / chunk + 1];
+            for (uint32_t q = 0; q < nchunks; ++q) first[q + 1] += first[q];
+            std::vector<uint32_t> at(first, first + nchunks);
+            for (uint32_t i = 0; i < m; ++i) sorted[(size_t)t * m + at[idx[(size_t)j * m + i] / chunk]++] = i;
         }
-        for (uint32_t q = 0; q < nchunks; ++q) {
-            uint32_t longest = 0;
-            for (uint32_t l = 0; l < 64; ++l)
-                longest = std::max<uint32_t>(longest, (uint32_t)bucket[l][q].size());
-            const uint32_t steps = (longest + step_quantum - 1) / step_quantum * step_quantum;
-            steps_out[(size_t)w * nchunks + q] = steps;
+        // stage lengths (done[t] = samples lane t has visited when it takes the earliest range first)
+        done.assign(lanes, 0);
+        uint32_t *len = &steps_out[(size_t)y * stages];
+        for (uint32_t s = 0; s < stages && s < nchunks; ++s) {
+            uint32_t must = 0;
+            for (uint32_t t = 0; t < lanes; ++t) {
+                const uint32_t due = first_of_range[(size_t)t * (nchunks + 1) + s + 1];
+                if (due > done[t]) must = std::max(must, due - done[t]);
+            }
+            len[s] = (must + step_quantum - 1) / step_quantum * step_quantum;
+            const uint32_t last = std::min(nchunks - 1, s + look);
+            for (uint32_t t = 0; t < lanes; ++t) {
+                const uint32_t readable = first_of_range[(size_t)t * (nchunks + 1) + last + 1] - done[t];
+                done[t] += std::min(len[s], readable);
+            }
+        }
+        // Spare steps.  Without padding the busiest bank class of a pass group is wanted more
+        // often than there are steps, and every such sample costs an extra pass of the LDS
+        // read; a padding entry costs one pass, too, but it is a wildcard that lets the
+        // matching shift the load.  Lengthen the stages in proportion until a tile has
+        // min_steps steps.
+        size_t wg_steps = 0;
+        for (uint32_t s = 0; s < stages; ++s) wg_steps += len[s];
+        if (wg_steps && wg_steps < min_steps) {
+            const uint64_t extra = min_steps - wg_steps;
+            uint64_t before = 0, given = 0;
+            for (uint32_t s = 0; s < stages; ++s) {
+                before += len[s];
+                const uint64_t upto = extra * before / wg_steps / step_quantum * step_quantum;
+                len[s] += (uint32_t)(upto - given);
+                given = upto;
+            }
+            wg_steps += given;
+        }
+        for (uint32_t set = set0; set < set1; ++set) {
             const size_t base = order_out.size();
-            order_out.resize(base + (size_t)steps * 64, kPadSample);
-            for (uint32_t g0 = 0; g0 < 64 && steps; g0 += group) {
-                lanes_of_group.clear();
-                for (uint32_t e = 0; e < group; ++e) lanes_of_group.push_back(pass_order[g0 + e]);
-                cls.assign(lanes_of_group.size(), {});
-                for (size_t t = 0; t < lanes_of_group.size(); ++t) {
-                    const uint32_t l = lanes_of_group[t];
-                    const uint32_t j = w * 64 + l;
-                    for (uint32_t pos : bucket[l][q]) cls[t].push_back(idx[(size_t)j * m + pos] % classes);
+            order_out.resize(base + wg_steps * 64, kPadSample);
+            for (uint32_t g0 = 0; g0 < 64; g0 += group) {
+                cls.assign(group, {});
+                rng.assign(group, {});
+                for (uint32_t e = 0; e < group; ++e) {
+                    const uint32_t l = pass_order[g0 + e], t = (set - set0) * 64 + l, j = set * 64 + l;
+                    if (j >= k) continue;
+                    for (uint32_t i = 0; i < m; ++i) {
+                        const uint32_t c = idx[(size_t)j * m + sorted[(size_t)t * m + i]];
+                        cls[e].push_back(c % classes);
+                        rng[e].push_back(c / chunk);
+                    }
                 }
-                cost += g.run(cls, (int)classes, (int)steps, out);
-                for (size_t t = 0; t < lanes_of_group.size(); ++t) {
-                    const uint32_t l = lanes_of_group[t];
-                    for (uint32_t s = 0; s < steps; ++s) {
-                        const uint32_t e = out[t][s];
-                        order_out[base + (size_t)s * 64 + l] = (e & kPadSample) ? e : bucket[l][q][e];
+                cost += ws.run(rng, cls, (int)classes, (int)nchunks, (int)look, len, (int)stages, out);
+                for (uint32_t e = 0; e < group; ++e) {
+                    const uint32_t l = pass_order[g0 + e], t = (set - set0) * 64 + l;
+                    for (size_t st = 0; st < wg_steps; ++st) {
+                        const uint32_t v = out[e][st];
+                        order_out[base + st * 64 + l] = (v & kPadSample) ? v : sorted[(size_t)t * m + v];
                     }
                 }
             }

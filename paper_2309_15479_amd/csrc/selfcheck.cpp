@@ -46,36 +46,45 @@ double compare(const lsh_params *p, const std::vector<double> &v, const std::vec
 }
 
 double walk_ranged(const lsh_params *p, const std::vector<double> &v) {
+    // Follows every gathering wave through one tile as the kernel does: block after block, the
+    // stage advancing by the barrier counts, every entry's slot number resolved against what
+    // the ring holds at that stage (slot x holds the range r in stage .. stage + 6 with
+    // r % 8 == x; the eighth slot is being refilled and must not be read).
     const SampledPlan &pl = p->plan;
-    std::vector<uint32_t> words, list_len, info;
-    build_ranged_tables(p, words, list_len, info);
-    const uint32_t R = pl.nchunks, CW = kRangeComputeWaves, U = kRangeBlockQuads, fpt = pl.fpt;
+    std::vector<uint32_t> words, barriers, info;
+    build_ranged_tables(p, words, barriers, info);
+    const uint32_t CW = kRangeComputeWaves, fpt = pl.fpt, qpf = pl.qpf, U = fpt * qpf;
+    const uint32_t bar_stride = (uint32_t)(barriers.size() / pl.kblocks);
     const size_t block_words = (size_t)U * 64 * 6, off_base = (size_t)U * 64 * 4;
     std::vector<double> walked(p->k, 0.0);
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
             const uint32_t stream = y * CW + cw, first = info[(size_t)stream * 2], blocks = info[(size_t)stream * 2 + 1];
-            uint32_t next = 0;
-            for (uint32_t r = 0; r < R; ++r)
-                for (uint32_t f = 0; f < fpt; ++f) {
-                    const uint32_t T = list_len[((size_t)stream * R + r) * fpt + f];
-                    for (uint32_t e = 0; e < T; ++e) {
-                        const uint32_t *blk = &words[(size_t)(first + next + e / (4 * U)) * block_words];
-                        const uint32_t quad = e / 4 % U, pos = e % 4;
+            if (blocks + 1 > bar_stride) return INFINITY;
+            const uint32_t *bar = &barriers[(size_t)y * bar_stride];
+            uint32_t stage = bar[0];
+            for (uint32_t b = 0; b < blocks; ++b) {
+                if (stage >= pl.stages) return INFINITY;  // entries after the tile's last barrier
+                const uint32_t *blk = &words[(size_t)(first + b) * block_words];
+                for (uint32_t u = 0; u < U; ++u)
+                    for (uint32_t pos = 0; pos < 4; ++pos)
                         for (uint32_t l = 0; l < 64; ++l) {
                             float c;
-                            std::memcpy(&c, &blk[((size_t)quad * 64 + l) * 4 + pos], 4);
-                            const uint32_t pair = blk[off_base + ((size_t)quad * 64 + l) * 2 + pos / 2];
-                            const uint32_t slot = ((pair >> (16 * (pos % 2))) & 0xFFFFu) / 16;
-                            const uint32_t coord = r * pl.chunk + slot;
-                            const uint32_t j = ((y * fpt + f) * CW + cw) * 64 + l;
+                            std::memcpy(&c, &blk[((size_t)u * 64 + l) * 4 + pos], 4);
+                            const uint32_t pair = blk[off_base + ((size_t)u * 64 + l) * 2 + pos / 2];
+                            const uint32_t slot = (pair >> (16 * (pos % 2))) & 0xFFFFu;
+                            const uint32_t ring = slot / (4 * kWindowCoords), in_range = slot % (4 * kWindowCoords);
+                            if (ring >= kWindowSlots || in_range >= kWindowCoords) return INFINITY;
+                            const uint32_t r = stage + (ring + kWindowSlots - stage % kWindowSlots) % kWindowSlots;
+                            if (r > stage + kWindowLook || r >= pl.nchunks) return INFINITY;  // not (yet) in the ring
+                            const uint32_t coord = r * kWindowCoords + in_range;
+                            const uint32_t j = ((y * fpt + u / qpf) * CW + cw) * 64 + l;
                             if (j < p->k) walked[j] += (double)c * (coord < p->n ? v[coord] : 0.0);
                             else if (c != 0.f) return INFINITY;  // a lane beyond k must not contribute
                         }
-                    }
-                    next += (T / 4 + U - 1) / U;
-                }
-            if (next != blocks) return INFINITY;  // the stream must end where the next tile's begins
+                stage += bar[b + 1];
+            }
+            if (stage != pl.stages) return INFINITY;  // one barrier per stage of the tile
         }
     return compare(p, v, walked);
 }
