@@ -6,6 +6,16 @@
 
 namespace lsh {
 
+// Workgroup barrier that orders LDS traffic only, for kernels that hand tiles from wave to wave
+// through LDS and never through global memory: a wave's global loads (tiles for stages to come,
+// the next list block) and its stores stay in flight across the barrier, where __syncthreads()
+// would wait for all of them.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // 4 x 4 transpose across the four lanes of a quad: on entry lane u holds x[t] = value of
 // (function u of the quad, vector t); on exit x[t] = value of (function t, vector u).
 // Two butterfly stages of quad-permute DPP moves (no LDS traffic).

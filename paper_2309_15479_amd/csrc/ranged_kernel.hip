@@ -27,7 +27,8 @@
 //    barrier per stage.  A loading wave keeps the loads of three stages in flight (the stages
 //    are short: 2 us at m = 64) and writes each, transposed, into its slot one barrier before
 //    the first list may read it.  The two kinds of wave have their own counters of outstanding
-//    memory operations, so a gatherer's wait for list entries never waits for tile data.
+//    memory operations, so a gatherer's wait for list entries never waits for tile data; the
+//    barrier orders LDS traffic only, so neither waits there for what it has in flight.
 //
 //  * Packed lists.  The kernel is bound by vector-ALU issue (sixteen multiply-adds per list
 //    entry), so everything else an entry costs is kept small: a lane's list is stored in quads
@@ -70,6 +71,7 @@ constexpr int kSlotBytes = 4 * kSubBytes;      // one ring slot: 16 KB
 constexpr int kLdsBytes = kSlots * kSlotBytes; // 128 KB
 constexpr int kPieces = kC / 64;               // 64-coordinate pieces of a slot
 constexpr int kDepth = 4;                      // register sets of a loading wave: loads of kDepth - 1 stages in flight
+static_assert(kWindowSlots % kDepth == 0, "the stages of a workgroup are a multiple of the loaders' register sets");
 static_assert(kWindowLook + 2 == kWindowSlots, "one slot is being filled, the others are readable");
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -136,16 +138,6 @@ __device__ __forceinline__ void gather_quad(const uint4 c, const uint2 o, float 
     __builtin_amdgcn_sched_barrier(0);
     fma_entry(__uint_as_float(c.w), x[1], acc);
     __builtin_amdgcn_sched_barrier(0);
-}
-
-// The barrier between stages orders LDS traffic only: a wave's loads from global memory (the
-// next list block of a gatherer, the tiles a loader has in flight for the stages to come) stay
-// in flight across it.  (__syncthreads() would wait for them, too, and so expose the latency of
-// HBM once per stage.)
-__device__ __forceinline__ void stage_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // FPT functions per lane, QPF quads of each per list block
@@ -215,14 +207,14 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
             // barrier x - 6.
 #pragma unroll
             for (int d = 0; d + 1 < kDepth; ++d) fetch(pre[d]);
+            // (a tile has a multiple of eight stages, so `total` is a multiple of kDepth: no
+            // test inside the unrolled body, which keeps the count of loads in flight exact)
             for (uint64_t x = 0; x < total; x += kDepth) {
 #pragma unroll
                 for (int d = 0; d < kDepth; ++d) {
-                    if (x + d < total) {
-                        if (x + d > (uint64_t)kWindowLook) stage_barrier();
-                        fetch(pre[(d + kDepth - 1) % kDepth]);
-                        stash(pre[d]);
-                    }
+                    if (x + d > (uint64_t)kWindowLook) lds_barrier();
+                    fetch(pre[(d + kDepth - 1) % kDepth]);
+                    stash(pre[d]);
                 }
             }
         };
@@ -230,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
         else loader(std::false_type{});
         // the barriers the gatherers still pass: total + 1 in all
         const uint64_t passed = total > (uint64_t)kWindowLook + 1 ? total - (kWindowLook + 1) : 0;
-        for (uint64_t b = passed; b < total + 1; ++b) stage_barrier();
+        for (uint64_t b = passed; b < total + 1; ++b) lds_barrier();
         return;
     }
 
@@ -280,10 +272,10 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
             for (int q = 0; q < QPF; ++q) gather_quad(blk.coef[f * QPF + q], blk.off[f * QPF + q], acc[f]);
     };
     auto pass = [&](uint32_t count) __attribute__((always_inline)) {
-        for (uint32_t i = 0; i < count; ++i) stage_barrier();
+        for (uint32_t i = 0; i < count; ++i) lds_barrier();
     };
 
-    stage_barrier();  // the first seven stages are in the ring
+    lds_barrier();  // the first seven stages are in the ring
     for (uint64_t t = first_tile; t < ntiles; t += gridDim.x) {
         float acc[FPT][4][4];
 #pragma unroll
