@@ -125,9 +125,11 @@ int lsh_params_get_mips_coeffs(const lsh_params_t *params, float *out);
  *                    coordinate c in class (c + c / classes) % classes, and every sample is
  *                    read from the copy that evens out the classes' loads), or
  *                    0x80000000 | class for a padding sample (coefficient 0), or 0xFFFFFFFF
- *                    (unused tail: for large n the lists are cut by coordinate range and
- *                    padded per range and per 64 functions, so rows differ in length; steps
- *                    is then the longest row)
+ *                    (unused tail: for large n the samples are visited range by range, a
+ *                    sample of the r-th range of 256 coordinates in one of the stages
+ *                    r - 6 .. r of a tile, with all functions of a workgroup of up to 2048
+ *                    in lockstep; rows of different workgroups may differ in length and
+ *                    steps is then the longest row)
  *   modelled_passes  sum over lane groups and steps of the largest number of lanes sharing a
  *                    class (k/group * steps when the schedule is conflict-free)
  * Any out pointer may be NULL.  Errors: INVALID_ARG, UNSUPPORTED (n too large for the kernel).

@@ -237,7 +237,7 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
                 p->schedule_cost =
                     pl.ranged ? schedule_windowed(p->idx, k, m, pl.chunk, pl.nchunks, pl.stages, kWindowLook,
                                                   pl.fpt * kRangeComputeWaves, 4 * pl.qpf,
-                                                  m + (uint32_t)std::sqrt((double)m),  // spare steps: see schedule_windowed
+                                                  m + (uint32_t)(0.5 * std::sqrt((double)m)),  // spare steps: see schedule_windowed
                                                   pl.group, pl.classes,
                                                   p->chunk_steps, p->order)
                               : schedule_samples(p->idx, k, m, pl.m_pad, pl.group, pl.classes, pl.copies,
