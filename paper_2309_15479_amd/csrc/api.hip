@@ -85,6 +85,8 @@ int upload_tables(lsh_params *p) {
             std::vector<uint32_t> words, list_len, stream_info;
             build_ranged_tables(p, words, list_len, stream_info);
             p->ranged_bar_stride = (uint32_t)(list_len.size() / p->plan.kblocks);
+            for (size_t i = 1; i < stream_info.size(); i += 2)
+                if (stream_info[i] % 2) rc = LSH_ERR_UNSUPPORTED;  // the kernel takes a tile's blocks two at a time
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;

@@ -285,18 +285,15 @@ __global__ __launch_bounds__(kThreads) void sampled_ranged_kernel(const SampledA
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[f][st][r] = 0.f;
         pass(bar[0]);
-        // blocks two at a time, the registers of one being refilled while the other is used
+        // blocks two at a time (the host makes their number even), the registers of one being
+        // refilled while the other is used: no block is ever copied from register to register
         for (uint32_t q = 0; q < sblocks; q += 2) {
             load_block(Q);
             gather_block(P, acc);
-            if (q + 1 < sblocks) {
-                pass(bar[q + 1]);
-                load_block(P);
-                gather_block(Q, acc);
-                if (q + 2 < sblocks) pass(bar[q + 2]);
-            } else {
-                P = Q;
-            }
+            pass(bar[q + 1]);
+            load_block(P);
+            gather_block(Q, acc);
+            if (q + 2 < sblocks) pass(bar[q + 2]);
         }
 #pragma unroll
         for (int f = 0; f < FPT; ++f)

@@ -598,6 +598,15 @@ uint64_t schedule_windowed(const std::vector<uint32_t> &idx, uint32_t k, uint32_
             }
             wg_steps += given;
         }
+        // an even number of list blocks (of step_quantum steps) per tile: the kernel keeps two
+        // blocks in registers and alternates between them without ever copying one
+        if (wg_steps / step_quantum % 2) {
+            uint32_t last = 0;
+            for (uint32_t s = 0; s < stages; ++s)
+                if (len[s]) last = s;
+            len[last] += step_quantum;
+            wg_steps += step_quantum;
+        }
         for (uint32_t set = set0; set < set1; ++set) {
             const size_t base = order_out.size();
             order_out.resize(base + wg_steps * 64, kPadSample);

@@ -60,7 +60,7 @@ double walk_ranged(const lsh_params *p, const std::vector<double> &v) {
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
             const uint32_t stream = y * CW + cw, first = info[(size_t)stream * 2], blocks = info[(size_t)stream * 2 + 1];
-            if (blocks + 1 > bar_stride) return INFINITY;
+            if (blocks + 1 > bar_stride || blocks % 2) return INFINITY;  // the kernel takes the blocks two at a time
             const uint32_t *bar = &barriers[(size_t)y * bar_stride];
             uint32_t stage = bar[0];
             for (uint32_t b = 0; b < blocks; ++b) {
