@@ -207,8 +207,13 @@ def test_windowed_gather_schedule_needs_little_padding(n, k, m, entries, lds):
 @pytest.mark.parametrize("n,k,m,w,seed,repl,L", [
     (4096, 2048, 64, 8.0, 4, False, 0),      # ranged gather kernel, four functions per lane
     (4096, 520, 256, 8.0, 5, True, 0),       # k not a multiple of 64, duplicates in S
-    (4100, 512, 40, 2.0, 6, False, 0),       # a fifth range of four coordinates
-    (16384, 1024, 96, 1.0, 7, False, 0),     # sixteen ranges
+    (4100, 512, 40, 2.0, 6, False, 0),       # seventeen ranges in 24 stages, the last of four coordinates
+    (16384, 1024, 96, 1.0, 7, False, 0),     # 64 ranges
+    (2049, 512, 7, 2.0, 38, False, 0),       # one function per lane, one-quad blocks, odd n
+    (2304, 1536, 100, 1.0, 39, True, 0),     # three functions per lane
+    (9004, 2048, 700, 4.0, 40, False, 0),    # 36 ranges in 40 stages
+    (3000, 1000, 33, 1.0, 41, True, 0),      # two functions per lane, k not a multiple of 64
+    (16384, 4096, 512, 1.0, 5, False, 0),    # two workgroups along the functions
     (4096, 2048, 64, 8.0, 4, False, 128),    # one sample per table: short lists, blocks of eight steps
     (4096, 2048, 256, 8.0, 4, False, 128),   # long lists, blocks of six steps
     (4096, 1024, 1024, 8.0, 4, False, 32),   # tables of 32 functions (two blocks), blocks of four steps

@@ -135,6 +135,10 @@ RAGGED = [
     (9, 16384, 128, 512, 1.0, 29, False, 0),     # 2-vector tiles
     (40, 16384, 640, 96, 1.0, 33, False, 0),     # coordinate-range chunks, ragged functions
     (21, 5000, 1100, 40, 2.0, 34, True, 0),      # chunks, two workgroups along the functions
+    (70, 2049, 512, 7, 2.0, 38, False, 0),       # nine ranges in sixteen stages, one function per lane, one-quad blocks, odd n
+    (45, 2304, 1536, 100, 1.0, 39, True, 0),     # three functions per lane, nine ranges
+    (33, 9004, 2048, 700, 4.0, 40, False, 64),   # 36 ranges in 40 stages, four functions per lane, keys
+    (19, 3000, 1000, 33, 1.0, 41, True, 0),      # two functions per lane, one-quad blocks, k not a multiple of 64
     (5, 30000, 64, 40, 1.0, 30, False, 0),       # 1-vector tiles
     (3, 40384, 64, 33, 1.0, 32, True, 0),        # the largest dimension one LDS tile holds
     (300, 64, 2100, 16, 2.0, 31, False, 0),      # more functions than one workgroup holds
