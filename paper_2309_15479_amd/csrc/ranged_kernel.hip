@@ -20,8 +20,8 @@
 //    gathering waves of a workgroup run the same number of entries per stage, but a lane may
 //    spend a stage's entries on any readable range, so a function with few samples in the
 //    current range works ahead on the next six: since all functions have m samples, almost no
-//    entry is padding (schedule.cpp; with one fixed stage per range, 1.6 entries per sample
-//    were visited at m = 64, n = 4096, now 1.06).
+//    entry is padding (schedule.cpp; with one fixed stage per range, 1.63 / 1.28 entries per
+//    sample were visited at m = 64 / 256, n = 4096, now 1.13 / 1.03).
 //
 //  * Loader waves.  A workgroup is 8 gathering waves plus 4 loading waves, which meet at one
 //    barrier per stage.  A loading wave keeps the loads of three stages in flight (the stages
@@ -36,14 +36,15 @@
 //    one shift with a sub-word operand turns into the entry's address (one instruction per entry;
 //    a vector memory instruction per two entries).  A lane owns up to four functions (sets of 64
 //    functions, 8 sets apart, so that a workgroup covers up to 2048 functions per tile load)
-//    and a list block holds the next quad (or two, or four: always three or four quads) of
-//    each of them.  The blocks of one gathering wave form one contiguous stream that wraps
+//    and a list block holds the next quad of each of them (two or four quads with two or one
+//    functions per lane, unless a range holds fewer samples than that), an even number of
+//    blocks per tile.  The blocks of one gathering wave form one contiguous stream that wraps
 //    around at the end of a tile; the block after the one in use is always on its way, across
 //    stages and tiles.  Where the stages end is a table of barrier counts per block, read with
 //    scalar loads.
 //
-// Padding entries (where a lane has nothing readable left, and to fill a stage up to a whole
-// block) carry coefficient 0 and read one of the first 16 slots of the stage's own range,
+// Padding entries (where a lane has nothing readable left, to fill a stage up to a whole
+// block, and the spare steps that let the bank schedule move samples) carry coefficient 0 and read one of the first 16 slots of the stage's own range,
 // whichever bank class the schedule wants; the loaders write zeros to the slots beyond the
 // last coordinate, so such an entry always multiplies a finite value of the same vector by
 // zero.
@@ -121,7 +122,7 @@ __device__ __forceinline__ uint32_t slot_address(uint32_t pair) {
 // Four entries of a lane's list against the 16 vectors of the tile; the LDS reads of an entry go
 // out before the multiply-adds of the entry before it.  (Deeper read-ahead, tried with a ring of
 // three register sets and with all reads of a group up front, changes nothing but the register
-// count: the vector ALU is busy in 96 % of the cycles.)
+// count: the vector ALU is the busy unit either way.)
 __device__ __forceinline__ void gather_quad(const uint4 c, const uint2 o, float (&acc)[4][4]) {
     floatx4 x[2][4];
     __builtin_amdgcn_sched_barrier(0);
