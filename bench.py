@@ -45,7 +45,7 @@ CSRC = os.path.join(ROOT, "paper_2309_15479_amd", "csrc")
 # source files still hash to the recorded values; otherwise `traffic` is null.  (FETCH_SIZE counts
 # 64 bytes per read request and these kernels fetch 128-byte lines: a lower bound, see the summary.)
 _KIB = 1024
-_RANGED = {"ranged_kernel.hip": "58d21b68da5b2294", "sampled_common.h": "9d6a9ea08ffad892", "schedule.cpp": "e034f03d037e1a15"}
+_RANGED = {"ranged_kernel.hip": "27e4edf7a84e975a", "sampled_common.h": "9d6a9ea08ffad892", "schedule.cpp": "e034f03d037e1a15"}
 _STREAMED = {"sampled_kernel.hip": "bea9b29ed7d9a478", "sampled_common.h": "9d6a9ea08ffad892"}
 _SUMMARY = "profiles/hbm_traffic_all_workloads.md"
 MEASURED_TRAFFIC = {
