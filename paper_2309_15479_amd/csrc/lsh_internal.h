@@ -155,6 +155,7 @@ constexpr uint32_t kWindowSlots = 8;         // ring slots in LDS
 constexpr uint32_t kWindowLook = 6;          // a stage may read its own range and this many after it (the last slot is being filled)
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
                   uint32_t L, void *stream, void *d_out2 = nullptr);
+bool ranged_schedule_valid(const lsh_params *p);  // selfcheck.cpp: run at create time
 void build_ranged_tables(const lsh_params *p, std::vector<uint32_t> &words, std::vector<uint32_t> &list_len,
                          std::vector<uint32_t> &stream_info);
 constexpr uint32_t kSharedRangeBlocksPerWave = 16;  // blocks of 16 functions a contracting wave owns at most

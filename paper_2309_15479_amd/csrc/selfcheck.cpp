@@ -4,7 +4,9 @@
 // index arithmetic) on a pseudo-random vector, in double precision; the result must be the
 // projection of Eq. 5, p_j = sum_i a~_j[i] v[S_j[i]], computed straight from the canonical
 // tables.  Needs no GPU: the most intricate host code of the library is testable where it is
-// written.
+// written.  ranged_schedule_valid() is the part of it that runs whenever an object for the gather
+// kernel by coordinate ranges is created: a schedule the kernel could not follow is refused there.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -44,6 +46,46 @@ double compare(const lsh_params *p, const std::vector<double> &v, const std::vec
     }
     return worst;
 }
+
+}  // namespace
+
+// Cheap check of the ranged kernel's schedule, run whenever such an object is created: every
+// function's samples appear exactly once, each in a stage whose ring holds its range (stage <=
+// range <= stage + look), and a tile is an even number of list blocks.
+bool ranged_schedule_valid(const lsh_params *p) {
+    const SampledPlan &pl = p->plan;
+    const uint32_t sets_per_wg = pl.fpt * kRangeComputeWaves, nsets = (p->k + 63) / 64, S = pl.stages;
+    if (p->chunk_steps.size() != (size_t)pl.kblocks * S) return false;
+    std::vector<uint8_t> seen(p->m);
+    size_t base = 0;
+    for (uint32_t set = 0; set < nsets; ++set) {
+        const uint32_t *len = &p->chunk_steps[(size_t)(set / sets_per_wg) * S];
+        uint32_t steps = 0;
+        for (uint32_t s = 0; s < S; ++s) steps += len[s];
+        if (steps % (4 * pl.qpf) || steps / (4 * pl.qpf) % 2) return false;
+        if (base + (size_t)steps * 64 > p->order.size()) return false;
+        for (uint32_t l = 0; l < 64; ++l) {
+            const uint32_t j = set * 64 + l;
+            std::fill(seen.begin(), seen.end(), 0);
+            uint32_t found = 0, at = 0;
+            for (uint32_t s = 0; s < S; ++s)
+                for (uint32_t e = 0; e < len[s]; ++e, ++at) {
+                    const uint32_t ent = p->order[base + (size_t)at * 64 + l];
+                    if (ent & kPadSample) continue;
+                    if (j >= p->k || ent >= p->m || seen[ent]) return false;
+                    const uint32_t range = p->idx[(size_t)j * p->m + ent] / pl.chunk;
+                    if (range < s || range > s + kWindowLook) return false;
+                    seen[ent] = 1;
+                    ++found;
+                }
+            if (found != (j < p->k ? p->m : 0u)) return false;
+        }
+        base += (size_t)steps * 64;
+    }
+    return base == p->order.size();
+}
+
+namespace {
 
 double walk_ranged(const lsh_params *p, const std::vector<double> &v) {
     // Follows every gathering wave through one tile as the kernel does: block after block, the
