@@ -248,7 +248,11 @@ int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64
                 rc = LSH_ERR_ALLOC;
             }
             // a schedule the kernel could not follow must never reach the device
-            if (rc == LSH_OK && p->plan.ranged && !ranged_schedule_valid(p)) rc = LSH_ERR_UNSUPPORTED;
+            try {
+                if (rc == LSH_OK && p->plan.ranged && !ranged_schedule_valid(p)) rc = LSH_ERR_UNSUPPORTED;
+            } catch (const std::bad_alloc &) {
+                rc = LSH_ERR_ALLOC;
+            }
         }
     }
     if (rc == LSH_OK) rc = upload_tables(p);
