@@ -8,18 +8,23 @@
 //   [3][kpad][npad] (row j = a_j, zero rows up to a multiple of 256, zero columns up to a
 //   multiple of 16).
 //
-// Workgroup = 8 waves, tile = 256 functions x 128 vectors, contraction in stages of 16
-// coordinates.  A wave owns 64 functions x 64 vectors (2 x 2 blocks of
-// v_mfma_f32_32x32x16_bf16; functions are the row operand, so an accumulator lane holds runs of
-// four consecutive functions of one vector).  Per stage every thread brings 16 bytes of the
-// vector tile (4 fp32, split here on their way to LDS) and 16 bytes of each coefficient plane
-// (8 bf16); LDS holds three stages, [plane][row][32 bytes], the two 16-byte halves of a row
-// swapped in rows whose number has bit 3 set, which makes the 16-byte operand reads of 32
-// consecutive rows (and the writes) conflict-free without padding.  While stage s is
-// contracted, the operand registers it has finished with are refilled from stage s + 1,
-// stage s + 2 is written to LDS, and the global loads of stage s + 5 go out (a ring of three
-// register sets: one stage of matrix work per wave is far shorter than a trip to memory).
-// One barrier per stage, placed where the matrix pipe has products queued.
+// Workgroup = 4 waves, one per SIMD; tile = 256 functions x 256 vectors, contraction in stages
+// of 16 coordinates.  A wave owns 128 functions x 128 vectors: 4 x 4 blocks of
+// v_mfma_f32_32x32x16_bf16, 256 accumulator registers (functions are the row operand, so an
+// accumulator lane holds runs of four consecutive functions of one vector).  The large tile is
+// what counts: the time of this kernel follows the instructions that bring operands in (global
+// loads, LDS writes, LDS reads) per multiply-add, and a 128 x 128 wave tile needs half as many
+// as a 64 x 64 one.  Per stage a thread brings 16 bytes of four vector rows (4 fp32 each,
+// split here on their way to LDS) and 16 bytes of each plane of two coefficient rows (8 bf16);
+// LDS holds three stages, [plane][row][32 bytes], the two 16-byte halves of a row swapped in
+// rows whose number has bit 3 set, which makes the 16-byte operand reads of 32 consecutive rows
+// (and the writes) conflict-free without padding.  While stage s is contracted, the operand
+// registers it has finished with are refilled from stage s + 1, stage s + 2 is written to LDS
+// and the loads of stage s + 3 go out into the registers just stored (one set: a stage is 96
+// MFMAs per wave, about 1.8 us).  With one wave per SIMD nothing else hides what a wave
+// issues between two MFMAs, so the stage is written out MFMA by MFMA with at most one memory
+// instruction or the split of one vector element after each (scheduling barriers keep that
+// order); one LDS-only barrier per stage.
 //
 // Placement: workgroup g runs on XCD g % 8.  With at least 8 function tiles XCD x takes the
 // tiles x, x + 8, ..., with fewer the XCDs share them; the CUs of an XCD walk the vector tiles
@@ -30,8 +35,11 @@
 
 #include <cmath>
 #include <cstring>
+#include <type_traits>
+#include <utility>
 #include <vector>
 
+#include "device_utils.h"
 #include "lsh_internal.h"
 
 namespace lsh {
@@ -44,12 +52,13 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int TF = 256;    // functions per tile
-constexpr int TVW = 128;   // vectors per tile
+constexpr int TVW = 256;   // vectors per tile
+constexpr int NB = 4;      // 32 x 32 blocks of a wave along either axis: a wave owns 128 functions x 128 vectors
 constexpr int KB = 16;     // coordinates per stage = one MFMA step
 constexpr int ROWB = 32;   // bytes per row and plane in a stage: two 16-byte halves, swapped in rows with bit 3 set
 constexpr int A_PLANE = TF * ROWB, V_PLANE = TVW * ROWB;
-constexpr int STAGE = 3 * (A_PLANE + V_PLANE);  // 36864 bytes
-constexpr int kThreadsW = 512;
+constexpr int STAGE = 3 * (A_PLANE + V_PLANE);  // 49152 bytes
+constexpr int kThreadsW = 256;
 constexpr int kLdsBytesW = 3 * STAGE;
 
 struct WideArgs {
@@ -74,10 +83,10 @@ __device__ __forceinline__ void split3(float x, __bf16 &x1, __bf16 &x2, __bf16 &
 // then the same float as (p + b) / w).  VEC: k is a multiple of 4 (16-byte stores).
 template <bool PROJ, bool POW2, bool VEC>
 __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideArgs a) {
-    extern __shared__ __align__(16) char lds_w[];  // 3 stages x ([3][256][32] coefficients, [3][128][32] vectors)
+    extern __shared__ __align__(16) char lds_w[];  // 3 stages x ([3][256][32] coefficients, [3][256][32] vectors)
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lr = lane & 31, lh = lane >> 5;
-    const uint32_t fw = wave & 3, vw = wave >> 2;  // the wave's quarter of the functions, half of the vectors
+    const uint32_t fw = wave & 1, vw = wave >> 1;  // the wave's half of the functions, half of the vectors
 
     // which (function tile, vector tile) pairs this workgroup takes
     const uint32_t F = a.kpad / TF;
@@ -93,13 +102,13 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
     }
 
     // loading roles: 16 bytes of the vector tile and of each coefficient plane per stage
-    const uint32_t vr = threadIdx.x >> 2, vq = threadIdx.x & 3;  // vector row, 4-coordinate piece
-    const uint32_t ar = threadIdx.x >> 1, ah = threadIdx.x & 1;  // coefficient row, 8-coordinate half
+    const uint32_t vr = threadIdx.x >> 2, vq = threadIdx.x & 3;  // vector rows vr + 64 h (h < 4), 4-coordinate piece
+    const uint32_t ar = threadIdx.x >> 1, ah = threadIdx.x & 1;  // coefficient rows ar and ar + 128, 8-coordinate half
     const uint32_t stages = a.npad / KB;
 
     // operand read and write offsets inside a stage (half h of row r sits at 16 * (h ^ bit 3 of r))
-    const uint32_t rd_a = (fw * 64 + lr) * ROWB + ((lh ^ ((lr >> 3) & 1)) << 4);                // + rb * 32 rows + plane
-    const uint32_t rd_v = 3 * A_PLANE + (vw * 64 + lr) * ROWB + ((lh ^ ((lr >> 3) & 1)) << 4);  // + cb * 32 rows + plane
+    const uint32_t rd_a = (fw * 32 * NB + lr) * ROWB + ((lh ^ ((lr >> 3) & 1)) << 4);                // + rb * 32 rows + plane
+    const uint32_t rd_v = 3 * A_PLANE + (vw * 32 * NB + lr) * ROWB + ((lh ^ ((lr >> 3) & 1)) << 4);  // + cb * 32 rows + plane
     const uint32_t wr_a = ar * ROWB + ((ah ^ ((ar >> 3) & 1)) << 4);
     const uint32_t wr_v = 3 * A_PLANE + vr * ROWB + (((vq >> 1) ^ ((vr >> 3) & 1)) << 4) + ((vq & 1) << 3);
 
@@ -107,115 +116,173 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
         const uint16_t *arow = a.planes + ((size_t)ft * TF + ar) * a.npad + ah * 8;
         const size_t plane_stride = (size_t)a.kpad * a.npad;
         for (uint64_t vt = (uint64_t)i * reps + rep; vt < Vt; vt += (uint64_t)per_xcd * reps) {
-            uint64_t row = vt * TVW + vr;
-            row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
-            const float *vrow = a.data + row * a.n + vq * 4;
+            const float *vrow[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                uint64_t row = vt * TVW + vr + h * 64;
+                row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
+                vrow[h] = a.data + row * a.n + vq * 4;
+            }
 
-            // ring of three register sets for the global loads: set s % 3 holds stage s
-            floatx4 gv[3];
-            uintx4 ga[3][3];
+            // the registers of the global loads: the stage on its way to LDS
+            floatx4 gv[4];
+            uintx4 ga[2][3];
             // Every load is issued unconditionally (the compiler can then count the loads in flight
-            // exactly and wait for the oldest set only): stages beyond the last read the last
-            // stage's coefficients against zeros.
-            auto gload = [&](uint32_t s, floatx4 &v, uintx4 (&c)[3]) __attribute__((always_inline)) {
+            // exactly and wait for the oldest only): stages beyond the last read the last stage's
+            // coefficients against zeros.
+            auto gload = [&](uint32_t s, floatx4 (&v)[4], uintx4 (&c)[2][3]) __attribute__((always_inline)) {
                 const uint32_t k0 = s * KB;
                 // coordinates beyond n read the row's first ones instead; lstore() replaces them by zeros
-                v = *reinterpret_cast<const floatx4 *>(vrow + (k0 + vq * 4 < a.n ? k0 : 0u));
+#pragma unroll
+                for (int h = 0; h < 4; ++h) v[h] = *reinterpret_cast<const floatx4 *>(vrow[h] + (k0 + vq * 4 < a.n ? k0 : 0u));
                 const uint32_t ka = s < stages ? k0 : (stages - 1) * KB;
 #pragma unroll
-                for (int p = 0; p < 3; ++p) c[p] = *reinterpret_cast<const uintx4 *>(arow + p * plane_stride + ka);
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int p = 0; p < 3; ++p)
+                        c[h][p] = *reinterpret_cast<const uintx4 *>(arow + (size_t)h * 128 * a.npad + p * plane_stride + ka);
             };
-            auto lstore = [&](char *stage, uint32_t s, const floatx4 &v, const uintx4 (&c)[3]) __attribute__((always_inline)) {
+            auto lstore = [&](char *stage, uint32_t s, const floatx4 (&v)[4], const uintx4 (&c)[2][3]) __attribute__((always_inline)) {
                 const bool inside = s * KB + vq * 4 < a.n;
-                bf16x4 h[3];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    __bf16 x1, x2, x3;
-                    split3(inside ? v[e] : 0.f, x1, x2, x3);
-                    h[0][e] = x1;
-                    h[1][e] = x2;
-                    h[2][e] = x3;
+                for (int r = 0; r < 4; ++r) {
+                    bf16x4 h[3];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        __bf16 x1, x2, x3;
+                        split3(inside ? v[r][e] : 0.f, x1, x2, x3);
+                        h[0][e] = x1;
+                        h[1][e] = x2;
+                        h[2][e] = x3;
+                    }
+#pragma unroll
+                    for (int p = 0; p < 3; ++p) *reinterpret_cast<bf16x4 *>(stage + wr_v + r * 64 * ROWB + p * V_PLANE) = h[p];
                 }
 #pragma unroll
-                for (int p = 0; p < 3; ++p) {
-                    *reinterpret_cast<bf16x4 *>(stage + wr_v + p * V_PLANE) = h[p];
-                    *reinterpret_cast<uintx4 *>(stage + wr_a + p * A_PLANE) = c[p];
-                }
+                for (int r = 0; r < 2; ++r)
+#pragma unroll
+                    for (int p = 0; p < 3; ++p) *reinterpret_cast<uintx4 *>(stage + wr_a + r * 128 * ROWB + p * A_PLANE) = c[r][p];
             };
 
-            floatx16 acc[2][2];
+            floatx16 acc[NB][NB];
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
+            for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
+                for (int cb = 0; cb < NB; ++cb)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[rb][cb][e] = 0.f;
 
             // Operand registers of the stage being contracted: fa[block][plane], fv[block][plane].
             // A plane's registers are read again, for the next stage, as soon as the last product
             // that uses them has been issued.
-            bf16x8 fa[2][3], fv[2][3];
+            bf16x8 fa[NB][3], fv[NB][3];
             auto read_a = [&](const char *stage, int p) __attribute__((always_inline)) {
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
+                for (int b = 0; b < NB; ++b)
                     fa[b][p] = *reinterpret_cast<const bf16x8 *>(stage + rd_a + b * 32 * ROWB + p * A_PLANE);
             };
             auto read_v = [&](const char *stage, int p) __attribute__((always_inline)) {
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
+                for (int b = 0; b < NB; ++b)
                     fv[b][p] = *reinterpret_cast<const bf16x8 *>(stage + rd_v + b * 32 * ROWB + p * V_PLANE);
             };
-#define LSH_PRODUCT(PA, PV) \
-    _Pragma("unroll") for (int rb = 0; rb < 2; ++rb) \
-        _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) \
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[rb][PA], fv[cb][PV], acc[rb][cb], 0, 0, 0);
+            auto read_a1 = [&](const char *stage, int b, int p) __attribute__((always_inline)) {
+                fa[b][p] = *reinterpret_cast<const bf16x8 *>(stage + rd_a + b * 32 * ROWB + p * A_PLANE);
+            };
+            auto read_v1 = [&](const char *stage, int b, int p) __attribute__((always_inline)) {
+                fv[b][p] = *reinterpret_cast<const bf16x8 *>(stage + rd_v + b * 32 * ROWB + p * V_PLANE);
+            };
+            // single loads of the next stage's operands, small enough to go out in the shadow of one MFMA
+            auto load_v_row = [&](uint32_t s, int h, floatx4 (&v)[4]) __attribute__((always_inline)) {
+                const uint32_t k0 = s * KB;
+                v[h] = *reinterpret_cast<const floatx4 *>(vrow[h] + (k0 + vq * 4 < a.n ? k0 : 0u));
+            };
+            auto load_a_piece = [&](uint32_t s, int h, int p, uintx4 (&c)[2][3]) __attribute__((always_inline)) {
+                const uint32_t ka = s < stages ? s * KB : (stages - 1) * KB;
+                c[h][p] = *reinterpret_cast<const uintx4 *>(arow + (size_t)h * 128 * a.npad + p * plane_stride + ka);
+            };
 
             // One stage.  LDS holds three stages: s (in the operand registers by now), s + 1 (written
             // during the previous iteration, read into the freed operand registers during this one)
-            // and s + 2 (written during this one from register set (s + 2) % 3, which then takes
-            // the loads of stage s + 5).  The barrier sits after the first two products: what it
-            // waits for was issued long before, and the matrix pipe has work queued.
-            auto iteration = [&](uint32_t s, floatx4 &v_set, uintx4 (&c_set)[3]) __attribute__((always_inline)) {
+            // and s + 2 (written during this one from the load registers, which then take the loads
+            // of stage s + 3).  A wave is alone on its SIMD, so everything that is not an MFMA is cut
+            // into pieces that go out one after each MFMA: an operand register is refilled right
+            // after the last MFMA that reads it, the stores to LDS and the global loads ride along.
+            auto iteration = [&](uint32_t s, floatx4 (&v_set)[4], uintx4 (&c_set)[2][3]) __attribute__((always_inline)) {
+                const char *cur = lds_w + (s % 3) * STAGE;
                 const char *nxt = lds_w + ((s + 1) % 3) * STAGE;
-                char *far = lds_w + ((s + 2) % 3) * STAGE;
-                // product order and refills: every plane is read again at least eight MFMAs before
-                // the next stage's first product that needs it
+                char *far = lds_w + ((s + 2) % 3) * STAGE;  // last read two iterations ago: free since the barrier before this one
+                const bool inside = (s + 2) * KB + vq * 4 < a.n;
+                bf16x4 h[3];  // a vector row on its way: split in one product, written during the next
+                auto split_element = [&](int r, int e) __attribute__((always_inline)) {
+                    __bf16 x1, x2, x3;
+                    split3(inside ? v_set[r][e] : 0.f, x1, x2, x3);
+                    h[0][e] = x1;
+                    h[1][e] = x2;
+                    h[2][e] = x3;
+                };
+                auto write_plane = [&](int r, int pl) __attribute__((always_inline)) {
+                    *reinterpret_cast<bf16x4 *>(far + wr_v + r * 64 * ROWB + pl * V_PLANE) = h[pl];
+                };
+                auto store_a = [&](int r, int pl) __attribute__((always_inline)) {
+                    *reinterpret_cast<uintx4 *>(far + wr_a + r * 128 * ROWB + pl * A_PLANE) = c_set[r][pl];
+                };
+                // What goes out after MFMA i (0..15) of product k (0..5) of the stage: at most one
+                // memory instruction, or the split of one vector element.  Products 0, 1, 2 and 5 run
+                // row by row, 3 and 4 column by column, so that after every fourth MFMA one operand
+                // register has been read for the last time and is refilled from the next stage.
+                auto after = [&](auto K_, auto I_) __attribute__((always_inline)) {
+                    constexpr int k = decltype(K_)::value, i = decltype(I_)::value;
+                    if constexpr (i % 4 == 3) {
+                        constexpr int q = i / 4;
+                        if constexpr (k == 0) read_v1(cur, q, 2);  // read in every row of the stage before's last product
+                        if constexpr (k == 1) read_a1(nxt, q, 1);
+                        if constexpr (k == 2) read_a1(nxt, q, 2);
+                        if constexpr (k == 3) read_v1(nxt, q, 1);
+                        if constexpr (k == 4) read_v1(nxt, q, 0);
+                        if constexpr (k == 5) read_a1(nxt, q, 0);
+                    } else if constexpr (k == 0 || k == 5) {  // the two coefficient rows: store, then load again
+                        constexpr int r = k == 0 ? 0 : 1;
+                        if constexpr (i < 3) store_a(r, i);
+                        if constexpr (i >= 4 && i < 7) load_a_piece(s + 3, r, i - 4, c_set);
+                        if constexpr (k == 0 && i >= 8 && i < 13) split_element(0, i < 11 ? i - 8 : 3);
+                    } else {  // products 1..4: write vector row k - 1, load it again, split row k
+                        if constexpr (i < 3) write_plane(k - 1, i);
+                        if constexpr (i == 4) load_v_row(s + 3, k - 1, v_set);
+                        if constexpr (k < 4 && (i == 5 || i == 6 || i == 8 || i == 9)) split_element(k, i < 7 ? i - 5 : i - 6);
+                    }
+                };
+                auto product = [&](auto K_, auto PA_, auto PV_, auto BY_ROW_) __attribute__((always_inline)) {
+                    constexpr int pa = decltype(PA_)::value, pv = decltype(PV_)::value;
+                    constexpr bool by_row = decltype(BY_ROW_)::value;
+                    [&]<int... I>(std::integer_sequence<int, I...>) __attribute__((always_inline)) {
+                        (([&] {
+                            constexpr int rb = by_row ? I / 4 : I % 4, cb = by_row ? I % 4 : I / 4;
+                            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[rb][pa], fv[cb][pv], acc[rb][cb], 0, 0, 0);
+                            __builtin_amdgcn_sched_barrier(0);
+                            after(K_, std::integral_constant<int, I>{});
+                            __builtin_amdgcn_sched_barrier(0);
+                        }()), ...);
+                    }(std::make_integer_sequence<int, 16>{});
+                };
+                using std::integral_constant;
                 __builtin_amdgcn_sched_barrier(0);
-                LSH_PRODUCT(1, 1)
-                LSH_PRODUCT(1, 0)
+                product(integral_constant<int, 0>{}, integral_constant<int, 1>{}, integral_constant<int, 1>{}, std::true_type{});
+                lds_barrier();  // stage s + 1 is complete in LDS (the product before touched stage s and the free slot only)
                 __builtin_amdgcn_sched_barrier(0);
-                __syncthreads();  // stage s + 1 is complete in LDS; nobody reads stage s - 1 any more
-                read_a(nxt, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                LSH_PRODUCT(2, 0)
-                __builtin_amdgcn_sched_barrier(0);
-                read_a(nxt, 2);
-                lstore(far, s + 2, v_set, c_set);
-                __builtin_amdgcn_sched_barrier(0);
-                LSH_PRODUCT(0, 1)
-                __builtin_amdgcn_sched_barrier(0);
-                read_v(nxt, 1);
-                gload(s + 5, v_set, c_set);
-                __builtin_amdgcn_sched_barrier(0);
-                LSH_PRODUCT(0, 0)
-                __builtin_amdgcn_sched_barrier(0);
-                read_v(nxt, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                LSH_PRODUCT(0, 2)
-                __builtin_amdgcn_sched_barrier(0);
-                read_a(nxt, 0);
-                read_v(nxt, 2);
-                __builtin_amdgcn_sched_barrier(0);
+                product(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 0>{}, std::true_type{});
+                product(integral_constant<int, 2>{}, integral_constant<int, 2>{}, integral_constant<int, 0>{}, std::true_type{});
+                product(integral_constant<int, 3>{}, integral_constant<int, 0>{}, integral_constant<int, 1>{}, std::false_type{});
+                product(integral_constant<int, 4>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{}, std::false_type{});
+                product(integral_constant<int, 5>{}, integral_constant<int, 0>{}, integral_constant<int, 2>{}, std::true_type{});
             };
 
-            // prologue: stages 0 and 1 to LDS, stages 2, 3, 4 on their way (stage j lives in set j % 3)
-            gload(0, gv[0], ga[0]);
-            gload(1, gv[1], ga[1]);
-            gload(2, gv[2], ga[2]);
-            lstore(lds_w, 0, gv[0], ga[0]);
-            gload(3, gv[0], ga[0]);
-            lstore(lds_w + STAGE, 1, gv[1], ga[1]);
-            gload(4, gv[1], ga[1]);
+            // prologue: stages 0 and 1 to LDS, stage 2 on its way
+            gload(0, gv, ga);
+            lstore(lds_w, 0, gv, ga);
+            gload(1, gv, ga);
+            lstore(lds_w + STAGE, 1, gv, ga);
+            gload(2, gv, ga);
             __syncthreads();
             read_a(lds_w, 1);  // in the order of the refills
             read_a(lds_w, 2);
@@ -223,23 +290,16 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
             read_v(lds_w, 0);
             read_a(lds_w, 0);
             read_v(lds_w, 2);
-            // the stage count is rounded up to the ring's three: a stage beyond the last multiplies
-            // coefficients with zeros
-            for (uint32_t s = 0; s < stages; s += 3) {
-                iteration(s, gv[2], ga[2]);
-                iteration(s + 1, gv[0], ga[0]);
-                iteration(s + 2, gv[1], ga[1]);
-            }
-#undef LSH_PRODUCT
+            for (uint32_t s = 0; s < stages; ++s) iteration(s, gv, ga);
             __syncthreads();  // the next tile's prologue writes stages that the last iterations read
 
             // epilogue: register 4q + e of block (rb, cb) is function 8q + 4 (l / 32) + e of the
             // block's 32, vector l % 32
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
+            for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const uint32_t j = ft * TF + fw * 64 + rb * 32 + 8 * q + 4 * lh;  // < kpad
+                    const uint32_t j = ft * TF + fw * 32 * NB + rb * 32 + 8 * q + 4 * lh;  // < kpad
                     float b4[4] = {0.f, 0.f, 0.f, 0.f};
                     if constexpr (!PROJ) {
                         const floatx4 t = *reinterpret_cast<const floatx4 *>(a.off + j);
@@ -247,8 +307,8 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
                         for (int e = 0; e < 4; ++e) b4[e] = POW2 ? t[e] * a.inv_w : t[e];
                     }
 #pragma unroll
-                    for (int cb = 0; cb < 2; ++cb) {
-                        const uint64_t vec = vt * TVW + vw * 64 + cb * 32 + lr;
+                    for (int cb = 0; cb < NB; ++cb) {
+                        const uint64_t vec = vt * TVW + vw * 32 * NB + cb * 32 + lr;
                         uintx4 v;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -334,7 +394,7 @@ int launch_dense_wide(const lsh_params *p, bool proj, const float *d_data, uint6
     int exp2 = 0;
     const bool pw = proj || std::frexp(p->w, &exp2) == 0.5f;
     const bool vec = p->k % 4 == 0;
-    // one workgroup per CU (108 KB of LDS), a multiple of 8 so that every XCD gets the same number
+    // one workgroup per CU (144 KB of LDS), a multiple of 8 so that every XCD gets the same number
     uint32_t wgs = (uint32_t)(p->num_cus > 0 ? p->num_cus : 256) / 8 * 8;
     if (wgs < 8) wgs = 8;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
