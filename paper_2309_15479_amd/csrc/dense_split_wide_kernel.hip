@@ -4,9 +4,9 @@
 // error: what is left out is below 2^-23 of each term |a_i v_i|).  The fp32 MFMA runs at a
 // sixteenth of the bf16 rate, so six bf16 products are 16/6 of its speed at best.
 //
-//   V [N][n] fp32 row-major; A already split on the host into three bf16 planes
-//   [3][kpad][npad] (row j = a_j, zero rows up to a multiple of 256, zero columns up to a
-//   multiple of 16).
+//   V [N][n] fp32 row-major; A already split on the host into three bf16 planes, stored in the
+//   order of use: [function tile of 256][stage of 16 coordinates][plane][row][coordinate]
+//   (zero rows up to a multiple of 256, zero columns up to a multiple of 16).
 //
 // Workgroup = 4 waves, one per SIMD; tile = 256 functions x 256 vectors, contraction in stages
 // of 16 coordinates.  A wave owns 128 functions x 128 vectors: 4 x 4 blocks of
@@ -59,11 +59,12 @@ constexpr int ROWB = 32;   // bytes per row and plane in a stage: two 16-byte ha
 constexpr int A_PLANE = TF * ROWB, V_PLANE = TVW * ROWB;
 constexpr int STAGE = 3 * (A_PLANE + V_PLANE);  // 49152 bytes
 constexpr int kThreadsW = 256;
+constexpr int kStagePlanes = 3 * TF * KB;  // bf16 elements of one function tile's three planes in one stage
 constexpr int kLdsBytesW = 3 * STAGE;
 
 struct WideArgs {
     const float *data;       // [N][n]
-    const uint16_t *planes;  // [3][kpad][npad] bf16 bit patterns
+    const uint16_t *planes;  // [kpad / 256][npad / 16][3][256][16] bf16 bit patterns
     const float *off;        // [>= kpad]
     uint64_t N;
     uint32_t n, npad, k, kpad;
@@ -113,8 +114,9 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
     const uint32_t wr_v = 3 * A_PLANE + vr * ROWB + (((vq >> 1) ^ ((vr >> 3) & 1)) << 4) + ((vq & 1) << 3);
 
     for (uint32_t ft = ft_first; ft < F; ft += ft_step) {
-        const uint16_t *arow = a.planes + ((size_t)ft * TF + ar) * a.npad + ah * 8;
-        const size_t plane_stride = (size_t)a.kpad * a.npad;
+        // the planes are stored stage by stage: [function tile][stage][plane][256 rows][16 coordinates],
+        // so the 64 lanes of a load read 1 KB in one piece (thread t: 16 bytes at 16 t of rows 0-127)
+        const uint16_t *arow = a.planes + (size_t)ft * stages * kStagePlanes + threadIdx.x * 8;
         for (uint64_t vt = (uint64_t)i * reps + rep; vt < Vt; vt += (uint64_t)per_xcd * reps) {
             const float *vrow[4];
 #pragma unroll
@@ -135,12 +137,12 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
                 // coordinates beyond n read the row's first ones instead; lstore() replaces them by zeros
 #pragma unroll
                 for (int h = 0; h < 4; ++h) v[h] = *reinterpret_cast<const floatx4 *>(vrow[h] + (k0 + vq * 4 < a.n ? k0 : 0u));
-                const uint32_t ka = s < stages ? k0 : (stages - 1) * KB;
+                const uint32_t ka = s < stages ? s : stages - 1;  // stage
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int p = 0; p < 3; ++p)
-                        c[h][p] = *reinterpret_cast<const uintx4 *>(arow + (size_t)h * 128 * a.npad + p * plane_stride + ka);
+                        c[h][p] = *reinterpret_cast<const uintx4 *>(arow + (size_t)ka * kStagePlanes + p * (TF * KB) + h * 128 * KB);
             };
             auto lstore = [&](char *stage, uint32_t s, const floatx4 (&v)[4], const uintx4 (&c)[2][3]) __attribute__((always_inline)) {
                 const bool inside = s * KB + vq * 4 < a.n;
@@ -198,8 +200,8 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
                 v[h] = *reinterpret_cast<const floatx4 *>(vrow[h] + (k0 + vq * 4 < a.n ? k0 : 0u));
             };
             auto load_a_piece = [&](uint32_t s, int h, int p, uintx4 (&c)[2][3]) __attribute__((always_inline)) {
-                const uint32_t ka = s < stages ? s * KB : (stages - 1) * KB;
-                c[h][p] = *reinterpret_cast<const uintx4 *>(arow + (size_t)h * 128 * a.npad + p * plane_stride + ka);
+                const uint32_t ka = s < stages ? s : stages - 1;  // stage
+                c[h][p] = *reinterpret_cast<const uintx4 *>(arow + (size_t)ka * kStagePlanes + p * (TF * KB) + h * 128 * KB);
             };
 
             // One stage.  LDS holds three stages: s (in the operand registers by now), s + 1 (written
@@ -355,11 +357,12 @@ float from_bf16(uint16_t h) {
 uint32_t dense_wide_row_tile() { return TF; }
 uint32_t dense_wide_col_step() { return KB; }
 
-// the three bf16 planes [3][kpad][npad] of a coefficient matrix [k][n]
+// The three bf16 planes of a coefficient matrix [k][n] in the order the kernel reads them:
+// [function tile of 256][stage of 16 coordinates][plane][row][coordinate], zeros beyond k and n.
 void build_dense_planes(const float *a, uint32_t k, uint32_t n, uint32_t kpad, uint32_t npad,
                         std::vector<uint16_t> &planes) {
     planes.assign((size_t)3 * kpad * npad, 0);
-    const size_t plane = (size_t)kpad * npad;
+    const uint32_t stages = npad / KB;
     for (uint32_t j = 0; j < k; ++j)
         for (uint32_t c = 0; c < n; ++c) {
             const float x = a[(size_t)j * n + c];
@@ -367,10 +370,10 @@ void build_dense_planes(const float *a, uint32_t k, uint32_t n, uint32_t kpad, u
             const float r1 = x - from_bf16(h1);
             const uint16_t h2 = to_bf16(r1);
             const uint16_t h3 = to_bf16(r1 - from_bf16(h2));
-            const size_t at = (size_t)j * npad + c;
+            const size_t at = ((size_t)(j / TF) * stages + c / KB) * kStagePlanes + (size_t)(j % TF) * KB + c % KB;
             planes[at] = h1;
-            planes[plane + at] = h2;
-            planes[2 * plane + at] = h3;
+            planes[at + TF * KB] = h2;
+            planes[at + 2 * TF * KB] = h3;
         }
 }
 

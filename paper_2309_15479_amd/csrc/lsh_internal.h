@@ -106,7 +106,7 @@ struct lsh_params {
     float *d_off = nullptr;            // [kpad]
     float *d_dense = nullptr;          // [kpad_dense][n]: row j = a_j written out over all n coordinates; m == n or n == 128, else null
     uint32_t kpad_dense = 0;
-    void *d_dense_planes = nullptr;    // m == n, n != 128: the same matrix as three bf16 planes [3][kpad 256][npad 16]
+    void *d_dense_planes = nullptr;    // m == n, n != 128: the same matrix as three bf16 planes, [kpad / 256][npad / 16][3][256][16]
     int dense_arithmetic = LSH_DENSE_AUTO;  // see lsh_params_set_dense_arithmetic
     // one sample per table: operand tables of the shared-sample kernel (null when unsupported)
     lsh::SharedPlan shared_plan;
