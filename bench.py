@@ -49,14 +49,14 @@ _RANGED = {"ranged_kernel.hip": "27e4edf7a84e975a", "sampled_common.h": "9d6a9ea
 _STREAMED = {"sampled_kernel.hip": "bea9b29ed7d9a478", "sampled_common.h": "9d6a9ea08ffad892"}
 _SUMMARY = "profiles/hbm_traffic_all_workloads.md"
 MEASURED_TRAFFIC = {
-    "highdim/fastlsh/m64": (1766085 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
-    "highdim/fastlsh/m256": (2219530 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
-    "highdim/fastlsh/m1024": (4065159 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
-    "highdim/e2lsh": (15958325 * _KIB, 2959132 * _KIB, _SUMMARY, {"dense_split_wide_kernel.hip": "9b3b9b757a0619f0"}),
+    "highdim/fastlsh/m64": (1770761 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
+    "highdim/fastlsh/m256": (2219108 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
+    "highdim/fastlsh/m1024": (4062070 * _KIB, 1600000 * _KIB, _SUMMARY, _RANGED),
+    "highdim/e2lsh": (26035972 * _KIB, 3332171 * _KIB, _SUMMARY, {"dense_split_wide_kernel.hip": "bad4885b0dee9bd9"}),
     "sift/fastlsh/m32": (250604 * _KIB, 2000000 * _KIB, _SUMMARY, _STREAMED),
-    "gist/fastlsh/m128": (2373531 * _KIB, 4000000 * _KIB, _SUMMARY, _STREAMED),
-    "gist/e2lsh": (8517693 * _KIB, 5043912 * _KIB, _SUMMARY, {"dense_split_wide_kernel.hip": "9b3b9b757a0619f0"}),
-    "angular/signs/m512": (55201800 * _KIB, 250022 * _KIB, _SUMMARY, _RANGED),
+    "gist/fastlsh/m128": (2372924 * _KIB, 4000000 * _KIB, _SUMMARY, _STREAMED),
+    "gist/e2lsh": (8557728 * _KIB, 6273800 * _KIB, _SUMMARY, {"dense_split_wide_kernel.hip": "bad4885b0dee9bd9"}),
+    "angular/signs/m512": (55593954 * _KIB, 250023 * _KIB, _SUMMARY, _RANGED),
 }
 
 
