@@ -26,11 +26,13 @@
 // instruction or the split of one vector element after each (scheduling barriers keep that
 // order); one LDS-only barrier per stage.
 //
-// Placement: workgroup g runs on XCD g % 8.  With at least 8 function tiles XCD x takes the
-// tiles x, x + 8, ..., with fewer the XCDs share them; the CUs of an XCD walk the vector tiles
-// of one function tile in step, so the coefficient stages (the larger operand) are fetched into
-// that XCD's L2 once per stage, and the vector tiles, read by the XCDs at about the same time,
-// come from memory once.
+// Placement: workgroup g runs on XCD g % 8.  XCD x takes the vector tiles x, x + 8, ...; the
+// F function tiles of a vector tile go to F workgroups of that XCD, which walk the stages in
+// step, so a vector stage is fetched into the XCD's L2 once and the other F - 1 workgroups hit
+// there; a workgroup keeps its function tile for all its vector tiles, and the workgroups of
+// an XCD that have the same one (workgroups per XCD / F of them) share its stages in L2, too.
+// (With a number of function tiles that does not divide the workgroups of an XCD: function
+// tiles dealt to the XCDs, every XCD walking all vectors.)
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -113,11 +115,24 @@ __global__ __launch_bounds__(kThreadsW) void dense_split_wide_kernel(const WideA
     const uint32_t wr_a = ar * ROWB + ((ah ^ ((ar >> 3) & 1)) << 4);
     const uint32_t wr_v = 3 * A_PLANE + vr * ROWB + (((vq >> 1) ^ ((vr >> 3) & 1)) << 4) + ((vq & 1) << 3);
 
+    // When the number of function tiles divides an XCD's workgroups (the usual case), XCD x
+    // takes the vector tiles x, x + 8, ... and F of its workgroups contract one of them at the
+    // same time, each with its own function tile: the vector tile is then fetched into that
+    // XCD's L2 once instead of once per XCD.
+    const bool by_vector = per_xcd % F == 0 && F <= per_xcd;
+    uint64_t vt_first = (uint64_t)i * reps + rep, vt_step = (uint64_t)per_xcd * reps;
+    if (by_vector) {
+        ft_first = i % F;
+        ft_step = F;  // one function tile per workgroup
+        const uint32_t groups = per_xcd / F;
+        vt_first = x + 8ull * (i / F);
+        vt_step = 8ull * groups;
+    }
     for (uint32_t ft = ft_first; ft < F; ft += ft_step) {
         // the planes are stored stage by stage: [function tile][stage][plane][256 rows][16 coordinates],
         // so the 64 lanes of a load read 1 KB in one piece (thread t: 16 bytes at 16 t of rows 0-127)
         const uint16_t *arow = a.planes + (size_t)ft * stages * kStagePlanes + threadIdx.x * 8;
-        for (uint64_t vt = (uint64_t)i * reps + rep; vt < Vt; vt += (uint64_t)per_xcd * reps) {
+        for (uint64_t vt = vt_first; vt < Vt; vt += vt_step) {
             const float *vrow[4];
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
