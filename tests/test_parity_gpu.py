@@ -206,11 +206,12 @@ def test_shared_sample_shapes(lsh, N, n, k, m, w, seed, repl, L):
 @pytest.mark.parametrize("fp32_only", [False, True])
 @pytest.mark.parametrize("N,n,k", [(130, 128, 128), (129, 100, 200), (1, 37, 5), (515, 36, 257), (64, 4096, 64),
                                    (300, 128, 192), (257, 128, 70), (400, 124, 256),
-                                   # the bf16 x 3 kernel for n != 128: 128-vector x 256-function tiles in stages of
+                                   # the bf16 x 3 kernel for n != 128: 256-vector x 256-function tiles in stages of
                                    # 16 coordinates; partial tiles both ways, n not a multiple of 16, k not of 4,
-                                   # more function tiles than XCDs, a single vector
+                                   # more function tiles than XCDs, a single vector, numbers of function tiles that
+                                   # do and do not divide an XCD's workgroups, more vector tiles than XCDs
                                    (300, 960, 320), (131, 4096, 520), (257, 132, 260), (1000, 64, 2304), (1, 16, 4),
-                                   (128, 20, 256), (640, 512, 1027)])
+                                   (128, 20, 256), (640, 512, 1027), (3000, 64, 512), (2500, 48, 768)])
 def test_dense_shapes(lsh, N, n, k, fp32_only):
     say(f"dense case N={N} n={n} k={k} fp32_only={fp32_only}")
     g = torch.Generator(device="cuda")
