@@ -582,6 +582,16 @@ class Bench:
                 e["roofline"] = with_traffic(gather_roofline(N, n, k, p.m, 4 * k, ms[leg]), f"highdim/fastlsh/m{p.m}")
                 e["speedup_over_e2lsh"] = ms["e2lsh"] / ms[leg]
                 e["operation_count_ratio_n_over_m"] = n / p.m
+                if p.m * 8 >= n:
+                    # dense enough for the matrix cores to compete: the same call with the sampled
+                    # coefficients written out over all n coordinates (LSH_DENSE_MATRIX), timed
+                    # outside the step
+                    p.set_dense_arithmetic(lsh.DENSE_MATRIX)
+                    mat_ms = self.timer.measure(lambda: lsh.hash_fastlsh(p, data, out=out))
+                    mat_parity = self.check_ids(p, wl, data, out, False, count=48)
+                    p.set_dense_arithmetic(lsh.DENSE_AUTO)
+                    e["matrix_core_route"] = {"ms": mat_ms, "parity": mat_parity,
+                                              "roofline": dense_roofline(N, n, k, mat_ms, {"products": 6})}
             entries.append(e)
         # the variant with one sample S per table (Sec. 3.1 read literally), timed outside the step
         L = wl.L or 128

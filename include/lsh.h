@@ -193,13 +193,22 @@ int lsh_hash_e2lsh(const lsh_params_t *params, const float *d_data, uint64_t N,
  * products skipped); any other shape uses fp32 MFMA.
  * LSH_DENSE_FP32: fp32 MFMA for every dense product, and the gathered fp32 kernels for FastLSH
  * ids, projections, keys and signs at every n.
+ * LSH_DENSE_MATRIX: as LSH_DENSE_AUTO, and lsh_hash_fastlsh and lsh_project_fastlsh of an object
+ * with m < n and any n that is a multiple of 4 also run as that bf16 x 3 product over the
+ * coefficients written out over all n coordinates (same error bound).  It costs n multiply-adds
+ * per function where the gather costs m, on matrix cores that are several times faster per
+ * multiply-add: on the 4096-dimensional shape it is the faster route from about m = n / 5 on.
+ * The first call with this mode builds the object's bf16 planes (6 bytes x k x n of device
+ * memory, freed with the object; call it with the object's device current).
  * The mode is a plain field of the object, read by every hash call when it launches: set it
  * while no other thread is calling into the same object (calls already enqueued keep the mode
  * they were launched with).
- * Errors: INVALID_ARG (null, unknown mode).
+ * Errors: INVALID_ARG (null, unknown mode, another device current); for LSH_DENSE_MATRIX also
+ * UNSUPPORTED (n not a multiple of 4), NO_DEVICE, ALLOC, HIP.
  */
 #define LSH_DENSE_AUTO 0
 #define LSH_DENSE_FP32 1
+#define LSH_DENSE_MATRIX 2
 int lsh_params_set_dense_arithmetic(lsh_params_t *params, int mode);
 
 /*

@@ -18,6 +18,7 @@ SAMPLE_WITHOUT_REPLACEMENT = 0
 SAMPLE_WITH_REPLACEMENT = 1
 DENSE_AUTO = 0
 DENSE_FP32 = 1
+DENSE_MATRIX = 2
 
 EXPORTS = [
     "lsh_params_create", "lsh_params_create_ex", "lsh_params_create_shared", "lsh_params_destroy",
@@ -170,7 +171,8 @@ class LshParams:
         return out
 
     def set_dense_arithmetic(self, mode):
-        """DENSE_AUTO: bf16 x 3 matrix-core product where the shape allows; DENSE_FP32: fp32 MFMA."""
+        """DENSE_AUTO: bf16 x 3 matrix-core product where the shape allows; DENSE_FP32: fp32 MFMA;
+        DENSE_MATRIX: as DENSE_AUTO, and FastLSH ids / projections with m < n as a dense product too."""
         _check(load_library().lsh_params_set_dense_arithmetic(self.handle, int(mode)), "set_dense_arithmetic")
 
     def mips_coeffs(self):

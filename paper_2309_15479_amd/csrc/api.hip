@@ -67,8 +67,10 @@ int upload_tables(lsh_params *p) {
     // n == 128: the matrix-core sign kernel takes any object's coefficients written out densely
     if (p->m == p->n || p->n == 128) p->kpad_dense = (p->k + dense_col_tile() - 1) / dense_col_tile() * dense_col_tile();
     // the wide matrix-core kernel reads offsets up to its function tiles
+    // (every object with n a multiple of 4 may be switched to that kernel later, see
+    // lsh_params_set_dense_arithmetic; the planes themselves are built here only for m == n)
     const bool wide = p->m == p->n && p->n != 128 && p->n % 4 == 0;
-    const uint32_t kpad_wide = wide ? (p->k + dense_wide_row_tile() - 1) / dense_wide_row_tile() * dense_wide_row_tile() : 0;
+    const uint32_t kpad_wide = p->n % 4 == 0 ? (p->k + dense_wide_row_tile() - 1) / dense_wide_row_tile() * dense_wide_row_tile() : 0;
     uint32_t off_len = kpad > p->kpad_dense ? kpad : p->kpad_dense;
     if (off_len < kpad_wide) off_len = kpad_wide;
 
@@ -365,8 +367,10 @@ int lsh_hash_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, int
     if (rc != LSH_OK || N == 0) return rc;
     if (p->shared_plan.supported) return launch_shared(p, 0, d_data, N, d_out, stream);
     if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 0, d_data, N, d_out, stream);
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_supported(p))
         return launch_dense_split(p, 0, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_MATRIX && p->d_dense_planes)
+        return launch_dense_wide(p, false, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Ids, d_data, N, d_out, 0, stream);
 }
 
@@ -375,15 +379,17 @@ int lsh_project_fastlsh(const lsh_params_t *p, const float *d_data, uint64_t N, 
     if (rc != LSH_OK || N == 0) return rc;
     if (p->shared_plan.supported) return launch_shared(p, 1, d_data, N, d_out, stream);
     if (p->shared_ranged_plan.supported) return launch_shared_ranged(p, 1, d_data, N, d_out, stream);
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_supported(p))
         return launch_dense_split(p, 1, d_data, N, d_out, stream);
+    if (p->dense_arithmetic == LSH_DENSE_MATRIX && p->d_dense_planes)
+        return launch_dense_wide(p, true, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Proj, d_data, N, d_out, 0, stream);
 }
 
 int lsh_hash_signs(const lsh_params_t *p, const float *d_data, uint64_t N, uint64_t *d_out, void *stream) {
     int rc = check_hash_args(p, d_data, d_out, N);
     if (rc != LSH_OK || N == 0) return rc;
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_signs_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_signs_supported(p))
         return launch_dense_split(p, 2, d_data, N, d_out, stream);
     return launch_sampled(p, Epilogue::Signs, d_data, N, d_out, 0, stream);
 }
@@ -397,7 +403,7 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
     if (!is_pow2(g) || g > 64) return LSH_ERR_UNSUPPORTED;
     if (N == 0) return LSH_OK;
     if (shared_keys_ok(p, L)) return launch_shared(p, 2, d_data, N, d_out, stream);
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && !p->shared_plan.supported && dense_split_keys_supported(p, L))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && !p->shared_plan.supported && dense_split_keys_supported(p, L))
         return launch_dense_split(p, 3, d_data, N, d_out, stream, L);
     return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
 }
@@ -411,9 +417,9 @@ int lsh_hash_fastlsh_ids_keys(const lsh_params_t *p, const float *d_data, uint64
     // one launch where a kernel has the epilogue for it; the results are those of the two calls
     // either way (the keys are folded from the very ids that are stored)
     const bool per_function = !p->shared_plan.supported && !p->shared_ranged_plan.supported;
-    if (per_function && p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_keys_supported(p, L))
+    if (per_function && p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_keys_supported(p, L))
         return launch_dense_split(p, 4, d_data, N, d_ids, stream, L, d_keys);
-    if (per_function && !(p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p)) &&
+    if (per_function && !(p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_supported(p)) &&
         sampled_ids_keys_supported(p, L))
         return launch_sampled(p, Epilogue::IdsKeys, d_data, N, d_ids, L, stream, d_keys);
     rc = lsh_hash_fastlsh(p, d_data, N, d_ids, stream);
@@ -477,9 +483,9 @@ int lsh_hash_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, int32
     if (rc != LSH_OK) return rc;
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_supported(p))
         return launch_dense_split(p, 0, d_data, N, d_out, stream);
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_wide_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_wide_supported(p))
         return launch_dense_wide(p, false, d_data, N, d_out, stream);
     return launch_dense(p, false, d_data, N, d_out, stream);
 }
@@ -489,15 +495,48 @@ int lsh_project_e2lsh(const lsh_params_t *p, const float *d_data, uint64_t N, fl
     if (rc != LSH_OK) return rc;
     if (p->m != p->n) return LSH_ERR_INVALID_ARG;
     if (N == 0) return LSH_OK;
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_split_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_supported(p))
         return launch_dense_split(p, 1, d_data, N, d_out, stream);
-    if (p->dense_arithmetic == LSH_DENSE_AUTO && dense_wide_supported(p))
+    if (p->dense_arithmetic != LSH_DENSE_FP32 && dense_wide_supported(p))
         return launch_dense_wide(p, true, d_data, N, d_out, stream);
     return launch_dense(p, true, d_data, N, d_out, stream);
 }
 
 int lsh_params_set_dense_arithmetic(lsh_params_t *p, int mode) {
-    if (!p || (mode != LSH_DENSE_AUTO && mode != LSH_DENSE_FP32)) return LSH_ERR_INVALID_ARG;
+    if (!p || (mode != LSH_DENSE_AUTO && mode != LSH_DENSE_FP32 && mode != LSH_DENSE_MATRIX)) return LSH_ERR_INVALID_ARG;
+    if (mode == LSH_DENSE_MATRIX && p->n != 128 && !p->d_dense_planes) {
+        // the sampled coefficients written out over all n coordinates (zeros where a function does
+        // not sample, sums where it samples a coordinate more than once), as the bf16 planes of
+        // the matrix-core kernel for any n: built on first use
+        if (p->n % 4 != 0 || (uint64_t)p->k * 4 >= (1ull << 32)) return LSH_ERR_UNSUPPORTED;
+        if (p->device < 0) return LSH_ERR_NO_DEVICE;
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess) return LSH_ERR_HIP;
+        if (dev != p->device) return LSH_ERR_INVALID_ARG;
+        try {
+            std::vector<float> dense((size_t)p->k * p->n, 0.f);
+            for (uint32_t j = 0; j < p->k; ++j)
+                for (uint32_t i = 0; i < p->m; ++i)
+                    dense[(size_t)j * p->n + p->idx[(size_t)j * p->m + i]] += p->coef[(size_t)j * p->m + i];
+            const uint32_t kpad_wide = (p->k + dense_wide_row_tile() - 1) / dense_wide_row_tile() * dense_wide_row_tile();
+            const uint32_t npad = (p->n + dense_wide_col_step() - 1) / dense_wide_col_step() * dense_wide_col_step();
+            std::vector<uint16_t> planes;
+            build_dense_planes(dense.data(), p->k, p->n, kpad_wide, npad, planes);
+            void *d = nullptr;
+            if (hipMalloc(&d, planes.size() * sizeof(uint16_t)) != hipSuccess) {
+                (void)hipGetLastError();
+                return LSH_ERR_ALLOC;
+            }
+            if (hipMemcpy(d, planes.data(), planes.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
+                (void)hipFree(d);
+                (void)hipGetLastError();
+                return LSH_ERR_HIP;
+            }
+            p->d_dense_planes = d;
+        } catch (const std::bad_alloc &) {
+            return LSH_ERR_ALLOC;
+        }
+    }
     p->dense_arithmetic = mode;
     return LSH_OK;
 }

@@ -57,9 +57,20 @@ def test_dense_arithmetic_modes():
     with binding.LshParams(128, 64, 32, 4.0, 1) as p:
         p.set_dense_arithmetic(binding.DENSE_FP32)
         p.set_dense_arithmetic(binding.DENSE_AUTO)
+        p.set_dense_arithmetic(binding.DENSE_MATRIX)     # n == 128: nothing more to build
+        p.set_dense_arithmetic(binding.DENSE_AUTO)
         with pytest.raises(binding.LshError) as e:
-            p.set_dense_arithmetic(2)
+            p.set_dense_arithmetic(3)
         assert e.value.status == -1
+    with binding.LshParams(961, 64, 100, 4.0, 1) as p:   # n not a multiple of 4: no matrix-core kernel
+        with pytest.raises(binding.LshError) as e:
+            p.set_dense_arithmetic(binding.DENSE_MATRIX)
+        assert e.value.status == -4
+    with binding.LshParams(960, 64, 100, 4.0, 1) as p:   # builds device tables: needs a device
+        try:
+            p.set_dense_arithmetic(binding.DENSE_MATRIX)
+        except binding.LshError as e:
+            assert e.status == -5
 
 
 CASES = [

@@ -36,7 +36,7 @@ def _tables(p):
     return p.indices(), p.coeffs(), p.offsets()
 
 
-def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=True, dense_fp32=False):
+def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=True, dense_fp32=False, matrix=True):
     """Runs every entry point on data_gpu and checks the given rows against the oracle."""
     idx, coef, off = _tables(p)
     rows_t = torch.as_tensor(np.asarray(rows), device=data_gpu.device)
@@ -59,6 +59,15 @@ def _compare_all(lsh, p, data_gpu, rows, L=None, label="", dense=False, signs=Tr
         p.set_dense_arithmetic(lsh.DENSE_AUTO)
         stats["proj_worst_gathered"] = check_proj(proj_g[rows_t].cpu().numpy(), ora, label + " fastlsh proj (gathered)")
         check_ids(ids_g[rows_t].cpu().numpy(), ora, label + " fastlsh ids (gathered)")
+    if p.n != 128 and p.n % 4 == 0 and p.m < p.n and matrix:
+        # the same hashes as a dense product over all n coordinates on the matrix cores
+        p.set_dense_arithmetic(lsh.DENSE_MATRIX)
+        ids_m = lsh.hash_fastlsh(p, data_gpu)
+        proj_m = lsh.project_fastlsh(p, data_gpu)
+        torch.cuda.synchronize()
+        p.set_dense_arithmetic(lsh.DENSE_AUTO)
+        stats["proj_worst_matrix"] = check_proj(proj_m[rows_t].cpu().numpy(), ora, label + " fastlsh proj (matrix cores)")
+        check_ids(ids_m[rows_t].cpu().numpy(), ora, label + " fastlsh ids (matrix cores)")
     if dense:
         assert p.m == p.n
         if dense_fp32:
