@@ -145,9 +145,9 @@ int upload_tables(lsh_params *p) {
         }
         if (rc == LSH_OK && p->shared_ranged_plan.supported) {
             std::vector<float> lists;
-            std::vector<uint32_t> offs, range_groups, stream_info;
+            std::vector<uint32_t> offs, stage_turns, stream_info;
             std::vector<float> extra;
-            build_shared_ranged_tables(p, p->shared_ranged_plan, lists, offs, range_groups, stream_info, &extra);
+            build_shared_ranged_tables(p, p->shared_ranged_plan, lists, offs, stage_turns, stream_info, &extra);
             auto upload = [&](void **dst, const void *src, size_t bytes) {
                 if (rc == LSH_OK && hipMalloc(dst, bytes) != hipSuccess) rc = LSH_ERR_ALLOC;
                 if (rc == LSH_OK && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = LSH_ERR_HIP;
@@ -155,7 +155,7 @@ int upload_tables(lsh_params *p) {
             upload(&p->d_sr_lists, lists.data(), lists.size() * sizeof(float));
             upload(&p->d_sr_offs, offs.data(), offs.size() * sizeof(uint32_t));
             upload(&p->d_sr_extra, extra.data(), extra.size() * sizeof(float));
-            upload(&p->d_sr_list_len, range_groups.data(), range_groups.size() * sizeof(uint32_t));
+            upload(&p->d_sr_list_len, stage_turns.data(), stage_turns.size() * sizeof(uint32_t));
             upload(&p->d_sr_stream, stream_info.data(), stream_info.size() * sizeof(uint32_t));
         }
         if (rc == LSH_OK && p->kpad_dense) {

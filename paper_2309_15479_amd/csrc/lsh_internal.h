@@ -64,9 +64,8 @@ struct SharedRangedPlan {
     uint32_t nblocks = 0;           // L * blocks_per_table
     uint32_t kblocks = 0;           // workgroups along the function axis
     uint32_t bpw = 0;               // blocks per contracting wave (4, 8 or 16)
-    uint32_t R = 0;                 // coordinate ranges
-    uint32_t block_steps = 0;       // MFMA steps per list block (set when the lists are built)
-    bool short_lists = false;       // every list is one block (else whole turns of the four-block ring)
+    uint32_t nchunks = 0;           // coordinate ranges of kWindowCoords that hold data
+    uint32_t stages = 0;            // stages per tile: nchunks rounded up to a multiple of the ring slots
     bool supported = false;
 };
 
@@ -148,9 +147,8 @@ int launch_sampled(const lsh_params *p, Epilogue ep, const float *d_data, uint64
                    uint32_t L, void *stream, void *d_out2 = nullptr);
 bool sampled_ids_keys_supported(const lsh_params *p, uint32_t L);
 // ranged kernel (ranged_kernel.hip): geometry constants the host tables are built for
-constexpr uint32_t kRangeCoords = 1024;      // shared-sample ranged kernel: coordinates per range
 constexpr uint32_t kRangeComputeWaves = 8;   // waves of a workgroup that gather or contract (the others load tiles)
-constexpr uint32_t kWindowCoords = 256;      // gather ranged kernel: coordinates per range (one ring slot holds 16 vectors of them)
+constexpr uint32_t kWindowCoords = 256;      // coordinates per range (one ring slot holds 16 vectors of them)
 constexpr uint32_t kWindowSlots = 8;         // ring slots in LDS
 constexpr uint32_t kWindowLook = 6;          // a stage may read its own range and this many after it (the last slot is being filled)
 int launch_ranged(const lsh_params *p, Epilogue ep, const float *d_data, uint64_t N, void *d_out,
@@ -161,7 +159,7 @@ void build_ranged_tables(const lsh_params *p, std::vector<uint32_t> &words, std:
 constexpr uint32_t kSharedRangeBlocksPerWave = 16;  // blocks of 16 functions a contracting wave owns at most
 SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::vector<float> &coefs,
-                                std::vector<uint32_t> &offs, std::vector<uint32_t> &range_groups,
+                                std::vector<uint32_t> &offs, std::vector<uint32_t> &stage_turns,
                                 std::vector<uint32_t> &stream_info, std::vector<float> *extra = nullptr);
 int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uint64_t N, void *d_out, void *stream,
                          const float *d_kappa2 = nullptr, int raw = 0);

@@ -132,36 +132,48 @@ double walk_ranged(const lsh_params *p, const std::vector<double> &v) {
 }
 
 double walk_shared_ranged(const lsh_params *p, const std::vector<double> &v) {
+    // Follows every contracting wave through one tile: stage after stage, turn after turn of the
+    // list ring, step i of a turn on block i / (32 / bpw) of the wave; every offset is resolved
+    // against what the ring holds at that stage, as in walk_ranged.
     SharedRangedPlan pl = p->shared_ranged_plan;
     std::vector<float> coefs;
-    std::vector<uint32_t> offs, groups, info;
-    build_shared_ranged_tables(p, pl, coefs, offs, groups, info);
-    const uint32_t U = pl.block_steps, OW = (U + 1) / 2, CW = kRangeComputeWaves, ring = 4;
+    std::vector<uint32_t> offs, turns, info;
+    build_shared_ranged_tables(p, pl, coefs, offs, turns, info);
+    const uint32_t U = 8, OW = 4, ring = 4, CW = kRangeComputeWaves, Q = ring * U / pl.bpw;
+    const uint32_t row = kWindowSlots * kWindowCoords;
+    if (turns.size() != pl.stages || pl.stages % kWindowSlots) return INFINITY;
     std::vector<double> walked(p->k, 0.0);
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
             const uint32_t stream = y * CW + cw, first = info[(size_t)stream * 2], blocks = info[(size_t)stream * 2 + 1];
             uint32_t next = 0;
-            for (uint32_t r = 0; r < pl.R; ++r)
-                for (uint32_t f = 0; f < pl.bpw; ++f) {
-                    const uint32_t nb = pl.short_lists ? 1 : ring * groups[r];
-                    const uint32_t blk = (y * pl.bpw + f) * CW + cw;  // global block number
-                    for (uint32_t b = 0; b < nb; ++b, ++next) {
+            for (uint32_t s = 0; s < pl.stages; ++s)
+                for (uint32_t turn = 0; turn < turns[s]; ++turn)
+                    for (uint32_t b = 0; b < ring; ++b, ++next) {
+                        if (next >= blocks) return INFINITY;
                         const float *cb = &coefs[(size_t)(first + next) * U * 64];
                         const uint32_t *ob = &offs[(size_t)(first + next) * 4 * OW];
-                        for (uint32_t s = 0; s < U; ++s)
+                        for (uint32_t e = 0; e < U; ++e) {
+                            const uint32_t f = (b * U + e) / Q;
+                            const uint32_t blk = (y * pl.bpw + f) * CW + cw;  // global block number
                             for (uint32_t l = 0; l < 64; ++l) {
-                                const uint32_t four = s / 4 * 4, width = U - four >= 4 ? 4 : 2;
-                                const float c = cb[(size_t)four * 64 + l * width + s % 4];
-                                const uint32_t off = (ob[(l / 16) * OW + s / 2] >> (16 * (s & 1))) & 0xFFFFu;
-                                const uint32_t coord = off / 4 < kRangeCoords ? r * kRangeCoords + off / 4 : p->n;  // beyond the range: a zero float
+                                const float c = cb[(size_t)(e / 4 * 4) * 64 + l * 4 + e % 4];
+                                const uint32_t off = (ob[(l / 16) * OW + e / 2] >> (16 * (e & 1))) & 0xFFFFu;
+                                uint32_t coord = p->n;  // beyond the row: a zero float
+                                if (off % 4 || off / 4 >= row + 4) return INFINITY;
+                                if (off / 4 < row) {
+                                    const uint32_t slot = off / 4 / kWindowCoords;
+                                    const uint32_t r = s + (slot + kWindowSlots - s % kWindowSlots) % kWindowSlots;
+                                    if (r > s + kWindowLook || r >= pl.nchunks) return INFINITY;  // not (yet) in the ring
+                                    coord = r * kWindowCoords + off / 4 % kWindowCoords;
+                                }
                                 const uint32_t in_table = (blk % pl.blocks_per_table) * 16 + l % 16;
                                 const uint32_t j = (blk / pl.blocks_per_table) * pl.g + in_table;
                                 if (blk < pl.nblocks && in_table < pl.g) walked[j] += (double)c * (coord < p->n ? v[coord] : 0.0);
                                 else if (c != 0.f) return INFINITY;
                             }
+                        }
                     }
-                }
             if (next != blocks || blocks < ring) return INFINITY;
         }
     return compare(p, v, walked);

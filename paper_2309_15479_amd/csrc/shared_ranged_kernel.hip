@@ -6,39 +6,40 @@
 //
 // Per (vector, table) the m sampled coordinates are gathered once and contracted with the
 // table's g coefficient vectors on the matrix cores: k * m / g gathers per vector instead of
-// k * m, and the multiply-adds leave the vector ALU.  The launch is then bound by reading the
-// data.
+// k * m, and the multiply-adds leave the vector ALU.
 //
-// A tile is 16 vectors x a range of 1024 coordinates, kept row-major in LDS ([vector][1024 + 4]
-// floats, two buffers); as in ranged_kernel.hip a workgroup is 8 contracting waves plus 4
-// loading waves that fetch the next (tile, range) behind the contraction, one barrier per step.
+// A tile is 16 vectors.  LDS holds a ring of eight ranges of 256 coordinates of every vector,
+// row-major ([vector][8 x 256 + 4] floats: coordinate c of a vector always sits at float
+// c % 2048 of its row); as in ranged_kernel.hip a workgroup is 8 contracting waves plus 4
+// loading waves, and a tile passes in stages: in stage s the loading waves write range s + 7
+// while the contracting waves may read the ranges s .. s + 6.  A sample of range r can therefore
+// be contracted in any of the stages r - 6 .. r, and the host uses that freedom to give every
+// table the same number of MFMA steps in a stage (next paragraph) with next to no padding.
+//
 // A contracting wave owns up to 16 blocks of 16 consecutive functions of one table (the MFMA
-// rows of v_mfma_f32_16x16x4_f32, the 16 vectors being its columns).  The host buckets every
-// table's samples by range and deals them to MFMA steps of four samples; per step a lane reads
-// one coefficient (row l % 16, sample l / 16 of the step) and one LDS offset from its list,
-// reads the sampled coordinate of vector l % 16 from the tile (the four coordinates of a step
-// differ modulo 4 where the table allows it, so that the 64 lanes hit 64 banks), and issues
-// one MFMA.
+// rows of v_mfma_f32_16x16x4_f32, the 16 vectors being its columns); their accumulators persist
+// over the stages of a tile.  Per MFMA step of four samples a lane reads one coefficient (row
+// l % 16, sample l / 16 of the step) and one LDS offset from its list, reads the sampled
+// coordinate of vector l % 16 from the ring (the four coordinates of a step differ modulo 4
+// where the table allows it, so that the 64 lanes hit 64 banks), and issues one MFMA.
 //
 // With the samples gathered once per table, what is left to stream per tile is the lists: they
-// come from L2, many times the bytes of the tile itself, and set the pace of the launch.  So
-// they are kept small and cheap to fetch: a list block of U steps holds U x 64 coefficients (one
-// per lane and step, a lane's four consecutive steps side by side so that one 16-byte load
-// brings them) and, apart from them, one record of U 16-bit offsets per sample slot l / 16,
-// which the sixteen lanes of a slot all read from the same address (a few bytes per block out
-// of L2 instead of a word per lane and step).  A vector memory instruction costs the CU's
-// memory pipeline 9 to 14 clocks whatever it hits, so their number per MFMA is what counts.
+// come from L2, many times the bytes of the tile itself.  So they are kept small and cheap to
+// fetch: a list block of 8 steps holds 8 x 64 coefficients (one per lane and step, a lane's four
+// consecutive steps side by side so that one 16-byte load brings them) and, apart from them, one
+// record of eight 16-bit offsets per sample slot l / 16, which the sixteen lanes of a slot all
+// read from the same address.  A vector memory instruction costs the CU's memory pipeline 9 to
+// 14 clocks whatever it hits, so their number per MFMA is what counts.
 //
-// The lists are also what a wave waits for if they arrive late, so they are asked for well ahead: a
-// wave's list blocks (U steps each) form one stream in consumption order (range after range,
-// block of functions after block) that runs through a ring of four register sets, a block
-// being requested while the block three places before it is used.  The position in the ring
-// must be the same on every path through the code (the compiler counts outstanding loads per
-// path and otherwise waits for the newest), so list lengths are uniform: all lists of a range
-// are padded with zero coefficients to the longest one, which is either one block for every
-// range (short lists: the 16 blocks of a wave go round the ring) or a multiple of four blocks
-// (a list goes round the ring whole turns).  The matrix pipe has time to spare for the padding
-// steps: with the lists on time the launch is bound by reading the data.
+// The lists are also what a wave waits for if they arrive late, so they are asked for well
+// ahead: a wave's list blocks form one stream in consumption order that runs through a ring of
+// four register sets, a block being requested while the block three places before it is used.
+// The position in that ring must be the same on every path through the code (the compiler
+// counts outstanding loads per path and otherwise waits for the newest), so the unit of work is
+// a turn of the ring: 32 steps, 32 / B for each of the wave's B blocks in turn (the accumulator of
+// a step is then fixed by its place in the turn), and a stage is a whole number of turns, the
+// same for every wave (the host's table of turns per stage).  The barriers between stages order
+// LDS traffic only, so list requests and id stores stay in flight across them.
 //
 // Maximum inner product search (appendix; one sample per table): as in shared_kernel.hip the
 // lanes hold the sampled coordinates, so ||S_l(v)||^2 costs one multiply-add per LDS read
@@ -54,22 +55,32 @@
 #include <cstring>
 #include <vector>
 
+#include "device_utils.h"
 #include "lsh_internal.h"
 
 namespace lsh {
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCWs = (int)kRangeComputeWaves;  // contracting waves
 constexpr int kLWs = 4;                        // loading waves: wave kCWs + s loads vectors 4s .. 4s + 3
 constexpr int kThreadsSR = (kCWs + kLWs) * 64;
-constexpr int kLongRing = 4;                   // ring sets for long lists (short lists: four)
-constexpr int kCs = (int)kRangeCoords;
-constexpr int kRowFloats = kCs + 4;            // row stride: 4 floats of padding spread the vectors over the banks
-constexpr int kBufBytesSR = 16 * kRowFloats * 4;
+constexpr int kRing = 4;                       // register sets of the list ring
+constexpr int kU = 8;                          // MFMA steps per list block
+constexpr int kTurnSteps = kRing * kU;         // steps of one turn of the list ring
+constexpr int kOW = kU / 2;                    // words of 16-bit offsets per sample slot and block
+constexpr int kCs = (int)kWindowCoords;        // coordinates per range
+constexpr int kSlotsSR = (int)kWindowSlots;    // ranges in the LDS ring
+constexpr int kLookSR = (int)kWindowLook;      // a stage reads its own range and this many after it
+constexpr int kRowFloats = kSlotsSR * kCs + 4; // row stride: the 4 floats of padding spread the vectors over the banks
+constexpr int kRingBytesSR = 16 * kRowFloats * 4;
+// after the ring: the offsets b~ of the workgroup's functions, [wave][block][16], then the turns of every stage
+constexpr int kLdsLimitSR = 160 * 1024;
+constexpr int kAhead = 4;                      // register sets of a loading wave: a range is requested three stages before it is written
+static_assert(kRowFloats * 4 + 16 <= 65536, "list offsets are 16 bits");
+static_assert(kSlotsSR == kLookSR + 2 && kSlotsSR % kAhead == 0, "ring geometry");
 
 // Returns v through an empty asm: values derived from it are recomputed where they are used
 // instead of being kept in registers across the contraction loops.
@@ -81,7 +92,8 @@ __device__ __forceinline__ uint32_t fresh(uint32_t v) {
 struct SharedRangedArgs {
     const float *data;  // [N][n]
     uint64_t N;
-    uint32_t n, k, g, blocks_per_table, nblocks, R;
+    uint32_t n, k, g, blocks_per_table, nblocks;
+    uint32_t nchunks, stages;  // ranges that hold data; stages per tile (a multiple of the ring slots)
     const float *off;   // [>= k]
     float w, inv_w;
     int w_is_pow2, proj;
@@ -89,120 +101,144 @@ struct SharedRangedArgs {
     const float *extra;     // [nblocks][64] row operand (a0, b~, 0, 0) of the extra step (maximum inner product)
     const float *kappa2;    // [tables] kappa~_l^2, input of the data hash
     int raw;                // maximum-inner-product modes: projections instead of ids
-    const float *coefs;     // list blocks: U steps x 64 lanes
-    const uint32_t *offs;   // per list block: 4 sample slots x (U + 1) / 2 words of two 16-bit LDS byte offsets
+    const float *coefs;     // list blocks: 8 steps x 64 lanes
+    const uint32_t *offs;   // per list block: 4 sample slots x 4 words of two 16-bit byte offsets into a row of the ring
 };
 
-// BPW: blocks of 16 functions per contracting wave; U: steps per list block; SHORT: every list is one block;
+// BPW: blocks of 16 functions per contracting wave (a turn of the list ring gives each of them 32 / BPW steps);
 // MODE: 0 ids or projections, 3 kappa~^2, 4 maximum-inner-product data hash, 5 query hash
-template <int BPW, int U, bool SHORT, int MODE>
+template <int BPW, int MODE>
 __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedRangedArgs a,
-                                                                   const uint32_t *__restrict__ range_groups,
+                                                                   const uint32_t *__restrict__ stage_turns,
                                                                    const uint2 *__restrict__ streams) {
-    static_assert(!SHORT || BPW % 4 == 0, "short lists go round the ring of four by blocks");
-    static_assert(U % 2 == 0, "a lane loads the coefficients of four or two steps at a time");
-    constexpr int NR = SHORT ? 4 : kLongRing;  // ring sets
+    static_assert(kTurnSteps % BPW == 0, "a turn deals the same number of steps to every block");
+    constexpr int Q = kTurnSteps / BPW;  // consecutive steps of one block within a turn
     constexpr bool KAPPA = MODE == 3, MDATA = MODE == 4, MQUERY = MODE == 5, NORMS = MODE >= 3;
-    extern __shared__ __align__(16) char lds_sr[];  // 2 buffers x [16 vectors][1028 floats]
+    extern __shared__ __align__(16) char lds_sr[];  // [16 vectors][8 ranges x 256 + 4 floats], offsets, turns
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
-    const uint32_t n = a.n, R = a.R;
+    const uint32_t n = a.n, S = a.stages;
+    float *lds_off = reinterpret_cast<float *>(lds_sr + kRingBytesSR) + wave * (BPW * 16);  // this wave's [BPW][16]
+    uint32_t *lds_turns = reinterpret_cast<uint32_t *>(lds_sr + kRingBytesSR + kCWs * BPW * 64);
     const uint64_t ntiles = (a.N + 15) / 16;
     const uint64_t first_tile = blockIdx.x;  // the host launches at most ntiles workgroups along x
+    const uint64_t my_tiles = (ntiles - first_tile + gridDim.x - 1) / gridDim.x;
+    // Barriers, counted from the first: barrier b ends stage b - 1 (barrier 0 opens stage 0).  The
+    // loading waves write item x (range x % S of the workgroup's tile x / S) after barrier x - 7,
+    // when the range that lived in its slot has had its last stage, and before barrier x - 6,
+    // which opens the first stage that may read it.
 
     if (wave >= (uint32_t)kCWs) {
-        // ---- loading waves: four vectors each, a vector's range as four pieces of 256 coordinates
-        // (a wave instruction moves 1 KB of one vector), all sixteen pieces in flight at once
+        // ---- loading waves: four vectors each, one 1 KB instruction per vector and range; a
+        // range is requested three stages before it is written to LDS
         const uint32_t v0 = (wave - kCWs) * 4;
-        uint64_t t_next = first_tile;
-        uint32_t r_next = 0, b = 1;
-        for (;;) {
-            const bool more = t_next < ntiles;
-            if (more) {
-                const uint32_t c0 = r_next * kCs;
-                char *dst = lds_sr + (b ^ 1) * kBufBytesSR + lane * 16;
-                floatx4 pre[4][4];
+        const uint64_t total = my_tiles * S;  // a multiple of 8
+        uint64_t f_tile = first_tile, s_tile = first_tile;
+        uint32_t f_r = 0, s_r = 0;
+        auto fetch = [&](floatx4 (&pre)[4]) __attribute__((always_inline)) {
+            // items past the data (ranges beyond n, tiles beyond the last) load the first tile's
+            // first range: the number of requests in flight is the same on every path
+            const bool real = f_tile < ntiles && f_r < a.nchunks;
+            const uint64_t tile = real ? f_tile : first_tile;
+            const uint32_t c = (real ? f_r : 0u) * kCs + lane * 4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                uint64_t row = tile * 16 + v0 + v;
+                row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
+                // coordinates beyond n read the row's first ones; zeros are stored for them
+                pre[v] = *reinterpret_cast<const floatx4 *>(a.data + row * n + (c < n ? c : 0u));
+            }
+            if (++f_r == S) {
+                f_r = 0;
+                f_tile += gridDim.x;
+            }
+        };
+        auto stash = [&](const floatx4 (&pre)[4]) __attribute__((always_inline)) {
+            if (s_tile < ntiles && s_r < a.nchunks) {
+                const bool inside = s_r * kCs + lane * 4 < n;
+                char *dst = lds_sr + ((s_r % kSlotsSR) * kCs + lane * 4) * 4;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    uint64_t row = t_next * 16 + v0 + v;
-                    row = row < a.N ? row : a.N - 1;  // rows beyond the data repeat the last vector (never stored)
-                    const float *src = a.data + row * n;
-#pragma unroll
-                    for (int piece = 0; piece < 4; ++piece) {
-                        const uint32_t c = c0 + piece * 256 + lane * 4;
-                        // coordinates beyond n read the row's first ones; zeros are stored for them
-                        pre[v][piece] = *reinterpret_cast<const floatx4 *>(src + (c < n ? c : 0u));
-                    }
+                    const floatx4 x = pre[v];
+                    const floatx4 z = {inside ? x[0] : 0.f, inside ? x[1] : 0.f, inside ? x[2] : 0.f, inside ? x[3] : 0.f};
+                    *reinterpret_cast<floatx4 *>(dst + (v0 + v) * kRowFloats * 4) = z;
                 }
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-#pragma unroll
-                    for (int piece = 0; piece < 4; ++piece) {
-                        const bool inside = c0 + piece * 256 + lane * 4 < n;
-                        const floatx4 x = pre[v][piece];
-                        const floatx4 z = {inside ? x[0] : 0.f, inside ? x[1] : 0.f, inside ? x[2] : 0.f, inside ? x[3] : 0.f};
-                        *reinterpret_cast<floatx4 *>(dst + (v0 + v) * kRowFloats * 4 + piece * 1024) = z;
-                    }
             }
-            __syncthreads();
-            if (!more) break;
-            b ^= 1;
-            if (++r_next == R) {
-                r_next = 0;
-                t_next += gridDim.x;
+            if (++s_r == S) {
+                s_r = 0;
+                s_tile += gridDim.x;
+            }
+        };
+        floatx4 pre[kAhead][4];
+#pragma unroll
+        for (int d = 0; d < kAhead - 1; ++d) fetch(pre[d]);
+        for (uint64_t x = 0; x < total; x += kAhead) {
+#pragma unroll
+            for (int d = 0; d < kAhead; ++d) {
+                if (x + d > (uint64_t)kLookSR) lds_barrier();  // barrier x + d - 7
+                fetch(pre[(d + kAhead - 1) % kAhead]);
+                stash(pre[d]);
             }
         }
+        // barriers total - 7 .. total of the contracting waves
+#pragma unroll
+        for (int i = 0; i < kLookSR + 2; ++i) lds_barrier();
         return;
     }
 
     // ---- contracting waves
     const uint32_t stream_id = blockIdx.y * kCWs + wave;
-    const uint2 si = streams[stream_id];  // {first list block, list blocks}
-    constexpr int OW = (U + 1) / 2;  // words of offsets per sample slot and block
+    const uint2 si = streams[stream_id];  // {first list block, list blocks per tile}
     // uniform block pointers plus a per-lane index: the loads take a scalar base and a 32-bit lane offset
-    const float *cbase = a.coefs + (size_t)si.x * (U * 64);
-    const uint32_t *obase = a.offs + (size_t)si.x * (4 * OW);
-    const uint32_t oslot = (lane >> 4) * OW;
-    const uint32_t sblocks = si.y;  // at least the ring
-    // Block i of the stream lives in ring set i % NR; when block i is about to be used, block
-    // i + NR - 1 is requested into the set used just before.
-    float ring_c[NR][U];
-    uint32_t ring_o[NR][OW];
+    const float *cbase = a.coefs + (size_t)si.x * (kU * 64);
+    const uint32_t *obase = a.offs + (size_t)si.x * (4 * kOW);
+    const uint32_t oslot = (lane >> 4) * kOW;
+    const uint32_t sblocks = si.y;  // a multiple of the ring, at least one turn
+    // Block i of the stream lives in ring set i % 4; when block i is about to be used, block
+    // i + 3 is requested into the set used just before.
+    float ring_c[kRing][kU];
+    uint32_t ring_o[kRing][kOW];
     uint32_t next_block = 0;
     auto load_block = [&](int set) __attribute__((always_inline)) {
-        const float *cs = cbase + (size_t)next_block * (U * 64);
-        const uint32_t *os = obase + (size_t)next_block * (4 * OW);
-        // coefficients of four steps per load, [steps / 4][lane][4], then of the last two, [lane][2]
+        const float *cs = cbase + (size_t)next_block * (kU * 64);
+        const uint32_t *os = obase + (size_t)next_block * (4 * kOW);
+        // coefficients of four steps per load: [steps / 4][lane][4]
 #pragma unroll
-        for (int i = 0; i < U / 4; ++i) {
+        for (int i = 0; i < kU / 4; ++i) {
             const floatx4 c4 = *reinterpret_cast<const floatx4 *>(cs + i * 256 + lane * 4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) ring_c[set][4 * i + e] = c4[e];
         }
-        if constexpr (U % 4 == 2) {
-            const floatx2 c2 = *reinterpret_cast<const floatx2 *>(cs + (U / 4) * 256 + lane * 2);
-            ring_c[set][U - 2] = c2[0];
-            ring_c[set][U - 1] = c2[1];
-        }
 #pragma unroll
-        for (int i = 0; i < OW; ++i) ring_o[set][i] = os[oslot + i];
+        for (int i = 0; i < kOW; ++i) ring_o[set][i] = os[oslot + i];
         next_block = next_block + 1 == sblocks ? 0 : next_block + 1;
         __builtin_amdgcn_sched_barrier(0);  // the request stays here, three blocks ahead of its use
     };
 #pragma unroll
-    for (int i = 0; i < NR - 1; ++i) load_block(i);
-    const uint32_t row_off = (lane & 15) * kRowFloats * 4;  // this lane's vector in the tile
-    // the four floats after a row's 1024 coordinates stay zero: what padding steps read
-    if (wave == 0) {
-        const uint32_t buffer = lane >> 5, row = (lane >> 1) & 15, half = lane & 1;
-        *reinterpret_cast<uint2 *>(lds_sr + buffer * kBufBytesSR + row * kRowFloats * 4 + kCs * 4 + half * 8) = make_uint2(0u, 0u);
+    for (int i = 0; i < kRing - 1; ++i) load_block(i);
+    const char *row = lds_sr + (lane & 15) * kRowFloats * 4;  // this lane's vector in the ring
+    // the four floats after a row's coordinates stay zero: what padding steps read
+    if (wave == 0 && lane < 16) *reinterpret_cast<floatx4 *>(lds_sr + (lane * kRowFloats + kSlotsSR * kCs) * 4) = floatx4{0.f, 0.f, 0.f, 0.f};
+    // The offsets b~ of the wave's functions and the table of turns are read from LDS where they
+    // are needed: a vector memory load there would make the wave wait for everything it has in
+    // flight, the id stores of the block before included.
+    if (wave == 1)
+        for (uint32_t i = lane; i < S; i += 64) lds_turns[i] = stage_turns[i];
+    if constexpr (!NORMS) {
+#pragma unroll
+        for (int f = 0; f < BPW; ++f) {
+            const uint32_t blk = (blockIdx.y * BPW + f) * kCWs + wave;
+            const uint32_t in_table = (blk % a.blocks_per_table) * 16 + lane;
+            if (lane < 16)
+                lds_off[f * 16 + lane] = blk < a.nblocks && in_table < a.g ? a.off[(blk / a.blocks_per_table) * a.g + in_table] : 0.f;
+        }
     }
     [[maybe_unused]] float kmax[KAPPA ? BPW : 1];  // kappa~^2 pass: largest ||S(v)||^2 seen per block
 #pragma unroll
     for (int f = 0; f < (KAPPA ? BPW : 1); ++f) kmax[f] = 0.f;
 
-    __syncthreads();  // first buffer written
-    uint32_t b = 0;
+    lds_barrier();  // barrier 0: the ranges 0 .. 6 of the first tile are written
+    uint32_t turns_next = lds_turns[0];
     for (uint64_t t = first_tile; t < ntiles; t += gridDim.x) {
         floatx4 acc[BPW];
         [[maybe_unused]] float nrm[NORMS ? BPW : 1];  // this lane's share of ||S(v)||^2 per block
@@ -210,48 +246,34 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
         for (int f = 0; f < BPW; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int f = 0; f < (NORMS ? BPW : 1); ++f) nrm[f] = 0.f;
-        for (uint32_t r = 0; r < R; ++r) {
-            const char *buf = lds_sr + b * kBufBytesSR + row_off;
-            // one block: all reads, then the MFMAs
-            auto run = [&](int set, floatx4 &c, [[maybe_unused]] float &n2) __attribute__((always_inline)) {
-                float x[U];
-                // the offsets are taken apart here, not where they were requested (which would wait for them there)
+        for (uint32_t s = 0; s < S; ++s) {
+            uint32_t turns = __builtin_amdgcn_readfirstlane(turns_next);
+            turns_next = lds_turns[s + 1 == S ? 0 : s + 1];  // arrives behind the stage's own LDS reads
+            for (; turns; --turns) {
 #pragma unroll
-                for (int i = 0; i < OW; ++i) asm volatile("" : "+v"(ring_o[set][i]));
+                for (int q = 0; q < kRing; ++q) {
+                    load_block((q + kRing - 1) % kRing);
+                    // one block: all reads, then the MFMAs; step 8 q + e of the turn belongs to block (8 q + e) / Q
+                    float x[kU];
+                    // the offsets are taken apart here, not where they were requested (which would wait for them there)
 #pragma unroll
-                for (int s = 0; s < U; ++s) {
-                    const uint32_t off = (ring_o[set][s >> 1] >> (16 * (s & 1))) & 0xFFFFu;
-                    x[s] = *reinterpret_cast<const float *>(buf + off);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // all reads of the block go out before its first MFMA
+                    for (int i = 0; i < kOW; ++i) asm volatile("" : "+v"(ring_o[q][i]));
 #pragma unroll
-                for (int s = 0; s < U; ++s) {
-                    if constexpr (!KAPPA) c = __builtin_amdgcn_mfma_f32_16x16x4f32(ring_c[set][s], x[s], c, 0, 0, 0);
-                    if constexpr (NORMS) n2 = fmaf(x[s], x[s], n2);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            };
-            if constexpr (SHORT) {
+                    for (int e = 0; e < kU; ++e) {
+                        const uint32_t off = (ring_o[q][e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                        x[e] = *reinterpret_cast<const float *>(row + off);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // all reads of the block go out before its first MFMA
 #pragma unroll
-                for (int f = 0; f < BPW; ++f) {
-                    load_block((f + 3) & 3);
-                    run(f & 3, acc[f], nrm[NORMS ? f : 0]);
-                }
-            } else {
-                const uint32_t groups = range_groups[r];  // turns of the ring per list in this range, at least one
-#pragma unroll
-                for (int f = 0; f < BPW; ++f) {
-                    uint32_t left = groups;
-                    do {
-#pragma unroll
-                        for (int q = 0; q < NR; ++q) {
-                            load_block((q + NR - 1) % NR);
-                            run(q, acc[f], nrm[NORMS ? f : 0]);
-                        }
-                    } while (--left);
+                    for (int e = 0; e < kU; ++e) {
+                        const int f = (kU * q + e) / Q;
+                        if constexpr (!KAPPA) acc[f] = __builtin_amdgcn_mfma_f32_16x16x4f32(ring_c[q][e], x[e], acc[f], 0, 0, 0);
+                        if constexpr (NORMS) nrm[f] = fmaf(x[e], x[e], nrm[f]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (r + 1 == R) {
+            if (s + 1 == S) {
                 // register e of a block's accumulator: function 4 (l / 16) + e of the block, vector l % 16
                 const uint32_t ln = fresh(lane);
                 const uint64_t vec = t * 16 + (ln & 15);
@@ -299,7 +321,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                             for (int e = 0; e < 4; ++e)  // b~ is in the accumulator already
                                 v[e] = (uint32_t)(int)floorf(a.w_is_pow2 ? acc[f][e] * a.inv_w : acc[f][e] / a.w);
                         } else {
-                            const floatx4 bq = *reinterpret_cast<const floatx4 *>(a.off + j);
+                            const floatx4 bq = *reinterpret_cast<const floatx4 *>(lds_off + f * 16 + 4 * (ln >> 4));
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const float h = a.w_is_pow2 ? fmaf(acc[f][e], a.inv_w, bq[e] * a.inv_w) : (acc[f][e] + bq[e]) / a.w;
@@ -310,8 +332,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                     }
                 }
             }
-            __syncthreads();  // the other buffer is complete, everyone is done with this one
-            b ^= 1;
+            lds_barrier();  // ends stage s: the next range is written, everyone is done with the oldest one
         }
     }
     if constexpr (KAPPA) {
@@ -349,18 +370,25 @@ SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t
     uint32_t inst = 4;
     while (inst < pl.bpw) inst *= 2;
     pl.bpw = inst;
-    pl.R = (n + kRangeCoords - 1) / kRangeCoords;
+    pl.nchunks = (n + kWindowCoords - 1) / kWindowCoords;
+    pl.stages = (pl.nchunks + kWindowSlots - 1) / kWindowSlots * kWindowSlots;
+    if (kRingBytesSR + kCWs * pl.bpw * 64 + (size_t)pl.stages * 4 > (size_t)kLdsLimitSR) return pl;  // the table of turns no longer fits LDS
     pl.supported = true;
     return pl;
 }
 
-// Host tables: per contracting wave one stream of list blocks in consumption order (range after
-// range, within a range the wave's blocks one after the other); per step and lane the
-// coefficient of (row l % 16, sample l / 16) and the LDS byte offset of that sample's coordinate
-// inside the range.  Chooses the list layout (steps per block, short or long lists) and notes
-// it in the plan; range_groups holds, per range, the turns of the ring a list takes (long lists).
+// Host tables.  First the schedule: every table's samples are dealt to the stages of a tile, a
+// sample of range r to one of the stages r - 6 .. r (what the ring holds), every table getting
+// the same number of MFMA steps in a stage, a multiple of the 32 / bpw steps a turn of the list
+// ring gives a block.  Stage after stage the length is the smallest that takes the samples whose
+// last stage this is, for the table that has most of them; a table fills the rest of its steps
+// with the samples that are due soonest, so later stages find less left to do.  Then the lists:
+// per contracting wave one stream of list blocks in consumption order (stage after stage, turn
+// after turn, within a turn the wave's blocks one after the other); per step and lane the
+// coefficient of (row l % 16, sample l / 16) and the byte offset of that sample's coordinate in a
+// row of the ring.  stage_turns holds the turns of the list ring per stage.
 void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::vector<float> &coefs,
-                                std::vector<uint32_t> &offs, std::vector<uint32_t> &range_groups,
+                                std::vector<uint32_t> &offs, std::vector<uint32_t> &stage_turns,
                                 std::vector<uint32_t> &stream_info, std::vector<float> *extra) {
     if (extra) {  // row operand of the extra step: sample slot 0 holds a0_j, slot 1 the offset b~_j
         extra->assign((size_t)pl.nblocks * 64, 0.f);
@@ -372,108 +400,103 @@ void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::
             }
         }
     }
-    const uint32_t R = pl.R, CW = kRangeComputeWaves, bpw = pl.bpw, m = p->m;
+    const uint32_t S = pl.stages, CW = kRangeComputeWaves, bpw = pl.bpw, m = p->m;
+    const uint32_t Q = kTurnSteps / bpw;  // steps of a block per turn
     const uint32_t tables = pl.nblocks / pl.blocks_per_table, streams = pl.kblocks * CW;
-    // per table and range: the samples dealt to steps of four, coordinates of a step distinct
-    // modulo 4 where the classes allow it; 0xFFFFFFFF marks a padding slot
     constexpr uint32_t kPad = 0xFFFFFFFFu;
-    std::vector<std::vector<uint32_t>> slots((size_t)tables * R);
-    std::vector<uint32_t> longest(R, 0);  // steps of the longest list of a range
+    // samples of every table by range, then stage after stage
+    std::vector<std::vector<uint32_t>> by_range((size_t)tables * S);
     for (uint32_t table = 0; table < tables; ++table) {
-        const uint32_t *S = &p->idx[(size_t)table * pl.g * m];
-        std::vector<std::vector<uint32_t>> cls((size_t)R * 4);
-        for (uint32_t smp = m; smp-- > 0;) cls[(size_t)(S[smp] / kRangeCoords) * 4 + (S[smp] & 3)].push_back(smp);
-        for (uint32_t r = 0; r < R; ++r) {
-            std::vector<uint32_t> *c = &cls[(size_t)r * 4];
-            size_t left = c[0].size() + c[1].size() + c[2].size() + c[3].size();
-            std::vector<uint32_t> &out = slots[(size_t)table * R + r];
+        const uint32_t *smp_coord = &p->idx[(size_t)table * pl.g * m];
+        for (uint32_t smp = m; smp-- > 0;) by_range[(size_t)table * S + smp_coord[smp] / kWindowCoords].push_back(smp);
+    }
+    // slots[table * S + s]: the stage's samples dealt to steps of four, 0xFFFFFFFF marks a padding slot
+    std::vector<std::vector<uint32_t>> slots((size_t)tables * S);
+    stage_turns.assign(S, 0);
+    for (uint32_t s = 0; s < S; ++s) {
+        size_t due = 0;
+        for (uint32_t table = 0; table < tables; ++table) due = std::max(due, by_range[(size_t)table * S + s].size());
+        const uint32_t turns = (uint32_t)((due + 4 * Q - 1) / (4 * Q));
+        stage_turns[s] = turns;
+        const uint32_t steps = turns * Q;
+        for (uint32_t table = 0; table < tables; ++table) {
+            const uint32_t *smp_coord = &p->idx[(size_t)table * pl.g * m];
+            // the stage's samples: those due now, then the soonest due, by coordinate class modulo 4
+            std::vector<uint32_t> cls[4];
+            uint32_t room = 4 * steps;
+            for (uint32_t r = s; r < S && r <= s + kWindowLook && room; ++r) {
+                std::vector<uint32_t> &have = by_range[(size_t)table * S + r];
+                while (!have.empty() && room) {
+                    cls[smp_coord[have.back()] & 3].push_back(have.back());
+                    have.pop_back();
+                    --room;
+                }
+            }
+            // steps of four samples whose coordinates differ modulo 4 where the classes allow it
+            std::vector<uint32_t> &out = slots[(size_t)table * S + s];
+            size_t left = cls[0].size() + cls[1].size() + cls[2].size() + cls[3].size();
             while (left) {
                 bool taken[4] = {false, false, false, false};
                 for (uint32_t kq = 0; kq < 4; ++kq) {
                     int best = -1;
                     for (int pass = 0; pass < 2 && best < 0; ++pass)
                         for (int q = 0; q < 4; ++q)
-                            if (!c[q].empty() && (pass == 1 || !taken[q]) && (best < 0 || c[q].size() > c[best].size()))
+                            if (!cls[q].empty() && (pass == 1 || !taken[q]) && (best < 0 || cls[q].size() > cls[best].size()))
                                 best = q;
                     if (best < 0) {
                         out.push_back(kPad);
                     } else {
-                        out.push_back(c[best].back());
-                        c[best].pop_back();
+                        out.push_back(cls[best].back());
+                        cls[best].pop_back();
                         taken[best] = true;
                         --left;
                     }
                 }
             }
-            longest[r] = std::max(longest[r], (uint32_t)out.size() / 4);
+            out.resize((size_t)4 * steps, kPad);
         }
     }
-    // layout: short lists (one block of 4, 6 or 8 steps per list) if every list fits, else whole
-    // turns of the long-list ring (4 blocks of 4, 6 or 8 steps), whichever pads least
-    const uint32_t top = *std::max_element(longest.begin(), longest.end());
-    range_groups.assign(R, 1);
-    if (top <= 8) {
-        pl.short_lists = true;
-        pl.block_steps = top <= 4 ? 4 : top <= 6 ? 6 : 8;
-    } else {
-        pl.short_lists = false;
-        uint64_t best = ~0ull;
-        for (uint32_t u = 4; u <= 8; u += 2) {
-            uint64_t cost = 0;
-            for (uint32_t r = 0; r < R; ++r) cost += std::max(1u, (longest[r] + kLongRing * u - 1) / (kLongRing * u)) * kLongRing * u;
-            if (cost <= best) {  // ties: the larger block (requests reach further ahead)
-                best = cost;
-                pl.block_steps = u;
-            }
-        }
-        for (uint32_t r = 0; r < R; ++r)
-            range_groups[r] = std::max(1u, (longest[r] + kLongRing * pl.block_steps - 1) / (kLongRing * pl.block_steps));
-    }
-    const uint32_t U = pl.block_steps, OW = (U + 1) / 2;
-    std::vector<uint32_t> list_blocks(R);
-    uint32_t per_stream = 0;
-    for (uint32_t r = 0; r < R; ++r) {
-        list_blocks[r] = pl.short_lists ? 1 : kLongRing * range_groups[r];
-        per_stream += list_blocks[r] * bpw;
+    uint32_t per_stream = 0;  // list blocks of a stream per tile
+    std::vector<uint32_t> stage_first(S);
+    for (uint32_t s = 0; s < S; ++s) {
+        stage_first[s] = per_stream;
+        per_stream += stage_turns[s] * kRing;
     }
     stream_info.assign((size_t)streams * 2, 0);
-    coefs.assign((size_t)streams * per_stream * U * 64, 0.f);
+    coefs.assign((size_t)streams * per_stream * kU * 64, 0.f);
     // steps and slots that only pad (coefficient zero) read one of the four zero floats that follow a
-    // row's 1024 coordinates: four different banks per vector, like a step of real samples, and
+    // row's coordinates: four different banks per vector, like a step of real samples, and
     // nothing for the squared norms of the maximum-inner-product modes
-    offs.assign((size_t)streams * per_stream * 4 * OW, 0u);
-    for (size_t rec = 0; rec < offs.size() / OW; ++rec)
-        for (uint32_t s = 0; s < U; ++s)
-            offs[rec * OW + s / 2] |= ((kRangeCoords + (uint32_t)(rec & 3)) * 4u) << (16 * (s & 1));
+    offs.assign((size_t)streams * per_stream * 4 * kOW, 0u);
+    for (size_t rec = 0; rec < offs.size() / kOW; ++rec)
+        for (uint32_t e = 0; e < (uint32_t)kU; ++e)
+            offs[rec * kOW + e / 2] |= ((kWindowSlots * kWindowCoords + (uint32_t)(rec & 3)) * 4u) << (16 * (e & 1));
     for (uint32_t y = 0; y < pl.kblocks; ++y)
         for (uint32_t cw = 0; cw < CW; ++cw) {
             const uint32_t stream = y * CW + cw;
-            uint32_t blocks = stream * per_stream;
-            stream_info[(size_t)stream * 2] = blocks;
+            stream_info[(size_t)stream * 2] = stream * per_stream;
             stream_info[(size_t)stream * 2 + 1] = per_stream;
-            for (uint32_t r = 0; r < R; ++r)
-                for (uint32_t f = 0; f < bpw; ++f, blocks += list_blocks[r]) {
-                    const uint32_t blk = (y * bpw + f) * CW + cw;
-                    if (blk >= pl.nblocks) continue;  // a list of zeros
-                    const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
-                    const std::vector<uint32_t> &sl = slots[(size_t)table * R + r];
-                    const uint32_t steps = (uint32_t)sl.size() / 4;
-                    for (uint32_t s = 0; s < steps; ++s)
+            for (uint32_t s = 0; s < S; ++s)
+                for (uint32_t turn = 0; turn < stage_turns[s]; ++turn)
+                    for (uint32_t i = 0; i < (uint32_t)kTurnSteps; ++i) {
+                        const uint32_t f = i / Q, blk = (y * bpw + f) * CW + cw;
+                        if (blk >= pl.nblocks) continue;  // a list of zeros
+                        const uint32_t table = blk / pl.blocks_per_table, first = (blk % pl.blocks_per_table) * 16;
+                        const uint32_t step = turn * Q + i % Q;  // of this block's table in the stage
+                        const size_t block = (size_t)stream * per_stream + stage_first[s] + turn * kRing + i / kU;
+                        const uint32_t in_block = i % kU;
                         for (uint32_t kq = 0; kq < 4; ++kq) {
-                            const uint32_t smp = sl[(size_t)s * 4 + kq];
+                            const uint32_t smp = slots[(size_t)table * S + s][(size_t)step * 4 + kq];
                             if (smp == kPad) continue;
-                            const size_t block = (size_t)blocks + s / U;
-                            const uint32_t in_block = s % U;
-                            const uint32_t coord = p->idx[(size_t)table * pl.g * m + smp] - r * kRangeCoords;
-                            uint32_t &word = offs[(block * 4 + kq) * OW + in_block / 2];
-                            word = (word & ~(0xFFFFu << (16 * (in_block & 1)))) | (coord * 4) << (16 * (in_block & 1));
-                            // steps in fours [lane][4]; the last two of a block of six [lane][2]
-                            const uint32_t four = in_block / 4 * 4, width = U - four >= 4 ? 4 : 2;
-                            for (uint32_t i = 0; i < 16 && first + i < pl.g; ++i)  // rows beyond the table keep zero
-                                coefs[(block * U + four) * 64 + (kq * 16 + i) * width + in_block % 4] =
-                                    p->coef[(size_t)(table * pl.g + first + i) * m + smp];
+                            const uint32_t in_row = p->idx[(size_t)table * pl.g * m + smp] % (kWindowSlots * kWindowCoords);
+                            uint32_t &word = offs[(block * 4 + kq) * kOW + in_block / 2];
+                            word = (word & ~(0xFFFFu << (16 * (in_block & 1)))) | (in_row * 4) << (16 * (in_block & 1));
+                            // a lane's four consecutive steps side by side: [steps / 4][lane][4]
+                            for (uint32_t r16 = 0; r16 < 16 && first + r16 < pl.g; ++r16)  // rows beyond the table keep zero
+                                coefs[(block * kU + in_block / 4 * 4) * 64 + (kq * 16 + r16) * 4 + in_block % 4] =
+                                    p->coef[(size_t)(table * pl.g + first + r16) * m + smp];
                         }
-                }
+                    }
         }
 }
 
@@ -483,6 +506,7 @@ int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uin
                          const float *d_kappa2, int raw) {
     const SharedRangedPlan &pl = p->shared_ranged_plan;
     if (!pl.supported || !p->d_sr_lists || !p->d_sr_offs) return LSH_ERR_UNSUPPORTED;
+    if (!N) return LSH_OK;
     SharedRangedArgs a;
     a.data = d_data;
     a.N = N;
@@ -491,7 +515,8 @@ int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uin
     a.g = pl.g;
     a.blocks_per_table = pl.blocks_per_table;
     a.nblocks = pl.nblocks;
-    a.R = pl.R;
+    a.nchunks = pl.nchunks;
+    a.stages = pl.stages;
     a.off = p->d_off;
     a.w = p->w;
     a.inv_w = 1.0f / p->w;
@@ -505,47 +530,35 @@ int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uin
     a.out = d_out;
     a.coefs = static_cast<const float *>(p->d_sr_lists);
     a.offs = static_cast<const uint32_t *>(p->d_sr_offs);
-    const uint32_t *groups = static_cast<const uint32_t *>(p->d_sr_list_len);
+    const uint32_t *turns = static_cast<const uint32_t *>(p->d_sr_list_len);
     const uint2 *streams = static_cast<const uint2 *>(p->d_sr_stream);
     const uint64_t ntiles = (N + 15) / 16;
-    // one workgroup per CU (two 64 KB buffers); the kblocks workgroups of a tile run on one XCD
+    // one workgroup per CU (the ring takes 128 KB of LDS); the kblocks workgroups of a tile run on one XCD
     uint64_t gx = (uint64_t)p->num_cus / pl.kblocks;
     gx = gx < 8 ? 8 : gx / 8 * 8;
     if (gx > ntiles) gx = ntiles;
     const dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-#define LSH_SR_LAUNCH(B_, U_, S_, M_) \
+    const uint32_t lds_bytes = kRingBytesSR + kCWs * pl.bpw * 64 + pl.stages * 4;
+#define LSH_SR_LAUNCH(B_, M_) \
     { \
-        auto fn = &shared_ranged_kernel<B_, U_, S_, M_>; \
-        if (ensure_lds_limit(reinterpret_cast<const void *>(fn), 2 * kBufBytesSR) != LSH_OK) return LSH_ERR_HIP; \
-        hipLaunchKernelGGL(fn, grid, dim3(kThreadsSR), 2 * kBufBytesSR, s, a, groups, streams); \
+        auto fn = &shared_ranged_kernel<B_, M_>; \
+        if (ensure_lds_limit(reinterpret_cast<const void *>(fn), lds_bytes) != LSH_OK) return LSH_ERR_HIP; \
+        hipLaunchKernelGGL(fn, grid, dim3(kThreadsSR), lds_bytes, s, a, turns, streams); \
     }
-#define LSH_SR_MODES(B_, U_, S_) \
-    { \
-        if (mode <= 1) LSH_SR_LAUNCH(B_, U_, S_, 0) \
-        else if (mode == 3) LSH_SR_LAUNCH(B_, U_, S_, 3) \
-        else if (mode == 4) LSH_SR_LAUNCH(B_, U_, S_, 4) \
-        else if (mode == 5) LSH_SR_LAUNCH(B_, U_, S_, 5) \
-        else return LSH_ERR_INVALID_ARG; \
-    }
-#define LSH_SR_STEPS(B_, U_) \
-    case U_: \
-        if (pl.short_lists) LSH_SR_MODES(B_, U_, true) else LSH_SR_MODES(B_, U_, false) \
-        break;
 #define LSH_SR_CASE(B_) \
     case B_: \
-        switch (pl.block_steps) { \
-            LSH_SR_STEPS(B_, 4) LSH_SR_STEPS(B_, 6) LSH_SR_STEPS(B_, 8) \
-            default: return LSH_ERR_UNSUPPORTED; \
-        } \
+        if (mode <= 1) LSH_SR_LAUNCH(B_, 0) \
+        else if (mode == 3) LSH_SR_LAUNCH(B_, 3) \
+        else if (mode == 4) LSH_SR_LAUNCH(B_, 4) \
+        else if (mode == 5) LSH_SR_LAUNCH(B_, 5) \
+        else return LSH_ERR_INVALID_ARG; \
         break;
     switch (pl.bpw) {
         LSH_SR_CASE(4) LSH_SR_CASE(8) LSH_SR_CASE(16)
         default: return LSH_ERR_UNSUPPORTED;
     }
 #undef LSH_SR_CASE
-#undef LSH_SR_STEPS
-#undef LSH_SR_MODES
 #undef LSH_SR_LAUNCH
     return hipGetLastError() == hipSuccess ? LSH_OK : LSH_ERR_HIP;
 }

@@ -225,11 +225,14 @@ def test_windowed_gather_schedule_needs_little_padding(n, k, m, entries, lds):
     (9004, 2048, 700, 4.0, 40, False, 0),    # 36 ranges in 40 stages
     (3000, 1000, 33, 1.0, 41, True, 0),      # two functions per lane, k not a multiple of 64
     (16384, 4096, 512, 1.0, 5, False, 0),    # two workgroups along the functions
-    (4096, 2048, 64, 8.0, 4, False, 128),    # one sample per table: short lists, blocks of eight steps
-    (4096, 2048, 256, 8.0, 4, False, 128),   # long lists, blocks of six steps
-    (4096, 1024, 1024, 8.0, 4, False, 32),   # tables of 32 functions (two blocks), blocks of four steps
-    (4100, 96, 40, 2.0, 58, True, 8),        # tables of 12, idle blocks, a short last range
+    (4096, 2048, 64, 8.0, 4, False, 128),    # one sample per table: 16 stages, some of them without a turn of the list ring
+    (4096, 2048, 256, 8.0, 4, False, 128),   # several turns per stage
+    (4096, 1024, 1024, 8.0, 4, False, 32),   # tables of 32 functions (two blocks), eight blocks per wave
+    (4100, 96, 40, 2.0, 58, True, 8),        # tables of 12, idle blocks, a seventeenth range of four coordinates in 24 stages
     (8192, 2048, 4, 8.0, 63, False, 128),    # nearly empty lists
+    (1264, 64, 65, 2.0, 55, False, 4),       # five ranges in eight stages, four blocks per wave (turns of eight steps per block)
+    (16384, 128, 512, 1.0, 61, False, 4),    # 64 stages
+    (2048, 1024, 30, 4.0, 59, False, 64),    # one ring of ranges holds the whole vector
 ])
 def test_list_tables_walked_on_the_host(n, k, m, w, seed, repl, L):
     """The list tables of the kernels that work by coordinate ranges, built as for the device and
