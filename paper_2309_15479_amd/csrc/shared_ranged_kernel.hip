@@ -76,7 +76,8 @@ constexpr int kSlotsSR = (int)kWindowSlots;    // ranges in the LDS ring
 constexpr int kLookSR = (int)kWindowLook;      // a stage reads its own range and this many after it
 constexpr int kRowFloats = kSlotsSR * kCs + 4; // row stride: the 4 floats of padding spread the vectors over the banks
 constexpr int kRingBytesSR = 16 * kRowFloats * 4;
-// after the ring: the offsets b~ of the workgroup's functions, [wave][block][16], then the turns of every stage
+// after the ring: the offsets b~ of the workgroup's functions (maximum inner product: the row operand of the
+// extra step, a0 and b~), [wave][block][32], then the turns of every stage
 constexpr int kLdsLimitSR = 160 * 1024;
 constexpr int kAhead = 4;                      // register sets of a loading wave: a range is requested three stages before it is written
 static_assert(kRowFloats * 4 + 16 <= 65536, "list offsets are 16 bits");
@@ -118,8 +119,8 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t n = a.n, S = a.stages;
-    float *lds_off = reinterpret_cast<float *>(lds_sr + kRingBytesSR) + wave * (BPW * 16);  // this wave's [BPW][16]
-    uint32_t *lds_turns = reinterpret_cast<uint32_t *>(lds_sr + kRingBytesSR + kCWs * BPW * 64);
+    float *lds_off = reinterpret_cast<float *>(lds_sr + kRingBytesSR) + wave * (BPW * 32);  // this wave's [BPW][32]
+    uint32_t *lds_turns = reinterpret_cast<uint32_t *>(lds_sr + kRingBytesSR + kCWs * BPW * 128);
     const uint64_t ntiles = (a.N + 15) / 16;
     const uint64_t first_tile = blockIdx.x;  // the host launches at most ntiles workgroups along x
     const uint64_t my_tiles = (ntiles - first_tile + gridDim.x - 1) / gridDim.x;
@@ -224,13 +225,27 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
     // flight, the id stores of the block before included.
     if (wave == 1)
         for (uint32_t i = lane; i < S; i += 64) lds_turns[i] = stage_turns[i];
-    if constexpr (!NORMS) {
+    {
+        // lanes 0 .. 15: the offsets of the 16 functions of every block; maximum inner product: lanes
+        // 0 .. 31, the first two sample slots of the extra step's row operand (a0_j, then b~_j)
+        float own[BPW];
 #pragma unroll
         for (int f = 0; f < BPW; ++f) {
             const uint32_t blk = (blockIdx.y * BPW + f) * kCWs + wave;
-            const uint32_t in_table = (blk % a.blocks_per_table) * 16 + lane;
-            if (lane < 16)
-                lds_off[f * 16 + lane] = blk < a.nblocks && in_table < a.g ? a.off[(blk / a.blocks_per_table) * a.g + in_table] : 0.f;
+            if constexpr (NORMS) {
+                const bool live = blk < a.nblocks && lane < 32;
+                own[f] = a.extra[live ? (size_t)blk * 64 + lane : 0];
+                own[f] = live ? own[f] : 0.f;
+            } else {
+                const uint32_t in_table = (blk % a.blocks_per_table) * 16 + (lane & 15);
+                const bool live = blk < a.nblocks && in_table < a.g;
+                own[f] = a.off[live ? (blk / a.blocks_per_table) * a.g + in_table : 0u];
+                own[f] = live ? own[f] : 0.f;
+            }
+        }
+        if (lane < (NORMS ? 32 : 16)) {
+#pragma unroll
+            for (int f = 0; f < BPW; ++f) lds_off[f * 32 + lane] = own[f];
         }
     }
     [[maybe_unused]] float kmax[KAPPA ? BPW : 1];  // kappa~^2 pass: largest ||S(v)||^2 seen per block
@@ -308,7 +323,8 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                             const uint32_t slot = ln >> 4;
                             const float one = a.raw ? 0.f : 1.f;
                             const float colx = slot == 0 ? (MDATA ? scale : 0.f) : (slot == 1 ? one : 0.f);
-                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.extra[(size_t)blk * 64 + ln], colx, acc[f], 0, 0, 0);
+                            const float rowx = lds_off[f * 32 + (ln & 31)];  // the last two sample slots multiply zeros
+                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x4f32(rowx, colx, acc[f], 0, 0, 0);
                         }
                     }
                     if (blk < a.nblocks && in_table < a.g && vec < a.N) {  // g is a multiple of 4: whole quads
@@ -321,7 +337,7 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                             for (int e = 0; e < 4; ++e)  // b~ is in the accumulator already
                                 v[e] = (uint32_t)(int)floorf(a.w_is_pow2 ? acc[f][e] * a.inv_w : acc[f][e] / a.w);
                         } else {
-                            const floatx4 bq = *reinterpret_cast<const floatx4 *>(lds_off + f * 16 + 4 * (ln >> 4));
+                            const floatx4 bq = *reinterpret_cast<const floatx4 *>(lds_off + f * 32 + 4 * (ln >> 4));
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const float h = a.w_is_pow2 ? fmaf(acc[f][e], a.inv_w, bq[e] * a.inv_w) : (acc[f][e] + bq[e]) / a.w;
@@ -372,7 +388,7 @@ SharedRangedPlan plan_shared_ranged(uint32_t n, uint32_t k, uint32_t m, uint32_t
     pl.bpw = inst;
     pl.nchunks = (n + kWindowCoords - 1) / kWindowCoords;
     pl.stages = (pl.nchunks + kWindowSlots - 1) / kWindowSlots * kWindowSlots;
-    if (kRingBytesSR + kCWs * pl.bpw * 64 + (size_t)pl.stages * 4 > (size_t)kLdsLimitSR) return pl;  // the table of turns no longer fits LDS
+    if (kRingBytesSR + kCWs * pl.bpw * 128 + (size_t)pl.stages * 4 > (size_t)kLdsLimitSR) return pl;  // the table of turns no longer fits LDS
     pl.supported = true;
     return pl;
 }
@@ -539,7 +555,7 @@ int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uin
     if (gx > ntiles) gx = ntiles;
     const dim3 grid((uint32_t)gx, pl.kblocks);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const uint32_t lds_bytes = kRingBytesSR + kCWs * pl.bpw * 64 + pl.stages * 4;
+    const uint32_t lds_bytes = kRingBytesSR + kCWs * pl.bpw * 128 + pl.stages * 4;
 #define LSH_SR_LAUNCH(B_, M_) \
     { \
         auto fn = &shared_ranged_kernel<B_, M_>; \
