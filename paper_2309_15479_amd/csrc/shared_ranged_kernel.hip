@@ -132,6 +132,8 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
     if (wave >= (uint32_t)kCWs) {
         // ---- loading waves: four vectors each, one 1 KB instruction per vector and range; a
         // range is requested three stages before it is written to LDS
+        // the loading waves' few instructions go first: a range requested late is bandwidth lost
+        __builtin_amdgcn_s_setprio(3);
         const uint32_t v0 = (wave - kCWs) * 4;
         const uint64_t total = my_tiles * S;  // a multiple of 8
         uint64_t f_tile = first_tile, s_tile = first_tile;

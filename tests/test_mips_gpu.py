@@ -118,9 +118,9 @@ CASES = [
     (150, 10, 128, 1024, 16, 2.0, 68, False, 32),    # tables of 32 = a wave's two blocks
     (90, 12, 960, 128, 128, 1.0, 69, False, 8),      # 32 MFMA steps, 16-vector tiles
     (200, 12, 256, 256, 100, 4.0, 70, True, 16),     # 32 steps with padded samples
-    (100, 12, 4096, 256, 64, 8.0, 71, False, 16),    # large n: the kernel that works by coordinate ranges, short lists
-    (37, 5, 4100, 96, 40, 2.0, 72, True, 8),         # a fifth range of four coordinates, tables of 12, duplicates
-    (33, 4, 16384, 128, 512, 1.0, 73, False, 4),     # sixteen ranges, long lists, tables of 32
+    (100, 12, 4096, 256, 64, 8.0, 71, False, 16),    # large n: the kernel that works by coordinate ranges, 16 stages
+    (37, 5, 4100, 96, 40, 2.0, 72, True, 8),         # a seventeenth range of four coordinates, tables of 12, duplicates
+    (33, 4, 16384, 128, 512, 1.0, 73, False, 4),     # 64 stages, tables of 32
     (60, 6, 2048, 1024, 30, 4.0, 74, False, 64),     # eight blocks per wave
     (50, 7, 1264, 256, 200, 2.0, 75, False, 16),     # just above the whole-vector kernel's largest n
 ]

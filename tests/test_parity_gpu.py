@@ -186,16 +186,16 @@ SHARED = [
     (90, 960, 128, 128, 1.0, 49, False, 8),      # 64 < m <= 128: 32 MFMA steps, 16-vector tiles (the GIST shape's geometry)
     (300, 256, 512, 100, 4.0, 53, True, 32),     # 32 steps with padded samples, 64-vector tiles
     (33, 1260, 64, 65, 2.0, 54, False, 4),       # the widest n the 32-step kernel takes
-    (40, 1264, 64, 65, 2.0, 55, False, 4),       # one more: the kernel for large dimensions, two ranges
-    (40, 960, 128, 160, 1.0, 56, False, 8),      # m > 128: the same kernel, one range
-    (100, 4096, 256, 64, 8.0, 57, False, 16),    # four ranges, tables of 16 = one block each, two blocks per wave
-    (37, 4100, 96, 40, 2.0, 58, True, 8),        # a fifth range of 4 coordinates, tables of 12, duplicates in S
+    (40, 1264, 64, 65, 2.0, 55, False, 4),       # one more: the kernel for large dimensions, five ranges in eight stages
+    (40, 960, 128, 160, 1.0, 56, False, 8),      # m > 128: the same kernel, four ranges (the last one of 192 coordinates)
+    (100, 4096, 256, 64, 8.0, 57, False, 16),    # 16 stages, tables of 16 = one block each, four blocks per wave with idle ones
+    (37, 4100, 96, 40, 2.0, 58, True, 8),        # a seventeenth range of 4 coordinates in 24 stages, tables of 12, duplicates in S
     (50, 2048, 1024, 30, 4.0, 59, False, 64),    # eight blocks per wave
     (20, 4096, 4096, 64, 8.0, 60, False, 128),   # tables of 32 (two blocks each), four workgroups along the functions
-    (33, 16384, 128, 512, 1.0, 61, False, 4),    # sixteen ranges, long lists
+    (33, 16384, 128, 512, 1.0, 61, False, 4),    # 64 stages
     (1, 4096, 64, 32, 4.0, 62, False, 4),        # one vector, one block per wave and idle blocks
     (17, 8192, 2048, 4, 8.0, 63, False, 128),    # four samples per table: most lists of a range are empty
-    (45, 1264, 256, 200, 2.0, 64, True, 16),     # just above the whole-vector kernel's n: a second range of 240 coordinates, blocks of six steps
+    (45, 1264, 256, 200, 2.0, 64, True, 16),     # just above the whole-vector kernel's n: a fifth range of 240 coordinates, duplicates in S
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
 ]
 
