@@ -233,6 +233,9 @@ def test_windowed_gather_schedule_needs_little_padding(n, k, m, entries, lds):
     (1264, 64, 65, 2.0, 55, False, 4),       # five ranges in eight stages, four blocks per wave (turns of eight steps per block)
     (16384, 128, 512, 1.0, 61, False, 4),    # 64 stages
     (2048, 1024, 30, 4.0, 59, False, 64),    # one ring of ranges holds the whole vector
+    (40000, 64, 100, 2.0, 65, False, 4),     # 157 ranges in 160 stages
+    (1000000, 16, 8, 2.0, 3, False, 1),      # 3912 stages: the table of turns nearly fills what LDS the ring leaves
+    (1100000, 16, 8, 2.0, 3, False, 1),      # one more ring and it no longer fits: the object falls back to the gather kernel
 ])
 def test_list_tables_walked_on_the_host(n, k, m, w, seed, repl, L):
     """The list tables of the kernels that work by coordinate ranges, built as for the device and

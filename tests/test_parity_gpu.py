@@ -197,6 +197,8 @@ SHARED = [
     (17, 8192, 2048, 4, 8.0, 63, False, 128),    # four samples per table: most lists of a range are empty
     (45, 1264, 256, 200, 2.0, 64, True, 16),     # just above the whole-vector kernel's n: a fifth range of 240 coordinates, duplicates in S
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
+    (20, 40000, 64, 100, 2.0, 65, False, 4),     # 157 ranges in 160 stages, most of them without a turn
+    (3, 262144, 512, 64, 4.0, 66, True, 2),      # 1024 stages (the table of turns takes 4 KB of LDS), tables of 256 functions
 ]
 
 
