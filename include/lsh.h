@@ -80,10 +80,11 @@ int lsh_params_create_ex(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t s
  * Every hash call accepts such an object; lsh_hash_fastlsh, lsh_project_fastlsh and (called
  * with the same L, g <= 32) lsh_hash_fastlsh_keys then gather each table's sub-vector once and
  * contract it with the g coefficient vectors on the matrix cores when the shape allows
- * (n % 4 == 0 and g % 4 == 0; lsh_hash_fastlsh_keys only with m <= 64 and n <= 612 or
- * 64 < m <= 128 and n <= 1260, where whole vectors stay in LDS; ids and projections at any
- * larger n or m < n too, by coordinate ranges, up to n of about 10^6), and fall back to the
- * per-function gather kernels otherwise.  L == 0 is lsh_params_create_ex.
+ * (n % 4 == 0 and g % 4 == 0; with m <= 64 and n <= 612 or 64 < m <= 128 and n <= 1260 whole
+ * vectors stay in LDS and lsh_hash_fastlsh_keys takes g <= 32; at any larger n or m < n the
+ * kernel works by coordinate ranges, up to n of about 10^6, and lsh_hash_fastlsh_keys and
+ * lsh_hash_fastlsh_ids_keys take g <= 16 in one launch), and fall back to the per-function
+ * gather kernels otherwise.  L == 0 is lsh_params_create_ex.
  * Errors: as lsh_params_create, and INVALID_ARG when k % L != 0.
  */
 int lsh_params_create_shared(uint32_t n, uint32_t k, uint32_t m, float w, uint64_t seed,

@@ -403,6 +403,7 @@ int lsh_hash_fastlsh_keys(const lsh_params_t *p, const float *d_data, uint64_t N
     if (!is_pow2(g) || g > 64) return LSH_ERR_UNSUPPORTED;
     if (N == 0) return LSH_OK;
     if (shared_keys_ok(p, L)) return launch_shared(p, 2, d_data, N, d_out, stream);
+    if (shared_ranged_keys_ok(p, L)) return launch_shared_ranged(p, 6, d_data, N, nullptr, stream, nullptr, 0, d_out);
     if (p->dense_arithmetic != LSH_DENSE_FP32 && !p->shared_plan.supported && dense_split_keys_supported(p, L))
         return launch_dense_split(p, 3, d_data, N, d_out, stream, L);
     return launch_sampled(p, Epilogue::Keys, d_data, N, d_out, L, stream);
@@ -416,6 +417,7 @@ int lsh_hash_fastlsh_ids_keys(const lsh_params_t *p, const float *d_data, uint64
     if (N == 0) return LSH_OK;
     // one launch where a kernel has the epilogue for it; the results are those of the two calls
     // either way (the keys are folded from the very ids that are stored)
+    if (shared_ranged_keys_ok(p, L)) return launch_shared_ranged(p, 6, d_data, N, d_ids, stream, nullptr, 0, d_keys);
     const bool per_function = !p->shared_plan.supported && !p->shared_ranged_plan.supported;
     if (per_function && p->dense_arithmetic != LSH_DENSE_FP32 && dense_split_keys_supported(p, L))
         return launch_dense_split(p, 4, d_data, N, d_ids, stream, L, d_keys);

@@ -162,7 +162,7 @@ void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::
                                 std::vector<uint32_t> &offs, std::vector<uint32_t> &stage_turns,
                                 std::vector<uint32_t> &stream_info, std::vector<float> *extra = nullptr);
 int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uint64_t N, void *d_out, void *stream,
-                         const float *d_kappa2 = nullptr, int raw = 0);
+                         const float *d_kappa2 = nullptr, int raw = 0, uint64_t *d_keys = nullptr);
 SharedPlan plan_shared(uint32_t n, uint32_t k, uint32_t m, uint32_t L);
 void build_shared_tables(const lsh_params *p, std::vector<float> &coef, std::vector<uint32_t> &sample_off,
                          std::vector<float> &offset, std::vector<float> &extra);
@@ -175,6 +175,7 @@ int launch_shared(const lsh_params *p, int ep, const float *d_data, uint64_t N, 
 int clear_floats(float *d, uint32_t count, void *stream);
 // the shared-sample kernel can fold keys when a table lies inside one wave's blocks
 bool shared_keys_ok(const lsh_params *p, uint32_t L);
+bool shared_ranged_keys_ok(const lsh_params *p, uint32_t L);
 // raises a kernel's dynamic LDS limit once (per kernel and size)
 int ensure_lds_limit(const void *fn, uint32_t lds_bytes);
 int launch_dense(const lsh_params *p, bool proj, const float *d_data, uint64_t N, void *d_out,

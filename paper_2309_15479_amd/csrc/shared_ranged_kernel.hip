@@ -102,19 +102,22 @@ struct SharedRangedArgs {
     const float *extra;     // [nblocks][64] row operand (a0, b~, 0, 0) of the extra step (maximum inner product)
     const float *kappa2;    // [tables] kappa~_l^2, input of the data hash
     int raw;                // maximum-inner-product modes: projections instead of ids
+    uint64_t *keys;         // key mode: [N][tables]; out is then the ids' array or null
     const float *coefs;     // list blocks: 8 steps x 64 lanes
     const uint32_t *offs;   // per list block: 4 sample slots x 4 words of two 16-bit byte offsets into a row of the ring
 };
 
 // BPW: blocks of 16 functions per contracting wave (a turn of the list ring gives each of them 32 / BPW steps);
-// MODE: 0 ids or projections, 3 kappa~^2, 4 maximum-inner-product data hash, 5 query hash
+// MODE: 0 ids or projections, 3 kappa~^2, 4 maximum-inner-product data hash, 5 query hash,
+// 6 one 64-bit key per table (tables of at most 16 functions: one block each), and the ids too if asked for
 template <int BPW, int MODE>
 __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedRangedArgs a,
                                                                    const uint32_t *__restrict__ stage_turns,
                                                                    const uint2 *__restrict__ streams) {
     static_assert(kTurnSteps % BPW == 0, "a turn deals the same number of steps to every block");
     constexpr int Q = kTurnSteps / BPW;  // consecutive steps of one block within a turn
-    constexpr bool KAPPA = MODE == 3, MDATA = MODE == 4, MQUERY = MODE == 5, NORMS = MODE >= 3;
+    constexpr bool KAPPA = MODE == 3, MDATA = MODE == 4, MQUERY = MODE == 5, NORMS = MODE >= 3 && MODE <= 5;
+    constexpr bool KEYS = MODE == 6;
     extern __shared__ __align__(16) char lds_sr[];  // [16 vectors][8 ranges x 256 + 4 floats], offsets, turns
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
@@ -250,6 +253,14 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
             for (int f = 0; f < BPW; ++f) lds_off[f * 32 + lane] = own[f];
         }
     }
+    // key mode (Sec. 3.2): a lane folds its four ids, weighs the fold by the power of the multiplier that
+    // belongs to the last of them, C^(g - 1 - t), and the four lanes of a vector add up
+    [[maybe_unused]] uint64_t key_pow = 1;
+    if constexpr (KEYS) {
+        const uint32_t t_last = 4 * (lane >> 4) + 3;
+        for (uint32_t e = 0; e + 1 + t_last < a.g; ++e) key_pow *= kKeyMultiplier;
+        if (t_last >= a.g) key_pow = 0;  // rows beyond the table
+    }
     [[maybe_unused]] float kmax[KAPPA ? BPW : 1];  // kappa~^2 pass: largest ||S(v)||^2 seen per block
 #pragma unroll
     for (int f = 0; f < (KAPPA ? BPW : 1); ++f) kmax[f] = 0.f;
@@ -328,6 +339,29 @@ __global__ __launch_bounds__(kThreadsSR) void shared_ranged_kernel(const SharedR
                             const float rowx = lds_off[f * 32 + (ln & 31)];  // the last two sample slots multiply zeros
                             acc[f] = __builtin_amdgcn_mfma_f32_16x16x4f32(rowx, colx, acc[f], 0, 0, 0);
                         }
+                    }
+                    if constexpr (KEYS) {
+                        // every lane takes part in the exchange; blocks and rows beyond the data fold zeros or
+                        // values nobody stores
+                        const floatx4 bq = *reinterpret_cast<const floatx4 *>(lds_off + f * 32 + 4 * (ln >> 4));
+                        uintx4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float h = a.w_is_pow2 ? fmaf(acc[f][e], a.inv_w, bq[e] * a.inv_w) : (acc[f][e] + bq[e]) / a.w;
+                            v[e] = (uint32_t)(int)floorf(h);
+                        }
+                        uint64_t part = v[0];
+#pragma unroll
+                        for (int e = 1; e < 4; ++e) part = part * kKeyMultiplier + v[e];
+                        part *= key_pow;
+                        part += __shfl_xor(part, 16);
+                        part += __shfl_xor(part, 32);
+                        if (blk < a.nblocks && vec < a.N) {  // one block per table: the block number is the table
+                            if (ln < 16) a.keys[vec * a.nblocks + blk] = part;
+                            if (a.out && in_table < a.g)
+                                *reinterpret_cast<uintx4 *>(reinterpret_cast<uint32_t *>(a.out) + vec * a.k + j) = v;
+                        }
+                        continue;
                     }
                     if (blk < a.nblocks && in_table < a.g && vec < a.N) {  // g is a multiple of 4: whole quads
                         uintx4 v;
@@ -518,10 +552,17 @@ void build_shared_ranged_tables(const lsh_params *p, SharedRangedPlan &pl, std::
         }
 }
 
+// Keys come out of the kernel when the key groups are the tables and a table is one block.
+bool shared_ranged_keys_ok(const lsh_params *p, uint32_t L) {
+    const SharedRangedPlan &pl = p->shared_ranged_plan;
+    return pl.supported && p->d_sr_lists && L == p->shared_tables && pl.blocks_per_table == 1;
+}
+
 // mode: 0 bucket ids, 1 raw projections, 3 kappa~^2 per table (atomic maximum into d_out), 4 and 5
-// the maximum-inner-product data and query hashes (raw != 0: their projections)
+// the maximum-inner-product data and query hashes (raw != 0: their projections), 6 the tables'
+// keys into d_keys (tables of at most 16 functions) and, if d_out is not null, the ids as well
 int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uint64_t N, void *d_out, void *stream,
-                         const float *d_kappa2, int raw) {
+                         const float *d_kappa2, int raw, uint64_t *d_keys) {
     const SharedRangedPlan &pl = p->shared_ranged_plan;
     if (!pl.supported || !p->d_sr_lists || !p->d_sr_offs) return LSH_ERR_UNSUPPORTED;
     if (!N) return LSH_OK;
@@ -544,7 +585,9 @@ int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uin
     a.extra = static_cast<const float *>(p->d_sr_extra);
     a.kappa2 = d_kappa2;
     a.raw = raw;
-    if (mode >= 3 && !p->d_sr_extra) return LSH_ERR_UNSUPPORTED;
+    a.keys = d_keys;
+    if (mode >= 3 && mode <= 5 && !p->d_sr_extra) return LSH_ERR_UNSUPPORTED;
+    if (mode == 6 && (pl.blocks_per_table != 1 || !d_keys)) return LSH_ERR_UNSUPPORTED;
     a.out = d_out;
     a.coefs = static_cast<const float *>(p->d_sr_lists);
     a.offs = static_cast<const uint32_t *>(p->d_sr_offs);
@@ -570,6 +613,7 @@ int launch_shared_ranged(const lsh_params *p, int mode, const float *d_data, uin
         else if (mode == 3) LSH_SR_LAUNCH(B_, 3) \
         else if (mode == 4) LSH_SR_LAUNCH(B_, 4) \
         else if (mode == 5) LSH_SR_LAUNCH(B_, 5) \
+        else if (mode == 6) LSH_SR_LAUNCH(B_, 6) \
         else return LSH_ERR_INVALID_ARG; \
         break;
     switch (pl.bpw) {

@@ -197,6 +197,8 @@ SHARED = [
     (17, 8192, 2048, 4, 8.0, 63, False, 128),    # four samples per table: most lists of a range are empty
     (45, 1264, 256, 200, 2.0, 64, True, 16),     # just above the whole-vector kernel's n: a fifth range of 240 coordinates, duplicates in S
     (40, 128, 60, 16, 1.0, 50, False, 10),       # tables of 6: gather kernels
+    (60, 4096, 64, 48, 2.0, 67, False, 16),      # tables of 4: keys folded from one lane group of a block
+    (61, 5000, 128, 80, 2.0, 68, True, 16),      # tables of 8: two lane groups
     (20, 40000, 64, 100, 2.0, 65, False, 4),     # 157 ranges in 160 stages, most of them without a turn
     (3, 262144, 512, 64, 4.0, 66, True, 2),      # 1024 stages (the table of turns takes 4 KB of LDS), tables of 256 functions
 ]
@@ -391,6 +393,9 @@ def test_pack_keys_group_sizes(lsh, k, L):
     (37, 4100, 512, 40, 8, 2.0, False, 0),       # ranged kernel, tables of 64, ragged last range
     (50, 2048, 520, 30, 130, 4.0, False, 0),     # ranged kernel, k not a multiple of 64
     (200, 128, 512, 32, 32, 16.0, False, 32),    # one sample per table: two launches
+    (70, 4096, 256, 64, 16, 8.0, False, 16),     # one sample per table at large n, tables of 16: one launch
+    (45, 5000, 96, 50, 12, 3.0, False, 12),      # tables of 8, idle blocks, w not a power of two
+    (30, 4096, 128, 64, 4, 8.0, False, 4),       # tables of 32 = two blocks: two launches
 ])
 def test_ids_and_keys_in_one_call(lsh, N, n, k, m, L, w, fp32, shared):
     """lsh_hash_fastlsh_ids_keys: the ids are those of lsh_hash_fastlsh bit for bit, and the keys
