@@ -603,6 +603,8 @@ class Bench:
                                 "hashes_per_s": N * k / (sms * 1e-3), "vectors_per_s": N / (sms * 1e-3),
                                 "dtype": "f32", "timed": "outside the step",
                                 "parity": self.check_ids(p, wl, data, out, dense=False),
+                                "schedule": {"mfma_steps_per_block_and_tile": p.shared_schedule()[1],
+                                             "sample_slots_per_sample": 4.0 * p.shared_schedule()[1] / m},
                                 "roofline": shared_roofline(N, n, k, m, sms),
                                 "speedup_over_per_function_samples": ms[f"fastlsh_m{m}"] / sms})
         dominant = max(legs, key=lambda leg: ms[leg])

@@ -151,6 +151,16 @@ int lsh_params_get_schedule(const lsh_params_t *params, uint32_t *order, uint32_
 int lsh_params_check_lists(const lsh_params_t *params, uint64_t seed, double *worst);
 
 /*
+ * One sample per table (Sec. 3.1, 4.1) at large n: how the matrix-core kernel that works by
+ * coordinate ranges deals a table's m samples to its stages.  *stages receives the stages of a
+ * tile of 16 vectors and *steps the MFMA steps of four samples that every block of 16
+ * functions takes per tile (all tables get the same number; steps * 4 - m of the sample slots
+ * are padding).  Needs no GPU.
+ * Errors: INVALID_ARG (null), UNSUPPORTED (the object does not run on that kernel), ALLOC.
+ */
+int lsh_params_get_shared_schedule(const lsh_params_t *params, uint32_t *stages, uint32_t *steps);
+
+/*
  * FastLSH bucket ids (Eq. 5): d_out_buckets[v*k + j] = floor((a~_j^T S_j(v) + b~_j) / w)
  * as int32 (saturating), for v < N, j < k.  Sampled-projection kernel: each vector
  * tile is read from HBM once, kept in LDS, and every function gathers its m

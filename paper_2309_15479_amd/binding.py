@@ -24,6 +24,7 @@ EXPORTS = [
     "lsh_params_create", "lsh_params_create_ex", "lsh_params_create_shared", "lsh_params_destroy",
     "lsh_params_get_indices", "lsh_params_get_coeffs", "lsh_params_get_offsets", "lsh_params_get_shape",
     "lsh_params_get_tables", "lsh_params_get_mips_coeffs", "lsh_params_get_schedule", "lsh_params_check_lists",
+    "lsh_params_get_shared_schedule",
     "lsh_params_set_dense_arithmetic",
     "lsh_hash_fastlsh",
     "lsh_hash_e2lsh", "lsh_hash_signs", "lsh_pack_keys", "lsh_hash_fastlsh_keys", "lsh_hash_fastlsh_ids_keys",
@@ -200,6 +201,16 @@ class LshParams:
         lib.lsh_params_check_lists.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
         _check(lib.lsh_params_check_lists(self.handle, seed, ctypes.addressof(worst)), "lsh_params_check_lists")
         return worst.value
+
+    def shared_schedule(self):
+        """(stages per tile, MFMA steps of four samples per block of 16 functions and tile) of the
+        one-sample-per-table kernel that works by coordinate ranges."""
+        stages, steps = ctypes.c_uint32(), ctypes.c_uint32()
+        lib = load_library()
+        lib.lsh_params_get_shared_schedule.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        _check(lib.lsh_params_get_shared_schedule(self.handle, ctypes.addressof(stages), ctypes.addressof(steps)),
+               "lsh_params_get_shared_schedule")
+        return stages.value, steps.value
 
     def shared_tables(self):
         L = ctypes.c_uint32()

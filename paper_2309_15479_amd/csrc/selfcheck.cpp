@@ -195,3 +195,21 @@ int lsh_params_check_lists(const lsh_params_t *p, uint64_t seed, double *worst) 
     }
     return LSH_OK;
 }
+
+int lsh_params_get_shared_schedule(const lsh_params_t *p, uint32_t *stages, uint32_t *steps) {
+    if (!p || !stages || !steps) return LSH_ERR_INVALID_ARG;
+    if (!p->shared_ranged_plan.supported) return LSH_ERR_UNSUPPORTED;
+    try {
+        lsh::SharedRangedPlan pl = p->shared_ranged_plan;
+        std::vector<float> coefs;
+        std::vector<uint32_t> offs, turns, info;
+        lsh::build_shared_ranged_tables(p, pl, coefs, offs, turns, info);
+        uint32_t total = 0;
+        for (uint32_t t : turns) total += t;
+        *stages = pl.stages;
+        *steps = total * (4 * 8 / pl.bpw);  // a turn of the list ring: four blocks of eight steps, dealt to the wave's blocks
+    } catch (const std::bad_alloc &) {
+        return LSH_ERR_ALLOC;
+    }
+    return LSH_OK;
+}

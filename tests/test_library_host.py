@@ -246,6 +246,24 @@ def test_list_tables_walked_on_the_host(n, k, m, w, seed, repl, L):
             assert p.check_lists(vector_seed) < 1e-14
 
 
+@pytest.mark.parametrize("n,k,m,L,steps_max", [(4096, 2048, 64, 128, 18), (4096, 2048, 256, 128, 66),
+                                               (4096, 2048, 1024, 128, 260), (16384, 4096, 512, 256, 141)])
+def test_shared_sample_schedule_needs_little_padding(n, k, m, L, steps_max):
+    """One sample per table on the high-dimensional shapes: the stages of a tile give every table
+    the same number of MFMA steps of four samples, and dealing the samples by their last possible
+    stage keeps that number within a few percent of m / 4 (12 % at m = 64, where a turn of the
+    list ring is two steps per block; one fixed stage per 1024-coordinate range needed 32, 96,
+    320 steps on the first three shapes)."""
+    with binding.LshParams(n, k, m, 8.0, 4, shared_tables=L) as p:
+        stages, steps = p.shared_schedule()
+        assert stages == (n + 255) // 256 and stages % 8 == 0
+        assert m <= 4 * steps <= 4 * steps_max
+    with binding.LshParams(n, k, m, 8.0, 4) as p:   # per-function samples: the gather kernel
+        with pytest.raises(binding.LshError) as e:
+            p.shared_schedule()
+        assert e.value.status == -4
+
+
 def test_list_check_needs_a_ranged_kernel():
     with binding.LshParams(128, 64, 32, 4.0, 1) as p:   # whole vectors in LDS, lists in registers
         with pytest.raises(binding.LshError) as e:
